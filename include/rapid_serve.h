@@ -1,0 +1,260 @@
+/*
+ * rapid_serve.h -- C ABI of the MI355X (gfx950) prefill/decode co-execution library.
+ *
+ * One Llama-style decoder layer is evaluated in two ways that share one paged KV
+ * cache on one GPU (paper: abstract, sections 2.1, 4.1):
+ *   - PREFILL: a whole prompt at once, compute bound, fills the cache;
+ *   - DECODE : one new token per running request, bandwidth bound, reads the cache.
+ * The two run concurrently, never in one batch, each on its own HIP stream whose
+ * hardware queue is confined to a set of compute units by a CU mask (section 4.2).
+ * An adaptive resource manager picks the split (section 4.5.3).
+ *
+ * Conventions
+ *   - Every call returns an int32 status: RS_OK (0) or a negative RS_ERR_*.
+ *     rs_last_error() gives a thread-local text for the last failure.  Nothing
+ *     throws across this boundary.
+ *   - "device" pointers are HIP device memory owned by the CALLER (weights, KV pools,
+ *     activations, block tables, context lengths).  The library borrows them until
+ *     the enqueued work has finished (rs_sync).  "host" pointers are ordinary memory,
+ *     read before the call returns.
+ *   - The library owns: its CU-masked streams and events, the block free list, the
+ *     profile table, the rotary table and two activation workspaces it allocates in
+ *     rs_init (one per side, sized from rs_limits).
+ *   - Layer calls only ENQUEUE work on the side's current stream and return.
+ *   - All matrices are bf16, row major.  Projection weights are [out_features,
+ *     in_features].  Accumulation is fp32.  Indices are int32.
+ *   - KV pools (bf16), block = 16 tokens:
+ *         K pool: [n_layers][n_blocks][n_kv_heads][16][head_dim]
+ *         V pool: [n_layers][n_blocks][n_kv_heads][head_dim][16]   (token-minor)
+ *     K is stored after the rotary embedding.
+ *   - A context created with device = RS_HOST_ONLY touches no GPU: the allocator,
+ *     the manager and the request state machine work, layer calls fail with RS_ERR_STATE.
+ */
+#ifndef RAPID_SERVE_H
+#define RAPID_SERVE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RS_OK 0
+#define RS_ERR_BAD_ARG (-1)   /* null pointer, size out of range, unsupported shape */
+#define RS_ERR_NO_BLOCKS (-2) /* KV pool exhausted; allocator state unchanged */
+#define RS_ERR_BAD_SPLIT (-3) /* illegal CU split */
+#define RS_ERR_BAD_BLOCK (-4) /* block id outside the pool, or table too short for a context */
+#define RS_ERR_HIP (-5)       /* a HIP runtime call failed */
+#define RS_ERR_STATE (-6)     /* call not valid in the context's current state */
+
+#define RS_SIDE_PREFILL 0
+#define RS_SIDE_DECODE 1
+
+#define RS_TOTAL_CUS 256
+#define RS_CU_GRANULE 32        /* splits are multiples of this (4 CUs in each of the 8 XCDs) */
+#define RS_KV_BLOCK 16          /* tokens per KV block */
+#define RS_MAX_PREFILL_REQS 64  /* prompts per rs_prefill_layer call */
+#define RS_HOST_ONLY (-1)
+
+typedef struct rs_ctx rs_ctx;
+
+/* Layer dimensions.  Supported: head_dim 64 or 128; d_model, ffn_dim multiples of 8;
+ * n_q_heads a multiple of n_kv_heads with at most 16 query heads per KV head. */
+typedef struct {
+    int32_t d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, n_layers;
+    float rms_eps;    /* inside the square root */
+    float rope_base;  /* theta_i = rope_base^(-2i/head_dim), rotate-half pairing (i, i+head_dim/2) */
+    int32_t max_pos;  /* rows of the rotary table: positions 0..max_pos-1 are legal */
+} rs_model_desc;
+
+/* Caller-allocated KV pools (device).  layer_stride = elements between layers. */
+typedef struct {
+    void *k_pool, *v_pool;
+    int64_t layer_stride;
+    int32_t n_blocks;
+} rs_pool_desc;
+
+/* Upper bounds that size the two activation workspaces. */
+typedef struct {
+    int32_t max_prefill_tokens; /* total tokens of one rs_prefill_layer call */
+    int32_t max_decode_batch;   /* rows of one rs_decode_layer call */
+    int32_t max_context;        /* largest ctx_len + 1 a decode row may attend to */
+} rs_limits;
+
+/* Offline profile for the manager (host memory, copied by rs_init; may be NULL = manager
+ * always over-allocates).  Section 4.5.3: per decode load, latency of a decode step for each
+ * distinct split and under over-allocation, measured while prefill co-runs.
+ * lat_distinct_us is [n_batch][n_ctx][n_split], lat_over_us is [n_batch][n_ctx]. */
+typedef struct {
+    int32_t n_batch, n_ctx, n_split;
+    const int32_t *batch_edges; /* ascending decode batch sizes */
+    const int32_t *ctx_edges;   /* ascending totals of cached tokens */
+    const int32_t *decode_cus;  /* ascending decode CU counts, multiples of RS_CU_GRANULE */
+    const int32_t *lat_distinct_us;
+    const int32_t *lat_over_us;
+    int32_t slo_us;             /* inter-token latency objective (section 5.3: 50 or 100 ms) */
+} rs_profile;
+
+/* Device pointers to one layer's bf16 weights. */
+typedef struct {
+    const void *g1;   /* [d_model]                       first RMSNorm gain */
+    const void *wqkv; /* [(Hq+2Hkv)*hd, d_model]         rows: q heads, k heads, v heads */
+    const void *wo;   /* [d_model, Hq*hd] */
+    const void *g2;   /* [d_model]                       second RMSNorm gain */
+    const void *wg;   /* [ffn_dim, d_model]              SwiGLU gate */
+    const void *wu;   /* [ffn_dim, d_model]              SwiGLU up */
+    const void *wd;   /* [d_model, ffn_dim] */
+} rs_layer_weights;
+
+/* ---- life cycle ---------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device` (or RS_HOST_ONLY).  Allocates workspaces, the
+ * rotary table (angles formed in float64 on the host) and the default stream pair for the
+ * split (256,256).  pool may have null pointers only for RS_HOST_ONLY.  prof may be NULL. */
+int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_limits *limits,
+                const rs_profile *prof, int32_t device, rs_ctx **out);
+/* Waits for both sides, frees everything the library owns. */
+int32_t rs_destroy(rs_ctx *ctx);
+/* Registers (borrows) the weights of one layer. */
+int32_t rs_set_weights(rs_ctx *ctx, int32_t layer, const rs_layer_weights *w);
+const char *rs_last_error(void);
+
+/* ---- KV cache manager (section 4.5.1; request flow, section 4.4) ------------------------
+ * Single owner of the block pool.  rs_kv_alloc makes request req_id own exactly
+ * ceil(n_tokens_total/16) blocks, allocating only the missing tail (a request never shrinks),
+ * and writes the request's full ordered id list to block_ids_out[0..*n_blocks_out) (host,
+ * capacity cap).  The count depends on the length alone, so prompt blocks can be handed to
+ * the prefill side before it runs.  On RS_ERR_NO_BLOCKS (or cap too small: RS_ERR_BAD_ARG)
+ * nothing changes.  Free list is LIFO: a fresh pool hands out 0,1,2,..; a released
+ * request's blocks are reused next, in their original order. */
+int32_t rs_kv_alloc(rs_ctx *ctx, int64_t req_id, int32_t n_tokens_total, int32_t *block_ids_out,
+                    int32_t cap, int32_t *n_blocks_out);
+int32_t rs_kv_free(rs_ctx *ctx, int64_t req_id);
+int32_t rs_kv_num_free(rs_ctx *ctx, int32_t *n_free_out);
+
+/* ---- layer passes ---------------------------------------------------------------------- */
+
+/* Un-chunked prefill of n_req whole prompts through layer `layer` (sections 2.1, 4.5.2:
+ * a prefill finishes in one step, positions start at 0).  Enqueued on the PREFILL stream.
+ *   x_in, x_out  device bf16 [T, d_model], T = cu_seqlens[n_req] (may alias each other)
+ *   cu_seqlens   host int32 [n_req+1], ascending from 0; n_req <= RS_MAX_PREFILL_REQS
+ *   block_tables device int32 [n_req, max_blk]; row r holds >= ceil(len_r/16) valid ids
+ * Writes K/V of every token into the pools through the tables, then causal attention per
+ * prompt, output projection + residual, SwiGLU FFN + residual.  A block id outside the pool
+ * is never dereferenced: the access is skipped and rs_sync reports RS_ERR_BAD_BLOCK. */
+int32_t rs_prefill_layer(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_out,
+                         const int32_t *cu_seqlens, int32_t n_req, const int32_t *block_tables,
+                         int32_t max_blk);
+
+/* One decode step through layer `layer` for a batch of B running requests (section 2.1).
+ * Enqueued on the DECODE stream.
+ *   x_in, x_out  device bf16 [B, d_model]
+ *   ctx_lens     device int32 [B]: tokens already cached; row i is the token at position
+ *                ctx_lens[i], its K/V are appended there and it attends to ctx_lens[i]+1 keys
+ *   block_tables device int32 [B, max_blk]; row i holds >= ceil((ctx_lens[i]+1)/16) valid ids
+ *   max_ctx      host upper bound of ctx_lens[i]+1 over the batch (sizes the launch)
+ * Results do not depend on the CU split nor on what runs on the other side: every reduction
+ * shape is a function of the problem shape alone. */
+int32_t rs_decode_layer(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_out,
+                        const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
+                        int32_t B, int32_t max_ctx);
+
+/* ---- CU partitioning (sections 4.2, 4.5.3) -------------------------------------------------
+ * Selects the masks for SUBSEQUENT enqueues.  Each count is 0 or a multiple of
+ * RS_CU_GRANULE up to 256.  prefill+decode <= 256 gives disjoint masks (prefill takes mask
+ * bits from 0 upward, decode from 255 downward; consecutive bits fall in different XCDs, so
+ * each side keeps CUs in all 8 XCDs).  (256,256) is over-allocation: both sides see every
+ * CU.  Any other overlapping pair is RS_ERR_BAD_SPLIT.  A side with 0 CUs refuses work
+ * (RS_ERR_STATE).  Work already enqueued keeps the mask it was enqueued with; later work of
+ * the same side is ordered after it. */
+int32_t rs_set_cu_split(rs_ctx *ctx, int32_t prefill_cus, int32_t decode_cus);
+int32_t rs_get_cu_split(rs_ctx *ctx, int32_t *prefill_cus, int32_t *decode_cus);
+/* The mask words (8 x uint32) a side's stream was created with, for inspection. */
+int32_t rs_get_cu_mask(rs_ctx *ctx, int32_t side, uint32_t mask_out[8]);
+
+/* The manager's choice (pure function of its arguments and the profile given to rs_init):
+ *   no prefill pending -> (0,256); no decode running -> (256,0); profiled over-allocation
+ *   latency meets the objective -> (256,256); else the fewest decode CUs that meet it and the
+ *   rest to prefill; if none meets it, the profiled-fastest split.  Loads are rounded up to
+ *   the next profiled bucket. */
+int32_t rs_choose_split(rs_ctx *ctx, int32_t decode_batch, int64_t sum_ctx, int32_t prefill_pending,
+                        int32_t *prefill_cus, int32_t *decode_cus);
+
+/* ---- streams, synchronisation, timing ------------------------------------------------------ */
+
+/* The hipStream_t a side currently enqueues on (valid until the next rs_set_cu_split). */
+int32_t rs_get_stream(rs_ctx *ctx, int32_t side, void **hip_stream_out);
+/* Blocks until the side's work is done; reports RS_ERR_BAD_BLOCK if a kernel met a bad id
+ * since the last rs_sync (the flag is then cleared). */
+int32_t rs_sync(rs_ctx *ctx, int32_t side);
+/* Timing on the side's own stream: rs_mark records event slot `slot` (0..RS_MAX_MARKS-1) on
+ * the side's current stream; rs_elapsed_ms gives the time between two completed marks. */
+#define RS_MAX_MARKS 4096
+int32_t rs_mark(rs_ctx *ctx, int32_t side, int32_t slot);
+int32_t rs_elapsed_ms(rs_ctx *ctx, int32_t side, int32_t slot_begin, int32_t slot_end, float *ms_out);
+
+/* Where a side's workgroups really run: launches n_workgroups short workgroups on the side's
+ * stream and counts them per physical compute unit.  hist_out (host, RS_CU_HIST_BINS int32) is
+ * indexed by (xcc_id << 8) | (se_id << 5) | (sh_id << 4) | cu_id as read from the hardware-id
+ * registers.  Blocks until done.  Used to check that a CU mask confines work (section 4.2). */
+#define RS_CU_HIST_BINS 4096
+int32_t rs_debug_cu_histogram(rs_ctx *ctx, int32_t side, int32_t n_workgroups, int32_t *hist_out);
+
+/* Copies an intermediate activation buffer of a side's last layer call to host memory (after
+ * waiting for that side): which = 0 first RMSNorm output [M,d]; 1 q|k|v with rotated q and k
+ * [M,(Hq+2Hkv)hd]; 2 attention output [M,Hq*hd]; 3 hidden state after the attention residual
+ * [M,d]; 4 silu(gate)*up [M,ffn].  All bf16, first n_bytes bytes.  For stage-by-stage checks. */
+int32_t rs_debug_read_workspace(rs_ctx *ctx, int32_t side, int32_t which, void *host_out, int64_t n_bytes);
+
+/* ---- serving step (request flow of section 4.4, FCFS of 4.5.2, manager of 4.5.3) -------------
+ * The library keeps the request table: WAITING (no blocks yet) -> PREFILL_READY (prompt
+ * blocks allocated, ids available to the prefill side) -> PREFILLING -> PREFILL_DONE (event
+ * completed: the "notification") -> RUNNING (in the decode batch) -> FINISHED (blocks freed).
+ *
+ * rs_submit adds a request in arrival order.  prompt_hidden is device bf16
+ * [prompt_len, d_model] (there is no embedding on this path; hidden states are inputs).
+ *
+ * rs_step performs one scheduling step:
+ *   1. promotes requests whose prefill event has completed into the decode batch (FCFS,
+ *      up to max_decode_batch) and retires requests that produced all their tokens;
+ *   2. allocates prompt blocks for waiting requests in arrival order while the pool allows;
+ *   3. asks rs_choose_split and applies it;
+ *   4. enqueues one decode step over all n_layers for the running batch (growing each
+ *      request's blocks as needed), with decode_hidden (device bf16 [>=batch, d_model]) as
+ *      the step's input rows;
+ *   5. if the prefill side is idle and a request is PREFILL_READY, enqueues its whole prompt
+ *      over all n_layers on the prefill side and records its completion event.
+ * Never blocks on the GPU except when `wait_decode` is non-zero (then it waits for this
+ * step's decode work, which is what a caller measuring inter-token latency wants). */
+typedef struct {
+    const void *decode_hidden; /* device */
+    void *decode_out;          /* device bf16 [>=batch, d_model], last layer's output */
+    int32_t wait_decode;
+} rs_step_in;
+
+typedef struct {
+    int32_t prefill_cus, decode_cus; /* split used for this step */
+    int32_t decode_batch;            /* rows in this step's decode batch */
+    int64_t decode_sum_ctx;          /* cached tokens over the batch */
+    int32_t prefill_started_tokens;  /* tokens of the prompt whose prefill was enqueued, or 0 */
+    int64_t prefill_started_req;     /* its id, or -1 */
+    int32_t n_promoted;              /* requests that joined the decode batch */
+    int32_t n_finished;              /* requests retired in this step */
+    int32_t n_waiting;               /* requests still without blocks */
+    float decode_ms;                 /* GPU time of this step's decode work if wait_decode, else -1 */
+} rs_step_out;
+
+int32_t rs_submit(rs_ctx *ctx, int64_t req_id, int32_t prompt_len, int32_t output_len,
+                  const void *prompt_hidden);
+int32_t rs_step(rs_ctx *ctx, const rs_step_in *in, rs_step_out *out);
+/* State of a request: 0 WAITING, 1 PREFILL_READY, 2 PREFILLING, 3 PREFILL_DONE, 4 RUNNING,
+ * 5 FINISHED; RS_ERR_BAD_ARG if unknown. */
+int32_t rs_request_state(rs_ctx *ctx, int64_t req_id);
+/* Host-only contexts have no events: this marks a PREFILLING request's event as completed
+ * (lets the state machine be exercised without a GPU).  RS_ERR_STATE on a GPU context. */
+int32_t rs_debug_complete_prefill(rs_ctx *ctx, int64_t req_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPID_SERVE_H */

@@ -1,0 +1,393 @@
+// Attention kernels over the paged KV cache (gfx950, bf16 MFMA, fp32 softmax).
+//
+// Pool layouts (one layer):  K [n_blocks][Hkv][16][hd]   V [n_blocks][Hkv][hd][16]
+// so one (block, kv head) is a contiguous 16*hd*2-byte run in each pool, K rows feed the MFMA
+// "row x k" operand directly and V, being token-minor, feeds the operand whose contraction
+// index is the token without any transpose.
+//
+// Both kernels evaluate S^T = K Q^T and O^T = V^T P^T, so that a lane owns one query column:
+// the running maximum and sum of the online softmax are per-lane scalars.
+#include "kernels.h"
+
+#define NEG_INF (-__builtin_huge_valf())
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// =============================================================================================
+// Decode: one query token per request, keys gathered through the block table.
+// Workgroup = (512-token chunk, kv head, request); its 4 waves take 128 tokens each, two
+// 16-token blocks per iteration.  The G = Hq/Hkv query heads that share the kv head are the
+// (zero padded) 16 columns of the MFMA tiles, so every K/V byte is fetched once per kv head.
+// The chunking depends on the context length only, never on the launch's CU share.
+// =============================================================================================
+template <int HD>
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
+    constexpr int KS = HD / 32;  // 16x16x32 steps over head_dim for S^T
+    constexpr int DT = HD / 16;  // 16-row tiles of O^T
+    __shared__ float s_o[4][HD][16];
+    __shared__ float s_m[4][16];
+    __shared__ float s_l[4][16];
+
+    const int chunk = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c16 = lane & 15, h = lane >> 4;
+    const int G = a.Hq / a.Hkv;
+
+    int n_keys = a.ctx_lens[b] + 1;
+    if (n_keys < 1 || n_keys > a.max_ctx) {
+        if (tid == 0 && chunk == 0 && hk == 0) atomicOr(a.err_flag, 4);
+        if (n_keys < 1) return;
+        n_keys = a.max_ctx;
+    }
+    if (chunk * RS_DECODE_CHUNK >= n_keys) return;
+
+    bf16x8 qf[KS];
+    {
+        const bf16_t *qp = a.q + (size_t)b * a.q_stride + (size_t)(hk * G + c16) * HD;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = (c16 < G) ? ld_bf16x8(qp + 32 * s + 8 * h) : zero_bf16x8();
+    }
+
+    const int t0 = chunk * RS_DECODE_CHUNK + wave * 128;
+    const int t1 = min(t0 + 128, n_keys);
+    const int32_t *tab = a.tables + (size_t)b * a.max_blk;
+
+    float m_run = NEG_INF, l_run = 0.f;
+    f32x4 o[DT];
+#pragma unroll
+    for (int i = 0; i < DT; ++i) o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int base = t0; base < t1; base += 32) {
+        const int blk0 = tab[base >> 4];
+        const bool ok0 = (unsigned)blk0 < (unsigned)a.n_blocks;
+        const bool has1 = base + 16 < t1;
+        const int blk1 = has1 ? tab[(base >> 4) + 1] : -1;
+        const bool ok1 = has1 && (unsigned)blk1 < (unsigned)a.n_blocks;
+        if ((!ok0 || (has1 && !ok1)) && lane == 0) atomicOr(a.err_flag, 2);
+
+        const bf16_t *k0p = a.k_pool + (((size_t)(ok0 ? blk0 : 0) * a.Hkv + hk) * 16 + c16) * HD + 8 * h;
+        const bf16_t *k1p = a.k_pool + (((size_t)(ok1 ? blk1 : 0) * a.Hkv + hk) * 16 + c16) * HD + 8 * h;
+        f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+        bf16x8 kA[KS], kB[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            kA[s] = ok0 ? ld_bf16x8(k0p + 32 * s) : zero_bf16x8();
+            kB[s] = ok1 ? ld_bf16x8(k1p + 32 * s) : zero_bf16x8();
+        }
+        // V fragments: rows d = 16*dt + c16, tokens 4h..4h+3 of each block
+        const bf16_t *v0p = a.v_pool + (((size_t)(ok0 ? blk0 : 0) * a.Hkv + hk) * HD + c16) * 16 + 4 * h;
+        const bf16_t *v1p = a.v_pool + (((size_t)(ok1 ? blk1 : 0) * a.Hkv + hk) * HD + c16) * 16 + 4 * h;
+        bf16x4 vA[DT], vB[DT];
+        const bf16x4 z4 = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            vA[dt] = ok0 ? *(const bf16x4 *)(v0p + dt * 256) : z4;
+            vB[dt] = ok1 ? *(const bf16x4 *)(v1p + dt * 256) : z4;
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            sA = mfma16(kA[s], qf[s], sA);
+            sB = mfma16(kB[s], qf[s], sB);
+        }
+        // scale, mask tokens beyond the context (and blocks that were skipped)
+        float m_tile = NEG_INF;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tokA = base + 4 * h + i, tokB = tokA + 16;
+            sA[i] = (ok0 && tokA < n_keys) ? sA[i] * a.scale_log2 : NEG_INF;
+            sB[i] = (ok1 && tokB < n_keys) ? sB[i] * a.scale_log2 : NEG_INF;
+            m_tile = fmaxf(m_tile, fmaxf(sA[i], sB[i]));
+        }
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, 64));
+        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+        const float m_new = fmaxf(m_run, m_tile);
+        const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+        const float alpha = exp2f(m_run - m_safe);
+        bf16x8 pf;
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float pa = exp2f(sA[i] - m_safe), pb = exp2f(sB[i] - m_safe);
+            psum += pa + pb;
+            pf[i] = (bf16_t)pa;
+            pf[4 + i] = (bf16_t)pb;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        // zero V of tokens past the context so that 0 * garbage cannot produce NaN
+        const bool partial = base + 32 > n_keys;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            bf16x8 vf;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                vf[i] = vA[dt][i];
+                vf[4 + i] = vB[dt][i];
+            }
+            if (partial) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (base + 4 * h + i >= n_keys) vf[i] = (bf16_t)0.f;
+                    if (base + 16 + 4 * h + i >= n_keys) vf[4 + i] = (bf16_t)0.f;
+                }
+            }
+            o[dt] = o[dt] * alpha;
+            o[dt] = mfma16(vf, pf, o[dt]);
+        }
+    }
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+
+    // combine the 4 waves (fixed order) and emit the chunk's partial result
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_o[wave][16 * dt + 4 * h + i][c16] = o[dt][i];
+    if (h == 0) {
+        s_m[wave][c16] = m_run;
+        s_l[wave][c16] = l_run;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += 256) {
+        const int gg = idx / HD, d = idx % HD;
+        float mx = fmaxf(fmaxf(s_m[0][gg], s_m[1][gg]), fmaxf(s_m[2][gg], s_m[3][gg]));
+        const float ms = (mx == NEG_INF) ? 0.f : mx;
+        float acc = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float e = exp2f(s_m[w][gg] - ms);
+            acc += s_o[w][d][gg] * e;
+            l += s_l[w][gg] * e;
+        }
+        const size_t pi = ((size_t)b * a.Hq + hk * G + gg) * a.n_chunks + chunk;
+        a.part_o[pi * HD + d] = acc;
+        if (d == 0) {
+            a.part_ml[pi * 2] = mx;
+            a.part_ml[pi * 2 + 1] = l;
+        }
+    }
+}
+
+// Merges the per-chunk partial results of one (request, query head) in chunk order.
+template <int HD>
+__global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
+    const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    int n_keys = a.ctx_lens[b] + 1;
+    bf16_t *op = a.out + (size_t)b * a.Hq * HD + (size_t)hq * HD + d;
+    if (n_keys < 1) {
+        *op = (bf16_t)0.f;
+        return;
+    }
+    if (n_keys > a.max_ctx) n_keys = a.max_ctx;
+    const int nch = (n_keys + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
+    const size_t p0 = ((size_t)b * a.Hq + hq) * a.n_chunks;
+    float mx = NEG_INF;
+    for (int c = 0; c < nch; ++c) mx = fmaxf(mx, a.part_ml[(p0 + c) * 2]);
+    const float ms = (mx == NEG_INF) ? 0.f : mx;
+    float acc = 0.f, l = 0.f;
+    for (int c = 0; c < nch; ++c) {
+        const float e = exp2f(a.part_ml[(p0 + c) * 2] - ms);
+        acc += a.part_o[(p0 + c) * HD + d] * e;
+        l += a.part_ml[(p0 + c) * 2 + 1] * e;
+    }
+    *op = (bf16_t)(l > 0.f ? acc / l : 0.f);
+}
+
+void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
+    if (a.B <= 0) return;
+    dim3 grid(a.n_chunks, a.Hkv, a.B);
+    dim3 cgrid(a.Hq, a.B);
+    if (a.hd == 128) {
+        hipLaunchKernelGGL(decode_attn_kernel<128>, grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(128), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(decode_attn_kernel<64>, grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(64), 0, st, a);
+    }
+}
+
+// =============================================================================================
+// Prefill: causal attention of whole prompts, reading the K/V the same layer call has just
+// written to the pools.  Workgroup = (128-query tile of one prompt, query head); wave w owns 32
+// query rows; keys are consumed 64 (= 4 blocks) at a time through LDS.
+// =============================================================================================
+template <int HD>
+__global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttnArgs a) {
+    constexpr int CPR = HD / 8;  // 16-byte chunks per K row
+    constexpr int KS = HD / 16;  // 32x32x16 steps over head_dim
+    constexpr int DT = HD / 32;  // 32-row tiles of O^T
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * HD];  // [key][d], chunk ^= key&7
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[HD * 64];  // [d][key], chunk ^= d&7
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+
+    // heaviest (latest) query tiles first
+    int tile = (int)gridDim.x - 1 - (int)blockIdx.x;
+    int req = 0;
+    for (;; ++req) {
+        const int nt = (a.seq.cu[req + 1] - a.seq.cu[req] + 127) >> 7;
+        if (tile < nt || req + 1 >= a.seq.n_req) break;
+        tile -= nt;
+    }
+    const int row0 = a.seq.cu[req];
+    const int len = a.seq.cu[req + 1] - row0;
+    const int q0 = tile * 128;
+    if (q0 >= len) return;
+    const int hq = blockIdx.y;
+    const int G = a.Hq / a.Hkv;
+    const int hk = hq / G;
+    const int32_t *tab = a.tables + (size_t)req * a.max_blk;
+
+    const int q_local = q0 + wave * 32 + c32;
+    const bool q_valid = q_local < len;
+    const int q_pos = q_valid ? q_local : len - 1;
+    bf16x8 qf[KS];
+    {
+        const bf16_t *qp = a.q + (size_t)(row0 + q_pos) * a.q_stride + (size_t)hq * HD + 8 * h;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = ld_bf16x8(qp + 16 * s);
+    }
+    const int wave_q_max = min(q0 + wave * 32 + 31, len - 1);
+    const int kv_end = min(q0 + 128, len);
+    const int n_kv_tiles = (kv_end + 63) >> 6;
+
+    float m_run = NEG_INF, l_run = 0.f;
+    f32x16 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+
+    for (int kt = 0; kt < n_kv_tiles; ++kt) {
+        const int kv0 = kt * 64;
+        // ---- stage K tile: 64 rows x HD
+#pragma unroll
+        for (int j = 0; j < (64 * CPR) / 256; ++j) {
+            const int c = tid + 256 * j;
+            const int r = c / CPR, cc = c % CPR;
+            const int tok = kv0 + r;
+            bf16x8 v = zero_bf16x8();
+            if ((tok & ~15) < len) {
+                const int blk = tab[tok >> 4];
+                if ((unsigned)blk < (unsigned)a.n_blocks)
+                    v = ld_bf16x8(a.k_pool + (((size_t)blk * a.Hkv + hk) * 16 + (tok & 15)) * HD + cc * 8);
+                else if (cc == 0 && (tok & 15) == 0)
+                    atomicOr(a.err_flag, 2);
+            }
+            *(bf16x8 *)&Ks[r * HD + ((cc ^ (r & 7)) << 3)] = v;
+        }
+        // ---- stage V tile: HD rows x 64 keys (4 blocks x two 8-token halves)
+#pragma unroll
+        for (int j = 0; j < (HD * 8) / 256; ++j) {
+            const int c = tid + 256 * j;
+            const int d = c >> 3, cc = c & 7;
+            const int tok0 = kv0 + (cc >> 1) * 16 + (cc & 1) * 8;
+            bf16x8 v = zero_bf16x8();
+            if (tok0 < len) {
+                const int blk = tab[tok0 >> 4];
+                if ((unsigned)blk < (unsigned)a.n_blocks) {
+                    v = ld_bf16x8(a.v_pool + (((size_t)blk * a.Hkv + hk) * HD + d) * 16 + (cc & 1) * 8);
+                    if (tok0 + 8 > len) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (tok0 + i >= len) v[i] = (bf16_t)0.f;
+                    }
+                }
+            }
+            *(bf16x8 *)&Vs[d * 64 + ((cc ^ (d & 7)) << 3)] = v;
+        }
+        __syncthreads();
+        if (kv0 <= wave_q_max) {
+            f32x16 st[2];
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) st[t2][i] = 0.f;
+                const int row = 32 * t2 + c32;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    const bf16x8 kf = *(const bf16x8 *)&Ks[row * HD + (((2 * s + h) ^ (row & 7)) << 3)];
+                    st[t2] = mfma32(kf, qf[s], st[t2]);
+                }
+            }
+            float m_tile = NEG_INF;
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = kv0 + 32 * t2 + (i >> 2) * 8 + 4 * h + (i & 3);
+                    const float s = (key <= q_pos) ? st[t2][i] * a.scale_log2 : NEG_INF;
+                    st[t2][i] = s;
+                    m_tile = fmaxf(m_tile, s);
+                }
+            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+            const float m_new = fmaxf(m_run, m_tile);
+            const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+            const float alpha = exp2f(m_run - m_safe);
+            float psum = 0.f;
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = exp2f(st[t2][i] - m_safe);
+                    st[t2][i] = p;
+                    psum += p;
+                }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * alpha;
+#pragma unroll
+            for (int blk4 = 0; blk4 < 4; ++blk4) {  // one 16-token block per MFMA step
+                bf16x8 pf;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) pf[t] = (bf16_t)st[blk4 >> 1][8 * (blk4 & 1) + t];
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const int d = 32 * dt + c32;
+                    const bf16x4 lo = *(const bf16x4 *)&Vs[d * 64 + (((2 * blk4) ^ (d & 7)) << 3) + 4 * h];
+                    const bf16x4 hi = *(const bf16x4 *)&Vs[d * 64 + (((2 * blk4 + 1) ^ (d & 7)) << 3) + 4 * h];
+                    bf16x8 vf;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        vf[i] = lo[i];
+                        vf[4 + i] = hi[i];
+                    }
+                    o[dt] = mfma32(vf, pf, o[dt]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (q_valid) {
+        const float inv = 1.0f / l_run;
+        bf16_t *op = a.out + (size_t)(row0 + q_local) * (a.Hq * HD) + (size_t)hq * HD;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(o[dt][4 * j + i] * inv);
+                *(bf16x4 *)(op + 32 * dt + 8 * j + 4 * h) = v;
+            }
+    }
+}
+
+void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a) {
+    int tiles = 0;
+    for (int r = 0; r < a.seq.n_req; ++r) tiles += (a.seq.cu[r + 1] - a.seq.cu[r] + 127) / 128;
+    if (tiles <= 0) return;
+    dim3 grid(tiles, a.Hq);
+    if (a.hd == 128)
+        hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(256), 0, st, a);
+}

@@ -1,0 +1,39 @@
+// Shared device-side types and small helpers for the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define RS_WAVE 64
+#define RS_BLOCK_TOKENS 16
+
+// Prompt boundaries passed by value to kernels (no host->device copy on the launch path).
+struct SeqInfo {
+    int32_t n_req;
+    int32_t cu[65];  // cu[0..n_req]
+};
+
+// Rotary table entry: cos and sin of pos * base^(-2i/hd), formed in float64 on the host.
+struct CosSin {
+    float c, s;
+};
+
+__device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t *p) { return *(const bf16x8 *)p; }
+__device__ __forceinline__ void st_bf16x8(bf16_t *p, bf16x8 v) { *(bf16x8 *)p = v; }
+__device__ __forceinline__ bf16x8 zero_bf16x8() {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (bf16_t)0.0f;
+    return z;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}

@@ -1,0 +1,142 @@
+// RMSNorm and rotary-embedding + paged KV write kernels (bandwidth-trivial steps of the layer).
+#include "kernels.h"
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: one 256-thread workgroup per row.  The reduction tree depends on d only.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__ x,
+                                                      const bf16_t *__restrict__ g,
+                                                      bf16_t *__restrict__ out, int d, float eps) {
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x;
+    const bf16_t *xr = x + (size_t)row * d;
+    const int nchunk = d >> 3;
+    float ss = 0.f;
+    for (int c = tid; c < nchunk; c += 256) {
+        bf16x8 v = ld_bf16x8(xr + c * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float f = (float)v[i];
+            ss += f * f;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    bf16_t *orow = out + (size_t)row * d;
+    for (int c = tid; c < nchunk; c += 256) {
+        bf16x8 v = ld_bf16x8(xr + c * 8);
+        bf16x8 gv = ld_bf16x8(g + c * 8);
+        bf16x8 o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = (bf16_t)((float)v[i] * inv * (float)gv[i]);
+        st_bf16x8(orow + c * 8, o);
+    }
+}
+
+void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
+                    float eps) {
+    if (M <= 0) return;
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, st, x, g, out, d, eps);
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE on q (in place) and k, then K -> pool[blk][kvh][slot][:], V -> pool[blk][kvh][:][slot].
+// One workgroup per token row; work items of 8 elements are spread over the 256 threads.
+// A block id outside the pool, or a position outside the rotary table, is never dereferenced:
+// the item is skipped and the error flag raised.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x;
+    int req, pos;
+    if (a.ctx_lens) {
+        req = row;
+        pos = a.ctx_lens[row];
+    } else {
+        req = 0;
+        while (req + 1 < a.seq.n_req && row >= a.seq.cu[req + 1]) ++req;
+        pos = row - a.seq.cu[req];
+    }
+    if (pos < 0 || pos >= a.max_pos) {
+        if (tid == 0) atomicOr(a.err_flag, 1);
+        return;
+    }
+    const int bi = pos / RS_BLOCK_TOKENS, slot = pos % RS_BLOCK_TOKENS;
+    int blk = -1;
+    if (bi < a.max_blk) blk = a.tables[(size_t)req * a.max_blk + bi];
+    const bool blk_ok = (unsigned)blk < (unsigned)a.n_blocks;
+    if (!blk_ok && tid == 0) atomicOr(a.err_flag, 2);
+
+    const int hd = a.hd, half = hd >> 1;
+    const int cph = half >> 3;  // 8-element chunks per half head
+    const int nqkv = (a.Hq + 2 * a.Hkv) * hd;
+    bf16_t *rowp = a.qkv + (size_t)row * nqkv;
+    const CosSin *tab = a.table + (size_t)pos * half;
+
+    const int n_rot = (a.Hq + a.Hkv) * cph;
+    for (int it = tid; it < n_rot; it += 256) {
+        const int head = it / cph, c = it % cph;
+        bf16_t *hp = rowp + head * hd;
+        bf16x8 lo = ld_bf16x8(hp + c * 8);
+        bf16x8 hi = ld_bf16x8(hp + half + c * 8);
+        bf16x8 olo, ohi;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            CosSin cs = tab[c * 8 + i];
+            float x0 = (float)lo[i], x1 = (float)hi[i];
+            olo[i] = (bf16_t)(x0 * cs.c - x1 * cs.s);
+            ohi[i] = (bf16_t)(x1 * cs.c + x0 * cs.s);
+        }
+        if (head < a.Hq) {
+            st_bf16x8(hp + c * 8, olo);
+            st_bf16x8(hp + half + c * 8, ohi);
+        } else if (blk_ok) {
+            const int kvh = head - a.Hq;
+            bf16_t *dst = a.k_pool + (((size_t)blk * a.Hkv + kvh) * RS_BLOCK_TOKENS + slot) * hd;
+            st_bf16x8(dst + c * 8, olo);
+            st_bf16x8(dst + half + c * 8, ohi);
+        }
+    }
+    if (blk_ok) {
+        const int n_v = a.Hkv * (hd >> 3);
+        const bf16_t *vrow = rowp + (a.Hq + a.Hkv) * hd;
+        for (int it = tid; it < n_v; it += 256) {
+            const int kvh = it / (hd >> 3), c = it % (hd >> 3);
+            bf16x8 v = ld_bf16x8(vrow + kvh * hd + c * 8);
+            bf16_t *dst = a.v_pool + (((size_t)blk * a.Hkv + kvh) * hd + c * 8) * RS_BLOCK_TOKENS + slot;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[i * RS_BLOCK_TOKENS] = v[i];
+        }
+    }
+}
+
+void launch_rope_kvwrite(hipStream_t st, const RopeKvArgs &a) {
+    if (a.M <= 0) return;
+    hipLaunchKernelGGL(rope_kvwrite_kernel, dim3(a.M), dim3(256), 0, st, a);
+}
+
+// ---------------------------------------------------------------------------------------------
+// CU probe: every workgroup reads the hardware-id registers, spins briefly so that workgroups
+// spread over all CUs the queue may use, and bumps the bin of the CU it ran on.
+// HW_ID (register 4): cu_id bits 11:8, sh_id bit 12, se_id bits 15:13.  XCC_ID (register 20):
+// bits 3:0.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void cu_probe_kernel(int32_t *hist) {
+    const uint32_t hw = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+    const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+    const uint64_t t0 = wall_clock64();
+    while (wall_clock64() - t0 < 2000) {  // ~20 us at 100 MHz
+    }
+    if (threadIdx.x == 0) {
+        const uint32_t cu = (hw >> 8) & 15, sh = (hw >> 12) & 1, se = (hw >> 13) & 7;
+        atomicAdd(&hist[((xcc & 15) << 8) | (se << 5) | (sh << 4) | cu], 1);
+    }
+}
+
+void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups) {
+    hipLaunchKernelGGL(cu_probe_kernel, dim3(n_workgroups), dim3(64), 0, st, hist);
+}

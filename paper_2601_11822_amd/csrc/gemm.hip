@@ -1,0 +1,340 @@
+// bf16 GEMMs out = epi(A[M,K] * W[N,K]^T) on the gfx950 matrix cores (fp32 accumulation).
+//
+// Both operands are K-contiguous, so a lane's 8-element MFMA fragment is one 16-byte load.
+// The weight tile is the MFMA "row" operand and the activation tile the "column" operand:
+// a lane then owns 4 consecutive output columns of one output row, which makes the epilogues
+// (residual add, SwiGLU, bf16 pack) plain per-lane code with 8-byte stores.
+#include "kernels.h"
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---------------------------------------------------------------------------------------------
+// Tiled kernel: BM x BN output tile per 256-thread workgroup (2x2 waves), BK = 64, operands
+// staged global -> registers -> LDS (16-byte chunks, chunk index XOR row&7 against bank
+// conflicts), next tile's global loads in flight during the MFMAs.  Every tail (M, N, K) is
+// handled by predicated zero-filled loads and predicated stores.
+//
+// SwiGLU: the B tile interleaves 32 gate rows with the 32 matching up rows, so gate and up of
+// one output element sit in the same lane and register index of neighbouring accumulators.
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
+    constexpr int BK = 64;
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int CA = BM / 32, CB = BN / 32;  // 16-byte chunks per thread per tile
+    __shared__ __attribute__((aligned(16))) bf16_t As[BM * BK];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * BK];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int M = a.M, N = a.N, K = a.K;
+    const int bm = blockIdx.y * BM;
+    const int nb = blockIdx.x;
+
+    // global row pointers of this thread's chunks
+    const bf16_t *pa[CA];
+    const bf16_t *pb[CB];
+    const int cc = tid & 7;  // chunk column (same for all of a thread's chunks)
+#pragma unroll
+    for (int j = 0; j < CA; ++j) {
+        const int r = (tid >> 3) + 32 * j;
+        const int m = bm + r;
+        pa[j] = (m < M) ? a.A + (size_t)m * K + cc * 8 : nullptr;
+    }
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        const int r = (tid >> 3) + 32 * j;  // row of the B tile
+        if (EPI == EPI_SWIGLU) {
+            const int t = r >> 5;
+            const int f = nb * (BN / 2) + (t >> 1) * 32 + (r & 31);
+            pb[j] = (f < N) ? ((t & 1) ? a.W2 : a.W) + (size_t)f * K + cc * 8 : nullptr;
+        } else {
+            const int n = nb * BN + r;
+            pb[j] = (n < N) ? a.W + (size_t)n * K + cc * 8 : nullptr;
+        }
+    }
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 ra[CA], rb[CB];
+    auto gload = [&](int k0) {
+        const bool kin = k0 + cc * 8 < K;
+#pragma unroll
+        for (int j = 0; j < CA; ++j) ra[j] = (kin && pa[j]) ? ld_bf16x8(pa[j] + k0) : zero_bf16x8();
+#pragma unroll
+        for (int j = 0; j < CB; ++j) rb[j] = (kin && pb[j]) ? ld_bf16x8(pb[j] + k0) : zero_bf16x8();
+    };
+    gload(0);
+    for (int k0 = 0; k0 < K; k0 += BK) {
+#pragma unroll
+        for (int j = 0; j < CA; ++j) {
+            const int r = (tid >> 3) + 32 * j;
+            *(bf16x8 *)&As[r * BK + ((cc ^ (r & 7)) << 3)] = ra[j];
+        }
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const int r = (tid >> 3) + 32 * j;
+            *(bf16x8 *)&Bs[r * BK + ((cc ^ (r & 7)) << 3)] = rb[j];
+        }
+        __syncthreads();
+        if (k0 + BK < K) gload(k0 + BK);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            bf16x8 wf[TN], xf[TM];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int r = wn * WN + 32 * tn + c32;
+                wf[tn] = *(const bf16x8 *)&Bs[r * BK + (((2 * s + h) ^ (r & 7)) << 3)];
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int r = wm * WM + 32 * tm + c32;
+                xf[tm] = *(const bf16x8 *)&As[r * BK + (((2 * s + h) ^ (r & 7)) << 3)];
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[tn], xf[tm], acc[tn][tm]);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: lane owns row m, columns n0 + 8j + 4h + (0..3)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = bm + wm * WM + 32 * tm + c32;
+        if (m >= M) continue;
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int p = 0; p < TN / 2; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int f = nb * (BN / 2) + (wn * (TN / 2) + p) * 32 + 8 * j + 4 * h;
+                    if (f >= N) continue;
+                    bf16x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[i] = (bf16_t)(silu_f(acc[2 * p][tm][4 * j + i]) * acc[2 * p + 1][tm][4 * j + i]);
+                    *(bf16x4 *)(a.out + (size_t)m * N + f) = v;
+                }
+        } else {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = nb * BN + wn * WN + 32 * tn + 8 * j + 4 * h;
+                    if (n >= N) continue;
+                    bf16x4 v;
+                    if (EPI == EPI_RESIDUAL) {
+                        const bf16x4 r = *(const bf16x4 *)(a.resid + (size_t)m * N + n);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(acc[tn][tm][4 * j + i] + (float)r[i]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[tn][tm][4 * j + i];
+                    }
+                    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+                }
+        }
+    }
+}
+
+template <int BM, int BN>
+static void launch_tiled(hipStream_t st, const GemmArgs &a) {
+    const int n_virtual = (a.epi == EPI_SWIGLU) ? 2 * a.N : a.N;
+    // SwiGLU tiles hold BN/2 output columns, padded per 32-column group
+    dim3 grid(a.epi == EPI_SWIGLU ? (a.N + BN / 2 - 1) / (BN / 2) : (n_virtual + BN - 1) / BN,
+              (a.M + BM - 1) / BM);
+    switch (a.epi) {
+        case EPI_STORE:
+            hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, EPI_STORE>), grid, dim3(256), 0, st, a);
+            break;
+        case EPI_RESIDUAL:
+            hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, EPI_RESIDUAL>), grid, dim3(256), 0, st, a);
+            break;
+        default:
+            hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, EPI_SWIGLU>), grid, dim3(256), 0, st, a);
+            break;
+    }
+}
+
+void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
+    if (a.M <= 0 || a.N <= 0) return;
+    if (a.M >= 1024 && a.N >= 1024)
+        launch_tiled<256, 256>(st, a);
+    else
+        launch_tiled<128, 128>(st, a);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel (M <= 64): the weights are streamed once from HBM straight into MFMA fragments,
+// no LDS staging.  Workgroup = 64 (virtual) weight rows x one K slice; its 4 waves split the
+// slice and are summed in wave order through LDS; the S slices of K are summed in slice order
+// by the epilogue kernel.  S depends on (N, K) only, so results never depend on the CU share.
+// Within a 64-wide K window lane half h covers k in [32h, 32h+32): 64 contiguous bytes/lane.
+// ---------------------------------------------------------------------------------------------
+static inline int skinny_virtual_n(int N, int epi) {
+    return epi == EPI_SWIGLU ? ((N + 31) / 32) * 64 : ((N + 63) / 64) * 64;
+}
+static inline int skinny_splits(int N, int K, int epi) {
+    const int tiles = skinny_virtual_n(N, epi) / 64;
+    int S = 1;
+    while (tiles * S < 256 && S < 16 && (K + 2 * S - 1) / (2 * S) >= 256) S *= 2;
+    return S;
+}
+static inline int skinny_k_per_wg(int K, int S) {
+    const int per = (K + S - 1) / S;
+    return ((per + 255) / 256) * 256;  // 4 waves x whole 64-wide windows
+}
+size_t skinny_partial_elems(int M, int N, int K, int epi) {
+    return (size_t)skinny_splits(N, K, epi) * (size_t)M * (size_t)skinny_virtual_n(N, epi);
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
+                                                          int k_per_wg, int Nv) {
+    __shared__ float red[4][4][64][16];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int M = a.M, N = a.N, K = a.K;
+    const int kw = k_per_wg >> 2;
+    const int kb = blockIdx.y * k_per_wg + wave * kw;
+    const int ke = min(kb + kw, K);
+
+    const bf16_t *wp[2];
+    const bf16_t *xp[2];
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        if (EPI == EPI_SWIGLU) {
+            const int f = blockIdx.x * 32 + c32;
+            wp[tn] = (f < N) ? (tn ? a.W2 : a.W) + (size_t)f * K + 32 * h : nullptr;
+        } else {
+            const int n = blockIdx.x * 64 + 32 * tn + c32;
+            wp[tn] = (n < N) ? a.W + (size_t)n * K + 32 * h : nullptr;
+        }
+    }
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm) {
+        const int m = 32 * tm + c32;
+        xp[tm] = (m < M) ? a.A + (size_t)m * K + 32 * h : nullptr;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    for (int k0 = kb; k0 < ke; k0 += 64) {
+        bf16x8 wf[2][4], xf[2][4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bool kin = k0 + 32 * h + 8 * s < K;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                wf[t][s] = (kin && wp[t]) ? ld_bf16x8(wp[t] + k0 + 8 * s) : zero_bf16x8();
+                xf[t][s] = (kin && xp[t]) ? ld_bf16x8(xp[t] + k0 + 8 * s) : zero_bf16x8();
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < 2; ++tm) acc[tn][tm] = mfma32(wf[tn][s], xf[tm][s], acc[tn][tm]);
+    }
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[wave][tn * 2 + tm][lane][e] = acc[tn][tm][e];
+    __syncthreads();
+    // wave w finishes tile (tn, tm) = (w>>1, w&1): sum of the 4 waves in wave order
+    const int tn = wave >> 1, tm = wave & 1;
+    const int m = 32 * tm + c32;
+    if (m < M) {
+        float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * 64 + 32 * tn;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = 4 * j + i;
+                v[i] = ((red[0][wave][lane][e] + red[1][wave][lane][e]) + red[2][wave][lane][e]) +
+                       red[3][wave][lane][e];
+            }
+            *(f32x4 *)(dst + 8 * j + 4 * h) = v;
+        }
+    }
+}
+
+// Sums the K slices in order and applies the epilogue; one thread per 4 output columns.
+template <int EPI>
+__global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const float *__restrict__ part,
+                                                              int S, int Nv) {
+    const int M = a.M, N = a.N;
+    const int groups = N >> 2;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * groups) return;
+    const int m = idx / groups, n = (idx % groups) * 4;
+    bf16x4 v;
+    if (EPI == EPI_SWIGLU) {
+        const int col = (n >> 5) * 64 + (n & 31);
+        f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) {
+            const float *p = part + ((size_t)s * M + m) * Nv + col;
+            g += *(const f32x4 *)p;
+            u += *(const f32x4 *)(p + 32);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(silu_f(g[i]) * u[i]);
+    } else {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) acc += *(const f32x4 *)(part + ((size_t)s * M + m) * Nv + n);
+        if (EPI == EPI_RESIDUAL) {
+            const bf16x4 r = *(const bf16x4 *)(a.resid + (size_t)m * N + n);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(acc[i] + (float)r[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[i];
+        }
+    }
+    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+}
+
+void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
+    if (a.M <= 0 || a.N <= 0) return;
+    const int Nv = skinny_virtual_n(a.N, a.epi);
+    const int S = skinny_splits(a.N, a.K, a.epi);
+    const int kpw = skinny_k_per_wg(a.K, S);
+    dim3 grid(Nv / 64, S);
+    const int eblocks = (a.M * (a.N / 4) + 255) / 256;
+    switch (a.epi) {
+        case EPI_STORE:
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_STORE>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_STORE>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
+            break;
+        case EPI_RESIDUAL:
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_RESIDUAL>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_RESIDUAL>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
+            break;
+        default:
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_SWIGLU>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_SWIGLU>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
+            break;
+    }
+}

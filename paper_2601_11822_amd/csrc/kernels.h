@@ -1,0 +1,75 @@
+// Host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.h"
+
+// out[m,:] = x[m,:] * rsqrt(mean(x[m,:]^2) + eps) * g      (bf16 in, fp32 math, bf16 out)
+void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
+                    float eps);
+
+struct RopeKvArgs {
+    bf16_t *qkv;            // [M][nqkv]; q part rotated in place
+    const CosSin *table;    // [max_pos][hd/2]
+    bf16_t *k_pool;         // this layer: [n_blocks][Hkv][16][hd]
+    bf16_t *v_pool;         // this layer: [n_blocks][Hkv][hd][16]
+    const int32_t *tables;  // [n_req][max_blk]
+    const int32_t *ctx_lens;  // decode: position of row m (and request = m); prefill: nullptr
+    int32_t *err_flag;
+    int M, Hq, Hkv, hd, max_blk, n_blocks, max_pos;
+    SeqInfo seq;  // prefill only
+};
+void launch_rope_kvwrite(hipStream_t st, const RopeKvArgs &a);
+
+struct PrefillAttnArgs {
+    const bf16_t *q;  // [T][q_stride] (rotated)
+    int q_stride;
+    bf16_t *out;  // [T][Hq*hd]
+    const bf16_t *k_pool, *v_pool;
+    const int32_t *tables;
+    int32_t *err_flag;
+    int Hq, Hkv, hd, max_blk, n_blocks;
+    float scale_log2;  // log2(e)/sqrt(hd)
+    SeqInfo seq;
+};
+void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a);
+
+struct DecodeAttnArgs {
+    const bf16_t *q;  // [B][q_stride]
+    int q_stride;
+    bf16_t *out;  // [B][Hq*hd]
+    const bf16_t *k_pool, *v_pool;
+    const int32_t *tables;
+    const int32_t *ctx_lens;
+    int32_t *err_flag;
+    float *part_o;   // [B][Hq][n_chunks][hd]
+    float *part_ml;  // [B][Hq][n_chunks][2]
+    int B, Hq, Hkv, hd, max_blk, n_blocks, max_ctx, n_chunks;
+    float scale_log2;
+};
+#define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention
+void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a);
+
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+// out[M,N] = epi(A[M,K] * W[N,K]^T).  EPI_RESIDUAL adds resid[M,N].  EPI_SWIGLU:
+// out[M,N] = silu(A*W^T) * (A*W2^T) with W, W2 both [N,K].
+struct GemmArgs {
+    const bf16_t *A;
+    const bf16_t *W;
+    const bf16_t *W2;
+    const bf16_t *resid;
+    bf16_t *out;
+    int M, N, K;
+    int epi;
+};
+void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
+
+// Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through
+// `partials` (fp32, at least skinny_partial_elems(...) elements).
+size_t skinny_partial_elems(int M, int N, int K, int epi);
+void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
+
+// Counts workgroups per physical CU: hist[(xcc << 8) | (se << 5) | (sh << 4) | cu] += 1.
+void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);

@@ -1,0 +1,813 @@
+// Host runtime behind the C ABI: context, KV block allocator, CU-masked stream pool, adaptive
+// resource manager, layer drivers and the serving step.  Declarations and their contract are
+// in include/rapid_serve.h.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/rapid_serve.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int32_t fail(int32_t code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(RS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+struct Workspace {
+    bf16_t *h = nullptr, *qkv = nullptr, *attn = nullptr, *x1 = nullptr, *act = nullptr, *xbuf = nullptr;
+    float *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
+    int rows = 0;
+};
+
+enum ReqState { WAITING = 0, PREFILL_READY, PREFILLING, PREFILL_DONE, RUNNING, FINISHED };
+
+struct Request {
+    int64_t id;
+    int32_t prompt_len, output_len;
+    const void *prompt_hidden;
+    int state = WAITING;
+    int32_t ctx_len = 0;    // tokens cached so far
+    int32_t generated = 0;  // decode steps taken
+    hipEvent_t done = nullptr;
+    bool host_done = false;
+};
+
+struct Side {
+    int cus = RS_TOTAL_CUS;
+    hipStream_t stream = nullptr;
+    std::map<int, hipStream_t> pool;  // by CU count
+    std::vector<hipEvent_t> marks;
+    hipEvent_t order = nullptr;
+};
+
+}  // namespace
+
+struct rs_ctx {
+    rs_model_desc m{};
+    rs_pool_desc pool{};
+    rs_limits lim{};
+    int device = RS_HOST_ONLY;
+    bool gpu = false;
+    std::vector<rs_layer_weights> weights;
+    std::vector<bool> have_weights;
+    CosSin *rope = nullptr;
+    int32_t *err_flag = nullptr;
+    Workspace ws[2];
+    Side side[2];
+    bool over_alloc = true;
+
+    // allocator
+    std::vector<int32_t> free_list;
+    std::unordered_map<int64_t, std::vector<int32_t>> owned;
+
+    // manager profile
+    bool have_prof = false;
+    std::vector<int32_t> batch_edges, ctx_edges, decode_cus, lat_distinct, lat_over;
+    int32_t slo_us = 0;
+
+    // serving state
+    std::deque<int64_t> arrival;  // FCFS order of all live requests
+    std::unordered_map<int64_t, Request> reqs;
+    std::vector<int64_t> running;  // decode batch, in promotion order
+    int64_t prefilling = -1;
+    int32_t max_blk_per_req = 0;
+    int32_t *d_ctx = nullptr, *d_tab = nullptr, *d_ptab = nullptr;   // device staging
+    int32_t *h_ctx[2] = {nullptr, nullptr}, *h_tab[2] = {nullptr, nullptr}, *h_ptab = nullptr;
+    hipEvent_t staged[2] = {nullptr, nullptr};
+    hipEvent_t pstaged = nullptr;
+    int stage_flip = 0;
+};
+
+namespace {
+
+void mask_for(int side, int cus, uint32_t out[8]) {
+    for (int i = 0; i < 8; ++i) out[i] = 0;
+    // consecutive mask bits land in different XCDs, so any contiguous range that is a multiple
+    // of 8 bits wide takes the same number of CUs from each of the 8 XCDs
+    const int lo = side == RS_SIDE_PREFILL ? 0 : RS_TOTAL_CUS - cus;
+    for (int b = lo; b < lo + cus; ++b) out[b >> 5] |= 1u << (b & 31);
+}
+
+int32_t get_stream(rs_ctx *c, int side, int cus, hipStream_t *out) {
+    Side &s = c->side[side];
+    auto it = s.pool.find(cus);
+    if (it != s.pool.end()) {
+        *out = it->second;
+        return RS_OK;
+    }
+    uint32_t mask[8];
+    mask_for(side, cus, mask);
+    hipStream_t st;
+    HIP_TRY(hipExtStreamCreateWithCUMask(&st, 8, mask));
+    s.pool[cus] = st;
+    *out = st;
+    return RS_OK;
+}
+
+int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
+    const rs_model_desc &m = c->m;
+    const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
+    const size_t nqkv = qd + 2 * (size_t)m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+    w.rows = rows;
+    if (rows <= 0) return RS_OK;
+    HIP_TRY(hipMalloc(&w.h, rows * d * 2));
+    HIP_TRY(hipMalloc(&w.qkv, rows * nqkv * 2));
+    HIP_TRY(hipMalloc(&w.attn, rows * qd * 2));
+    HIP_TRY(hipMalloc(&w.x1, rows * d * 2));
+    HIP_TRY(hipMalloc(&w.act, rows * f * 2));
+    HIP_TRY(hipMalloc(&w.xbuf, rows * d * 2));
+    if (decode) {
+        const int Mmax = std::min(rows, 64);
+        size_t pe = 0;
+        pe = std::max(pe, skinny_partial_elems(Mmax, (int)nqkv, (int)d, EPI_STORE));
+        pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
+        pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
+        pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)f, EPI_RESIDUAL));
+        HIP_TRY(hipMalloc(&w.partials, pe * sizeof(float)));
+        const size_t nch = (c->lim.max_context + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
+        HIP_TRY(hipMalloc(&w.part_o, (size_t)rows * m.n_q_heads * nch * m.head_dim * sizeof(float)));
+        HIP_TRY(hipMalloc(&w.part_ml, (size_t)rows * m.n_q_heads * nch * 2 * sizeof(float)));
+    }
+    return RS_OK;
+}
+
+void free_ws(Workspace &w) {
+    void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    w = Workspace{};
+}
+
+int bucket(const std::vector<int32_t> &edges, int64_t v) {
+    for (size_t i = 0; i < edges.size(); ++i)
+        if (v <= edges[i]) return (int)i;
+    return (int)edges.size() - 1;
+}
+
+void choose_split(const rs_ctx *c, int32_t batch, int64_t sum_ctx, bool prefill_pending, int32_t *p,
+                  int32_t *d) {
+    if (!prefill_pending) { *p = 0; *d = RS_TOTAL_CUS; return; }
+    if (batch <= 0) { *p = RS_TOTAL_CUS; *d = 0; return; }
+    if (!c->have_prof) { *p = RS_TOTAL_CUS; *d = RS_TOTAL_CUS; return; }
+    const int b = bucket(c->batch_edges, batch), x = bucket(c->ctx_edges, sum_ctx);
+    const int nc = (int)c->ctx_edges.size(), ns = (int)c->decode_cus.size();
+    if (c->lat_over[b * nc + x] <= c->slo_us) { *p = RS_TOTAL_CUS; *d = RS_TOTAL_CUS; return; }
+    const int32_t *row = &c->lat_distinct[(size_t)(b * nc + x) * ns];
+    int pick = -1;
+    for (int s = 0; s < ns; ++s)
+        if (row[s] <= c->slo_us) { pick = s; break; }
+    if (pick < 0) {
+        pick = 0;
+        for (int s = 1; s < ns; ++s)
+            if (row[s] < row[pick]) pick = s;
+    }
+    *d = c->decode_cus[pick];
+    *p = RS_TOTAL_CUS - *d;
+}
+
+int32_t kv_alloc(rs_ctx *c, int64_t req_id, int32_t n_tokens, const std::vector<int32_t> **out) {
+    if (n_tokens < 0) return fail(RS_ERR_BAD_ARG, "negative token count");
+    const int need = (n_tokens + RS_KV_BLOCK - 1) / RS_KV_BLOCK;
+    auto it = c->owned.find(req_id);
+    const int have = it == c->owned.end() ? 0 : (int)it->second.size();
+    const int extra = need - have;
+    if (extra > (int)c->free_list.size())
+        return fail(RS_ERR_NO_BLOCKS, "request %lld needs %d more blocks, %zu free", (long long)req_id,
+                    extra, c->free_list.size());
+    std::vector<int32_t> &v = c->owned[req_id];
+    for (int i = 0; i < extra; ++i) {
+        v.push_back(c->free_list.back());
+        c->free_list.pop_back();
+    }
+    if (out) *out = &v;
+    return RS_OK;
+}
+
+int32_t set_split(rs_ctx *c, int32_t p, int32_t d) {
+    auto legal = [](int v) { return v >= 0 && v <= RS_TOTAL_CUS && v % RS_CU_GRANULE == 0; };
+    if (!legal(p) || !legal(d)) return fail(RS_ERR_BAD_SPLIT, "split (%d,%d): counts must be multiples of %d in [0,256]", p, d, RS_CU_GRANULE);
+    const bool over = (p == RS_TOTAL_CUS && d == RS_TOTAL_CUS);
+    if (!over && p + d > RS_TOTAL_CUS) return fail(RS_ERR_BAD_SPLIT, "split (%d,%d) overlaps; only (256,256) may", p, d);
+    const int want[2] = {p, d};
+    for (int s = 0; s < 2; ++s) {
+        Side &sd = c->side[s];
+        if (c->gpu && want[s] > 0) {
+            hipStream_t st;
+            int32_t rc = get_stream(c, s, want[s], &st);
+            if (rc) return rc;
+            if (st != sd.stream && sd.stream) {
+                // later work of this side is ordered after what the old stream still holds
+                HIP_TRY(hipEventRecord(sd.order, sd.stream));
+                HIP_TRY(hipStreamWaitEvent(st, sd.order, 0));
+            }
+            sd.stream = st;
+        }
+        sd.cus = want[s];
+    }
+    c->over_alloc = over;
+    return RS_OK;
+}
+
+int32_t check_layer_call(rs_ctx *c, int side, int32_t layer, const void *x_in, void *x_out,
+                         const int32_t *tables) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context cannot run layers");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
+    if (!c->have_weights[layer]) return fail(RS_ERR_STATE, "weights of layer %d not set", layer);
+    if (!x_in || !x_out || !tables) return fail(RS_ERR_BAD_ARG, "null pointer");
+    if (c->side[side].cus <= 0) return fail(RS_ERR_STATE, "side %d has no compute units in the current split", side);
+    return RS_OK;
+}
+
+// The dense part after attention, shared by both passes.
+void run_post_attention(rs_ctx *c, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
+                        const bf16_t *x, bf16_t *y, int M, bool skinny) {
+    const rs_model_desc &m = c->m;
+    const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
+    auto gemm = [&](const GemmArgs &g) {
+        if (skinny) launch_gemm_skinny(st, g, w.partials);
+        else launch_gemm_tiled(st, g);
+    };
+    gemm(GemmArgs{w.attn, (const bf16_t *)lw.wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
+    launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps);
+    gemm(GemmArgs{w.h, (const bf16_t *)lw.wg, (const bf16_t *)lw.wu, nullptr, w.act, M, f, d, EPI_SWIGLU});
+    gemm(GemmArgs{w.act, (const bf16_t *)lw.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
+}
+
+int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu,
+                      int32_t n_req, const int32_t *tables, int32_t max_blk) {
+    const rs_model_desc &m = c->m;
+    if (!cu || n_req < 1 || n_req > RS_MAX_PREFILL_REQS) return fail(RS_ERR_BAD_ARG, "n_req %d out of range", n_req);
+    if (cu[0] != 0) return fail(RS_ERR_BAD_ARG, "cu_seqlens must start at 0");
+    SeqInfo seq{};
+    seq.n_req = n_req;
+    int longest = 0;
+    for (int r = 0; r <= n_req; ++r) {
+        if (r && cu[r] < cu[r - 1]) return fail(RS_ERR_BAD_ARG, "cu_seqlens must ascend");
+        if (r) longest = std::max(longest, cu[r] - cu[r - 1]);
+        seq.cu[r] = cu[r];
+    }
+    const int T = cu[n_req];
+    Workspace &w = c->ws[RS_SIDE_PREFILL];
+    if (T < 1 || T > w.rows) return fail(RS_ERR_BAD_ARG, "%d prefill tokens, workspace holds %d", T, w.rows);
+    if (longest > m.max_pos) return fail(RS_ERR_BAD_ARG, "prompt of %d tokens exceeds max_pos %d", longest, m.max_pos);
+    if ((longest + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk)
+        return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for %d tokens", max_blk, longest);
+    const rs_layer_weights &lw = c->weights[layer];
+    hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+    const int d = m.d_model, hd = m.head_dim, qd = m.n_q_heads * hd, nqkv = qd + 2 * m.n_kv_heads * hd;
+    bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
+    bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
+
+    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, T, d, m.rms_eps);
+    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, T, nqkv, d, EPI_STORE});
+    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
+                  max_blk, c->pool.n_blocks, m.max_pos, seq};
+    launch_rope_kvwrite(st, ra);
+    PrefillAttnArgs pa{w.qkv, nqkv, w.attn, kp, vp, tables, c->err_flag, m.n_q_heads, m.n_kv_heads, hd,
+                       max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
+    launch_prefill_attention(st, pa);
+    run_post_attention(c, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
+    HIP_TRY(hipGetLastError());
+    return RS_OK;
+}
+
+int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
+                     const int32_t *tables, int32_t max_blk, int32_t B, int32_t max_ctx) {
+    const rs_model_desc &m = c->m;
+    Workspace &w = c->ws[RS_SIDE_DECODE];
+    if (!ctx_lens) return fail(RS_ERR_BAD_ARG, "null ctx_lens");
+    if (B < 1 || B > w.rows) return fail(RS_ERR_BAD_ARG, "decode batch %d, workspace holds %d", B, w.rows);
+    if (max_ctx < 1 || max_ctx > c->lim.max_context || max_ctx > m.max_pos)
+        return fail(RS_ERR_BAD_ARG, "max_ctx %d outside [1, min(%d,%d)]", max_ctx, c->lim.max_context, m.max_pos);
+    if ((max_ctx + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk)
+        return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for context %d", max_blk, max_ctx);
+    const rs_layer_weights &lw = c->weights[layer];
+    hipStream_t st = c->side[RS_SIDE_DECODE].stream;
+    const int d = m.d_model, hd = m.head_dim, qd = m.n_q_heads * hd, nqkv = qd + 2 * m.n_kv_heads * hd;
+    bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
+    bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
+    const bool skinny = B <= 64;
+
+    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
+    GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE};
+    if (skinny) launch_gemm_skinny(st, g, w.partials);
+    else launch_gemm_tiled(st, g);
+    SeqInfo none{};
+    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, ctx_lens, c->err_flag, B, m.n_q_heads, m.n_kv_heads, hd,
+                  max_blk, c->pool.n_blocks, m.max_pos, none};
+    launch_rope_kvwrite(st, ra);
+    DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
+                      B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
+                      (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
+                      (float)(1.4426950408889634 / std::sqrt((double)hd))};
+    launch_decode_attention(st, da);
+    run_post_attention(c, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
+    HIP_TRY(hipGetLastError());
+    return RS_OK;
+}
+
+}  // namespace
+
+// ================================================================================ C ABI
+
+extern "C" {
+
+const char *rs_last_error(void) { return g_err.c_str(); }
+
+int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_limits *limits,
+                const rs_profile *prof, int32_t device, rs_ctx **out) {
+    if (!model || !pool || !limits || !out) return fail(RS_ERR_BAD_ARG, "null argument");
+    const rs_model_desc &m = *model;
+    if (m.head_dim != 64 && m.head_dim != 128) return fail(RS_ERR_BAD_ARG, "head_dim %d: only 64 and 128", m.head_dim);
+    if (m.d_model < 8 || m.d_model % 8 || m.ffn_dim < 8 || m.ffn_dim % 8)
+        return fail(RS_ERR_BAD_ARG, "d_model and ffn_dim must be positive multiples of 8");
+    if (m.n_kv_heads < 1 || m.n_q_heads < 1 || m.n_q_heads % m.n_kv_heads || m.n_q_heads / m.n_kv_heads > 16)
+        return fail(RS_ERR_BAD_ARG, "need n_q_heads = G * n_kv_heads with 1 <= G <= 16");
+    if (m.n_layers < 1 || m.max_pos < 1 || !(m.rope_base > 1.0f) || !(m.rms_eps >= 0.0f))
+        return fail(RS_ERR_BAD_ARG, "bad n_layers / max_pos / rope_base / rms_eps");
+    if (pool->n_blocks < 1) return fail(RS_ERR_BAD_ARG, "pool needs at least one block");
+    const int64_t per_layer = (int64_t)pool->n_blocks * RS_KV_BLOCK * m.n_kv_heads * m.head_dim;
+    if (m.n_layers > 1 && pool->layer_stride < per_layer) return fail(RS_ERR_BAD_ARG, "layer_stride smaller than one layer's pool");
+    if (limits->max_prefill_tokens < 0 || limits->max_decode_batch < 0 || limits->max_context < 1)
+        return fail(RS_ERR_BAD_ARG, "bad limits");
+    if (device != RS_HOST_ONLY && (!pool->k_pool || !pool->v_pool)) return fail(RS_ERR_BAD_ARG, "null KV pool");
+    if (prof) {
+        if (prof->n_batch < 1 || prof->n_ctx < 1 || prof->n_split < 1 || !prof->batch_edges || !prof->ctx_edges ||
+            !prof->decode_cus || !prof->lat_distinct_us || !prof->lat_over_us)
+            return fail(RS_ERR_BAD_ARG, "incomplete profile");
+        for (int s = 0; s < prof->n_split; ++s) {
+            const int v = prof->decode_cus[s];
+            if (v <= 0 || v >= RS_TOTAL_CUS || v % RS_CU_GRANULE || (s && v <= prof->decode_cus[s - 1]))
+                return fail(RS_ERR_BAD_ARG, "profile decode_cus must ascend in (0,256), multiples of %d", RS_CU_GRANULE);
+        }
+    }
+    rs_ctx *c = new rs_ctx();
+    c->m = m;
+    c->pool = *pool;
+    c->lim = *limits;
+    c->device = device;
+    c->gpu = device != RS_HOST_ONLY;
+    c->weights.resize(m.n_layers);
+    c->have_weights.assign(m.n_layers, false);
+    c->free_list.resize(pool->n_blocks);
+    for (int i = 0; i < pool->n_blocks; ++i) c->free_list[i] = pool->n_blocks - 1 - i;  // pop -> 0,1,2,..
+    c->max_blk_per_req = (limits->max_context + RS_KV_BLOCK - 1) / RS_KV_BLOCK;
+    if (prof) {
+        c->have_prof = true;
+        c->batch_edges.assign(prof->batch_edges, prof->batch_edges + prof->n_batch);
+        c->ctx_edges.assign(prof->ctx_edges, prof->ctx_edges + prof->n_ctx);
+        c->decode_cus.assign(prof->decode_cus, prof->decode_cus + prof->n_split);
+        const size_t cells = (size_t)prof->n_batch * prof->n_ctx;
+        c->lat_distinct.assign(prof->lat_distinct_us, prof->lat_distinct_us + cells * prof->n_split);
+        c->lat_over.assign(prof->lat_over_us, prof->lat_over_us + cells);
+        c->slo_us = prof->slo_us;
+    }
+    *out = c;
+    if (!c->gpu) return RS_OK;
+
+    auto bail = [&](int32_t rc) { rs_destroy(c); *out = nullptr; return rc; };
+    int32_t rc;
+    auto gpu_setup = [&]() -> int32_t {
+        HIP_TRY(hipSetDevice(device));
+        // rotary table, angles in float64
+        const int half = m.head_dim / 2;
+        std::vector<CosSin> tab((size_t)m.max_pos * half);
+        for (int i = 0; i < half; ++i) {
+            const double theta = std::pow((double)m.rope_base, -2.0 * i / (double)m.head_dim);
+            for (int p = 0; p < m.max_pos; ++p) {
+                const double phi = (double)p * theta;
+                tab[(size_t)p * half + i] = CosSin{(float)std::cos(phi), (float)std::sin(phi)};
+            }
+        }
+        HIP_TRY(hipMalloc(&c->rope, tab.size() * sizeof(CosSin)));
+        HIP_TRY(hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(CosSin), hipMemcpyHostToDevice));
+        HIP_TRY(hipMalloc(&c->err_flag, sizeof(int32_t)));
+        HIP_TRY(hipMemset(c->err_flag, 0, sizeof(int32_t)));
+        int32_t r = alloc_ws(c, c->ws[RS_SIDE_PREFILL], limits->max_prefill_tokens, false);
+        if (r) return r;
+        r = alloc_ws(c, c->ws[RS_SIDE_DECODE], limits->max_decode_batch, true);
+        if (r) return r;
+        for (int s = 0; s < 2; ++s) {
+            HIP_TRY(hipEventCreateWithFlags(&c->side[s].order, hipEventDisableTiming));
+            c->side[s].marks.assign(RS_MAX_MARKS, nullptr);
+        }
+        // staging for the serving step
+        const size_t nb = std::max(1, limits->max_decode_batch);
+        const size_t tab_elems = nb * c->max_blk_per_req;
+        HIP_TRY(hipMalloc(&c->d_ctx, nb * sizeof(int32_t)));
+        HIP_TRY(hipMalloc(&c->d_tab, tab_elems * sizeof(int32_t)));
+        HIP_TRY(hipMalloc(&c->d_ptab, (size_t)c->max_blk_per_req * sizeof(int32_t)));
+        for (int i = 0; i < 2; ++i) {
+            HIP_TRY(hipHostMalloc(&c->h_ctx[i], nb * sizeof(int32_t)));
+            HIP_TRY(hipHostMalloc(&c->h_tab[i], tab_elems * sizeof(int32_t)));
+            HIP_TRY(hipEventCreateWithFlags(&c->staged[i], hipEventDisableTiming));
+        }
+        HIP_TRY(hipHostMalloc(&c->h_ptab, (size_t)c->max_blk_per_req * sizeof(int32_t)));
+        HIP_TRY(hipEventCreateWithFlags(&c->pstaged, hipEventDisableTiming));
+        return set_split(c, RS_TOTAL_CUS, RS_TOTAL_CUS);
+    };
+    rc = gpu_setup();
+    if (rc) return bail(rc);
+    return RS_OK;
+}
+
+int32_t rs_destroy(rs_ctx *c) {
+    if (!c) return RS_OK;
+    if (c->gpu) {
+        (void)hipSetDevice(c->device);
+        (void)hipDeviceSynchronize();
+        for (auto &kv : c->reqs)
+            if (kv.second.done) (void)hipEventDestroy(kv.second.done);
+        for (int s = 0; s < 2; ++s) {
+            for (hipEvent_t e : c->side[s].marks)
+                if (e) (void)hipEventDestroy(e);
+            if (c->side[s].order) (void)hipEventDestroy(c->side[s].order);
+            for (auto &kv : c->side[s].pool) (void)hipStreamDestroy(kv.second);
+            free_ws(c->ws[s]);
+        }
+        if (c->rope) (void)hipFree(c->rope);
+        if (c->err_flag) (void)hipFree(c->err_flag);
+        if (c->d_ctx) (void)hipFree(c->d_ctx);
+        if (c->d_tab) (void)hipFree(c->d_tab);
+        if (c->d_ptab) (void)hipFree(c->d_ptab);
+        for (int i = 0; i < 2; ++i) {
+            if (c->h_ctx[i]) (void)hipHostFree(c->h_ctx[i]);
+            if (c->h_tab[i]) (void)hipHostFree(c->h_tab[i]);
+            if (c->staged[i]) (void)hipEventDestroy(c->staged[i]);
+        }
+        if (c->h_ptab) (void)hipHostFree(c->h_ptab);
+        if (c->pstaged) (void)hipEventDestroy(c->pstaged);
+    }
+    delete c;
+    return RS_OK;
+}
+
+int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
+    if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
+    if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
+    c->weights[layer] = *w;
+    c->have_weights[layer] = true;
+    return RS_OK;
+}
+
+int32_t rs_kv_alloc(rs_ctx *c, int64_t req_id, int32_t n_tokens_total, int32_t *block_ids_out, int32_t cap,
+                    int32_t *n_blocks_out) {
+    if (!c || !n_blocks_out || (cap > 0 && !block_ids_out) || cap < 0) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (n_tokens_total < 0) return fail(RS_ERR_BAD_ARG, "negative token count");
+    const int need = (n_tokens_total + RS_KV_BLOCK - 1) / RS_KV_BLOCK;
+    auto it = c->owned.find(req_id);
+    const int have = it == c->owned.end() ? 0 : (int)it->second.size();
+    if (std::max(need, have) > cap) return fail(RS_ERR_BAD_ARG, "id buffer of %d too small for %d blocks", cap, std::max(need, have));
+    const std::vector<int32_t> *v = nullptr;
+    int32_t rc = kv_alloc(c, req_id, n_tokens_total, &v);
+    if (rc) return rc;
+    std::copy(v->begin(), v->end(), block_ids_out);
+    *n_blocks_out = (int32_t)v->size();
+    return RS_OK;
+}
+
+int32_t rs_kv_free(rs_ctx *c, int64_t req_id) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    auto it = c->owned.find(req_id);
+    if (it == c->owned.end()) return fail(RS_ERR_BAD_ARG, "request %lld owns no blocks", (long long)req_id);
+    for (auto b = it->second.rbegin(); b != it->second.rend(); ++b) c->free_list.push_back(*b);
+    c->owned.erase(it);
+    return RS_OK;
+}
+
+int32_t rs_kv_num_free(rs_ctx *c, int32_t *n) {
+    if (!c || !n) return fail(RS_ERR_BAD_ARG, "null argument");
+    *n = (int32_t)c->free_list.size();
+    return RS_OK;
+}
+
+int32_t rs_prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu_seqlens,
+                         int32_t n_req, const int32_t *block_tables, int32_t max_blk) {
+    int32_t rc = check_layer_call(c, RS_SIDE_PREFILL, layer, x_in, x_out, block_tables);
+    if (rc) return rc;
+    return prefill_layer(c, layer, x_in, x_out, cu_seqlens, n_req, block_tables, max_blk);
+}
+
+int32_t rs_decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
+                        const int32_t *block_tables, int32_t max_blk, int32_t B, int32_t max_ctx) {
+    int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
+    if (rc) return rc;
+    return decode_layer(c, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
+}
+
+int32_t rs_set_cu_split(rs_ctx *c, int32_t p, int32_t d) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    return set_split(c, p, d);
+}
+
+int32_t rs_get_cu_split(rs_ctx *c, int32_t *p, int32_t *d) {
+    if (!c || !p || !d) return fail(RS_ERR_BAD_ARG, "null argument");
+    *p = c->side[0].cus;
+    *d = c->side[1].cus;
+    return RS_OK;
+}
+
+int32_t rs_get_cu_mask(rs_ctx *c, int32_t side, uint32_t mask_out[8]) {
+    if (!c || !mask_out || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
+    mask_for(side, c->side[side].cus, mask_out);
+    return RS_OK;
+}
+
+int32_t rs_choose_split(rs_ctx *c, int32_t batch, int64_t sum_ctx, int32_t prefill_pending, int32_t *p, int32_t *d) {
+    if (!c || !p || !d) return fail(RS_ERR_BAD_ARG, "null argument");
+    choose_split(c, batch, sum_ctx, prefill_pending != 0, p, d);
+    return RS_OK;
+}
+
+int32_t rs_get_stream(rs_ctx *c, int32_t side, void **out) {
+    if (!c || !out || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context has no streams");
+    *out = (void *)c->side[side].stream;
+    return RS_OK;
+}
+
+int32_t rs_sync(rs_ctx *c, int32_t side) {
+    if (!c || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return RS_OK;
+    if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
+    int32_t flag = 0;
+    HIP_TRY(hipMemcpy(&flag, c->err_flag, sizeof flag, hipMemcpyDeviceToHost));
+    if (flag) {
+        HIP_TRY(hipMemset(c->err_flag, 0, sizeof flag));
+        return fail(RS_ERR_BAD_BLOCK, "a kernel skipped an illegal block id, position or context length (flag %d)", flag);
+    }
+    return RS_OK;
+}
+
+int32_t rs_mark(rs_ctx *c, int32_t side, int32_t slot) {
+    if (!c || side < 0 || side > 1 || slot < 0 || slot >= RS_MAX_MARKS) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    hipEvent_t &e = c->side[side].marks[slot];
+    if (!e) HIP_TRY(hipEventCreate(&e));
+    HIP_TRY(hipEventRecord(e, c->side[side].stream));
+    return RS_OK;
+}
+
+int32_t rs_elapsed_ms(rs_ctx *c, int32_t side, int32_t a, int32_t b, float *ms) {
+    if (!c || !ms || side < 0 || side > 1 || a < 0 || b < 0 || a >= RS_MAX_MARKS || b >= RS_MAX_MARKS)
+        return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    hipEvent_t ea = c->side[side].marks[a], eb = c->side[side].marks[b];
+    if (!ea || !eb) return fail(RS_ERR_STATE, "mark not recorded");
+    HIP_TRY(hipEventSynchronize(eb));
+    HIP_TRY(hipEventElapsedTime(ms, ea, eb));
+    return RS_OK;
+}
+
+int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *host_out, int64_t n_bytes) {
+    if (!c || !host_out || side < 0 || side > 1 || n_bytes < 0) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    const Workspace &w = c->ws[side];
+    const rs_model_desc &m = c->m;
+    const size_t qd = (size_t)m.n_q_heads * m.head_dim, nqkv = qd + 2 * (size_t)m.n_kv_heads * m.head_dim;
+    const void *src = nullptr;
+    size_t cap = 0;
+    switch (which) {
+        case 0: src = w.h; cap = (size_t)w.rows * m.d_model * 2; break;
+        case 1: src = w.qkv; cap = (size_t)w.rows * nqkv * 2; break;
+        case 2: src = w.attn; cap = (size_t)w.rows * qd * 2; break;
+        case 3: src = w.x1; cap = (size_t)w.rows * m.d_model * 2; break;
+        case 4: src = w.act; cap = (size_t)w.rows * m.ffn_dim * 2; break;
+        default: return fail(RS_ERR_BAD_ARG, "unknown workspace buffer %d", which);
+    }
+    if (!src || (size_t)n_bytes > cap) return fail(RS_ERR_BAD_ARG, "workspace buffer %d holds %zu bytes", which, cap);
+    if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
+    HIP_TRY(hipMemcpy(host_out, src, (size_t)n_bytes, hipMemcpyDeviceToHost));
+    return RS_OK;
+}
+
+int32_t rs_debug_cu_histogram(rs_ctx *c, int32_t side, int32_t n_workgroups, int32_t *hist_out) {
+    if (!c || !hist_out || side < 0 || side > 1 || n_workgroups < 1 || n_workgroups > (1 << 20))
+        return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    if (c->side[side].cus <= 0) return fail(RS_ERR_STATE, "side has no compute units");
+    int32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, RS_CU_HIST_BINS * sizeof(int32_t)));
+    hipStream_t st = c->side[side].stream;
+    hipError_t e = hipMemsetAsync(d, 0, RS_CU_HIST_BINS * sizeof(int32_t), st);
+    if (e == hipSuccess) {
+        launch_cu_probe(st, d, n_workgroups);
+        e = hipMemcpyAsync(hist_out, d, RS_CU_HIST_BINS * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d);
+    if (e != hipSuccess) return fail(RS_ERR_HIP, "cu probe: %s", hipGetErrorString(e));
+    return RS_OK;
+}
+
+// ---------------------------------------------------------------------------- serving step
+
+int32_t rs_submit(rs_ctx *c, int64_t req_id, int32_t prompt_len, int32_t output_len, const void *prompt_hidden) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (prompt_len < 1 || output_len < 1) return fail(RS_ERR_BAD_ARG, "prompt_len and output_len must be >= 1");
+    if (c->gpu && !prompt_hidden) return fail(RS_ERR_BAD_ARG, "null prompt_hidden");
+    if (c->reqs.count(req_id)) return fail(RS_ERR_BAD_ARG, "request %lld already known", (long long)req_id);
+    if (prompt_len + output_len > c->lim.max_context || prompt_len + output_len > c->m.max_pos)
+        return fail(RS_ERR_BAD_ARG, "prompt+output %d exceeds max_context/max_pos", prompt_len + output_len);
+    if (c->gpu && prompt_len > c->ws[RS_SIDE_PREFILL].rows) return fail(RS_ERR_BAD_ARG, "prompt longer than max_prefill_tokens");
+    Request r{};
+    r.id = req_id;
+    r.prompt_len = prompt_len;
+    r.output_len = output_len;
+    r.prompt_hidden = prompt_hidden;
+    c->reqs[req_id] = r;
+    c->arrival.push_back(req_id);
+    return RS_OK;
+}
+
+int32_t rs_request_state(rs_ctx *c, int64_t req_id) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end()) return fail(RS_ERR_BAD_ARG, "unknown request");
+    return it->second.state;
+}
+
+int32_t rs_debug_complete_prefill(rs_ctx *c, int64_t req_id) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->gpu) return fail(RS_ERR_STATE, "only for host-only contexts");
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end() || it->second.state != PREFILLING) return fail(RS_ERR_STATE, "request is not prefilling");
+    it->second.host_done = true;
+    return RS_OK;
+}
+
+int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
+    if (!c || !in || !out) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (c->gpu && (!in->decode_hidden || !in->decode_out)) return fail(RS_ERR_BAD_ARG, "null decode buffers");
+    *out = rs_step_out{};
+    out->prefill_started_req = -1;
+    out->decode_ms = -1.f;
+    const int maxB = c->lim.max_decode_batch;
+
+    // 1a. the prefill "notification": event completed -> PREFILL_DONE
+    if (c->prefilling >= 0) {
+        Request &r = c->reqs[c->prefilling];
+        bool done = r.host_done;
+        if (c->gpu) {
+            hipError_t q = hipEventQuery(r.done);
+            if (q == hipSuccess) done = true;
+            else if (q != hipErrorNotReady) return fail(RS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q));
+        }
+        if (done) {
+            r.state = PREFILL_DONE;
+            r.ctx_len = r.prompt_len;
+            c->prefilling = -1;
+        }
+    }
+    // 1b. retire requests that produced all their tokens
+    for (size_t i = 0; i < c->running.size();) {
+        Request &r = c->reqs[c->running[i]];
+        if (r.generated >= r.output_len) {
+            r.state = FINISHED;
+            rs_kv_free(c, r.id);
+            if (r.done) { (void)hipEventDestroy(r.done); r.done = nullptr; }
+            c->running.erase(c->running.begin() + i);
+            out->n_finished++;
+        } else {
+            ++i;
+        }
+    }
+    while (!c->arrival.empty() && c->reqs[c->arrival.front()].state == FINISHED) c->arrival.pop_front();
+    // 1c. promote finished prefills into the decode batch, FCFS
+    for (int64_t id : c->arrival) {
+        Request &r = c->reqs[id];
+        if (r.state == PREFILL_DONE && (int)c->running.size() < maxB) {
+            r.state = RUNNING;
+            c->running.push_back(id);
+            out->n_promoted++;
+        }
+    }
+    // 2. prompt blocks for waiting requests in arrival order (stop at the first that does not fit)
+    for (int64_t id : c->arrival) {
+        Request &r = c->reqs[id];
+        if (r.state != WAITING) continue;
+        if (kv_alloc(c, id, r.prompt_len, nullptr) != RS_OK) break;
+        r.state = PREFILL_READY;
+    }
+    for (int64_t id : c->arrival)
+        if (c->reqs[id].state == WAITING) out->n_waiting++;
+
+    // 3. the split for this step
+    int64_t next_prefill = -1;
+    if (c->prefilling < 0)
+        for (int64_t id : c->arrival)
+            if (c->reqs[id].state == PREFILL_READY) { next_prefill = id; break; }
+    const bool prefill_pending = c->prefilling >= 0 || next_prefill >= 0;
+    const int B = (int)c->running.size();
+    int64_t sum_ctx = 0;
+    for (int64_t id : c->running) sum_ctx += c->reqs[id].ctx_len;
+    int32_t p, d;
+    choose_split(c, B, sum_ctx, prefill_pending, &p, &d);
+    if (B == 0 && !prefill_pending) { p = c->side[0].cus; d = c->side[1].cus; }
+    else {
+        int32_t rc = set_split(c, p, d);
+        if (rc) return rc;
+    }
+    out->prefill_cus = p;
+    out->decode_cus = d;
+    out->decode_batch = B;
+    out->decode_sum_ctx = sum_ctx;
+
+    // 4. one decode step over the running batch
+    if (B > 0) {
+        int max_ctx = 1;
+        for (int64_t id : c->running) {
+            Request &r = c->reqs[id];
+            if (kv_alloc(c, id, r.ctx_len + 1, nullptr) != RS_OK)
+                return fail(RS_ERR_NO_BLOCKS, "no block to grow request %lld (preemption is not implemented)", (long long)id);
+            max_ctx = std::max(max_ctx, r.ctx_len + 1);
+        }
+        if (c->gpu) {
+            const int flip = c->stage_flip ^= 1;
+            HIP_TRY(hipEventSynchronize(c->staged[flip]));
+            const int mb = c->max_blk_per_req;
+            for (int i = 0; i < B; ++i) {
+                Request &r = c->reqs[c->running[i]];
+                c->h_ctx[flip][i] = r.ctx_len;
+                const std::vector<int32_t> &ids = c->owned[r.id];
+                for (int j = 0; j < mb; ++j) c->h_tab[flip][(size_t)i * mb + j] = j < (int)ids.size() ? ids[j] : -1;
+            }
+            hipStream_t st = c->side[RS_SIDE_DECODE].stream;
+            HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+            HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+            HIP_TRY(hipEventRecord(c->staged[flip], st));
+            if (in->wait_decode) { int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2); if (rc) return rc; }
+            for (int l = 0; l < c->m.n_layers; ++l) {
+                if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+                int32_t rc = decode_layer(c, l, l == 0 ? in->decode_hidden : in->decode_out, in->decode_out, c->d_ctx,
+                                          c->d_tab, mb, B, max_ctx);
+                if (rc) return rc;
+            }
+            if (in->wait_decode) {
+                int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 1);
+                if (rc) return rc;
+                rc = rs_elapsed_ms(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2, RS_MAX_MARKS - 1, &out->decode_ms);
+                if (rc) return rc;
+            }
+        }
+        for (int64_t id : c->running) {
+            Request &r = c->reqs[id];
+            r.ctx_len++;
+            r.generated++;
+        }
+    }
+
+    // 5. start the next whole-prompt prefill if the prefill side is idle
+    if (next_prefill >= 0 && c->side[RS_SIDE_PREFILL].cus > 0) {
+        Request &r = c->reqs[next_prefill];
+        if (c->gpu) {
+            const int mb = c->max_blk_per_req;
+            HIP_TRY(hipEventSynchronize(c->pstaged));
+            const std::vector<int32_t> &ids = c->owned[r.id];
+            for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)ids.size() ? ids[j] : -1;
+            hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+            HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+            HIP_TRY(hipEventRecord(c->pstaged, st));
+            const int32_t cu[2] = {0, r.prompt_len};
+            Workspace &w = c->ws[RS_SIDE_PREFILL];
+            for (int l = 0; l < c->m.n_layers; ++l) {
+                if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+                int32_t rc = prefill_layer(c, l, l == 0 ? r.prompt_hidden : (const void *)w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
+                if (rc) return rc;
+            }
+            if (!r.done) HIP_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
+            HIP_TRY(hipEventRecord(r.done, st));
+        }
+        r.state = PREFILLING;
+        c->prefilling = r.id;
+        out->prefill_started_req = r.id;
+        out->prefill_started_tokens = r.prompt_len;
+    }
+    return RS_OK;
+}
+
+}  // extern "C"

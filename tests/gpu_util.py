@@ -1,0 +1,114 @@
+"""Helpers for the GPU parity tests: device buffers via torch, calls through the C-ABI binding,
+and the error metric of the parity bar."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2601_11822_amd as rs
+import rs_synth as S
+
+TOL = 2e-2  # max relative error for bf16 activations with fp32 accumulation
+
+
+def to_dev(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> bf16 device tensor holding exactly those bits."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16).copy())
+    return t.view(torch.bfloat16).cuda()
+
+
+def to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def rel_err(got_f32: np.ndarray, ref_f32: np.ndarray) -> float:
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): relative error with the denominator
+    floored at the tensor's rms so that near-zero elements do not blow it up."""
+    ref = ref_f32.astype(np.float64)
+    got = got_f32.astype(np.float64)
+    rms = np.sqrt(np.mean(ref * ref))
+    den = np.maximum(np.abs(ref), max(rms, 1e-30))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+class Rig:
+    """One layer stack on the GPU with its pools, plus the matching oracle layers."""
+
+    def __init__(self, shape, n_blocks, max_prefill_tokens, max_decode_batch, max_context, n_layers=1,
+                 sentinel=0x7FC1, profile=None, with_oracle=True, max_pos=None):
+        self.shape, self.n_blocks, self.n_layers = shape, n_blocks, n_layers
+        self.sentinel = sentinel
+        Hkv, hd = shape.n_kv_heads, shape.head_dim
+        fill = torch.tensor([sentinel], dtype=torch.int32).to(torch.int16) if sentinel < 0x8000 else None
+        self.k_pool = torch.empty((n_layers, n_blocks, Hkv, 16, hd), dtype=torch.bfloat16, device="cuda")
+        self.v_pool = torch.empty((n_layers, n_blocks, Hkv, hd, 16), dtype=torch.bfloat16, device="cuda")
+        self.k_pool.view(torch.int16).fill_(int(np.array(sentinel, np.uint16).view(np.int16)))
+        self.v_pool.view(torch.int16).fill_(int(np.array(sentinel, np.uint16).view(np.int16)))
+        self.ctx = rs.Context.from_shape(shape, n_layers=n_layers, max_pos=max_pos or max(max_context, max_prefill_tokens, 1),
+                                         n_blocks=n_blocks, k_pool=self.k_pool, v_pool=self.v_pool,
+                                         max_prefill_tokens=max_prefill_tokens, max_decode_batch=max_decode_batch,
+                                         max_context=max_context, profile=profile, device=0)
+        self.wbits, self.wdev, self.olayers = [], [], []
+        for l in range(n_layers):
+            wb = S.layer_weights(shape, l)
+            wd = {k: to_dev(v) for k, v in wb.items()}
+            self.ctx.set_weights(l, wd["g1"], wd["wqkv"], wd["wo"], wd["g2"], wd["wg"], wd["wu"], wd["wd"])
+            self.wbits.append(wb); self.wdev.append(wd)
+            if with_oracle:
+                self.olayers.append(oracle.OracleLayer.from_shape(shape, wb))
+
+    def close(self):
+        self.ctx.destroy()
+
+    # ---- GPU calls
+    def prefill(self, x_bits, cu, tables, layer=0, sync=True):
+        x = to_dev(x_bits)
+        y = torch.empty_like(x)
+        tab = torch.from_numpy(np.ascontiguousarray(tables, dtype=np.int32)).cuda()
+        torch.cuda.synchronize()
+        self.ctx.prefill_layer(layer, x, y, cu, tab, tab.shape[1])
+        self._keep = (x, y, tab)
+        if sync:
+            self.ctx.sync(rs.RS_SIDE_PREFILL)
+            return to_bits(y)
+        return y
+
+    def decode(self, x_bits, ctx_lens, tables, layer=0, max_ctx=None, sync=True):
+        x = to_dev(x_bits)
+        y = torch.empty_like(x)
+        cl = torch.from_numpy(np.ascontiguousarray(ctx_lens, dtype=np.int32)).cuda()
+        tab = torch.from_numpy(np.ascontiguousarray(tables, dtype=np.int32)).cuda()
+        if max_ctx is None:
+            max_ctx = int(np.max(ctx_lens)) + 1
+        torch.cuda.synchronize()
+        self.ctx.decode_layer(layer, x, y, cl, tab, tab.shape[1], x.shape[0], max_ctx)
+        self._keepd = (x, y, cl, tab)
+        if sync:
+            self.ctx.sync(rs.RS_SIDE_DECODE)
+            return to_bits(y)
+        return y
+
+    # ---- pools in the oracle's logical order [n_blocks, 16, Hkv, hd]
+    def k_bits_logical(self, layer=0):
+        return to_bits(self.k_pool[layer].permute(0, 2, 1, 3).contiguous())
+
+    def v_bits_logical(self, layer=0):
+        return to_bits(self.v_pool[layer].permute(0, 3, 1, 2).contiguous())
+
+    def load_pools_from_logical(self, k_bits, v_bits, layer=0):
+        """k_bits, v_bits: uint16 [n_blocks,16,Hkv,hd] -> device pools in the library's layouts."""
+        self.k_pool[layer].copy_(to_dev(k_bits).permute(0, 2, 1, 3))
+        self.v_pool[layer].copy_(to_dev(v_bits).permute(0, 2, 3, 1))
+
+
+def check_cache_against_oracle(rig, Kc, Vc, oracle_sentinel, layer=0):
+    """Bit-exact indexing: the set of slots the GPU dirtied equals the oracle's set; dirtied
+    contents match to tolerance."""
+    kb, vb = rig.k_bits_logical(layer), rig.v_bits_logical(layer)
+    for bits, ref in ((kb, Kc), (vb, Vc)):
+        dirty_gpu = bits != np.uint16(rig.sentinel)
+        dirty_ref = ref != np.float32(oracle_sentinel)
+        assert np.array_equal(dirty_gpu, dirty_ref), "set of written cache slots differs from the oracle"
+        if dirty_ref.any():
+            got = S.bf16_bits_to_f32(bits)[dirty_ref]
+            e = rel_err(got, ref[dirty_ref])
+            assert e <= TOL, f"cache contents rel err {e}"

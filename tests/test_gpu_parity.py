@@ -1,0 +1,285 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact on cache indexing, <= 2e-2 max relative error on activations."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_11822_amd as rs
+import rs_synth as S
+from tests.gpu_util import TOL, Rig, check_cache_against_oracle, rel_err, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+ORC_SENT = np.float32(-777.0)
+f32 = S.bf16_bits_to_f32
+
+
+def _stage_report(rig, side, taps, rows, M):
+    """Per-stage relative errors against the oracle's taps (evaluated rows only)."""
+    sh = rig.shape
+    names = {0: ("h", sh.d_model), 1: ("qkv", sh.qkv_dim), 2: ("attn", sh.q_dim), 3: ("x1", sh.d_model),
+             4: ("act", sh.ffn_dim)}
+    out = {}
+    for which, (nm, width) in names.items():
+        got = f32(rig.ctx.debug_read_workspace(side, which, (M, width)))
+        ref = taps[nm]
+        if nm in ("attn", "x1", "act") and rows is not None:
+            got, ref = got[rows], ref[rows]
+        out[nm] = rel_err(got, ref)
+    return out
+
+
+def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    n_blocks = sum(S.blocks_for(n) for n in lens) + n_blocks_extra
+    tabs = S.shuffled_block_tables(lens, n_blocks, stream=stream)
+    xb = S.hidden_states(T, shape.d_model, stream=stream)
+    return cu, T, n_blocks, tabs, xb
+
+
+def _run_prefill_parity(shape, lens):
+    cu, T, n_blocks, tabs, xb = _prefill_case(shape, lens)
+    rig = Rig(shape, n_blocks, T, 1, max(lens) + 1)
+    try:
+        y_bits = rig.prefill(xb, cu, tabs)
+        L = rig.olayers[0]
+        Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
+        x = f32(xb)
+        y_ref, taps = L.prefill(x, cu, tabs, Kc, Vc, taps=True)
+        stages = _stage_report(rig, rs.RS_SIDE_PREFILL, taps, None, T)
+        print("prefill stage rel errs", shape.name, lens, stages)
+        for nm, e in stages.items():
+            assert e <= TOL, f"stage {nm}: {e}"
+        check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        e_attn = rel_err(f32(rig.ctx.debug_read_workspace(0, 3, (T, shape.d_model))) - x, taps["x1"] - x)
+        e_out = rel_err(f32(y_bits) - x, y_ref - x)
+        print("branch deltas: attention", e_attn, "whole layer", e_out)
+        assert e_attn <= TOL and e_out <= TOL
+        assert np.isfinite(f32(y_bits)).all()
+    finally:
+        rig.close()
+
+
+def test_cu_masks_confine_workgroups():
+    """Section 4.2: workgroups of a masked queue run only on the masked-in CUs."""
+    rig = Rig(S.TINY, 4, 16, 4, 64, with_oracle=False)
+    try:
+        seen = {}
+        for p, d in [(256, 256), (128, 128), (64, 192), (192, 64), (32, 224)]:
+            rig.ctx.set_cu_split(p, d)
+            hp = rig.ctx.debug_cu_histogram(0, 8192)
+            hd_ = rig.ctx.debug_cu_histogram(1, 8192)
+            assert hp.sum() == 8192 and hd_.sum() == 8192
+            cus_p, cus_d = set(np.nonzero(hp)[0]), set(np.nonzero(hd_)[0])
+            seen[(p, d)] = (cus_p, cus_d)
+            print("split", (p, d), "distinct CUs used:", len(cus_p), len(cus_d),
+                  "per XCC prefill", [sum(1 for c in cus_p if c >> 8 == x) for x in range(8)])
+            assert len(cus_p) == p and len(cus_d) == d
+            if p + d <= 256:
+                assert not (cus_p & cus_d), "disjoint split shares a CU"
+                for s_ in (cus_p, cus_d):
+                    per_xcc = [sum(1 for c in s_ if c >> 8 == x) for x in range(8)]
+                    assert len(set(per_xcc)) == 1, f"uneven XCD shares {per_xcc}"
+        assert len(seen[(256, 256)][0]) == 256
+    finally:
+        rig.close()
+
+
+def test_prefill_tiny_config():
+    _run_prefill_parity(S.TINY, [128])
+
+
+def test_prefill_tiny_ragged_multi_request():
+    _run_prefill_parity(S.TINY, [1, 17, 130, 64])
+
+
+def test_prefill_mid_gqa_ragged():
+    _run_prefill_parity(S.MID, [200, 100, 77])
+
+
+def _fill_contexts(rig, ctx, tabs, stream0):
+    """Prefill each request's context on GPU and oracle; returns oracle caches."""
+    shape = rig.shape
+    L = rig.olayers[0]
+    Kc, Vc = L.new_cache(rig.n_blocks, fill=ORC_SENT)
+    lens = [int(c) for c in ctx if c > 0]
+    idx = [i for i, c in enumerate(ctx) if c > 0]
+    if lens:
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        xb = S.hidden_states(int(cu[-1]), shape.d_model, stream=stream0)
+        rig.prefill(xb, cu, tabs[idx])
+        L.prefill(f32(xb), cu, tabs[idx], Kc, Vc)
+    return Kc, Vc
+
+
+def _run_decode_parity(shape, ctx, stream=0):
+    ctx = np.asarray(ctx, np.int32)
+    B = len(ctx)
+    counts = [int(c) + 1 for c in ctx]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 5
+    tabs = S.shuffled_block_tables(counts, n_blocks, stream=stream)
+    rig = Rig(shape, n_blocks, max(int(ctx.sum()), 1), B, int(ctx.max()) + 1)
+    try:
+        Kc, Vc = _fill_contexts(rig, ctx, tabs, 40 + stream)
+        L = rig.olayers[0]
+        xb = S.hidden_states(B, shape.d_model, stream=50 + stream)
+        y_bits = rig.decode(xb, ctx, tabs)
+        x = f32(xb)
+        y_ref, taps = L.decode(x, ctx, tabs, Kc, Vc, taps=True)
+        stages = _stage_report(rig, rs.RS_SIDE_DECODE, taps, None, B)
+        print("decode stage rel errs", shape.name, ctx.tolist(), stages)
+        for nm, e in stages.items():
+            assert e <= TOL, f"stage {nm}: {e}"
+        check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        e_out = rel_err(f32(y_bits) - x, y_ref - x)
+        print("decode whole-layer branch delta rel err", e_out)
+        assert e_out <= TOL
+        assert np.isfinite(f32(y_bits)).all()
+    finally:
+        rig.close()
+
+
+def test_decode_tiny_config():
+    _run_decode_parity(S.TINY, [64, 128, 192, 256])
+
+
+def test_decode_edge_contexts_tiny():
+    # empty cache, block edges, chunk (512) edges
+    _run_decode_parity(S.TINY, [0, 1, 15, 16, 17, 511, 512, 513], stream=1)
+
+
+def test_decode_mid_gqa_several_chunks():
+    _run_decode_parity(S.MID, [5, 127, 128, 640, 1100], stream=2)
+
+
+def test_decode_after_prefill_matches_prefill_rows_on_gpu():
+    shape = S.MID
+    n, extra = 60, 6
+    total = n + extra
+    tabs = S.shuffled_block_tables([total], 8)
+    xb = S.hidden_states(total, shape.d_model, stream=7)
+    rig = Rig(shape, 8, total, 1, total + 1)
+    try:
+        y_full = f32(rig.prefill(xb, [0, total], tabs))
+        rig.k_pool.view(torch.int16).fill_(0x7FC1); rig.v_pool.view(torch.int16).fill_(0x7FC1)
+        rig.prefill(xb[:n], [0, n], tabs)
+        x = f32(xb)
+        for t in range(n, total):
+            y_t = f32(rig.decode(xb[t:t + 1], [t], tabs))
+            e = rel_err(y_t[0] - x[t], y_full[t] - x[t])
+            assert e <= TOL, (t, e)
+    finally:
+        rig.close()
+
+
+def _decode_setup(shape, ctx, stream):
+    ctx = np.asarray(ctx, np.int32)
+    counts = [int(c) + 1 for c in ctx]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 40
+    return ctx, counts, n_blocks
+
+
+def test_decode_bit_identical_across_splits_concurrency_and_block_permutation():
+    """CU masking is transparent to kernels (section 4.2): same bits under every split, with or
+    without a prefill running on the other side, and under a permutation of physical blocks."""
+    shape = S.MID
+    ctx, counts, n_blocks = _decode_setup(shape, [33, 700, 1500, 64, 257, 900], 3)
+    B = len(ctx)
+    xb = S.hidden_states(B, shape.d_model, stream=60)
+    kb_log, vb_log = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
+    pre_T = 512
+    pre_x = S.hidden_states(pre_T, shape.d_model, stream=61)
+    results = []
+    for perm_stream in (0, 1):
+        tabs_all = S.shuffled_block_tables(counts + [pre_T], n_blocks + 40, stream=perm_stream)
+        tabs, ptab = tabs_all[:B], tabs_all[B:B + 1]
+        rig = Rig(shape, n_blocks + 40, pre_T, B, int(ctx.max()) + 1, with_oracle=False)
+        try:
+            # logical content: request i, position p holds row (i*4096 + p) % ... of a seeded pool
+            k_log = np.zeros((n_blocks + 40, 16) + kb_log.shape[2:], np.uint16)
+            v_log = np.zeros_like(k_log)
+            src_k = kb_log.reshape(-1, *kb_log.shape[2:]); src_v = vb_log.reshape(-1, *vb_log.shape[2:])
+            at = 0
+            for i, c in enumerate(ctx):
+                for p in range(int(c)):
+                    k_log[tabs[i, p // 16], p % 16] = src_k[at]; v_log[tabs[i, p // 16], p % 16] = src_v[at]
+                    at += 1
+            for split, concurrent in [((256, 256), False), ((128, 128), False), ((192, 64), True),
+                                      ((64, 192), True), ((256, 256), True), ((0, 256), False)]:
+                rig.load_pools_from_logical(k_log, v_log)
+                rig.ctx.set_cu_split(*split)
+                if concurrent:
+                    for _ in range(3):
+                        rig.prefill(pre_x, [0, pre_T], ptab, sync=False)
+                y = rig.decode(xb, ctx, tabs)
+                rig.ctx.sync(rs.RS_SIDE_PREFILL) if split[0] else None
+                results.append(y.copy())
+        finally:
+            rig.close()
+    for y in results[1:]:
+        assert np.array_equal(results[0], y)
+
+
+def test_bad_block_ids_are_reported_not_dereferenced():
+    shape = S.TINY
+    rig = Rig(shape, 8, 64, 2, 64, with_oracle=False)
+    try:
+        xb = S.hidden_states(40, shape.d_model)
+        before_k = rig.k_bits_logical().copy()
+        with pytest.raises(rs.RapidServeError) as e:
+            rig.prefill(xb, [0, 40], np.array([[0, 1 << 20, 2]], np.int32))
+        assert e.value.code == rs.RS_ERR_BAD_BLOCK
+        after_k = rig.k_bits_logical()
+        # block 1 << 20 was skipped; blocks 0 and 2 were written
+        assert (after_k[0] != before_k[0]).any() and (after_k[2, :8] != before_k[2, :8]).any()
+        rig.ctx.sync(0)          # flag cleared
+        with pytest.raises(rs.RapidServeError) as e:   # table too short is caught on the host
+            rig.ctx.prefill_layer(0, to_dev(xb), to_dev(xb), [0, 40], torch.zeros(2, dtype=torch.int32, device="cuda"), 2)
+        assert e.value.code == rs.RS_ERR_BAD_BLOCK
+        with pytest.raises(rs.RapidServeError) as e:
+            rig.decode(S.hidden_states(2, shape.d_model), [20, 30], np.array([[0, -1, -1, -1], [1, -5, 2, 3]], np.int32))
+        assert e.value.code == rs.RS_ERR_BAD_BLOCK
+    finally:
+        rig.close()
+
+
+def test_serving_step_small_stack_matches_oracle():
+    """rs_submit / rs_step: one request through a 2-layer stack; each decode step's output
+    equals the oracle's stack evaluated the same way."""
+    shape = S.TINY
+    n_layers, prompt, out_len = 2, 40, 3
+    rig = Rig(shape, 16, 64, 4, 64, n_layers=n_layers)
+    try:
+        pb = S.hidden_states(prompt, shape.d_model, stream=70)
+        p_dev = to_dev(pb)
+        rig.ctx.submit(5, prompt, out_len, p_dev)
+        dec_in = [S.hidden_states(1, shape.d_model, stream=71 + i) for i in range(out_len)]
+        d_out = torch.zeros((4, shape.d_model), dtype=torch.bfloat16, device="cuda")
+        so = rig.ctx.step(to_dev(dec_in[0]), d_out)
+        assert so.prefill_started_req == 5 and so.decode_batch == 0
+        rig.ctx.sync(rs.RS_SIDE_PREFILL)
+        # oracle: same block ids (fresh LIFO pool hands out 0,1,2)
+        tabs = np.array([[0, 1, 2, -1]], np.int32)
+        caches = [L.new_cache(16) for L in rig.olayers]
+        x = f32(pb)
+        for l, L in enumerate(rig.olayers):
+            x = L.prefill(x, [0, prompt], tabs, *caches[l])
+        outs = []
+        for i in range(out_len):
+            keep = to_dev(dec_in[i])
+            so = rig.ctx.step(keep, d_out, wait_decode=True)
+            assert so.decode_batch == 1 and so.decode_sum_ctx == prompt + i and so.decode_ms > 0
+            rig.ctx.sync(rs.RS_SIDE_DECODE)
+            got = f32(to_bits(d_out[:1]))
+            xr = f32(dec_in[i])
+            for l, L in enumerate(rig.olayers):
+                xr = L.decode(xr, [prompt + i], tabs, *caches[l])
+            e = rel_err(got - f32(dec_in[i]), xr - f32(dec_in[i]))
+            print("step", i, "rel err", e)
+            assert e <= 2 * TOL      # two layers deep: bf16 error of layer 0 feeds layer 1
+        so = rig.ctx.step(to_dev(dec_in[0]), d_out)
+        assert so.n_finished == 1 and rig.ctx.request_state(5) == 5 and rig.ctx.kv_num_free() == 16
+    finally:
+        rig.close()
