@@ -116,23 +116,30 @@ def normal_bf16(shape: Sequence[int], seed: int, stream: int = 0, mean: float = 
     return out.reshape(tuple(shape))
 
 
-def layer_weights(shape: LayerShape, layer: int = 0, seed: int = SEED_WEIGHTS) -> Dict[str, np.ndarray]:
+def layer_weights(shape: LayerShape, layer: int = 0, seed: int = SEED_WEIGHTS,
+                  std: float = 0.02, wo_std: float | None = None,
+                  wd_std: float | None = None) -> Dict[str, np.ndarray]:
     """bf16 bit patterns of one layer's weights.
 
     Projection matrices are stored [out_features, in_features] (row = one output
-    feature) and drawn N(0, 0.02).  The two RMSNorm gains are drawn 1 + N(0, 0.02)
-    so that a dropped or misplaced gain multiply is visible.
+    feature) and drawn N(0, std), std = 0.02 for the workloads.  wo_std / wd_std (default std)
+    apply to the two matrices that project back onto the residual stream: a larger value makes
+    that branch dominate the residual input, which some parity cases want.
+    The two RMSNorm gains are drawn 1 + N(0, 0.02) so that a dropped or misplaced gain
+    multiply is visible.
     """
     d, f = shape.d_model, shape.ffn_dim
     base = layer * 16
+    wo_std = std if wo_std is None else wo_std
+    wd_std = std if wd_std is None else wd_std
     return {
         "g1": normal_bf16((d,), seed, base + 0, 1.0, 0.02),
-        "wqkv": normal_bf16((shape.qkv_dim, d), seed, base + 1, 0.0, 0.02),
-        "wo": normal_bf16((d, shape.q_dim), seed, base + 2, 0.0, 0.02),
+        "wqkv": normal_bf16((shape.qkv_dim, d), seed, base + 1, 0.0, std),
+        "wo": normal_bf16((d, shape.q_dim), seed, base + 2, 0.0, wo_std),
         "g2": normal_bf16((d,), seed, base + 3, 1.0, 0.02),
-        "wg": normal_bf16((f, d), seed, base + 4, 0.0, 0.02),
-        "wu": normal_bf16((f, d), seed, base + 5, 0.0, 0.02),
-        "wd": normal_bf16((d, f), seed, base + 6, 0.0, 0.02),
+        "wg": normal_bf16((f, d), seed, base + 4, 0.0, std),
+        "wu": normal_bf16((f, d), seed, base + 5, 0.0, std),
+        "wd": normal_bf16((d, f), seed, base + 6, 0.0, wd_std),
     }
 
 

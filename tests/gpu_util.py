@@ -21,24 +21,38 @@ def to_bits(t: torch.Tensor) -> np.ndarray:
 
 
 def rel_err(got_f32: np.ndarray, ref_f32: np.ndarray) -> float:
-    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): relative error with the denominator
-    floored at the tensor's rms so that near-zero elements do not blow it up."""
-    ref = ref_f32.astype(np.float64)
-    got = got_f32.astype(np.float64)
-    rms = np.sqrt(np.mean(ref * ref))
-    den = np.maximum(np.abs(ref), max(rms, 1e-30))
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref row of i)): relative error whose denominator
+    is floored at the rms of the element's own row (one token's activation vector), so that
+    near-zero elements do not blow it up and rows of different scale are judged on their own."""
+    ref = np.atleast_2d(ref_f32.astype(np.float64))
+    got = np.atleast_2d(got_f32.astype(np.float64))
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    den = np.maximum(np.abs(ref), np.maximum(rms, 1e-30))
     return float(np.max(np.abs(got - ref) / den))
+
+
+def residual_err(y_got: np.ndarray, y_ref: np.ndarray, x: np.ndarray, roundings: int = 2) -> float:
+    """Error of a residual-stream output judged on its branch delta y - x, as a fraction of the
+    allowed error.  Allowed: TOL * max(|delta_i|, rms(delta row)) for the branch arithmetic, plus
+    `roundings` half-ulps of bf16 at |y_i| (bf16 keeps 8 significant bits, so half an ulp is up
+    to 2^-8 |y_i|): y, and the intermediate hidden state it is built on, are STORED in bf16, so
+    y - x cannot resolve finer than that whatever the branch computes.  <= 1 passes."""
+    x = np.atleast_2d(x.astype(np.float64))
+    d_ref = np.atleast_2d(y_ref.astype(np.float64)) - x
+    d_got = np.atleast_2d(y_got.astype(np.float64)) - x
+    rms = np.sqrt(np.mean(d_ref * d_ref, axis=-1, keepdims=True))
+    allowed = TOL * np.maximum(np.abs(d_ref), np.maximum(rms, 1e-30)) + roundings * 2.0 ** -8 * np.abs(y_ref)
+    return float(np.max(np.abs(d_got - d_ref) / allowed))
 
 
 class Rig:
     """One layer stack on the GPU with its pools, plus the matching oracle layers."""
 
     def __init__(self, shape, n_blocks, max_prefill_tokens, max_decode_batch, max_context, n_layers=1,
-                 sentinel=0x7FC1, profile=None, with_oracle=True, max_pos=None):
+                 sentinel=0x7FC1, profile=None, with_oracle=True, max_pos=None, wo_std=None, wd_std=None):
         self.shape, self.n_blocks, self.n_layers = shape, n_blocks, n_layers
         self.sentinel = sentinel
         Hkv, hd = shape.n_kv_heads, shape.head_dim
-        fill = torch.tensor([sentinel], dtype=torch.int32).to(torch.int16) if sentinel < 0x8000 else None
         self.k_pool = torch.empty((n_layers, n_blocks, Hkv, 16, hd), dtype=torch.bfloat16, device="cuda")
         self.v_pool = torch.empty((n_layers, n_blocks, Hkv, hd, 16), dtype=torch.bfloat16, device="cuda")
         self.k_pool.view(torch.int16).fill_(int(np.array(sentinel, np.uint16).view(np.int16)))
@@ -48,8 +62,9 @@ class Rig:
                                          max_prefill_tokens=max_prefill_tokens, max_decode_batch=max_decode_batch,
                                          max_context=max_context, profile=profile, device=0)
         self.wbits, self.wdev, self.olayers = [], [], []
+        self._keep = []   # device tensors of enqueued calls stay alive until the rig is closed
         for l in range(n_layers):
-            wb = S.layer_weights(shape, l)
+            wb = S.layer_weights(shape, l, wo_std=wo_std, wd_std=wd_std)
             wd = {k: to_dev(v) for k, v in wb.items()}
             self.ctx.set_weights(l, wd["g1"], wd["wqkv"], wd["wo"], wd["g2"], wd["wg"], wd["wu"], wd["wd"])
             self.wbits.append(wb); self.wdev.append(wd)
@@ -58,6 +73,7 @@ class Rig:
 
     def close(self):
         self.ctx.destroy()
+        self._keep.clear()
 
     # ---- GPU calls
     def prefill(self, x_bits, cu, tables, layer=0, sync=True):
@@ -66,7 +82,7 @@ class Rig:
         tab = torch.from_numpy(np.ascontiguousarray(tables, dtype=np.int32)).cuda()
         torch.cuda.synchronize()
         self.ctx.prefill_layer(layer, x, y, cu, tab, tab.shape[1])
-        self._keep = (x, y, tab)
+        self._keep.append((x, y, tab))
         if sync:
             self.ctx.sync(rs.RS_SIDE_PREFILL)
             return to_bits(y)
@@ -81,7 +97,7 @@ class Rig:
             max_ctx = int(np.max(ctx_lens)) + 1
         torch.cuda.synchronize()
         self.ctx.decode_layer(layer, x, y, cl, tab, tab.shape[1], x.shape[0], max_ctx)
-        self._keepd = (x, y, cl, tab)
+        self._keep.append((x, y, cl, tab))
         if sync:
             self.ctx.sync(rs.RS_SIDE_DECODE)
             return to_bits(y)

@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2601_11822_amd as rs
 import rs_synth as S
-from tests.gpu_util import TOL, Rig, check_cache_against_oracle, rel_err, to_bits, to_dev
+from tests.gpu_util import TOL, Rig, check_cache_against_oracle, rel_err, residual_err, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -15,19 +15,29 @@ ORC_SENT = np.float32(-777.0)
 f32 = S.bf16_bits_to_f32
 
 
-def _stage_report(rig, side, taps, rows, M):
-    """Per-stage relative errors against the oracle's taps (evaluated rows only)."""
+def _stage_report(rig, side, taps, M, x):
+    """Relative errors of the intermediate tensors against the oracle's taps.  The first RMSNorm
+    buffer is reused by the second one and the k columns of the qkv buffer stay unrotated (the
+    rotated keys live in the cache, which is checked separately), so those are not compared."""
     sh = rig.shape
-    names = {0: ("h", sh.d_model), 1: ("qkv", sh.qkv_dim), 2: ("attn", sh.q_dim), 3: ("x1", sh.d_model),
-             4: ("act", sh.ffn_dim)}
-    out = {}
-    for which, (nm, width) in names.items():
-        got = f32(rig.ctx.debug_read_workspace(side, which, (M, width)))
-        ref = taps[nm]
-        if nm in ("attn", "x1", "act") and rows is not None:
-            got, ref = got[rows], ref[rows]
-        out[nm] = rel_err(got, ref)
+    qd, kvd = sh.q_dim, sh.kv_dim
+    qkv = f32(rig.ctx.debug_read_workspace(side, 1, (M, sh.qkv_dim)))
+    out = {"q": rel_err(qkv[:, :qd], taps["qkv"][:, :qd]),
+           "v": rel_err(qkv[:, qd + kvd:], taps["qkv"][:, qd + kvd:]),
+           "attn": rel_err(f32(rig.ctx.debug_read_workspace(side, 2, (M, qd))), taps["attn"]),
+           "act": rel_err(f32(rig.ctx.debug_read_workspace(side, 4, (M, sh.ffn_dim))), taps["act"])}
+    x1 = f32(rig.ctx.debug_read_workspace(side, 3, (M, sh.d_model)))
+    out["x1_allowed_frac"] = residual_err(x1, taps["x1"], x, roundings=1)
     return out
+
+
+def _assert_stages(stages):
+    """Intermediate tensors are diagnostics (the bar proper is on the cache and on the layer
+    output).  q, v and attn are held to TOL; act = silu(gate)*up multiplies two GEMM outputs that
+    each carry the bf16 rounding of the normalised input, so its relative errors add: 2*TOL."""
+    for nm, e in stages.items():
+        lim = 1.0 if nm.endswith("_frac") else (2 * TOL if nm == "act" else TOL)
+        assert e <= lim, f"stage {nm}: {e}"
 
 
 def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
@@ -39,24 +49,27 @@ def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
     return cu, T, n_blocks, tabs, xb
 
 
-def _run_prefill_parity(shape, lens):
+def _run_prefill_parity(shape, lens, wo_std=None, wd_std=None):
     cu, T, n_blocks, tabs, xb = _prefill_case(shape, lens)
-    rig = Rig(shape, n_blocks, T, 1, max(lens) + 1)
+    rig = Rig(shape, n_blocks, T, 1, max(lens) + 1, wo_std=wo_std, wd_std=wd_std)
     try:
         y_bits = rig.prefill(xb, cu, tabs)
         L = rig.olayers[0]
         Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
         x = f32(xb)
         y_ref, taps = L.prefill(x, cu, tabs, Kc, Vc, taps=True)
-        stages = _stage_report(rig, rs.RS_SIDE_PREFILL, taps, None, T)
+        stages = _stage_report(rig, rs.RS_SIDE_PREFILL, taps, T, x)
         print("prefill stage rel errs", shape.name, lens, stages)
-        for nm, e in stages.items():
-            assert e <= TOL, f"stage {nm}: {e}"
+        if wo_std is not None:
+            # a loud attention branch perturbs everything downstream of it by the branch's own
+            # relative error: only the attention half of the layer is judged in this case
+            assert stages["x1_allowed_frac"] <= 1.0 and stages["attn"] <= TOL
+            return
+        _assert_stages(stages)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        e_attn = rel_err(f32(rig.ctx.debug_read_workspace(0, 3, (T, shape.d_model))) - x, taps["x1"] - x)
-        e_out = rel_err(f32(y_bits) - x, y_ref - x)
-        print("branch deltas: attention", e_attn, "whole layer", e_out)
-        assert e_attn <= TOL and e_out <= TOL
+        e_out = residual_err(f32(y_bits), y_ref, x)
+        print("whole-layer branch delta, fraction of allowed error:", e_out)
+        assert e_out <= 1.0
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -99,6 +112,13 @@ def test_prefill_mid_gqa_ragged():
     _run_prefill_parity(S.MID, [200, 100, 77])
 
 
+@pytest.mark.parametrize("which", ["wo", "wd"])
+def test_prefill_mid_loud_output_projection(which):
+    """One output projection drawn N(0, 0.2): that branch is several times larger than the
+    residual input, so its check is not cushioned by the bf16 quantum of the residual stream."""
+    _run_prefill_parity(S.MID, [150, 90], **{which + "_std": 0.2})
+
+
 def _fill_contexts(rig, ctx, tabs, stream0):
     """Prefill each request's context on GPU and oracle; returns oracle caches."""
     shape = rig.shape
@@ -114,13 +134,13 @@ def _fill_contexts(rig, ctx, tabs, stream0):
     return Kc, Vc
 
 
-def _run_decode_parity(shape, ctx, stream=0):
+def _run_decode_parity(shape, ctx, stream=0, wo_std=None, wd_std=None):
     ctx = np.asarray(ctx, np.int32)
     B = len(ctx)
     counts = [int(c) + 1 for c in ctx]
     n_blocks = sum(S.blocks_for(c) for c in counts) + 5
     tabs = S.shuffled_block_tables(counts, n_blocks, stream=stream)
-    rig = Rig(shape, n_blocks, max(int(ctx.sum()), 1), B, int(ctx.max()) + 1)
+    rig = Rig(shape, n_blocks, max(int(ctx.sum()), 1), B, int(ctx.max()) + 1, wo_std=wo_std, wd_std=wd_std)
     try:
         Kc, Vc = _fill_contexts(rig, ctx, tabs, 40 + stream)
         L = rig.olayers[0]
@@ -128,14 +148,16 @@ def _run_decode_parity(shape, ctx, stream=0):
         y_bits = rig.decode(xb, ctx, tabs)
         x = f32(xb)
         y_ref, taps = L.decode(x, ctx, tabs, Kc, Vc, taps=True)
-        stages = _stage_report(rig, rs.RS_SIDE_DECODE, taps, None, B)
+        stages = _stage_report(rig, rs.RS_SIDE_DECODE, taps, B, x)
         print("decode stage rel errs", shape.name, ctx.tolist(), stages)
-        for nm, e in stages.items():
-            assert e <= TOL, f"stage {nm}: {e}"
+        if wo_std is not None:
+            assert stages["x1_allowed_frac"] <= 1.0 and stages["attn"] <= TOL
+            return
+        _assert_stages(stages)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        e_out = rel_err(f32(y_bits) - x, y_ref - x)
-        print("decode whole-layer branch delta rel err", e_out)
-        assert e_out <= TOL
+        e_out = residual_err(f32(y_bits), y_ref, x)
+        print("decode whole-layer branch delta, fraction of allowed error:", e_out)
+        assert e_out <= 1.0
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -154,6 +176,11 @@ def test_decode_mid_gqa_several_chunks():
     _run_decode_parity(S.MID, [5, 127, 128, 640, 1100], stream=2)
 
 
+@pytest.mark.parametrize("which", ["wo", "wd"])
+def test_decode_mid_loud_output_projection(which):
+    _run_decode_parity(S.MID, [40, 513, 700], stream=4, **{which + "_std": 0.2})
+
+
 def test_decode_after_prefill_matches_prefill_rows_on_gpu():
     shape = S.MID
     n, extra = 60, 6
@@ -168,8 +195,8 @@ def test_decode_after_prefill_matches_prefill_rows_on_gpu():
         x = f32(xb)
         for t in range(n, total):
             y_t = f32(rig.decode(xb[t:t + 1], [t], tabs))
-            e = rel_err(y_t[0] - x[t], y_full[t] - x[t])
-            assert e <= TOL, (t, e)
+            e = residual_err(y_t[0], y_full[t], x[t], roundings=4)   # both sides are bf16 outputs
+            assert e <= 1.0, (t, e)
     finally:
         rig.close()
 
@@ -276,9 +303,9 @@ def test_serving_step_small_stack_matches_oracle():
             xr = f32(dec_in[i])
             for l, L in enumerate(rig.olayers):
                 xr = L.decode(xr, [prompt + i], tabs, *caches[l])
-            e = rel_err(got - f32(dec_in[i]), xr - f32(dec_in[i]))
-            print("step", i, "rel err", e)
-            assert e <= 2 * TOL      # two layers deep: bf16 error of layer 0 feeds layer 1
+            e = residual_err(got, xr, f32(dec_in[i]), roundings=4)   # two layers: four bf16 stores
+            print("step", i, "fraction of allowed error", e)
+            assert e <= 1.5          # and layer 0's branch error feeds layer 1
         so = rig.ctx.step(to_dev(dec_in[0]), d_out)
         assert so.n_finished == 1 and rig.ctx.request_state(5) == 5 and rig.ctx.kv_num_free() == 16
     finally:
