@@ -1,0 +1,345 @@
+#!/usr/bin/env python3
+"""Benchmark of the co-executed prefill/decode layer on one MI355X.
+
+Workload (the Llama-3-8B-shaped single layer): one prefill request of 2048 tokens co-running
+with a decode batch of 64 whose contexts are uniform in [512, 4096], 16-token KV blocks with
+shuffled block tables, bf16, seeded synthetic weights and activations.
+
+A "step" is one pass of the whole hot path: one prefill-layer pass (all 8 kernels) on the
+prefill partition while decode-layer passes run back to back on the decode partition.
+--steps K times K prefill passes under co-run; the decode side runs as many decode steps as fit
+that window.  Reported: prefill tokens/s under co-run (`value`), decode inter-token latency
+(p50 of the per-step GPU time of one layer), both also alone at the same mask and alone on all
+256 CUs, the normalised combined throughput, and the rooflines of the two dominant kernels.
+
+One GPU only: --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_rig(args):
+    import torch
+    import paper_2601_11822_amd as rs
+    import rs_synth as S
+
+    shape = S.LLAMA8B
+    T, B = args.prefill_tokens, args.decode_batch
+    ctx = S.uniform_context_lengths(B, args.ctx_lo, args.ctx_hi)
+    counts = [int(c) + 1 for c in ctx] + [T]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 64
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)))
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    wb = S.layer_weights(shape, 0)
+    log(f"[bench] weights drawn in {time.time() - t0:.1f}s")
+    to_dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+    w = {k: to_dev(v) for k, v in wb.items()}
+    g = torch.Generator(device=dev)
+    g.manual_seed(S.SEED_CACHE)
+    Hkv, hd = shape.n_kv_heads, shape.head_dim
+    k_pool = torch.randn((n_blocks, Hkv, 16, hd), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v_pool = torch.randn((n_blocks, Hkv, hd, 16), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    max_ctx = int(ctx.max()) + 1
+    c = rs.Context.from_shape(shape, max_pos=max(max_ctx, T), n_blocks=n_blocks, k_pool=k_pool, v_pool=v_pool,
+                              max_prefill_tokens=T, max_decode_batch=B, max_context=max_ctx, device=0)
+    c.set_weights(0, w["g1"], w["wqkv"], w["wo"], w["g2"], w["wg"], w["wu"], w["wd"])
+    rig = {
+        "shape": shape, "ctx_obj": c, "T": T, "B": B, "ctx": ctx, "max_ctx": max_ctx, "wbits": wb,
+        "xp": to_dev(S.hidden_states(T, shape.d_model, stream=0)),
+        "xd": to_dev(S.hidden_states(B, shape.d_model, stream=50)),
+        "ptab": torch.from_numpy(tabs[B:B + 1].copy()).to(dev), "dtab": torch.from_numpy(tabs[:B].copy()).to(dev),
+        "cl": torch.from_numpy(ctx.copy()).to(dev), "max_blk": tabs.shape[1], "keep": (w, k_pool, v_pool),
+    }
+    rig["yp"] = torch.empty_like(rig["xp"])
+    rig["yd"] = torch.empty_like(rig["xd"])
+    torch.cuda.synchronize()
+    return rig
+
+
+def enqueue_prefill(r):
+    r["ctx_obj"].prefill_layer(0, r["xp"], r["yp"], [0, r["T"]], r["ptab"], r["max_blk"])
+
+
+def enqueue_decode(r):
+    r["ctx_obj"].decode_layer(0, r["xd"], r["yd"], r["cl"], r["dtab"], r["max_blk"], r["B"], r["max_ctx"])
+
+
+def run_alone(r, side, steps, warmup, kernel_times=False):
+    """Back-to-back passes of one side; returns per-pass GPU ms (events on that side's stream)
+    and, if asked, the mean per-kernel ms."""
+    c = r["ctx_obj"]
+    fn = enqueue_prefill if side == 0 else enqueue_decode
+    for _ in range(warmup):
+        fn(r)
+    c.sync(side)
+    kt = []
+    if kernel_times:
+        c.set_kernel_timing(True)
+        per = []
+        for i in range(steps):
+            c.mark(side, 0)
+            fn(r)
+            c.mark(side, 1)
+            per.append(c.elapsed_ms(side, 0, 1))
+            kt.append(c.kernel_times(side))
+        c.set_kernel_timing(False)
+        return np.array(per), np.mean(kt, axis=0)
+    c.mark(side, 0)
+    for i in range(steps):
+        fn(r)
+        c.mark(side, i + 1)
+    c.sync(side)
+    per = np.array([c.elapsed_ms(side, i, i + 1) for i in range(steps)])
+    return per, None
+
+
+def run_corun(r, steps, warmup, t_p_ms, t_d_ms):
+    """K prefill passes on the prefill side while decode steps run back to back on the decode
+    side.  Returns prefill ms per pass under co-run and the decode step times that fell
+    entirely inside the prefill window."""
+    c = r["ctx_obj"]
+    P, D = 0, 1
+    n_dec = int(min(3900, math.ceil(1.6 * (steps + warmup) * t_p_ms / max(t_d_ms, 1e-3)) + 16))
+    per_pass = max(1, n_dec // (steps + warmup))
+    c.sync(P); c.sync(D)
+    di = 0
+    c.mark(D, 0)
+    for i in range(warmup + steps):
+        if i == warmup:
+            c.mark(P, 0)
+        enqueue_prefill(r)
+        if i >= warmup:
+            c.mark(P, i - warmup + 1)
+        for _ in range(per_pass):
+            if di < n_dec:
+                enqueue_decode(r)
+                di += 1
+                c.mark(D, di)
+    while di < n_dec:
+        enqueue_decode(r)
+        di += 1
+        c.mark(D, di)
+    c.sync(P); c.sync(D)
+    p_start = c.elapsed_ms(D, 0, 0, side_end=P)            # prefill timed-window start, decode clock
+    p_ms = np.array([c.elapsed_ms(P, i, i + 1) for i in range(steps)])
+    p_end = p_start + float(p_ms.sum())
+    d_ms = np.array([c.elapsed_ms(D, i, i + 1) for i in range(n_dec)])
+    d_end = np.cumsum(d_ms)
+    d_beg = d_end - d_ms
+    inside = (d_beg >= p_start) & (d_end <= p_end)
+    covered = bool(d_end[-1] >= p_end)
+    return p_ms, d_ms[inside], covered, n_dec
+
+
+def pct(a, q):
+    return float(np.percentile(a, q)) if len(a) else float("nan")
+
+
+def cpu_baseline(r, budget_rows=(64, 192)):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same
+    workload: K/V of all T prompt rows plus the rest of the layer for a few sampled rows (two
+    sample sizes give the per-row cost), and one decode step for a slice of the batch."""
+    import oracle
+    import rs_synth as S
+    shape, T = r["shape"], r["T"]
+    t0 = time.time()
+    L = oracle.OracleLayer.from_shape(shape, r["wbits"])
+    log(f"[bench] oracle weights widened in {time.time() - t0:.1f}s")
+    x = S.bf16_bits_to_f32(S.hidden_states(T, shape.d_model, stream=0))
+    nb = S.blocks_for(T)
+    tabs = S.identity_block_tables([T])
+    times = []
+    for n in budget_rows:
+        rows = np.linspace(0, T - 1, n).astype(np.int32)
+        Kc, Vc = L.new_cache(nb)
+        t0 = time.time()
+        L.prefill(x, [0, T], tabs, Kc, Vc, rows=rows)
+        times.append(time.time() - t0)
+        log(f"[bench] oracle prefill, {n} sampled rows of {T}: {times[-1]:.2f}s")
+    per_row = (times[1] - times[0]) / (budget_rows[1] - budget_rows[0])
+    fixed = max(times[0] - budget_rows[0] * per_row, 0.0)
+    full = fixed + T * per_row
+    # decode: 8 of the 64 requests
+    nd = 8
+    ctx = r["ctx"][:nd]
+    counts = [int(c_) + 1 for c_ in ctx]
+    dt = S.identity_block_tables(counts)
+    nbd = int(dt.max()) + 1
+    Kd = np.random.default_rng(0).standard_normal((nbd, 16, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
+    Vd = Kd.copy()
+    xd = S.bf16_bits_to_f32(S.hidden_states(nd, shape.d_model, stream=50))
+    t0 = time.time()
+    L.decode(xd, ctx, dt, Kd, Vd)
+    t_dec = time.time() - t0
+    log(f"[bench] oracle decode step, {nd} requests: {t_dec:.2f}s")
+    return {
+        "value": T / full, "unit": "tok/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"prefill layer T={T}: K/V of all rows + {budget_rows[0]} and {budget_rows[1]} sampled rows "
+                   f"({times[0]:.1f}s, {times[1]:.1f}s) extrapolated linearly to all rows ({full:.0f}s); "
+                   f"decode step on {nd} of {r['B']} requests"),
+        "prefill_layer_s_extrapolated": full,
+        "decode_step_ms_extrapolated": 1e3 * t_dec * r["B"] / nd,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--prefill-tokens", type=int, default=2048)
+    ap.add_argument("--decode-batch", type=int, default=64)
+    ap.add_argument("--ctx-lo", type=int, default=512)
+    ap.add_argument("--ctx-hi", type=int, default=4096)
+    ap.add_argument("--split", type=str, default="192,64", help="headline prefill,decode CUs")
+    ap.add_argument("--sweep", action="store_true", help="also co-run at 64/128/192 prefill CUs and 256/256")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alone-only", action="store_true", help="only the alone-at-256-CUs phases (for profiling)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (prefill and decode share it through CU masks); "
+                 "--gpus above 1 is not supported")
+    import torch
+    import paper_2601_11822_amd as rs
+    assert torch.cuda.is_available(), "no GPU"
+    r = build_rig(args)
+    c = r["ctx_obj"]
+    shape, T, B = r["shape"], r["T"], r["B"]
+    K, W = args.steps, args.warmup
+    P = shape.params_per_layer
+    flops_layer = 2.0 * T * P + 2.0 * shape.n_q_heads * shape.head_dim * T * (T + 1)
+    kv_tok_bytes = 2 * shape.n_kv_heads * shape.head_dim * 2
+    attn_bytes = float((r["ctx"].astype(np.int64) + 1).sum()) * kv_tok_bytes
+    bytes_layer = 2.0 * P + attn_bytes + B * kv_tok_bytes
+
+    # ---- alone on all 256 CUs, with per-kernel times (the roofline figures)
+    c.set_cu_split(256, 256)
+    p256, kt_p = run_alone(r, 0, K, W, kernel_times=True)
+    d256, kt_d = run_alone(r, 1, max(K, 50), W, kernel_times=True)
+    p256_bb, _ = run_alone(r, 0, K, W)
+    d256_bb, _ = run_alone(r, 1, max(4 * K, 100), W)
+    names = rs.KERNEL_SLOT_NAMES
+    log("[bench] prefill alone @256: %.3f ms/pass  " % np.median(p256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_p)))
+    log("[bench] decode  alone @256: %.3f ms/step  " % np.median(d256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_d)))
+    gu_flops = 2.0 * T * shape.d_model * 2 * shape.ffn_dim
+    roof = {"kernel": "gateup_swiglu_gemm (prefill, alone on 256 CUs)", "bound": "mfma",
+            "achieved": gu_flops / (kt_p[6] * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof_d = {"kernel": "paged decode attention + chunk merge (alone on 256 CUs)", "bound": "hbm",
+              "achieved": attn_bytes / (kt_d[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None}
+    roof_d["frac"] = roof_d["achieved"] / roof_d["peak"]
+    layer_p = {"tflops": flops_layer / (np.median(p256_bb) * 1e-3) / 1e12}
+    layer_p["frac_mfma"] = layer_p["tflops"] / MFMA_PEAK_TFLOPS
+    layer_d = {"gbs": bytes_layer / (np.median(d256_bb) * 1e-3) / 1e9}
+    layer_d["frac_hbm"] = layer_d["gbs"] / HBM_PEAK_GBS
+    if args.alone_only:
+        # a plain copy of known size, so that HBM byte counters can be scaled against it
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        src.fill_(1.0)
+        for _ in range(3):
+            dst = src.clone()
+        torch.cuda.synchronize()
+        print(json.dumps({"prefill_ms": float(np.median(p256_bb)), "decode_ms": float(np.median(d256_bb)),
+                          "prefill_kernels_ms": dict(zip(names, map(float, kt_p))),
+                          "decode_kernels_ms": dict(zip(names, map(float, kt_d))), "roofline": roof,
+                          "roofline_decode": roof_d}))
+        return
+
+    # ---- co-run at the requested split(s)
+    splits = [tuple(int(v) for v in args.split.split(","))]
+    if args.sweep:
+        for s in [(64, 192), (128, 128), (192, 64), (224, 32), (256, 256)]:
+            if s not in splits:
+                splits.append(s)
+    sweep = []
+    for (pc, dc) in splits:
+        c.set_cu_split(pc, dc)
+        pa, _ = run_alone(r, 0, max(K // 2, 5), W)
+        da, _ = run_alone(r, 1, max(K, 30), W)
+        p_co, d_co, covered, n_dec = run_corun(r, K, W, float(np.median(pa)), float(np.median(da)))
+        rec = {
+            "prefill_cus": pc, "decode_cus": dc,
+            "prefill_alone_ms": float(np.median(pa)), "decode_alone_ms": float(np.median(da)),
+            "prefill_corun_ms": float(np.mean(p_co)), "decode_corun_p50_ms": pct(d_co, 50),
+            "decode_corun_p95_ms": pct(d_co, 95), "decode_steps_in_window": int(len(d_co)),
+            "decode_covered_window": covered,
+            "prefill_tok_s_corun": T / (float(np.mean(p_co)) * 1e-3),
+            "decode_tok_s_corun": B / (pct(d_co, 50) * 1e-3) if len(d_co) else float("nan"),
+            "itl_vs_alone_256": pct(d_co, 50) / float(np.median(d256_bb)),
+            "itl_vs_alone_same_mask": pct(d_co, 50) / float(np.median(da)),
+            "prefill_vs_alone_same_mask": float(np.mean(p_co)) / float(np.median(pa)),
+        }
+        rec["combined_norm_throughput"] = (float(np.median(p256_bb)) / rec["prefill_corun_ms"]
+                                           + float(np.median(d256_bb)) / rec["decode_corun_p50_ms"])
+        share_p = pc / 256.0
+        rec["prefill_frac_mfma_of_share"] = flops_layer / (rec["prefill_corun_ms"] * 1e-3) / 1e12 / (MFMA_PEAK_TFLOPS * share_p)
+        rec["decode_frac_hbm"] = bytes_layer / (rec["decode_corun_p50_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        log("[bench] split %s: %s" % ((pc, dc), json.dumps(rec)))
+        sweep.append(rec)
+    head = sweep[0]
+
+    # ---- measured sequential baseline: same kernels, all CUs, the two phases alternating
+    c.set_cu_split(256, 256)
+    k_dec = max(1, int(round(float(np.median(p256_bb)) / float(np.median(d256_bb)))))
+    c.sync(0); c.sync(1)
+    t0 = time.perf_counter()
+    for _ in range(K):
+        enqueue_prefill(r)
+        c.sync(0)
+        for _ in range(k_dec):
+            enqueue_decode(r)
+        c.sync(1)
+    seq_s = time.perf_counter() - t0
+    seq_norm = (K * float(np.median(p256_bb)) + K * k_dec * float(np.median(d256_bb))) / (seq_s * 1e3)
+
+    out = {
+        "metric": "prefill tok/s under co-run with decode (decode p50 ITL alongside)",
+        "value": head["prefill_tok_s_corun"], "unit": "tok/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": head["prefill_corun_ms"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"llama3-8b-shaped layer: prefill 1x{T} tokens co-running with decode batch {B}, "
+                               f"contexts U[{args.ctx_lo},{args.ctx_hi}], 16-token blocks, "
+                               f"split {head['prefill_cus']}/{head['decode_cus']} CUs",
+                   "prefill_tokens": T, "decode_batch": B, "sum_ctx": int(r["ctx"].sum()),
+                   "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"]},
+        "decode_itl_p50_ms_corun": head["decode_corun_p50_ms"],
+        "decode_itl_p95_ms_corun": head["decode_corun_p95_ms"],
+        "decode_itl_ms_alone_256": float(np.median(d256_bb)),
+        "prefill_ms_alone_256": float(np.median(p256_bb)),
+        "itl_corun_vs_alone_256": head["itl_vs_alone_256"],
+        "combined_norm_throughput": head["combined_norm_throughput"],
+        "sequential_baseline_norm_throughput_measured": seq_norm,
+        "prefill_layer_alone_256": layer_p, "decode_layer_alone_256": layer_d,
+        "prefill_kernels_ms_alone_256": dict(zip(names, map(float, kt_p))),
+        "decode_kernels_ms_alone_256": dict(zip(names, map(float, kt_d))),
+        "roofline": roof, "roofline_decode": roof_d, "sweep": sweep,
+    }
+    if not args.no_cpu_baseline:
+        c.sync(0); c.sync(1)
+        out["cpu_baseline"] = cpu_baseline(r)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

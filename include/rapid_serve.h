@@ -187,11 +187,21 @@ int32_t rs_get_stream(rs_ctx *ctx, int32_t side, void **hip_stream_out);
 /* Blocks until the side's work is done; reports RS_ERR_BAD_BLOCK if a kernel met a bad id
  * since the last rs_sync (the flag is then cleared). */
 int32_t rs_sync(rs_ctx *ctx, int32_t side);
-/* Timing on the side's own stream: rs_mark records event slot `slot` (0..RS_MAX_MARKS-1) on
- * the side's current stream; rs_elapsed_ms gives the time between two completed marks. */
+/* Timing with HIP events on the side's own stream: rs_mark records event slot `slot`
+ * (0..RS_MAX_MARKS-1) on the side's current stream; rs_elapsed_ms waits for both marks and gives
+ * the time from (side_begin, slot_begin) to (side_end, slot_end). */
 #define RS_MAX_MARKS 4096
 int32_t rs_mark(rs_ctx *ctx, int32_t side, int32_t slot);
-int32_t rs_elapsed_ms(rs_ctx *ctx, int32_t side, int32_t slot_begin, int32_t slot_end, float *ms_out);
+int32_t rs_elapsed_ms(rs_ctx *ctx, int32_t side_begin, int32_t slot_begin, int32_t side_end, int32_t slot_end,
+                      float *ms_out);
+/* Per-kernel timing of layer calls.  While on, every layer call records an event between its
+ * kernels on the side's stream; rs_kernel_times waits for the side's most recent layer call and
+ * gives the duration of each step: 0 RMSNorm, 1 QKV GEMM, 2 RoPE + KV write, 3 attention
+ * (decode: with the chunk merge), 4 output GEMM + residual, 5 RMSNorm, 6 gate/up GEMM + SwiGLU,
+ * 7 down GEMM + residual (decode GEMMs: with their split-K epilogue). */
+#define RS_N_KERNEL_SLOTS 8
+int32_t rs_set_kernel_timing(rs_ctx *ctx, int32_t on);
+int32_t rs_kernel_times(rs_ctx *ctx, int32_t side, float ms_out[RS_N_KERNEL_SLOTS]);
 
 /* Where a side's workgroups really run: launches n_workgroups short workgroups on the side's
  * stream and counts them per physical compute unit.  hist_out (host, RS_CU_HIST_BINS int32) is

@@ -21,12 +21,15 @@ RS_ERR_BAD_ARG, RS_ERR_NO_BLOCKS, RS_ERR_BAD_SPLIT, RS_ERR_BAD_BLOCK, RS_ERR_HIP
 RS_SIDE_PREFILL, RS_SIDE_DECODE = 0, 1
 RS_TOTAL_CUS, RS_CU_GRANULE, RS_KV_BLOCK, RS_MAX_PREFILL_REQS, RS_HOST_ONLY = 256, 32, 16, 64, -1
 RS_MAX_MARKS = 4096
+RS_N_KERNEL_SLOTS = 8
+KERNEL_SLOT_NAMES = ("rmsnorm1", "qkv_gemm", "rope_kvwrite", "attention", "o_gemm", "rmsnorm2",
+                     "gateup_swiglu_gemm", "down_gemm")
 RS_CU_HIST_BINS = 4096
 
 EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_set_cu_split", "rs_get_cu_split",
-    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_elapsed_ms",
+    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_elapsed_ms", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
 ]
 
@@ -251,11 +254,21 @@ class Context:
     def mark(self, side: int, slot: int):
         _check(self._lib.rs_mark(self._h, ctypes.c_int32(side), ctypes.c_int32(slot)))
 
-    def elapsed_ms(self, side: int, slot_begin: int, slot_end: int) -> float:
+    def elapsed_ms(self, side_begin: int, slot_begin: int, slot_end: int, side_end: Optional[int] = None) -> float:
         ms = ctypes.c_float(0)
-        _check(self._lib.rs_elapsed_ms(self._h, ctypes.c_int32(side), ctypes.c_int32(slot_begin),
-                                       ctypes.c_int32(slot_end), ctypes.byref(ms)))
+        if side_end is None:
+            side_end = side_begin
+        _check(self._lib.rs_elapsed_ms(self._h, ctypes.c_int32(side_begin), ctypes.c_int32(slot_begin),
+                                       ctypes.c_int32(side_end), ctypes.c_int32(slot_end), ctypes.byref(ms)))
         return ms.value
+
+    def set_kernel_timing(self, on: bool):
+        _check(self._lib.rs_set_kernel_timing(self._h, ctypes.c_int32(1 if on else 0)))
+
+    def kernel_times(self, side: int) -> np.ndarray:
+        out = (ctypes.c_float * RS_N_KERNEL_SLOTS)()
+        _check(self._lib.rs_kernel_times(self._h, ctypes.c_int32(side), out))
+        return np.array(list(out), dtype=np.float64)
 
     # -- serving step
     def submit(self, req_id: int, prompt_len: int, output_len: int, prompt_hidden=None):

@@ -60,6 +60,8 @@ struct Side {
     std::map<int, hipStream_t> pool;  // by CU count
     std::vector<hipEvent_t> marks;
     hipEvent_t order = nullptr;
+    hipEvent_t kt[RS_N_KERNEL_SLOTS + 1] = {};  // boundaries of the last layer call's kernels
+    bool kt_valid = false;
 };
 
 }  // namespace
@@ -77,6 +79,7 @@ struct rs_ctx {
     Workspace ws[2];
     Side side[2];
     bool over_alloc = true;
+    bool kernel_timing = false;
 
     // allocator
     std::vector<int32_t> free_list;
@@ -241,8 +244,17 @@ int32_t check_layer_call(rs_ctx *c, int side, int32_t layer, const void *x_in, v
     return RS_OK;
 }
 
+// With kernel timing on, records boundary `i` of the current layer call on the side's stream.
+void tick(rs_ctx *c, int side, int i) {
+    if (!c->kernel_timing) return;
+    Side &s = c->side[side];
+    if (!s.kt[i] && hipEventCreate(&s.kt[i]) != hipSuccess) return;
+    (void)hipEventRecord(s.kt[i], s.stream);
+    if (i == RS_N_KERNEL_SLOTS) s.kt_valid = true;
+}
+
 // The dense part after attention, shared by both passes.
-void run_post_attention(rs_ctx *c, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
+void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
                         const bf16_t *x, bf16_t *y, int M, bool skinny) {
     const rs_model_desc &m = c->m;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
@@ -251,9 +263,13 @@ void run_post_attention(rs_ctx *c, hipStream_t st, Workspace &w, const rs_layer_
         else launch_gemm_tiled(st, g);
     };
     gemm(GemmArgs{w.attn, (const bf16_t *)lw.wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
+    tick(c, side, 5);
     launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps);
+    tick(c, side, 6);
     gemm(GemmArgs{w.h, (const bf16_t *)lw.wg, (const bf16_t *)lw.wu, nullptr, w.act, M, f, d, EPI_SWIGLU});
+    tick(c, side, 7);
     gemm(GemmArgs{w.act, (const bf16_t *)lw.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
+    tick(c, side, 8);
 }
 
 int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu,
@@ -281,15 +297,20 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
 
+    tick(c, RS_SIDE_PREFILL, 0);
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, T, d, m.rms_eps);
+    tick(c, RS_SIDE_PREFILL, 1);
     launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, T, nqkv, d, EPI_STORE});
+    tick(c, RS_SIDE_PREFILL, 2);
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
     launch_rope_kvwrite(st, ra);
+    tick(c, RS_SIDE_PREFILL, 3);
     PrefillAttnArgs pa{w.qkv, nqkv, w.attn, kp, vp, tables, c->err_flag, m.n_q_heads, m.n_kv_heads, hd,
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
-    run_post_attention(c, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
+    tick(c, RS_SIDE_PREFILL, 4);
+    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
     HIP_TRY(hipGetLastError());
     return RS_OK;
 }
@@ -311,20 +332,25 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
     const bool skinny = B <= 64;
 
+    tick(c, RS_SIDE_DECODE, 0);
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
+    tick(c, RS_SIDE_DECODE, 1);
     GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE};
     if (skinny) launch_gemm_skinny(st, g, w.partials);
     else launch_gemm_tiled(st, g);
+    tick(c, RS_SIDE_DECODE, 2);
     SeqInfo none{};
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, ctx_lens, c->err_flag, B, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, none};
     launch_rope_kvwrite(st, ra);
+    tick(c, RS_SIDE_DECODE, 3);
     DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
                       B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
                       (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
                       (float)(1.4426950408889634 / std::sqrt((double)hd))};
     launch_decode_attention(st, da);
-    run_post_attention(c, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
+    tick(c, RS_SIDE_DECODE, 4);
+    run_post_attention(c, RS_SIDE_DECODE, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
     HIP_TRY(hipGetLastError());
     return RS_OK;
 }
@@ -445,6 +471,8 @@ int32_t rs_destroy(rs_ctx *c) {
             for (hipEvent_t e : c->side[s].marks)
                 if (e) (void)hipEventDestroy(e);
             if (c->side[s].order) (void)hipEventDestroy(c->side[s].order);
+            for (hipEvent_t e : c->side[s].kt)
+                if (e) (void)hipEventDestroy(e);
             for (auto &kv : c->side[s].pool) (void)hipStreamDestroy(kv.second);
             free_ws(c->ws[s]);
         }
@@ -572,14 +600,34 @@ int32_t rs_mark(rs_ctx *c, int32_t side, int32_t slot) {
     return RS_OK;
 }
 
-int32_t rs_elapsed_ms(rs_ctx *c, int32_t side, int32_t a, int32_t b, float *ms) {
-    if (!c || !ms || side < 0 || side > 1 || a < 0 || b < 0 || a >= RS_MAX_MARKS || b >= RS_MAX_MARKS)
+int32_t rs_elapsed_ms(rs_ctx *c, int32_t side_a, int32_t a, int32_t side_b, int32_t b, float *ms) {
+    if (!c || !ms || side_a < 0 || side_a > 1 || side_b < 0 || side_b > 1 || a < 0 || b < 0 || a >= RS_MAX_MARKS ||
+        b >= RS_MAX_MARKS)
         return fail(RS_ERR_BAD_ARG, "bad argument");
     if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
-    hipEvent_t ea = c->side[side].marks[a], eb = c->side[side].marks[b];
+    hipEvent_t ea = c->side[side_a].marks[a], eb = c->side[side_b].marks[b];
     if (!ea || !eb) return fail(RS_ERR_STATE, "mark not recorded");
+    HIP_TRY(hipEventSynchronize(ea));
     HIP_TRY(hipEventSynchronize(eb));
     HIP_TRY(hipEventElapsedTime(ms, ea, eb));
+    return RS_OK;
+}
+
+int32_t rs_set_kernel_timing(rs_ctx *c, int32_t on) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    c->kernel_timing = on != 0;
+    c->side[0].kt_valid = c->side[1].kt_valid = false;
+    return RS_OK;
+}
+
+int32_t rs_kernel_times(rs_ctx *c, int32_t side, float ms_out[RS_N_KERNEL_SLOTS]) {
+    if (!c || !ms_out || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    Side &s = c->side[side];
+    if (!s.kt_valid) return fail(RS_ERR_STATE, "no timed layer call on this side yet");
+    HIP_TRY(hipEventSynchronize(s.kt[RS_N_KERNEL_SLOTS]));
+    for (int i = 0; i < RS_N_KERNEL_SLOTS; ++i) HIP_TRY(hipEventElapsedTime(&ms_out[i], s.kt[i], s.kt[i + 1]));
     return RS_OK;
 }
 
@@ -770,7 +818,7 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
             if (in->wait_decode) {
                 int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 1);
                 if (rc) return rc;
-                rc = rs_elapsed_ms(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2, RS_MAX_MARKS - 1, &out->decode_ms);
+                rc = rs_elapsed_ms(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2, RS_SIDE_DECODE, RS_MAX_MARKS - 1, &out->decode_ms);
                 if (rc) return rc;
             }
         }

@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_header_constants_match_binding():
     hdr = open(os.path.join(ROOT, "include", "rapid_serve.h")).read()
     for name in ("RS_TOTAL_CUS", "RS_CU_GRANULE", "RS_KV_BLOCK", "RS_MAX_PREFILL_REQS", "RS_MAX_MARKS",
-                 "RS_CU_HIST_BINS"):
+                 "RS_CU_HIST_BINS", "RS_N_KERNEL_SLOTS"):
         v = int(re.search(rf"#define {name}\s+\(?(-?\d+)", hdr).group(1))
         assert getattr(rs, name) == v
 
