@@ -150,6 +150,178 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Direct kernel (K % 64 == 0): same tiling and epilogues as the tiled kernel, but the operand
+// tiles go global -> LDS with the 16-byte LDS-DMA load (no register staging) into two LDS stages:
+// the loads of tile k+1 are issued before the MFMAs of tile k and waited for after them, one
+// barrier per K step.  A wave-wide load fills 1 KB = 8 rows x 128 B; the swizzle (chunk ^= row&7)
+// is applied by permuting which global chunk each lane fetches.  Rows past M or N are clamped to
+// the last valid row (their results are never stored).  The flat workgroup id is remapped so
+// that the workgroups resident on one XCD (ids congruent mod 8) cover a compact block of
+// tiles: all row tiles of a few column tiles, which that XCD's L2 then serves.
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
+    constexpr int BK = 64;
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int LA = BM / 32, LB = BN / 32;        // wave-wide loads per wave per stage
+    constexpr int STAGE = (BM + BN) * BK;            // elements per stage
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int M = a.M, N = a.N, K = a.K;
+
+    // XCD-aware tile order: xcd = id % 8 owns a contiguous run of column-major tiles
+    const int total = m_tiles * n_tiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (t >= total) return;
+    const int bm = (t % m_tiles) * BM;
+    const int nb = t / m_tiles;
+
+    const int lrow = lane >> 3;                       // row within the 8-row group of one load
+    const int lchunk = ((lane & 7) ^ lrow) << 3;      // element offset of the fetched chunk
+    const bf16_t *pa[LA];
+    const bf16_t *pb[LB];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+        const int r = (wave * LA + j) * 8 + lrow;
+        pa[j] = a.A + (size_t)min(bm + r, M - 1) * K + lchunk;
+    }
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        const int r = (wave * LB + j) * 8 + lrow;
+        if (EPI == EPI_SWIGLU) {
+            const int tt = r >> 5;
+            const int f = min(nb * (BN / 2) + (tt >> 1) * 32 + (r & 31), N - 1);
+            pb[j] = ((tt & 1) ? a.W2 : a.W) + (size_t)f * K + lchunk;
+        } else {
+            pb[j] = a.W + (size_t)min(nb * BN + r, N - 1) * K + lchunk;
+        }
+    }
+    auto issue = [&](int stage, int k0) {
+        bf16_t *sa = smem + stage * STAGE;
+        bf16_t *sb = sa + BM * BK;
+#pragma unroll
+        for (int j = 0; j < LA; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + k0),
+                                             (__attribute__((address_space(3))) void *)(sa + (wave * LA + j) * 512),
+                                             16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < LB; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j] + k0),
+                                             (__attribute__((address_space(3))) void *)(sb + (wave * LB + j) * 512),
+                                             16, 0, 0);
+    };
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int x7 = c32 & 7;
+    const int a_row = (wm * WM + c32) * BK, b_row = (wn * WN + c32) * BK;
+    const int nk = K / BK;
+    issue(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) issue(cur ^ 1, (kt + 1) * BK);
+        const bf16_t *sa = smem + cur * STAGE;
+        const bf16_t *sb = sa + BM * BK;
+        bf16x8 wf[2][TN], xf[2][TM];
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) wf[0][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + ((h ^ x7) << 3)];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) xf[0][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + ((h ^ x7) << 3)];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s < 3) {
+                const int co = ((2 * (s + 1) + h) ^ x7) << 3;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) wf[(s + 1) & 1][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + co];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) xf[(s + 1) & 1][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + co];
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[s & 1][tn], xf[s & 1][tm], acc[tn][tm]);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = bm + wm * WM + 32 * tm + c32;
+        if (m >= M) continue;
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int p = 0; p < TN / 2; ++p)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int f = nb * (BN / 2) + (wn * (TN / 2) + p) * 32 + 8 * j + 4 * h;
+                    if (f >= N) continue;
+                    bf16x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[i] = (bf16_t)(silu_f(acc[2 * p][tm][4 * j + i]) * acc[2 * p + 1][tm][4 * j + i]);
+                    *(bf16x4 *)(a.out + (size_t)m * N + f) = v;
+                }
+        } else {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = nb * BN + wn * WN + 32 * tn + 8 * j + 4 * h;
+                    if (n >= N) continue;
+                    bf16x4 v;
+                    if (EPI == EPI_RESIDUAL) {
+                        const bf16x4 r = *(const bf16x4 *)(a.resid + (size_t)m * N + n);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(acc[tn][tm][4 * j + i] + (float)r[i]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[tn][tm][4 * j + i];
+                    }
+                    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+                }
+        }
+    }
+}
+
+template <int BM, int BN, int EPI>
+static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
+    const int m_tiles = (a.M + BM - 1) / BM;
+    const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
+    const int total = m_tiles * n_tiles;
+    const int grid = ((total + 7) / 8) * 8;
+    constexpr int lds = 2 * (BM + BN) * 64 * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
+}
+
+template <int BM, int BN>
+static void launch_direct(hipStream_t st, const GemmArgs &a) {
+    switch (a.epi) {
+        case EPI_STORE: launch_direct_epi<BM, BN, EPI_STORE>(st, a); break;
+        case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL>(st, a); break;
+        default: launch_direct_epi<BM, BN, EPI_SWIGLU>(st, a); break;
+    }
+}
+
 template <int BM, int BN>
 static void launch_tiled(hipStream_t st, const GemmArgs &a) {
     const int n_virtual = (a.epi == EPI_SWIGLU) ? 2 * a.N : a.N;
@@ -171,10 +343,19 @@ static void launch_tiled(hipStream_t st, const GemmArgs &a) {
 
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
     if (a.M <= 0 || a.N <= 0) return;
-    if (a.M >= 1024 && a.N >= 1024)
+    const bool aligned = (a.K % 64 == 0) && a.K >= 64;
+    if (aligned && a.M >= 512 && a.N >= 1024) {
+        // the tile grid is a function of the problem shape only
+        const long tiles256 = (long)((a.M + 255) / 256) * ((a.epi == EPI_SWIGLU ? 2 * a.N : a.N) / 256);
+        if (tiles256 >= 256)
+            launch_direct<256, 256>(st, a);
+        else
+            launch_direct<128, 256>(st, a);
+    } else if (a.M >= 1024 && a.N >= 1024) {
         launch_tiled<256, 256>(st, a);
-    else
+    } else {
         launch_tiled<128, 128>(st, a);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

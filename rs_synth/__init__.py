@@ -72,7 +72,10 @@ LLAMA70B = LayerShape("llama3-70b-layer", 8192, 64, 8, 128, 28672, 1e-5, 500000.
 # A mid-size GQA shape for parity tests: several tiles, ragged tails, seconds on the CPU.
 MID = LayerShape("mid-gqa", 512, 8, 2, 128, 1376, 1e-5, 500000.0)
 
-SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA70B, MID)}
+# A wider GQA shape whose GEMMs all take the large-tile path (K multiples of 64, N >= 1024).
+WIDE = LayerShape("wide-gqa", 1024, 8, 2, 128, 2816, 1e-5, 500000.0)
+
+SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA70B, MID, WIDE)}
 
 
 def _rng(seed: int, stream: int = 0) -> np.random.Generator:

@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2601_11822_amd as rs
 import rs_synth as S
-from tests.gpu_util import TOL, Rig, check_cache_against_oracle, rel_err, residual_err, to_bits, to_dev
+from tests.gpu_util import TOL, Rig, check_cache_against_oracle, check_tensor, rel_err, residual_err, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -15,29 +15,19 @@ ORC_SENT = np.float32(-777.0)
 f32 = S.bf16_bits_to_f32
 
 
-def _stage_report(rig, side, taps, M, x):
-    """Relative errors of the intermediate tensors against the oracle's taps.  The first RMSNorm
-    buffer is reused by the second one and the k columns of the qkv buffer stay unrotated (the
-    rotated keys live in the cache, which is checked separately), so those are not compared."""
+def _check_stages(rig, side, taps, M, x, attention_only=False):
+    """Intermediate tensors against the oracle's taps, each at the bar.  The first RMSNorm buffer
+    is reused by the second one and the k columns of the qkv buffer stay unrotated (the rotated
+    keys live in the cache, which is checked separately), so those two are not compared."""
     sh = rig.shape
     qd, kvd = sh.q_dim, sh.kv_dim
     qkv = f32(rig.ctx.debug_read_workspace(side, 1, (M, sh.qkv_dim)))
-    out = {"q": rel_err(qkv[:, :qd], taps["qkv"][:, :qd]),
-           "v": rel_err(qkv[:, qd + kvd:], taps["qkv"][:, qd + kvd:]),
-           "attn": rel_err(f32(rig.ctx.debug_read_workspace(side, 2, (M, qd))), taps["attn"]),
-           "act": rel_err(f32(rig.ctx.debug_read_workspace(side, 4, (M, sh.ffn_dim))), taps["act"])}
-    x1 = f32(rig.ctx.debug_read_workspace(side, 3, (M, sh.d_model)))
-    out["x1_allowed_frac"] = residual_err(x1, taps["x1"], x, roundings=1)
-    return out
-
-
-def _assert_stages(stages):
-    """Intermediate tensors are diagnostics (the bar proper is on the cache and on the layer
-    output).  q, v and attn are held to TOL; act = silu(gate)*up multiplies two GEMM outputs that
-    each carry the bf16 rounding of the normalised input, so its relative errors add: 2*TOL."""
-    for nm, e in stages.items():
-        lim = 1.0 if nm.endswith("_frac") else (2 * TOL if nm == "act" else TOL)
-        assert e <= lim, f"stage {nm}: {e}"
+    check_tensor("q (rotated)", qkv[:, :qd], taps["qkv"][:, :qd])
+    check_tensor("v", qkv[:, qd + kvd:], taps["qkv"][:, qd + kvd:])
+    check_tensor("attention out", f32(rig.ctx.debug_read_workspace(side, 2, (M, qd))), taps["attn"])
+    check_tensor("x1 = x + attn Wo", f32(rig.ctx.debug_read_workspace(side, 3, (M, sh.d_model))), taps["x1"], x, 1)
+    if not attention_only:
+        check_tensor("silu(gate)*up", f32(rig.ctx.debug_read_workspace(side, 4, (M, sh.ffn_dim))), taps["act"])
 
 
 def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
@@ -58,18 +48,13 @@ def _run_prefill_parity(shape, lens, wo_std=None, wd_std=None):
         Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
         x = f32(xb)
         y_ref, taps = L.prefill(x, cu, tabs, Kc, Vc, taps=True)
-        stages = _stage_report(rig, rs.RS_SIDE_PREFILL, taps, T, x)
-        print("prefill stage rel errs", shape.name, lens, stages)
-        if wo_std is not None:
-            # a loud attention branch perturbs everything downstream of it by the branch's own
-            # relative error: only the attention half of the layer is judged in this case
-            assert stages["x1_allowed_frac"] <= 1.0 and stages["attn"] <= TOL
-            return
-        _assert_stages(stages)
+        print("prefill", shape.name, lens)
+        # a loud attention branch perturbs everything downstream of it by the branch's own
+        # relative error: only the attention half of the layer is judged in that case
+        _check_stages(rig, rs.RS_SIDE_PREFILL, taps, T, x, attention_only=wo_std is not None)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        e_out = residual_err(f32(y_bits), y_ref, x)
-        print("whole-layer branch delta, fraction of allowed error:", e_out)
-        assert e_out <= 1.0
+        if wo_std is None:
+            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2)
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -112,6 +97,17 @@ def test_prefill_mid_gqa_ragged():
     _run_prefill_parity(S.MID, [200, 100, 77])
 
 
+def test_prefill_wide_large_tile_path_ragged():
+    """d_model 1024: every prefill GEMM takes the large-tile LDS-DMA kernel; 600 rows is ragged
+    against both tile heights."""
+    _run_prefill_parity(S.WIDE, [333, 267])
+
+
+@pytest.mark.parametrize("which", ["wo", "wd"])
+def test_prefill_wide_loud_output_projection(which):
+    _run_prefill_parity(S.WIDE, [520], **{which + "_std": 0.2})
+
+
 @pytest.mark.parametrize("which", ["wo", "wd"])
 def test_prefill_mid_loud_output_projection(which):
     """One output projection drawn N(0, 0.2): that branch is several times larger than the
@@ -148,16 +144,11 @@ def _run_decode_parity(shape, ctx, stream=0, wo_std=None, wd_std=None):
         y_bits = rig.decode(xb, ctx, tabs)
         x = f32(xb)
         y_ref, taps = L.decode(x, ctx, tabs, Kc, Vc, taps=True)
-        stages = _stage_report(rig, rs.RS_SIDE_DECODE, taps, B, x)
-        print("decode stage rel errs", shape.name, ctx.tolist(), stages)
-        if wo_std is not None:
-            assert stages["x1_allowed_frac"] <= 1.0 and stages["attn"] <= TOL
-            return
-        _assert_stages(stages)
+        print("decode", shape.name, ctx.tolist())
+        _check_stages(rig, rs.RS_SIDE_DECODE, taps, B, x, attention_only=wo_std is not None)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        e_out = residual_err(f32(y_bits), y_ref, x)
-        print("decode whole-layer branch delta, fraction of allowed error:", e_out)
-        assert e_out <= 1.0
+        if wo_std is None:
+            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2)
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -308,5 +299,52 @@ def test_serving_step_small_stack_matches_oracle():
             assert e <= 1.5          # and layer 0's branch error feeds layer 1
         so = rig.ctx.step(to_dev(dec_in[0]), d_out)
         assert so.n_finished == 1 and rig.ctx.request_state(5) == 5 and rig.ctx.kv_num_free() == 16
+    finally:
+        rig.close()
+
+
+def test_full_size_8b_layer_sampled_rows():
+    """The benchmark's own configuration (Llama-3-8B-shaped layer, prefill 1x2048, decode batch 64
+    with contexts U[512,4096]) in the launch configuration bench.py times: the whole K/V cache
+    the prefill writes, sampled prefill rows and every decode row against the oracle."""
+    shape = S.LLAMA8B
+    T, B = 2048, 64
+    ctx = S.uniform_context_lengths(B, 512, 4096)
+    counts = [int(c) + 1 for c in ctx] + [T]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 64
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)))
+    dtab, ptab = tabs[:B], tabs[B:B + 1]
+    rig = Rig(shape, n_blocks, T, B, int(ctx.max()) + 1, sentinel=0x7FC1)
+    try:
+        L = rig.olayers[0]
+        # ---- prefill
+        xb = S.hidden_states(T, shape.d_model, stream=0)
+        x = f32(xb)
+        rig.ctx.set_cu_split(192, 64)
+        y_bits = rig.prefill(xb, [0, T], ptab)
+        rng = np.random.default_rng(11)
+        rows = np.unique(np.concatenate([[0, 1, 15, 16, 17, 127, 128, 255, 256, 1023, 1024, 2046, 2047],
+                                         rng.integers(0, T, 19)])).astype(np.int32)
+        Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
+        y_ref = L.prefill(x, [0, T], ptab, Kc, Vc, rows=rows)
+        check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        check_tensor("8B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2)
+        # ---- decode over a directly written cache (same bits on both sides)
+        kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
+        rig.load_pools_from_logical(kb, vb)
+        Kc, Vc = f32(kb), f32(vb)
+        db = S.hidden_states(B, shape.d_model, stream=50)
+        yd = rig.decode(db, ctx, dtab)
+        yd_ref = L.decode(f32(db), ctx, dtab, Kc, Vc)
+        check_tensor("8B decode y, batch 64", f32(yd), yd_ref, f32(db), 2)
+        # appended K/V of the new tokens: exact slots, contents to tolerance
+        kg, vg = f32(rig.k_bits_logical()), f32(rig.v_bits_logical())
+        changed = (rig.k_bits_logical() != kb).any(axis=(2, 3))
+        want = np.zeros_like(changed)
+        for i, c in enumerate(ctx):
+            want[dtab[i, c // 16], c % 16] = True
+            assert rel_err(kg[dtab[i, c // 16], c % 16].reshape(1, -1), Kc[dtab[i, c // 16], c % 16].reshape(1, -1)) <= TOL
+            assert rel_err(vg[dtab[i, c // 16], c % 16].reshape(1, -1), Vc[dtab[i, c // 16], c % 16].reshape(1, -1)) <= TOL
+        assert np.array_equal(changed, want), "decode wrote K/V slots other than each request's next position"
     finally:
         rig.close()
