@@ -4,6 +4,8 @@
 // The weight tile is the MFMA "row" operand and the activation tile the "column" operand:
 // a lane then owns 4 consecutive output columns of one output row, which makes the epilogues
 // (residual add, SwiGLU, bf16 pack) plain per-lane code with 8-byte stores.
+#include <type_traits>
+
 #include "kernels.h"
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -13,8 +15,8 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 
 // ---------------------------------------------------------------------------------------------
 // Tiled kernel: BM x BN output tile per 256-thread workgroup (2x2 waves), BK = 64, operands
-// staged global -> registers -> LDS (16-byte chunks, chunk index XOR row&7 against bank
-// conflicts), next tile's global loads in flight during the MFMAs.  Every tail (M, N, K) is
+// staged global -> registers -> LDS (16-byte chunks, chunk index XOR (row>>1)&7 against bank
+// conflicts on the 64-bank LDS), next tile's global loads in flight during the MFMAs.  Every tail (M, N, K) is
 // handled by predicated zero-filled loads and predicated stores.
 //
 // SwiGLU: the B tile interleaves 32 gate rows with the 32 matching up rows, so gate and up of
@@ -80,12 +82,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < CA; ++j) {
             const int r = (tid >> 3) + 32 * j;
-            *(bf16x8 *)&As[r * BK + ((cc ^ (r & 7)) << 3)] = ra[j];
+            *(bf16x8 *)&As[r * BK + ((cc ^ ((r >> 1) & 7)) << 3)] = ra[j];
         }
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
             const int r = (tid >> 3) + 32 * j;
-            *(bf16x8 *)&Bs[r * BK + ((cc ^ (r & 7)) << 3)] = rb[j];
+            *(bf16x8 *)&Bs[r * BK + ((cc ^ ((r >> 1) & 7)) << 3)] = rb[j];
         }
         __syncthreads();
         if (k0 + BK < K) gload(k0 + BK);
@@ -95,12 +97,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 const int r = wn * WN + 32 * tn + c32;
-                wf[tn] = *(const bf16x8 *)&Bs[r * BK + (((2 * s + h) ^ (r & 7)) << 3)];
+                wf[tn] = *(const bf16x8 *)&Bs[r * BK + (((2 * s + h) ^ ((r >> 1) & 7)) << 3)];
             }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
                 const int r = wm * WM + 32 * tm + c32;
-                xf[tm] = *(const bf16x8 *)&As[r * BK + (((2 * s + h) ^ (r & 7)) << 3)];
+                xf[tm] = *(const bf16x8 *)&As[r * BK + (((2 * s + h) ^ ((r >> 1) & 7)) << 3)];
             }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
@@ -151,22 +153,36 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Direct kernel (K % 64 == 0): same tiling and epilogues as the tiled kernel, but the operand
-// tiles go global -> LDS with the 16-byte LDS-DMA load (no register staging) into two LDS stages:
-// the loads of tile k+1 are issued before the MFMAs of tile k and waited for after them, one
-// barrier per K step.  A wave-wide load fills 1 KB = 8 rows x 128 B; the swizzle (chunk ^= row&7)
-// is applied by permuting which global chunk each lane fetches.  Rows past M or N are clamped to
-// the last valid row (their results are never stored).  The flat workgroup id is remapped so
-// that the workgroups resident on one XCD (ids congruent mod 8) cover a compact block of
-// tiles: all row tiles of a few column tiles, which that XCD's L2 then serves.
+// Direct kernel (K % 32 == 0): same tiling and epilogues as the tiled kernel, but the operand
+// tiles go global -> LDS with the 16-byte LDS-DMA load (no register staging) through a ring of
+// NS LDS stages of BK = 32, so that a K tile is requested NS-1 tiles (several microseconds of
+// MFMA work) before it is consumed: HBM latency is covered although only one wave runs per SIMD.
+//
+// A wave-wide load fills 1 KB = 16 rows x 64 B.  The LDS has 64 four-byte banks, so four rows
+// span the banks once; 16 lanes reading one logical 16-byte chunk of 16 consecutive rows are
+// conflict free when the stored chunk index is chunk ^ ((row >> 2) & 3).  The swizzle is applied
+// by permuting which global chunk each lane fetches.  Rows past M or N are clamped to the last
+// valid row (their results are never stored); K tiles past the end re-fetch the last tile into a
+// stage nobody reads, which keeps the loop body branch free.
+//
+// Per K tile (two MFMA steps, one barrier): the loads of tile kt+NS-1 trickle out between the
+// MFMAs; step 0 reads the step-1 fragments; step 1 waits until tile kt+1 has landed (vmcnt counts
+// the younger loads that may still fly), meets the other waves at the barrier and reads tile
+// kt+1's step-0 fragments.  In both steps the first MFMAs are issued before the reads, so a wait
+// in front of a step is already satisfied and the barrier never sits between idle matrix cores.
+//
+// The flat workgroup id is remapped so that the workgroups resident on one XCD (ids congruent
+// mod 8) cover a compact block of tiles: all row tiles of a few column tiles, served by that
+// XCD's L2.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS>
 __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
-    constexpr int BK = 64;
+    constexpr int BK = 32;
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int LA = BM / 32, LB = BN / 32;        // wave-wide loads per wave per stage
+    constexpr int LA = BM / 64, LB = BN / 64;        // wave-wide loads per wave per stage
     constexpr int STAGE = (BM + BN) * BK;            // elements per stage
+    constexpr int D = NS - 1;                        // prefetch distance in K tiles
     extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -182,18 +198,18 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tile
     const int bm = (t % m_tiles) * BM;
     const int nb = t / m_tiles;
 
-    const int lrow = lane >> 3;                       // row within the 8-row group of one load
-    const int lchunk = ((lane & 7) ^ lrow) << 3;      // element offset of the fetched chunk
+    const int lrow = lane >> 2;                                     // row within the 16-row group
+    const int lchunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 3;       // element offset of the fetched chunk
     const bf16_t *pa[LA];
     const bf16_t *pb[LB];
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        const int r = (wave * LA + j) * 8 + lrow;
+        const int r = (wave * LA + j) * 16 + lrow;
         pa[j] = a.A + (size_t)min(bm + r, M - 1) * K + lchunk;
     }
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
-        const int r = (wave * LB + j) * 8 + lrow;
+        const int r = (wave * LB + j) * 16 + lrow;
         if (EPI == EPI_SWIGLU) {
             const int tt = r >> 5;
             const int f = min(nb * (BN / 2) + (tt >> 1) * 32 + (r & 31), N - 1);
@@ -202,19 +218,25 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tile
             pb[j] = a.W + (size_t)min(nb * BN + r, N - 1) * K + lchunk;
         }
     }
-    auto issue = [&](int stage, int k0) {
+    const int nk = K / BK;
+    // loads [j0, j1) of the LA + LB wave-wide loads that bring K tile kt into its stage
+    auto issue = [&](int kt, int j0, int j1) {
+        const int stage = kt % NS;
+        const int k0 = min(kt, nk - 1) * BK;
         bf16_t *sa = smem + stage * STAGE;
         bf16_t *sb = sa + BM * BK;
 #pragma unroll
-        for (int j = 0; j < LA; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + k0),
-                                             (__attribute__((address_space(3))) void *)(sa + (wave * LA + j) * 512),
-                                             16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < LB; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j] + k0),
-                                             (__attribute__((address_space(3))) void *)(sb + (wave * LB + j) * 512),
-                                             16, 0, 0);
+        for (int j = 0; j < LA + LB; ++j) {
+            if (j < j0 || j >= j1) continue;
+            if (j < LA)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + k0),
+                                                 (__attribute__((address_space(3))) void *)(sa + (wave * LA + j) * 512),
+                                                 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j - LA] + k0),
+                                                 (__attribute__((address_space(3))) void *)(sb + (wave * LB + j - LA) * 512),
+                                                 16, 0, 0);
+        }
     };
 
     f32x16 acc[TN][TM];
@@ -225,39 +247,59 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tile
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int x7 = c32 & 7;
+    const int x3 = (c32 >> 2) & 3;
     const int a_row = (wm * WM + c32) * BK, b_row = (wn * WN + c32) * BK;
-    const int nk = K / BK;
-    issue(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) issue(cur ^ 1, (kt + 1) * BK);
-        const bf16_t *sa = smem + cur * STAGE;
+    bf16x8 wf[2][TN], xf[2][TM];
+    auto read_frags = [&](int set, int kt, int step) {
+        const bf16_t *sa = smem + (kt % NS) * STAGE;
         const bf16_t *sb = sa + BM * BK;
-        bf16x8 wf[2][TN], xf[2][TM];
+        const int co = ((2 * step + h) ^ x3) << 3;
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) wf[0][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + ((h ^ x7) << 3)];
+        for (int tn = 0; tn < TN; ++tn) wf[set][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + co];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) xf[0][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + ((h ^ x7) << 3)];
+        for (int tm = 0; tm < TM; ++tm) xf[set][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + co];
+    };
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (s < 3) {
-                const int co = ((2 * (s + 1) + h) ^ x7) << 3;
+    for (int i = 0; i < D; ++i) issue(i, 0, LA + LB);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((D - 1) * (LA + LB)) : "memory");
+    read_frags(0, 0, 0);
+
+    // One K tile = SL MFMA slots (two steps of TN x TM).  A load instruction holds up the
+    // issuing wave while the CU's one memory pipeline takes it, and a wave that cannot issue
+    // cannot feed its matrix core either; so the LT loads of the next tile are placed one at a
+    // time, evenly between the MFMAs, and wave w places its loads w quarter-spacings later than
+    // wave 0: the four lock-stepped waves never queue behind one another.
+    constexpr int SL = 2 * TN * TM, LT = LA + LB, SP = SL / LT;
+    auto k_loop = [&](auto wtag) {
+        constexpr int W = decltype(wtag)::value;
+        constexpr int SHIFT = (W * SP) / 4;
+        // loads of the current iteration already issued when the barrier of slot SL/2 is reached
+        constexpr int EARLY = ((SL / 2 - 1 - SHIFT) / SP) + 1;
+        for (int kt = 0; kt < nk; ++kt) {
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) wf[(s + 1) & 1][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + co];
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) xf[(s + 1) & 1][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + co];
+            for (int sl = 0; sl < SL; ++sl) {
+                const int step = sl / (TN * TM), tn = (sl % (TN * TM)) / TM, tm = sl % TM;
+                if (sl == SL / 2)
+                    // tile kt+1 has landed once only the younger loads are outstanding; this wave's
+                    // LDS reads are complete before it tells the others so at the barrier
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((D - 2) * LT + EARLY) : "memory");
+                acc[tn][tm] = mfma32(wf[step][tn], xf[step][tm], acc[tn][tm]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (sl == TM - 1) read_frags(1, kt, 1);
+                if (sl == SL / 2 + TM - 1) read_frags(0, kt + 1, 0);
+                if (sl >= SHIFT && (sl - SHIFT) % SP == 0 && (sl - SHIFT) / SP < LT)
+                    issue(kt + D, (sl - SHIFT) / SP, (sl - SHIFT) / SP + 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[s & 1][tn], xf[s & 1][tm], acc[tn][tm]);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+    };
+    switch (__builtin_amdgcn_readfirstlane(wave)) {
+        case 0: k_loop(std::integral_constant<int, 0>{}); break;
+        case 1: k_loop(std::integral_constant<int, 1>{}); break;
+        case 2: k_loop(std::integral_constant<int, 2>{}); break;
+        default: k_loop(std::integral_constant<int, 3>{}); break;
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -300,17 +342,19 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tile
 
 template <int BM, int BN, int EPI>
 static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
+    constexpr int NS = (BM + BN) >= 512 ? 4 : 5;     // 4 x 32 KB or 5 x 24 KB of LDS
     const int m_tiles = (a.M + BM - 1) / BM;
     const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     const int total = m_tiles * n_tiles;
     const int grid = ((total + 7) / 8) * 8;
-    constexpr int lds = 2 * (BM + BN) * 64 * 2;
+    constexpr int lds = NS * (BM + BN) * 32 * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI, NS>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
+    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI, NS>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
 }
 
 template <int BM, int BN>
@@ -343,7 +387,7 @@ static void launch_tiled(hipStream_t st, const GemmArgs &a) {
 
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
     if (a.M <= 0 || a.N <= 0) return;
-    const bool aligned = (a.K % 64 == 0) && a.K >= 64;
+    const bool aligned = (a.K % 32 == 0) && a.K >= 32;
     if (aligned && a.M >= 512 && a.N >= 1024) {
         // the tile grid is a function of the problem shape only
         const long tiles256 = (long)((a.M + 255) / 256) * ((a.epi == EPI_SWIGLU ? 2 * a.N : a.N) / 256);
