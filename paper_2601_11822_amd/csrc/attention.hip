@@ -10,6 +10,7 @@
 #include "kernels.h"
 
 #define NEG_INF (-__builtin_huge_valf())
+#define PREFILL_TAB_LDS 2048   // block ids of a prompt kept in LDS by the prefill kernel (32K tokens)
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -213,181 +214,278 @@ void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
 
 // =============================================================================================
 // Prefill: causal attention of whole prompts, reading the K/V the same layer call has just
-// written to the pools.  Workgroup = (128-query tile of one prompt, query head); wave w owns 32
-// query rows; keys are consumed 64 (= 4 blocks) at a time through LDS.
+// written to the pools.  A workgroup owns one query head and a PAIR of 128-query tiles of one
+// prompt, tile n-1-p then tile p, so that every workgroup does the same amount of causal work.
+// Wave w owns 32 query rows of the tile; keys are consumed 64 (= 4 blocks) at a time through two
+// LDS buffers: the next key tile's global loads are in flight while the current one is multiplied,
+// one barrier per key tile.  The prompt's block ids are copied to LDS once, so a key tile costs one
+// memory round trip (pool) instead of two chained ones (table, then pool).
+// LDS chunk indices are XOR-swizzled for the 64-bank LDS (K rows: chunk ^ row&15 at head_dim 128,
+// chunk ^ (row>>1)&7 at 64; V rows: chunk ^ (d>>1)&7 and the two 8-byte halves of a chunk swapped
+// when d&16).
 // =============================================================================================
 template <int HD>
-__global__ __launch_bounds__(256) void prefill_attn_kernel(PrefillAttnArgs a) {
-    constexpr int CPR = HD / 8;  // 16-byte chunks per K row
-    constexpr int KS = HD / 16;  // 32x32x16 steps over head_dim
-    constexpr int DT = HD / 32;  // 32-row tiles of O^T
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * HD];  // [key][d], chunk ^= key&7
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[HD * 64];  // [d][key], chunk ^= d&7
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a) {
+    constexpr int CPR = HD / 8;   // 16-byte chunks per K row
+    constexpr int KS = HD / 16;   // 32x32x16 steps over head_dim
+    constexpr int DT = HD / 32;   // 32-row tiles of O^T
+    constexpr int NKC = (64 * CPR) / 256, NVC = (HD * 8) / 256;  // chunks per thread per tile
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem_attn[];
+    bf16_t *Ks = smem_attn;                 // [2][64 * HD]
+    bf16_t *Vs = smem_attn + 2 * 64 * HD;   // [2][HD * 64]
+    int32_t *s_tab = (int32_t *)(smem_attn + 4 * 64 * HD);   // [PREFILL_TAB_LDS] block ids of this prompt
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c32 = lane & 31, h = lane >> 5;
 
-    // heaviest (latest) query tiles first
-    int tile = (int)gridDim.x - 1 - (int)blockIdx.x;
-    int req = 0;
+    // (request, pair) of this workgroup
+    int pr = blockIdx.x, req = 0, nt = 0;
     for (;; ++req) {
-        const int nt = (a.seq.cu[req + 1] - a.seq.cu[req] + 127) >> 7;
-        if (tile < nt || req + 1 >= a.seq.n_req) break;
-        tile -= nt;
+        nt = (a.seq.cu[req + 1] - a.seq.cu[req] + 127) >> 7;
+        const int np = (nt + 1) >> 1;
+        if (pr < np || req + 1 >= a.seq.n_req) break;
+        pr -= np;
     }
+    if (pr >= ((nt + 1) >> 1)) return;
     const int row0 = a.seq.cu[req];
     const int len = a.seq.cu[req + 1] - row0;
-    const int q0 = tile * 128;
-    if (q0 >= len) return;
     const int hq = blockIdx.y;
     const int G = a.Hq / a.Hkv;
     const int hk = hq / G;
     const int32_t *tab = a.tables + (size_t)req * a.max_blk;
+    const float sc = a.scale_log2;
+    const int n_blk = (len + 15) >> 4;
+    for (int i = tid; i < min(n_blk, PREFILL_TAB_LDS); i += 256) s_tab[i] = tab[i];
+    auto block_of = [&](int bi) { return bi < PREFILL_TAB_LDS ? s_tab[bi] : tab[bi]; };
 
-    const int q_local = q0 + wave * 32 + c32;
-    const bool q_valid = q_local < len;
-    const int q_pos = q_valid ? q_local : len - 1;
-    bf16x8 qf[KS];
-    {
-        const bf16_t *qp = a.q + (size_t)(row0 + q_pos) * a.q_stride + (size_t)hq * HD + 8 * h;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qf[s] = ld_bf16x8(qp + 16 * s);
-    }
-    const int wave_q_max = min(q0 + wave * 32 + 31, len - 1);
-    const int kv_end = min(q0 + 128, len);
-    const int n_kv_tiles = (kv_end + 63) >> 6;
+    auto kswz = [](int r, int cc) { return HD == 128 ? (cc ^ (r & 15)) : (cc ^ ((r >> 1) & 7)); };
 
-    float m_run = NEG_INF, l_run = 0.f;
-    f32x16 o[DT];
+    bf16x8 rk[NKC], rv[NVC];
+    // this thread's chunks of a key tile: K chunk j = (row (tid+256j)/CPR, 16-byte column kc),
+    // V chunk j = (dim (tid+256j)>>3, block vcc>>1, 8-token half vcc&1)
+    const int kc = tid % CPR, vcc = tid & 7;
+    auto load_regs = [&](int kv0) {
+        if (kv0 + 64 <= len) {   // whole tile inside the prompt (uniform): no per-element checks
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+            for (int j = 0; j < NKC; ++j) {
+                const int r = (tid + 256 * j) / CPR;
+                const int blk = block_of((kv0 + r) >> 4);
+                const bool ok = (unsigned)blk < (unsigned)a.n_blocks;
+                if (!ok && kc == 0 && (r & 15) == 0) atomicOr(a.err_flag, 2);
+                rk[j] = ok ? ld_bf16x8(a.k_pool + (((size_t)blk * a.Hkv + hk) * 16 + (r & 15)) * HD + kc * 8)
+                           : zero_bf16x8();
+            }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-
-    for (int kt = 0; kt < n_kv_tiles; ++kt) {
-        const int kv0 = kt * 64;
-        // ---- stage K tile: 64 rows x HD
+            for (int j = 0; j < NVC; ++j) {
+                const int d = (tid + 256 * j) >> 3;
+                const int blk = block_of((kv0 >> 4) + (vcc >> 1));
+                const bool ok = (unsigned)blk < (unsigned)a.n_blocks;
+                rv[j] = ok ? ld_bf16x8(a.v_pool + (((size_t)blk * a.Hkv + hk) * HD + d) * 16 + (vcc & 1) * 8)
+                           : zero_bf16x8();
+            }
+            return;
+        }
 #pragma unroll
-        for (int j = 0; j < (64 * CPR) / 256; ++j) {
+        for (int j = 0; j < NKC; ++j) {
             const int c = tid + 256 * j;
             const int r = c / CPR, cc = c % CPR;
             const int tok = kv0 + r;
             bf16x8 v = zero_bf16x8();
             if ((tok & ~15) < len) {
-                const int blk = tab[tok >> 4];
+                const int blk = block_of(tok >> 4);
                 if ((unsigned)blk < (unsigned)a.n_blocks)
                     v = ld_bf16x8(a.k_pool + (((size_t)blk * a.Hkv + hk) * 16 + (tok & 15)) * HD + cc * 8);
                 else if (cc == 0 && (tok & 15) == 0)
                     atomicOr(a.err_flag, 2);
             }
-            *(bf16x8 *)&Ks[r * HD + ((cc ^ (r & 7)) << 3)] = v;
+            rk[j] = v;
         }
-        // ---- stage V tile: HD rows x 64 keys (4 blocks x two 8-token halves)
 #pragma unroll
-        for (int j = 0; j < (HD * 8) / 256; ++j) {
+        for (int j = 0; j < NVC; ++j) {
             const int c = tid + 256 * j;
             const int d = c >> 3, cc = c & 7;
             const int tok0 = kv0 + (cc >> 1) * 16 + (cc & 1) * 8;
             bf16x8 v = zero_bf16x8();
             if (tok0 < len) {
-                const int blk = tab[tok0 >> 4];
+                const int blk = block_of(tok0 >> 4);
                 if ((unsigned)blk < (unsigned)a.n_blocks) {
                     v = ld_bf16x8(a.v_pool + (((size_t)blk * a.Hkv + hk) * HD + d) * 16 + (cc & 1) * 8);
-                    if (tok0 + 8 > len) {
+                    if (tok0 + 8 > len) {  // zero V past the prompt: 0 * garbage must not be NaN
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
                             if (tok0 + i >= len) v[i] = (bf16_t)0.f;
                     }
                 }
             }
-            *(bf16x8 *)&Vs[d * 64 + ((cc ^ (d & 7)) << 3)] = v;
+            rv[j] = v;
         }
-        __syncthreads();
-        if (kv0 <= wave_q_max) {
-            f32x16 st[2];
+    };
+    auto store_lds = [&](int buf) {
+        bf16_t *ks = Ks + buf * 64 * HD;
+        bf16_t *vs = Vs + buf * HD * 64;
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) st[t2][i] = 0.f;
-                const int row = 32 * t2 + c32;
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const bf16x8 kf = *(const bf16x8 *)&Ks[row * HD + (((2 * s + h) ^ (row & 7)) << 3)];
-                    st[t2] = mfma32(kf, qf[s], st[t2]);
-                }
-            }
-            float m_tile = NEG_INF;
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int key = kv0 + 32 * t2 + (i >> 2) * 8 + 4 * h + (i & 3);
-                    const float s = (key <= q_pos) ? st[t2][i] * a.scale_log2 : NEG_INF;
-                    st[t2][i] = s;
-                    m_tile = fmaxf(m_tile, s);
-                }
-            m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-            const float m_new = fmaxf(m_run, m_tile);
-            const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
-            const float alpha = exp2f(m_run - m_safe);
-            float psum = 0.f;
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = exp2f(st[t2][i] - m_safe);
-                    st[t2][i] = p;
-                    psum += p;
-                }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * alpha;
-#pragma unroll
-            for (int blk4 = 0; blk4 < 4; ++blk4) {  // one 16-token block per MFMA step
-                bf16x8 pf;
-#pragma unroll
-                for (int t = 0; t < 8; ++t) pf[t] = (bf16_t)st[blk4 >> 1][8 * (blk4 & 1) + t];
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const int d = 32 * dt + c32;
-                    const bf16x4 lo = *(const bf16x4 *)&Vs[d * 64 + (((2 * blk4) ^ (d & 7)) << 3) + 4 * h];
-                    const bf16x4 hi = *(const bf16x4 *)&Vs[d * 64 + (((2 * blk4 + 1) ^ (d & 7)) << 3) + 4 * h];
-                    bf16x8 vf;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        vf[i] = lo[i];
-                        vf[4 + i] = hi[i];
-                    }
-                    o[dt] = mfma32(vf, pf, o[dt]);
-                }
-            }
+        for (int j = 0; j < NKC; ++j) {
+            const int c = tid + 256 * j;
+            const int r = c / CPR, cc = c % CPR;
+            *(bf16x8 *)&ks[r * HD + (kswz(r, cc) << 3)] = rk[j];
         }
-        __syncthreads();
-    }
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (q_valid) {
-        const float inv = 1.0f / l_run;
-        bf16_t *op = a.out + (size_t)(row0 + q_local) * (a.Hq * HD) + (size_t)hq * HD;
+#pragma unroll
+        for (int j = 0; j < NVC; ++j) {
+            const int c = tid + 256 * j;
+            const int d = c >> 3, cc = c & 7;
+            bf16x8 v = rv[j];
+            if (d & 16) {
+                bf16x8 w;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w[i] = v[4 + i];
+                    w[4 + i] = v[i];
+                }
+                v = w;
+            }
+            *(bf16x8 *)&vs[d * 64 + ((cc ^ ((d >> 1) & 7)) << 3)] = v;
+        }
+    };
+
+    for (int which = 0; which < 2; ++which) {
+        const int tile = which == 0 ? nt - 1 - pr : pr;   // the heavier tile first
+        if (which == 1 && tile == nt - 1 - pr) break;
+        const int q0 = tile * 128;
+        const int q_local = q0 + wave * 32 + c32;
+        const bool q_valid = q_local < len;
+        const int q_pos = q_valid ? q_local : len - 1;
+        bf16x8 qf[KS];
+        {
+            const bf16_t *qp = a.q + (size_t)(row0 + q_pos) * a.q_stride + (size_t)hq * HD + 8 * h;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qf[s] = ld_bf16x8(qp + 16 * s);
+        }
+        const int wave_q_min = q0 + wave * 32;
+        const int wave_q_max = min(wave_q_min + 31, len - 1);
+        const int kv_end = min(q0 + 128, len);
+        const int n_kv_tiles = (kv_end + 63) >> 6;
+
+        float m_run = NEG_INF, l_run = 0.f;   // running max of raw scores, running sum
+        f32x16 o[DT];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bf16x4 v;
+            for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+
+        __syncthreads();   // s_tab visible; the previous tile's last reads done before buffer 0 is refilled
+        load_regs(0);
+        store_lds(0);
+        __syncthreads();
+        for (int kt = 0; kt < n_kv_tiles; ++kt) {
+            const int kv0 = kt * 64;
+            const bool more = kt + 1 < n_kv_tiles;
+            if (more) load_regs(kv0 + 64);
+            if (kv0 <= wave_q_max) {
+                const bf16_t *ks = Ks + (kt & 1) * 64 * HD;
+                const bf16_t *vs = Vs + (kt & 1) * HD * 64;
+                f32x16 st[2];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(o[dt][4 * j + i] * inv);
-                *(bf16x4 *)(op + 32 * dt + 8 * j + 4 * h) = v;
+                for (int t2 = 0; t2 < 2; ++t2) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) st[t2][i] = 0.f;
+                    const int row = 32 * t2 + c32;
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) {
+                        const bf16x8 kf = *(const bf16x8 *)&ks[row * HD + (kswz(row, 2 * s + h) << 3)];
+                        st[t2] = mfma32(kf, qf[s], st[t2]);
+                    }
+                }
+                if (kv0 + 63 > wave_q_min) {   // only tiles that touch the diagonal need the mask
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int key = kv0 + 32 * t2 + (i >> 2) * 8 + 4 * h + (i & 3);
+                            if (key > q_pos) st[t2][i] = NEG_INF;
+                        }
+                }
+                float m_tile = NEG_INF;
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m_tile = fmaxf(m_tile, st[t2][i]);
+                m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+                const float m_new = fmaxf(m_run, m_tile);
+                const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+                const float ms = m_safe * sc;
+                float psum = 0.f;
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = __builtin_amdgcn_exp2f(fmaf(st[t2][i], sc, -ms));
+                        st[t2][i] = p;
+                        psum += p;
+                    }
+                if (__any(m_new != m_run)) {   // the maximum rarely moves after the first tiles
+                    const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * sc);
+                    l_run *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * alpha;
+                    m_run = m_new;
+                }
+                l_run += psum;
+#pragma unroll
+                for (int blk4 = 0; blk4 < 4; ++blk4) {  // one 16-token block per MFMA step
+                    bf16x8 pf;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) pf[t] = (bf16_t)st[blk4 >> 1][8 * (blk4 & 1) + t];
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const int d = 32 * dt + c32;
+                        const int hs = (h ^ ((d >> 4) & 1)) << 2;
+                        const int x = (d >> 1) & 7;
+                        const bf16x4 lo = *(const bf16x4 *)&vs[d * 64 + (((2 * blk4) ^ x) << 3) + hs];
+                        const bf16x4 hi = *(const bf16x4 *)&vs[d * 64 + (((2 * blk4 + 1) ^ x) << 3) + hs];
+                        bf16x8 vf;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            vf[i] = lo[i];
+                            vf[4 + i] = hi[i];
+                        }
+                        o[dt] = mfma32(vf, pf, o[dt]);
+                    }
+                }
             }
+            if (more) store_lds((kt + 1) & 1);
+            __syncthreads();
+        }
+        l_run += __shfl_xor(l_run, 32, 64);
+        if (q_valid) {
+            const float inv = 1.0f / l_run;
+            bf16_t *op = a.out + (size_t)(row0 + q_local) * (a.Hq * HD) + (size_t)hq * HD;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(o[dt][4 * j + i] * inv);
+                    *(bf16x4 *)(op + 32 * dt + 8 * j + 4 * h) = v;
+                }
+        }
     }
 }
 
 void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a) {
-    int tiles = 0;
-    for (int r = 0; r < a.seq.n_req; ++r) tiles += (a.seq.cu[r + 1] - a.seq.cu[r] + 127) / 128;
-    if (tiles <= 0) return;
-    dim3 grid(tiles, a.Hq);
-    if (a.hd == 128)
-        hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(256), 0, st, a);
+    int pairs = 0;
+    for (int r = 0; r < a.seq.n_req; ++r) pairs += ((a.seq.cu[r + 1] - a.seq.cu[r] + 127) / 128 + 1) / 2;
+    if (pairs <= 0) return;
+    dim3 grid(pairs, a.Hq);
+    if (a.hd == 128) {
+        constexpr int lds = 4 * 64 * 128 * 2 + PREFILL_TAB_LDS * 4;
+        static bool set = false;
+        if (!set) {
+            (void)hipFuncSetAttribute((const void *)prefill_attn_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+            set = true;
+        }
+        hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(256), lds, st, a);
+    } else {
+        hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(256), 4 * 64 * 64 * 2 + PREFILL_TAB_LDS * 4, st, a);
+    }
 }
