@@ -21,23 +21,31 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // =============================================================================================
 // Decode: one query token per request, keys gathered through the block table.
-// Workgroup = (512-token chunk, kv head, request); its 4 waves take 128 tokens each, two
-// 16-token blocks per iteration.  The G = Hq/Hkv query heads that share the kv head are the
-// (zero padded) 16 columns of the MFMA tiles, so every K/V byte is fetched once per kv head.
+// Workgroup = (512-token chunk, kv head, request); its 4 waves take 128 tokens (8 blocks) each,
+// two blocks per iteration.  The G = Hq/Hkv query heads that share the kv head are the (zero
+// padded) 16 columns of the MFMA tiles, so every K/V byte is fetched once per kv head, straight
+// from the pools into MFMA fragments with 16-byte loads (no LDS staging).
 // The chunking depends on the context length only, never on the launch's CU share.
+//
+// Row permutation: the two 16x16 score tiles of an iteration do not hold "block 0" and "block 1"
+// but, with h = lane>>4, tile A row 4h+i <- token 8(h&1)+i of block h>>1 and tile B row 4h+i <-
+// token 8(h&1)+4+i of block h>>1.  A lane's 4+4 score registers are then 8 consecutive tokens of
+// one block, exactly the contraction slice k' = 8h..8h+7 that lane supplies to the 16x16x32 P V
+// product, and the matching V fragment V[block h>>1][d][8(h&1)..+8] is one 16-byte load.
 // =============================================================================================
 template <int HD>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
     constexpr int KS = HD / 32;  // 16x16x32 steps over head_dim for S^T
     constexpr int DT = HD / 16;  // 16-row tiles of O^T
-    __shared__ float s_o[4][HD][16];
-    __shared__ float s_m[4][16];
-    __shared__ float s_l[4][16];
+    extern __shared__ float smem_dec[];   // [4][HD][G] partial outputs, then [4][G] max, [4][G] sum
 
     const int chunk = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c16 = lane & 15, h = lane >> 4;
     const int G = a.Hq / a.Hkv;
+    float *s_o = smem_dec;
+    float *s_m = smem_dec + 4 * HD * G;
+    float *s_l = s_m + 4 * G;
 
     int n_keys = a.ctx_lens[b] + 1;
     if (n_keys < 1 || n_keys > a.max_ctx) {
@@ -47,6 +55,21 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
     }
     if (chunk * RS_DECODE_CHUNK >= n_keys) return;
 
+    const int t0 = chunk * RS_DECODE_CHUNK + wave * 128;
+    const int t1 = min(t0 + 128, n_keys);
+    // the wave's (up to) 8 block ids, fetched once: lane i holds the id of block i of the range
+    int my_blk = -1;
+    {
+        const int nb = t1 > t0 ? (t1 - t0 + 15) >> 4 : 0;
+        if (lane < nb) {
+            my_blk = a.tables[(size_t)b * a.max_blk + (t0 >> 4) + lane];
+            if ((unsigned)my_blk >= (unsigned)a.n_blocks) {
+                atomicOr(a.err_flag, 2);
+                my_blk = -1;
+            }
+        }
+    }
+
     bf16x8 qf[KS];
     {
         const bf16_t *qp = a.q + (size_t)b * a.q_stride + (size_t)(hk * G + c16) * HD;
@@ -54,116 +77,105 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
         for (int s = 0; s < KS; ++s) qf[s] = (c16 < G) ? ld_bf16x8(qp + 32 * s + 8 * h) : zero_bf16x8();
     }
 
-    const int t0 = chunk * RS_DECODE_CHUNK + wave * 128;
-    const int t1 = min(t0 + 128, n_keys);
-    const int32_t *tab = a.tables + (size_t)b * a.max_blk;
-
     float m_run = NEG_INF, l_run = 0.f;
     f32x4 o[DT];
 #pragma unroll
     for (int i = 0; i < DT; ++i) o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int base = t0; base < t1; base += 32) {
-        const int blk0 = tab[base >> 4];
-        const bool ok0 = (unsigned)blk0 < (unsigned)a.n_blocks;
-        const bool has1 = base + 16 < t1;
-        const int blk1 = has1 ? tab[(base >> 4) + 1] : -1;
-        const bool ok1 = has1 && (unsigned)blk1 < (unsigned)a.n_blocks;
-        if ((!ok0 || (has1 && !ok1)) && lane == 0) atomicOr(a.err_flag, 2);
+    // K operand: MFMA row c16 = 4 hr + ir comes from block (hr>>1), token 8(hr&1)+ir (+4 for tile B)
+    const int hr = c16 >> 2, ir = c16 & 3;
+    const int krow = 8 * (hr & 1) + ir;
 
-        const bf16_t *k0p = a.k_pool + (((size_t)(ok0 ? blk0 : 0) * a.Hkv + hk) * 16 + c16) * HD + 8 * h;
-        const bf16_t *k1p = a.k_pool + (((size_t)(ok1 ? blk1 : 0) * a.Hkv + hk) * 16 + c16) * HD + 8 * h;
-        f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 kA[KS], kB[KS];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int base = t0 + 32 * it;
+        if (base >= t1) break;
+        const int blkK = __shfl(my_blk, 2 * it + (hr >> 1), 64);   // block feeding this lane's K rows
+        const int blkV = __shfl(my_blk, 2 * it + (h >> 1), 64);    // block feeding this lane's V slice
+        const bool okK = blkK >= 0, okV = blkV >= 0;
+        const bf16_t *kp = a.k_pool + (((size_t)(okK ? blkK : 0) * a.Hkv + hk) * 16 + krow) * HD + 8 * h;
+        const bf16_t *vp = a.v_pool + (((size_t)(okV ? blkV : 0) * a.Hkv + hk) * HD + c16) * 16 + 8 * (h & 1);
+        bf16x8 kA[KS], kB[KS], vf[DT];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            kA[s] = ok0 ? ld_bf16x8(k0p + 32 * s) : zero_bf16x8();
-            kB[s] = ok1 ? ld_bf16x8(k1p + 32 * s) : zero_bf16x8();
+            kA[s] = okK ? ld_bf16x8(kp + 32 * s) : zero_bf16x8();
+            kB[s] = okK ? ld_bf16x8(kp + 4 * HD + 32 * s) : zero_bf16x8();
         }
-        // V fragments: rows d = 16*dt + c16, tokens 4h..4h+3 of each block
-        const bf16_t *v0p = a.v_pool + (((size_t)(ok0 ? blk0 : 0) * a.Hkv + hk) * HD + c16) * 16 + 4 * h;
-        const bf16_t *v1p = a.v_pool + (((size_t)(ok1 ? blk1 : 0) * a.Hkv + hk) * HD + c16) * 16 + 4 * h;
-        bf16x4 vA[DT], vB[DT];
-        const bf16x4 z4 = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            vA[dt] = ok0 ? *(const bf16x4 *)(v0p + dt * 256) : z4;
-            vB[dt] = ok1 ? *(const bf16x4 *)(v1p + dt * 256) : z4;
-        }
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = okV ? ld_bf16x8(vp + dt * 256) : zero_bf16x8();
+
+        f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             sA = mfma16(kA[s], qf[s], sA);
             sB = mfma16(kB[s], qf[s], sB);
         }
-        // scale, mask tokens beyond the context (and blocks that were skipped)
+        // this lane's 8 scores are tokens tok0 .. tok0+7 (A: +0..3, B: +4..7)
+        const int tok0 = base + 16 * (h >> 1) + 8 * (h & 1);
         float m_tile = NEG_INF;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int tokA = base + 4 * h + i, tokB = tokA + 16;
-            sA[i] = (ok0 && tokA < n_keys) ? sA[i] * a.scale_log2 : NEG_INF;
-            sB[i] = (ok1 && tokB < n_keys) ? sB[i] * a.scale_log2 : NEG_INF;
+            sA[i] = (okV && tok0 + i < n_keys) ? sA[i] * a.scale_log2 : NEG_INF;
+            sB[i] = (okV && tok0 + 4 + i < n_keys) ? sB[i] * a.scale_log2 : NEG_INF;
             m_tile = fmaxf(m_tile, fmaxf(sA[i], sB[i]));
         }
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, 64));
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
         const float m_new = fmaxf(m_run, m_tile);
         const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_safe);
         bf16x8 pf;
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float pa = exp2f(sA[i] - m_safe), pb = exp2f(sB[i] - m_safe);
+            const float pa = __builtin_amdgcn_exp2f(sA[i] - m_safe), pb = __builtin_amdgcn_exp2f(sB[i] - m_safe);
             psum += pa + pb;
             pf[i] = (bf16_t)pa;
             pf[4 + i] = (bf16_t)pb;
         }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        // zero V of tokens past the context so that 0 * garbage cannot produce NaN
-        const bool partial = base + 32 > n_keys;
+        if (__any(m_new != m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+            l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            bf16x8 vf;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                vf[i] = vA[dt][i];
-                vf[4 + i] = vB[dt][i];
-            }
-            if (partial) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (base + 4 * h + i >= n_keys) vf[i] = (bf16_t)0.f;
-                    if (base + 16 + 4 * h + i >= n_keys) vf[4 + i] = (bf16_t)0.f;
-                }
-            }
-            o[dt] = o[dt] * alpha;
-            o[dt] = mfma16(vf, pf, o[dt]);
+            for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * alpha;
+            m_run = m_new;
         }
+        l_run += psum;
+        // zero V of tokens past the context so that 0 * garbage cannot produce NaN
+        if (base + 32 > n_keys) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (tok0 + i >= n_keys) vf[dt][i] = (bf16_t)0.f;
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt] = mfma16(vf[dt], pf, o[dt]);
     }
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
 
     // combine the 4 waves (fixed order) and emit the chunk's partial result
+    if (c16 < G) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s_o[wave][16 * dt + 4 * h + i][c16] = o[dt][i];
-    if (h == 0) {
-        s_m[wave][c16] = m_run;
-        s_l[wave][c16] = l_run;
+            for (int i = 0; i < 4; ++i) s_o[(wave * HD + 16 * dt + 4 * h + i) * G + c16] = o[dt][i];
+        if (h == 0) {
+            s_m[wave * G + c16] = m_run;
+            s_l[wave * G + c16] = l_run;
+        }
     }
     __syncthreads();
     for (int idx = tid; idx < G * HD; idx += 256) {
         const int gg = idx / HD, d = idx % HD;
-        float mx = fmaxf(fmaxf(s_m[0][gg], s_m[1][gg]), fmaxf(s_m[2][gg], s_m[3][gg]));
+        const float mx = fmaxf(fmaxf(s_m[gg], s_m[G + gg]), fmaxf(s_m[2 * G + gg], s_m[3 * G + gg]));
         const float ms = (mx == NEG_INF) ? 0.f : mx;
         float acc = 0.f, l = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float e = exp2f(s_m[w][gg] - ms);
-            acc += s_o[w][d][gg] * e;
-            l += s_l[w][gg] * e;
+            const float e = __builtin_amdgcn_exp2f(s_m[w * G + gg] - ms);
+            acc += s_o[(w * HD + d) * G + gg] * e;
+            l += s_l[w * G + gg] * e;
         }
         const size_t pi = ((size_t)b * a.Hq + hk * G + gg) * a.n_chunks + chunk;
         a.part_o[pi * HD + d] = acc;
@@ -179,7 +191,9 @@ template <int HD>
 __global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
     const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     int n_keys = a.ctx_lens[b] + 1;
-    bf16_t *op = a.out + (size_t)b * a.Hq * HD + (size_t)hq * HD + d;
+    const int col = hq * HD + d;
+    bf16_t *op = a.out_packed ? a.out + packed_chunk_offset(b, col) + (col & 7)
+                              : a.out + (size_t)b * a.Hq * HD + col;
     if (n_keys < 1) {
         *op = (bf16_t)0.f;
         return;
@@ -203,11 +217,13 @@ void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
     if (a.B <= 0) return;
     dim3 grid(a.n_chunks, a.Hkv, a.B);
     dim3 cgrid(a.Hq, a.B);
+    const int G = a.Hq / a.Hkv;
+    const size_t lds = (size_t)(4 * a.hd * G + 8 * G) * sizeof(float);   // <= 33 KB at G = 16
     if (a.hd == 128) {
-        hipLaunchKernelGGL(decode_attn_kernel<128>, grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL(decode_attn_kernel<128>, grid, dim3(256), lds, st, a);
         hipLaunchKernelGGL(decode_combine_kernel<128>, cgrid, dim3(128), 0, st, a);
     } else {
-        hipLaunchKernelGGL(decode_attn_kernel<64>, grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL(decode_attn_kernel<64>, grid, dim3(256), lds, st, a);
         hipLaunchKernelGGL(decode_combine_kernel<64>, cgrid, dim3(64), 0, st, a);
     }
 }

@@ -37,3 +37,12 @@ __device__ __forceinline__ float wave_sum(float v) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
+
+// Fragment-packed layout of a skinny activation matrix X[M <= 64][K] (decode side only): the
+// 16 bytes that lane (h*32 + r) of a 32x32x16 MFMA column operand needs for rows 32*tm + r and
+// k in [16*kb + 8*h, +8) are stored contiguously in lane order, so that a wave-wide fragment
+// load is one contiguous 1 KB read.  Element offset of the 8-element chunk holding (m, k):
+__host__ __device__ __forceinline__ size_t packed_chunk_offset(int m, int k) {
+    const int kb = k >> 4, hh = (k >> 3) & 1, tm = m >> 5, r = m & 31;
+    return ((size_t)(kb * 2 + tm) * 64 + hh * 32 + r) * 8;
+}

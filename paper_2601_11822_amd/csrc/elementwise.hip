@@ -6,7 +6,7 @@
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__ x,
                                                       const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ out, int d, float eps) {
+                                                      bf16_t *__restrict__ out, int d, float eps, int packed) {
     __shared__ float red[4];
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
@@ -33,14 +33,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__
         bf16x8 o;
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i] = (bf16_t)((float)v[i] * inv * (float)gv[i]);
-        st_bf16x8(orow + c * 8, o);
+        st_bf16x8(packed ? out + packed_chunk_offset(row, c * 8) : orow + c * 8, o);
     }
 }
 
 void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
-                    float eps) {
+                    float eps, bool packed) {
     if (M <= 0) return;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, st, x, g, out, d, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, st, x, g, out, d, eps, packed ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -429,31 +429,55 @@ size_t skinny_partial_elems(int M, int N, int K, int epi) {
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
                                                           int k_per_wg, int Nv) {
-    __shared__ float red[4][4][64][16];
+    // 64 KB: per wave two 8 KB weight slabs [64 rows][64 k] (rows of 128 B, chunk ^= (row>>1)&7);
+    // after the K loop the same bytes hold the waves' accumulators for the in-order reduction
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_sk[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c32 = lane & 31, h = lane >> 5;
     const int M = a.M, N = a.N, K = a.K;
     const int kw = k_per_wg >> 2;
     const int kb = blockIdx.y * k_per_wg + wave * kw;
     const int ke = min(kb + kw, K);
+    const int nsteps = ke > kb ? (ke - kb + 63) >> 6 : 0;
+    bf16_t *slab = (bf16_t *)(smem_sk + wave * 16384);
 
-    const bf16_t *wp[2];
-    const bf16_t *xp[2];
+    // weight rows fetched by this lane in each of the 8 wave-wide DMA loads of a slab
+    const bf16_t *wrow[8];
+    int wchunk[8];
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
+    for (int g = 0; g < 8; ++g) {
+        const int row = 8 * g + (lane >> 3);
+        wchunk[g] = ((lane & 7) ^ ((row >> 1) & 7)) << 3;   // k offset of the chunk this lane stores
         if (EPI == EPI_SWIGLU) {
-            const int f = blockIdx.x * 32 + c32;
-            wp[tn] = (f < N) ? (tn ? a.W2 : a.W) + (size_t)f * K + 32 * h : nullptr;
+            const int f = min((int)blockIdx.x * 32 + (row & 31), N - 1);
+            wrow[g] = ((row >> 5) ? a.W2 : a.W) + (size_t)f * K;
         } else {
-            const int n = blockIdx.x * 64 + 32 * tn + c32;
-            wp[tn] = (n < N) ? a.W + (size_t)n * K + 32 * h : nullptr;
+            wrow[g] = a.W + (size_t)min((int)blockIdx.x * 64 + row, N - 1) * K;
         }
     }
+    auto issue_w = [&](int k0, int stage) {
 #pragma unroll
-    for (int tm = 0; tm < 2; ++tm) {
-        const int m = 32 * tm + c32;
-        xp[tm] = (m < M) ? a.A + (size_t)m * K + 32 * h : nullptr;
-    }
+        for (int g = 0; g < 8; ++g) {
+            // a chunk past K is replaced by the window's first chunk (finite data; X is zero there)
+            const int ko = (k0 + wchunk[g] < K) ? wchunk[g] : 0;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wrow[g] + k0 + ko),
+                                             (__attribute__((address_space(3))) void *)(slab + stage * 4096 + g * 512),
+                                             16, 0, 0);
+        }
+    };
+    // activation fragments straight from the fragment-packed matrix: contiguous 1 KB per load
+    auto load_x = [&](int k0, bf16x8 (&xf)[2][4]) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int kb16 = (k0 >> 4) + s;
+            const bool kin = 16 * kb16 + 8 * h < K;
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+                xf[tm][s] = (kin && 32 * tm + c32 < M) ? ld_bf16x8(a.A + ((size_t)(kb16 * 2 + tm) * 64 + lane) * 8)
+                                                       : zero_bf16x8();
+        }
+    };
+
     f32x16 acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -462,30 +486,52 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__r
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    for (int k0 = kb; k0 < ke; k0 += 64) {
-        bf16x8 wf[2][4], xf[2][4];
+    bf16x8 xcur[2][4], xnext[2][4];
+    if (nsteps > 0) {
+        issue_w(kb, 0);
+        load_x(kb, xcur);
+    }
+    const int x7 = (c32 >> 1) & 7;
+    for (int i = 0; i < nsteps; ++i) {
+        const bool more = i + 1 < nsteps;
+        if (more) {
+            issue_w(kb + 64 * (i + 1), (i + 1) & 1);
+            load_x(kb + 64 * (i + 1), xnext);
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // slab i landed; 8 + 8 younger loads may fly
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        const bf16_t *sl = slab + (i & 1) * 4096;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const bool kin = k0 + 32 * h + 8 * s < K;
+            bf16x8 wf[2];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                wf[t][s] = (kin && wp[t]) ? ld_bf16x8(wp[t] + k0 + 8 * s) : zero_bf16x8();
-                xf[t][s] = (kin && xp[t]) ? ld_bf16x8(xp[t] + k0 + 8 * s) : zero_bf16x8();
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
+            for (int tn = 0; tn < 2; ++tn)
+                wf[tn] = *(const bf16x8 *)&sl[(32 * tn + c32) * 64 + (((2 * s + h) ^ x7) << 3)];
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-                for (int tm = 0; tm < 2; ++tm) acc[tn][tm] = mfma32(wf[tn][s], xf[tm][s], acc[tn][tm]);
+                for (int tm = 0; tm < 2; ++tm) acc[tn][tm] = mfma32(wf[tn], xcur[tm][s], acc[tn][tm]);
+        }
+        if (more) {
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) xcur[tm][s] = xnext[tm][s];
+        }
     }
+    // in-order reduction of the 4 waves; each wave first overwrites only its own slab bytes
+    float *red = (float *)smem_sk;   // [wave][tile][lane][16]
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
         for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) red[wave][tn * 2 + tm][lane][e] = acc[tn][tm][e];
+            for (int j = 0; j < 4; ++j) {
+                f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
+                *(f32x4 *)&red[((wave * 4 + tn * 2 + tm) * 64 + lane) * 16 + 4 * j] = v;
+            }
     __syncthreads();
     // wave w finishes tile (tn, tm) = (w>>1, w&1): sum of the 4 waves in wave order
     const int tn = wave >> 1, tm = wave & 1;
@@ -494,13 +540,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__r
         float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * 64 + 32 * tn;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            f32x4 v;
+            f32x4 v = *(const f32x4 *)&red[((0 * 4 + wave) * 64 + lane) * 16 + 4 * j];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int e = 4 * j + i;
-                v[i] = ((red[0][wave][lane][e] + red[1][wave][lane][e]) + red[2][wave][lane][e]) +
-                       red[3][wave][lane][e];
-            }
+            for (int w = 1; w < 4; ++w) v += *(const f32x4 *)&red[((w * 4 + wave) * 64 + lane) * 16 + 4 * j];
             *(f32x4 *)(dst + 8 * j + 4 * h) = v;
         }
     }
@@ -538,7 +580,8 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
             for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[i];
         }
     }
-    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+    bf16_t *dst = a.out_packed ? a.out + packed_chunk_offset(m, n) + (n & 7) : a.out + (size_t)m * N + n;
+    *(bf16x4 *)dst = v;
 }
 
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
@@ -550,15 +593,15 @@ void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
     const int eblocks = (a.M * (a.N / 4) + 255) / 256;
     switch (a.epi) {
         case EPI_STORE:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_STORE>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_STORE>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
             hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_STORE>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
             break;
         case EPI_RESIDUAL:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_RESIDUAL>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_RESIDUAL>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
             hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_RESIDUAL>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
             break;
         default:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_SWIGLU>, grid, dim3(256), 0, st, a, partials, kpw, Nv);
+            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_SWIGLU>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
             hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_SWIGLU>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
             break;
     }

@@ -6,8 +6,9 @@
 #include "common.h"
 
 // out[m,:] = x[m,:] * rsqrt(mean(x[m,:]^2) + eps) * g      (bf16 in, fp32 math, bf16 out)
+// packed: write `out` in the fragment-packed layout (see packed_chunk_offset; M <= 64 only).
 void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
-                    float eps);
+                    float eps, bool packed = false);
 
 struct RopeKvArgs {
     bf16_t *qkv;            // [M][nqkv]; q part rotated in place
@@ -47,6 +48,7 @@ struct DecodeAttnArgs {
     float *part_ml;  // [B][Hq][n_chunks][2]
     int B, Hq, Hkv, hd, max_blk, n_blocks, max_ctx, n_chunks;
     float scale_log2;
+    int out_packed;  // write `out` fragment-packed (B <= 64)
 };
 #define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention
 void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a);
@@ -63,11 +65,12 @@ struct GemmArgs {
     bf16_t *out;
     int M, N, K;
     int epi;
+    int out_packed = 0;  // skinny path only: write `out` fragment-packed (it feeds another skinny GEMM)
 };
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 
 // Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through
-// `partials` (fp32, at least skinny_partial_elems(...) elements).
+// `partials` (fp32, at least skinny_partial_elems(...) elements).  A must be fragment-packed.
 size_t skinny_partial_elems(int M, int N, int K, int epi);
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
 

@@ -77,6 +77,7 @@ struct rs_ctx {
     CosSin *rope = nullptr;
     int32_t *err_flag = nullptr;
     Workspace ws[2];
+    bool decode_packed = false;  // the decode side's last layer call left h/attn/act fragment-packed
     Side side[2];
     bool over_alloc = true;
     bool kernel_timing = false;
@@ -135,11 +136,14 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     const size_t nqkv = qd + 2 * (size_t)m.n_kv_heads * m.head_dim, f = m.ffn_dim;
     w.rows = rows;
     if (rows <= 0) return RS_OK;
-    HIP_TRY(hipMalloc(&w.h, rows * d * 2));
+    // the decode side keeps its GEMM inputs fragment-packed: always 64 rows x (width rounded to 16)
+    const size_t prow = decode ? std::max<size_t>(rows, 64) : rows;
+    auto r16 = [&](size_t v) { return decode ? (v + 15) / 16 * 16 : v; };
+    HIP_TRY(hipMalloc(&w.h, prow * r16(d) * 2));
     HIP_TRY(hipMalloc(&w.qkv, rows * nqkv * 2));
-    HIP_TRY(hipMalloc(&w.attn, rows * qd * 2));
+    HIP_TRY(hipMalloc(&w.attn, prow * r16(qd) * 2));
     HIP_TRY(hipMalloc(&w.x1, rows * d * 2));
-    HIP_TRY(hipMalloc(&w.act, rows * f * 2));
+    HIP_TRY(hipMalloc(&w.act, prow * r16(f) * 2));
     HIP_TRY(hipMalloc(&w.xbuf, rows * d * 2));
     if (decode) {
         const int Mmax = std::min(rows, 64);
@@ -262,11 +266,12 @@ void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
         if (skinny) launch_gemm_skinny(st, g, w.partials);
         else launch_gemm_tiled(st, g);
     };
+    // on the skinny (decode) path every GEMM input is kept fragment-packed by its producer
     gemm(GemmArgs{w.attn, (const bf16_t *)lw.wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
     tick(c, side, 5);
-    launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps);
+    launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps, skinny);
     tick(c, side, 6);
-    gemm(GemmArgs{w.h, (const bf16_t *)lw.wg, (const bf16_t *)lw.wu, nullptr, w.act, M, f, d, EPI_SWIGLU});
+    gemm(GemmArgs{w.h, (const bf16_t *)lw.wg, (const bf16_t *)lw.wu, nullptr, w.act, M, f, d, EPI_SWIGLU, skinny ? 1 : 0});
     tick(c, side, 7);
     gemm(GemmArgs{w.act, (const bf16_t *)lw.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
     tick(c, side, 8);
@@ -331,9 +336,10 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
     const bool skinny = B <= 64;
+    c->decode_packed = skinny;
 
     tick(c, RS_SIDE_DECODE, 0);
-    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
+    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps, skinny);
     tick(c, RS_SIDE_DECODE, 1);
     GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE};
     if (skinny) launch_gemm_skinny(st, g, w.partials);
@@ -347,7 +353,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
                       B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
                       (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
-                      (float)(1.4426950408889634 / std::sqrt((double)hd))};
+                      (float)(1.4426950408889634 / std::sqrt((double)hd)), skinny ? 1 : 0};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
     run_post_attention(c, RS_SIDE_DECODE, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
@@ -640,7 +646,7 @@ int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *ho
     const void *src = nullptr;
     size_t cap = 0;
     switch (which) {
-        case 0: src = w.h; cap = (size_t)w.rows * m.d_model * 2; break;
+        case 0: src = w.h; cap = (size_t)w.rows * m.d_model * 2; break;  // (decode buffers are at least 64 rows)
         case 1: src = w.qkv; cap = (size_t)w.rows * nqkv * 2; break;
         case 2: src = w.attn; cap = (size_t)w.rows * qd * 2; break;
         case 3: src = w.x1; cap = (size_t)w.rows * m.d_model * 2; break;
@@ -649,6 +655,18 @@ int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *ho
     }
     if (!src || (size_t)n_bytes > cap) return fail(RS_ERR_BAD_ARG, "workspace buffer %d holds %zu bytes", which, cap);
     if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
+    if (side == RS_SIDE_DECODE && c->decode_packed && (which == 0 || which == 2 || which == 4)) {
+        // undo the fragment-packed layout of the decode side's GEMM inputs: row-major out
+        const int width = which == 0 ? m.d_model : which == 2 ? (int)qd : m.ffn_dim;
+        const int rows = (int)((size_t)n_bytes / 2 / width);
+        if (rows > 64) return fail(RS_ERR_BAD_ARG, "packed buffers hold at most 64 rows");
+        std::vector<uint16_t> raw((size_t)64 * width);
+        HIP_TRY(hipMemcpy(raw.data(), src, raw.size() * 2, hipMemcpyDeviceToHost));
+        uint16_t *dst = (uint16_t *)host_out;
+        for (int r = 0; r < rows; ++r)
+            for (int k = 0; k < width; ++k) dst[(size_t)r * width + k] = raw[packed_chunk_offset(r, k) + (k & 7)];
+        return RS_OK;
+    }
     HIP_TRY(hipMemcpy(host_out, src, (size_t)n_bytes, hipMemcpyDeviceToHost));
     return RS_OK;
 }
