@@ -24,9 +24,12 @@
  *   - All matrices are bf16, row major.  Projection weights are [out_features,
  *     in_features].  Accumulation is fp32.  Indices are int32.
  *   - KV pools (bf16), block = 16 tokens:
- *         K pool: [n_layers][n_blocks][n_kv_heads][16][head_dim]
+ *         K pool: [n_layers][n_blocks][n_kv_heads][head_dim/32][4][16][8]
  *         V pool: [n_layers][n_blocks][n_kv_heads][head_dim][16]   (token-minor)
- *     K is stored after the rotary embedding.
+ *     K is stored after the rotary embedding.  Inside one (block, kv head) of the K pool the
+ *     element of token slot t and dim d sits at (((d/32)*4 + (d/8)%4)*16 + p(t))*8 + d%8 with
+ *     p(t) = t with bits 2 and 3 swapped (slot order 0-3, 8-11, 4-7, 12-15): every MFMA fragment
+ *     load of the attention kernels is then one contiguous run of whole 128-byte lines.
  *   - A context created with device = RS_HOST_ONLY touches no GPU: the allocator,
  *     the manager and the request state machine work, layer calls fail with RS_ERR_STATE.
  */
@@ -209,6 +212,12 @@ int32_t rs_kernel_times(rs_ctx *ctx, int32_t side, float ms_out[RS_N_KERNEL_SLOT
  * registers.  Blocks until done.  Used to check that a CU mask confines work (section 4.2). */
 #define RS_CU_HIST_BINS 4096
 int32_t rs_debug_cu_histogram(rs_ctx *ctx, int32_t side, int32_t n_workgroups, int32_t *hist_out);
+
+/* Streaming-read probe: reads n_bytes (multiple of 16, >= 32 KiB) of device memory once with
+ * coalesced 16-byte loads on the side's stream, i.e. on the side's CU partition, and gives the
+ * GPU time.  n_bytes / time is the read bandwidth that partition can pull (section 3.3's
+ * question, asked of this GPU).  Blocks until done. */
+int32_t rs_debug_stream_read(rs_ctx *ctx, int32_t side, const void *buf, int64_t n_bytes, float *ms_out);
 
 /* Copies an intermediate activation buffer of a side's last layer call to host memory (after
  * waiting for that side): which = 0 first RMSNorm output [M,d]; 1 q|k|v with rotated q and k

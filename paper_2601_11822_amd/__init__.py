@@ -30,7 +30,7 @@ EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_set_cu_split", "rs_get_cu_split",
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_elapsed_ms", "rs_set_kernel_timing", "rs_kernel_times",
-    "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
+    "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
 ]
 
 
@@ -234,6 +234,13 @@ class Context:
         _check(self._lib.rs_debug_cu_histogram(self._h, ctypes.c_int32(side), ctypes.c_int32(n_workgroups),
                                                h.ctypes.data_as(_i32p)))
         return h
+
+    def debug_stream_read(self, side: int, buf, n_bytes: int) -> float:
+        """GPU milliseconds to read n_bytes of `buf` once on the side's CU partition."""
+        ms = ctypes.c_float(0)
+        _check(self._lib.rs_debug_stream_read(self._h, ctypes.c_int32(side), _ptr(buf), ctypes.c_int64(n_bytes),
+                                              ctypes.byref(ms)))
+        return ms.value
 
     def debug_read_workspace(self, side: int, which: int, shape) -> np.ndarray:
         """bf16 bit patterns (uint16) of an intermediate buffer, shaped `shape`."""

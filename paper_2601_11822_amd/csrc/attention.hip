@@ -1,9 +1,9 @@
 // Attention kernels over the paged KV cache (gfx950, bf16 MFMA, fp32 softmax).
 //
-// Pool layouts (one layer):  K [n_blocks][Hkv][16][hd]   V [n_blocks][Hkv][hd][16]
-// so one (block, kv head) is a contiguous 16*hd*2-byte run in each pool, K rows feed the MFMA
-// "row x k" operand directly and V, being token-minor, feeds the operand whose contraction
-// index is the token without any transpose.
+// Pool layouts (one layer):  K [n_blocks][Hkv][hd/32][4][16][8] (see kpool_chunk_offset)
+// V [n_blocks][Hkv][hd][16], so one (block, kv head) is a contiguous 16*hd*2-byte run in each
+// pool, a K fragment of the MFMA "row x k" operand is one contiguous 1 KB, and V, being token-
+// minor, feeds the operand whose contraction index is the token without any transpose.
 //
 // Both kernels evaluate S^T = K Q^T and O^T = V^T P^T, so that a lane owns one query column:
 // the running maximum and sum of the online softmax are per-lane scalars.
@@ -21,7 +21,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // =============================================================================================
 // Decode: one query token per request, keys gathered through the block table.
-// Workgroup = (512-token chunk, kv head, request); its 4 waves take 128 tokens (8 blocks) each,
+// Workgroup = (1024-token chunk, kv head, request); its 4 waves take 256 tokens (16 blocks) each,
 // two blocks per iteration.  The G = Hq/Hkv query heads that share the kv head are the (zero
 // padded) 16 columns of the MFMA tiles, so every K/V byte is fetched once per kv head, straight
 // from the pools into MFMA fragments with 16-byte loads (no LDS staging).
@@ -39,7 +39,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
     constexpr int DT = HD / 16;  // 16-row tiles of O^T
     extern __shared__ float smem_dec[];   // [4][HD][G] partial outputs, then [4][G] max, [4][G] sum
 
-    const int chunk = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    // kv head fastest: consecutive workgroup ids are dealt to the 8 XCDs in turn, and every kv head
+    // carries the same work, whereas chunk c only exists for contexts longer than c chunks
+    const int hk = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c16 = lane & 15, h = lane >> 4;
     const int G = a.Hq / a.Hkv;
@@ -55,9 +57,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
     }
     if (chunk * RS_DECODE_CHUNK >= n_keys) return;
 
-    const int t0 = chunk * RS_DECODE_CHUNK + wave * 128;
-    const int t1 = min(t0 + 128, n_keys);
-    // the wave's (up to) 8 block ids, fetched once: lane i holds the id of block i of the range
+    constexpr int WT = RS_DECODE_CHUNK / 4;   // tokens per wave
+    const int t0 = chunk * RS_DECODE_CHUNK + wave * WT;
+    const int t1 = min(t0 + WT, n_keys);
+    // the wave's (up to) WT/16 block ids, fetched once: lane i holds the id of block i of the range
     int my_blk = -1;
     {
         const int nb = t1 > t0 ? (t1 - t0 + 15) >> 4 : 0;
@@ -82,27 +85,38 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
 #pragma unroll
     for (int i = 0; i < DT; ++i) o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // K operand: MFMA row c16 = 4 hr + ir comes from block (hr>>1), token 8(hr&1)+ir (+4 for tile B)
-    const int hr = c16 >> 2, ir = c16 & 3;
-    const int krow = 8 * (hr & 1) + ir;
+    // K operand: MFMA row c16 = 4 hr + ir comes from block (hr>>1), token 8(hr&1)+ir (+4 for tile
+    // B): in the pool's permuted row order these are rows c16&7 (tile A) and 8 + (c16&7) (tile B)
+    const bool k_second = (c16 >> 3) != 0;   // this lane's K rows come from the iteration's second block
+    const bool v_second = (h >> 1) != 0;     // this lane's V slice comes from the second block
+    const size_t k_lane = (size_t)(h * 16 + (c16 & 7)) * 8;
+    const size_t v_lane = (size_t)c16 * 16 + 8 * (h & 1);
+    const size_t blk_stride = (size_t)a.Hkv * 16 * HD;
+    const bf16_t *k_head = a.k_pool + (size_t)hk * 16 * HD;
+    const bf16_t *v_head = a.v_pool + (size_t)hk * 16 * HD;
+    const float sc = a.scale_log2;
 
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < WT / 32; ++it) {
         const int base = t0 + 32 * it;
         if (base >= t1) break;
-        const int blkK = __shfl(my_blk, 2 * it + (hr >> 1), 64);   // block feeding this lane's K rows
-        const int blkV = __shfl(my_blk, 2 * it + (h >> 1), 64);    // block feeding this lane's V slice
-        const bool okK = blkK >= 0, okV = blkV >= 0;
-        const bf16_t *kp = a.k_pool + (((size_t)(okK ? blkK : 0) * a.Hkv + hk) * 16 + krow) * HD + 8 * h;
-        const bf16_t *vp = a.v_pool + (((size_t)(okV ? blkV : 0) * a.Hkv + hk) * HD + c16) * 16 + 8 * (h & 1);
+        // the iteration's two block ids as wave-uniform scalars
+        const int b0 = __builtin_amdgcn_readlane(my_blk, 2 * it);
+        const int b1 = __builtin_amdgcn_readlane(my_blk, 2 * it + 1);
+        const bool full = base + 32 <= n_keys && b0 >= 0 && b1 >= 0;   // uniform: every token valid
+        // blocks that are missing (past the context, or rejected) read block 0: valid memory whose
+        // contents are masked out below
+        const size_t o0 = (size_t)max(b0, 0) * blk_stride, o1 = (size_t)max(b1, 0) * blk_stride;
+        const bf16_t *kp = k_head + (k_second ? o1 : o0) + k_lane;
+        const bf16_t *vp = v_head + (v_second ? o1 : o0) + v_lane;
         bf16x8 kA[KS], kB[KS], vf[DT];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            kA[s] = okK ? ld_bf16x8(kp + 32 * s) : zero_bf16x8();
-            kB[s] = okK ? ld_bf16x8(kp + 4 * HD + 32 * s) : zero_bf16x8();
+            kA[s] = ld_bf16x8(kp + 512 * s);
+            kB[s] = ld_bf16x8(kp + 512 * s + 64);
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = okV ? ld_bf16x8(vp + dt * 256) : zero_bf16x8();
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = ld_bf16x8(vp + dt * 256);
 
         f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -110,44 +124,51 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
             sA = mfma16(kA[s], qf[s], sA);
             sB = mfma16(kB[s], qf[s], sB);
         }
-        // this lane's 8 scores are tokens tok0 .. tok0+7 (A: +0..3, B: +4..7)
-        const int tok0 = base + 16 * (h >> 1) + 8 * (h & 1);
-        float m_tile = NEG_INF;
+        // this lane's 8 scores are tokens tok0 .. tok0+7 (A: +0..3, B: +4..7) of its V block
+        if (!full) {
+            const int tok0 = base + 16 * (h >> 1) + 8 * (h & 1);
+            const int nv = ((v_second ? b1 : b0) >= 0) ? min(max(n_keys - tok0, 0), 8) : 0;   // valid tokens
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sA[i] = (okV && tok0 + i < n_keys) ? sA[i] * a.scale_log2 : NEG_INF;
-            sB[i] = (okV && tok0 + 4 + i < n_keys) ? sB[i] * a.scale_log2 : NEG_INF;
-            m_tile = fmaxf(m_tile, fmaxf(sA[i], sB[i]));
+            for (int i = 0; i < 4; ++i) {
+                if (i >= nv) sA[i] = NEG_INF;
+                if (4 + i >= nv) sB[i] = NEG_INF;
+            }
+            // zero V of invalid tokens so that 0 * garbage cannot produce NaN: dword j holds tokens 2j, 2j+1
+            uint32_t msk[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) msk[j] = nv >= 2 * j + 2 ? 0xffffffffu : (nv == 2 * j + 1 ? 0x0000ffffu : 0u);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+                u32x4v raw = __builtin_bit_cast(u32x4v, vf[dt]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) raw[j] &= msk[j];
+                vf[dt] = __builtin_bit_cast(bf16x8, raw);
+            }
         }
+        float m_tile = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3])));
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 16, 64));
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-        const float m_new = fmaxf(m_run, m_tile);
+        const float m_new = fmaxf(m_run, m_tile);            // running maximum of RAW scores
         const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+        const float ms = m_safe * sc;
         bf16x8 pf;
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float pa = __builtin_amdgcn_exp2f(sA[i] - m_safe), pb = __builtin_amdgcn_exp2f(sB[i] - m_safe);
+            const float pa = __builtin_amdgcn_exp2f(fmaf(sA[i], sc, -ms)), pb = __builtin_amdgcn_exp2f(fmaf(sB[i], sc, -ms));
             psum += pa + pb;
             pf[i] = (bf16_t)pa;
             pf[4 + i] = (bf16_t)pb;
         }
         if (__any(m_new != m_run)) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * sc);
             l_run *= alpha;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * alpha;
             m_run = m_new;
         }
         l_run += psum;
-        // zero V of tokens past the context so that 0 * garbage cannot produce NaN
-        if (base + 32 > n_keys) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (tok0 + i >= n_keys) vf[dt][i] = (bf16_t)0.f;
-        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[dt] = mfma16(vf[dt], pf, o[dt]);
     }
@@ -173,7 +194,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
         float acc = 0.f, l = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float e = __builtin_amdgcn_exp2f(s_m[w * G + gg] - ms);
+            const float e = __builtin_amdgcn_exp2f((s_m[w * G + gg] - ms) * a.scale_log2);
             acc += s_o[(w * HD + d) * G + gg] * e;
             l += s_l[w * G + gg] * e;
         }
@@ -206,7 +227,7 @@ __global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
     const float ms = (mx == NEG_INF) ? 0.f : mx;
     float acc = 0.f, l = 0.f;
     for (int c = 0; c < nch; ++c) {
-        const float e = exp2f(a.part_ml[(p0 + c) * 2] - ms);
+        const float e = exp2f((a.part_ml[(p0 + c) * 2] - ms) * a.scale_log2);   // maxima are raw scores
         acc += a.part_o[(p0 + c) * HD + d] * e;
         l += a.part_ml[(p0 + c) * 2 + 1] * e;
     }
@@ -215,7 +236,7 @@ __global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
 
 void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
     if (a.B <= 0) return;
-    dim3 grid(a.n_chunks, a.Hkv, a.B);
+    dim3 grid(a.Hkv, a.n_chunks, a.B);
     dim3 cgrid(a.Hq, a.B);
     const int G = a.Hq / a.Hkv;
     const size_t lds = (size_t)(4 * a.hd * G + 8 * G) * sizeof(float);   // <= 33 KB at G = 16
@@ -288,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                 const int blk = block_of((kv0 + r) >> 4);
                 const bool ok = (unsigned)blk < (unsigned)a.n_blocks;
                 if (!ok && kc == 0 && (r & 15) == 0) atomicOr(a.err_flag, 2);
-                rk[j] = ok ? ld_bf16x8(a.k_pool + (((size_t)blk * a.Hkv + hk) * 16 + (r & 15)) * HD + kc * 8)
+                rk[j] = ok ? ld_bf16x8(a.k_pool + ((size_t)blk * a.Hkv + hk) * 16 * HD + kpool_chunk_offset(r & 15, kc * 8))
                            : zero_bf16x8();
             }
 #pragma unroll
@@ -310,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
             if ((tok & ~15) < len) {
                 const int blk = block_of(tok >> 4);
                 if ((unsigned)blk < (unsigned)a.n_blocks)
-                    v = ld_bf16x8(a.k_pool + (((size_t)blk * a.Hkv + hk) * 16 + (tok & 15)) * HD + cc * 8);
+                    v = ld_bf16x8(a.k_pool + ((size_t)blk * a.Hkv + hk) * 16 * HD + kpool_chunk_offset(tok & 15, cc * 8));
                 else if (cc == 0 && (tok & 15) == 0)
                     atomicOr(a.err_flag, 2);
             }

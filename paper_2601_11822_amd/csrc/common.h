@@ -46,3 +46,13 @@ __host__ __device__ __forceinline__ size_t packed_chunk_offset(int m, int k) {
     const int kb = k >> 4, hh = (k >> 3) & 1, tm = m >> 5, r = m & 31;
     return ((size_t)(kb * 2 + tm) * 64 + hh * 32 + r) * 8;
 }
+
+// K pool layout inside one (block, kv head): [hd/32][4][16][8] = (32-wide dim group s, 8-wide
+// sub-chunk kh, permuted token row, 8 dims).  A 16x16x32 MFMA row operand for dim group s is then
+// one contiguous 1 KB (lane = kh*16 + row), and the token order 0-3, 8-11, 4-7, 12-15 (bits 2 and
+// 3 of the slot swapped) makes each of the two score tiles of the decode kernel read whole 128-byte
+// lines.  Element offset of the 8-dim chunk holding (token slot t, dim d) within the block/head:
+__host__ __device__ __forceinline__ int kpool_chunk_offset(int t, int d) {
+    const int prow = (t & 3) | ((t & 8) >> 1) | ((t & 4) << 1);
+    return (((d >> 5) * 4 + ((d >> 3) & 3)) * 16 + prow) * 8;
+}

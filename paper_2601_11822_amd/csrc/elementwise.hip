@@ -44,7 +44,8 @@ void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *ou
 }
 
 // ---------------------------------------------------------------------------------------------
-// RoPE on q (in place) and k, then K -> pool[blk][kvh][slot][:], V -> pool[blk][kvh][:][slot].
+// RoPE on q (in place) and k, then K -> pool[blk][kvh] in the dim-group / permuted-row chunk order
+// of kpool_chunk_offset, V -> pool[blk][kvh][:][slot].
 // One workgroup per token row; work items of 8 elements are spread over the 256 threads.
 // A block id outside the pool, or a position outside the rotary table, is never dereferenced:
 // the item is skipped and the error flag raised.
@@ -96,9 +97,9 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
             st_bf16x8(hp + half + c * 8, ohi);
         } else if (blk_ok) {
             const int kvh = head - a.Hq;
-            bf16_t *dst = a.k_pool + (((size_t)blk * a.Hkv + kvh) * RS_BLOCK_TOKENS + slot) * hd;
-            st_bf16x8(dst + c * 8, olo);
-            st_bf16x8(dst + half + c * 8, ohi);
+            bf16_t *dst = a.k_pool + ((size_t)blk * a.Hkv + kvh) * RS_BLOCK_TOKENS * hd;
+            st_bf16x8(dst + kpool_chunk_offset(slot, c * 8), olo);
+            st_bf16x8(dst + kpool_chunk_offset(slot, half + c * 8), ohi);
         }
     }
     if (blk_ok) {
@@ -139,4 +140,29 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(int32_t *hist) {
 
 void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups) {
     hipLaunchKernelGGL(cu_probe_kernel, dim3(n_workgroups), dim3(64), 0, st, hist);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streaming read: grid-stride 16-byte loads, 8 in flight per thread; measures the read bandwidth
+// a CU partition can pull.  The XOR fold is compared with a value it cannot take for all-equal
+// input words, so nothing is stored.
+// ---------------------------------------------------------------------------------------------
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t *__restrict__ src, u32x4_t *sink, size_t n16) {
+    size_t i = (size_t)blockIdx.x * 2048 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 2048;
+    u32x4_t acc = {0, 0, 0, 0};
+    for (; i + 256 * 7 < n16; i += stride) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + 256 * u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && sink) sink[0] = acc;
+}
+
+void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_workgroups), dim3(256), 0, st, (const u32x4_t *)src, (u32x4_t *)nullptr,
+                       bytes / 16);
 }

@@ -50,7 +50,7 @@ struct DecodeAttnArgs {
     float scale_log2;
     int out_packed;  // write `out` fragment-packed (B <= 64)
 };
-#define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention
+#define RS_DECODE_CHUNK 1024  // tokens per workgroup of the decode attention
 void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a);
 
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
@@ -76,3 +76,6 @@ void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
 
 // Counts workgroups per physical CU: hist[(xcc << 8) | (se << 5) | (sh << 4) | cu] += 1.
 void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);
+
+// Reads `bytes` (multiple of 16) once with coalesced 16-byte loads.
+void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups);

@@ -671,6 +671,19 @@ int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *ho
     return RS_OK;
 }
 
+int32_t rs_debug_stream_read(rs_ctx *c, int32_t side, const void *buf, int64_t n_bytes, float *ms_out) {
+    if (!c || !buf || !ms_out || side < 0 || side > 1 || n_bytes < 32768 || n_bytes % 16) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    if (c->side[side].cus <= 0) return fail(RS_ERR_STATE, "side has no compute units");
+    hipStream_t st = c->side[side].stream;
+    int32_t rc = rs_mark(c, side, RS_MAX_MARKS - 4);
+    if (rc) return rc;
+    launch_stream_read(st, buf, (size_t)n_bytes, c->side[side].cus * 16);
+    rc = rs_mark(c, side, RS_MAX_MARKS - 3);
+    if (rc) return rc;
+    return rs_elapsed_ms(c, side, RS_MAX_MARKS - 4, side, RS_MAX_MARKS - 3, ms_out);
+}
+
 int32_t rs_debug_cu_histogram(rs_ctx *c, int32_t side, int32_t n_workgroups, int32_t *hist_out) {
     if (!c || !hist_out || side < 0 || side > 1 || n_workgroups < 1 || n_workgroups > (1 << 20))
         return fail(RS_ERR_BAD_ARG, "bad argument");

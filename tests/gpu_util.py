@@ -143,15 +143,23 @@ class Rig:
         return y
 
     # ---- pools in the oracle's logical order [n_blocks, 16, Hkv, hd]
+    # K pool: [n_blocks][Hkv][hd/32][4][16 permuted slots][8]; slot t sits in row t with bits 2, 3 swapped
+    _PROW = [(t & 3) | ((t & 8) >> 1) | ((t & 4) << 1) for t in range(16)]
+
     def k_bits_logical(self, layer=0):
-        return to_bits(self.k_pool[layer].permute(0, 2, 1, 3).contiguous())
+        nb, Hkv, _, hd = self.k_pool[layer].shape
+        k = self.k_pool[layer].reshape(nb, Hkv, hd // 32, 4, 16, 8)[:, :, :, :, self._PROW, :]   # -> slot order
+        return to_bits(k.permute(0, 4, 1, 2, 3, 5).reshape(nb, 16, Hkv, hd).contiguous())
 
     def v_bits_logical(self, layer=0):
         return to_bits(self.v_pool[layer].permute(0, 3, 1, 2).contiguous())
 
     def load_pools_from_logical(self, k_bits, v_bits, layer=0):
         """k_bits, v_bits: uint16 [n_blocks,16,Hkv,hd] -> device pools in the library's layouts."""
-        self.k_pool[layer].copy_(to_dev(k_bits).permute(0, 2, 1, 3))
+        nb, Hkv, _, hd = self.k_pool[layer].shape
+        k = to_dev(k_bits).reshape(nb, 16, Hkv, hd // 32, 4, 8).permute(0, 2, 3, 4, 1, 5)   # [nb,Hkv,s,kh,slot,8]
+        inv = [self._PROW.index(r) for r in range(16)]                                        # row r holds slot inv[r]
+        self.k_pool[layer].copy_(k[:, :, :, :, inv, :].reshape(nb, Hkv, 16, hd))
         self.v_pool[layer].copy_(to_dev(v_bits).permute(0, 2, 3, 1))
 
 
