@@ -497,7 +497,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__r
         if (more) {
             issue_w(kb + 64 * (i + 1), (i + 1) & 1);
             load_x(kb + 64 * (i + 1), xnext);
-            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // slab i landed; 8 + 8 younger loads may fly
+            // LDS-DMA loads and register loads each complete in order, but not with respect to one
+            // another: the younger (fast, L2-resident) activation loads may all be done while older
+            // weight DMAs still fly.  "At most 8 outstanding" is the largest count that still implies
+            // step i is complete: were a load of W(i) or X(i) pending, so were the 8 of its kind
+            // from step i+1, i.e. 16 in total.
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
