@@ -32,6 +32,15 @@ if ROOT not in sys.path:
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 
+# Bytes that crossed the L2 <-> fabric boundary per launch at the default workload, from two
+# hardware-counter passes (read size, then write size) over `bench.py --alone-only`, each scaled by
+# what the same counter reads for the 1 GiB device copy that run ends with (reads x2.0, writes
+# x1.0); the summaries are under profiles/.  Valid for the default workload only.
+TRAFFIC_BYTES = {
+    "gateup": (377248 * 2.0 + 57345) * 1024.0,
+    "decode_attn": ((326739 + 1656) * 2.0 + 3175 + 512) * 1024.0,
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -211,8 +220,8 @@ def main():
     ap.add_argument("--decode-batch", type=int, default=64)
     ap.add_argument("--ctx-lo", type=int, default=512)
     ap.add_argument("--ctx-hi", type=int, default=4096)
-    ap.add_argument("--split", type=str, default="192,64", help="headline prefill,decode CUs")
-    ap.add_argument("--sweep", action="store_true", help="also co-run at 64/128/192 prefill CUs and 256/256")
+    ap.add_argument("--split", type=str, default="128,128", help="headline prefill,decode CUs")
+    ap.add_argument("--sweep", action="store_true", help="also co-run at other splits, from 64/192 to 224/32, and unpartitioned")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--alone-only", action="store_true", help="only the alone-at-256-CUs phases (for profiling)")
     args = ap.parse_args()
@@ -231,6 +240,9 @@ def main():
     kv_tok_bytes = 2 * shape.n_kv_heads * shape.head_dim * 2
     attn_bytes = float((r["ctx"].astype(np.int64) + 1).sum()) * kv_tok_bytes
     bytes_layer = 2.0 * P + attn_bytes + B * kv_tok_bytes
+    default_workload = (T, B, args.ctx_lo, args.ctx_hi) == (2048, 64, 512, 4096)
+    probe = torch.empty(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB, read by the bandwidth probe
+    probe.fill_(1.0)
 
     # ---- alone on all 256 CUs, with per-kernel times (the roofline figures)
     c.set_cu_split(256, 256)
@@ -244,10 +256,11 @@ def main():
     gu_flops = 2.0 * T * shape.d_model * 2 * shape.ffn_dim
     roof = {"kernel": "gateup_swiglu_gemm (prefill, alone on 256 CUs)", "bound": "mfma",
             "achieved": gu_flops / (kt_p[6] * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "traffic": None}
+            "traffic": TRAFFIC_BYTES["gateup"] if default_workload else None}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof_d = {"kernel": "paged decode attention + chunk merge (alone on 256 CUs)", "bound": "hbm",
-              "achieved": attn_bytes / (kt_d[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None}
+              "achieved": attn_bytes / (kt_d[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "traffic": TRAFFIC_BYTES["decode_attn"] if default_workload else None}
     roof_d["frac"] = roof_d["achieved"] / roof_d["peak"]
     layer_p = {"tflops": flops_layer / (np.median(p256_bb) * 1e-3) / 1e12}
     layer_p["frac_mfma"] = layer_p["tflops"] / MFMA_PEAK_TFLOPS
@@ -255,10 +268,8 @@ def main():
     layer_d["frac_hbm"] = layer_d["gbs"] / HBM_PEAK_GBS
     if args.alone_only:
         # a plain copy of known size, so that HBM byte counters can be scaled against it
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
-        src.fill_(1.0)
         for _ in range(3):
-            dst = src.clone()
+            dst = probe.clone()
         torch.cuda.synchronize()
         print(json.dumps({"prefill_ms": float(np.median(p256_bb)), "decode_ms": float(np.median(d256_bb)),
                           "prefill_kernels_ms": dict(zip(names, map(float, kt_p))),
@@ -269,7 +280,7 @@ def main():
     # ---- co-run at the requested split(s)
     splits = [tuple(int(v) for v in args.split.split(","))]
     if args.sweep:
-        for s in [(64, 192), (128, 128), (192, 64), (224, 32), (256, 256)]:
+        for s in [(64, 192), (96, 160), (128, 128), (160, 96), (192, 64), (224, 32), (256, 256)]:
             if s not in splits:
                 splits.append(s)
     sweep = []
@@ -292,6 +303,12 @@ def main():
         }
         rec["combined_norm_throughput"] = (float(np.median(p256_bb)) / rec["prefill_corun_ms"]
                                            + float(np.median(d256_bb)) / rec["decode_corun_p50_ms"])
+        # what a plain streaming read achieves on the decode partition alone: the ceiling of that share
+        c.debug_stream_read(1, probe, probe.numel() * 4)
+        bw_ms = min(c.debug_stream_read(1, probe, probe.numel() * 4) for _ in range(3))
+        rec["decode_partition_stream_read_gbs"] = probe.numel() * 4 / (bw_ms * 1e-3) / 1e9
+        rec["decode_alone_frac_of_partition_stream"] = (bytes_layer / (rec["decode_alone_ms"] * 1e-3) / 1e9
+                                                        / rec["decode_partition_stream_read_gbs"])
         share_p = pc / 256.0
         rec["prefill_frac_mfma_of_share"] = flops_layer / (rec["prefill_corun_ms"] * 1e-3) / 1e12 / (MFMA_PEAK_TFLOPS * share_p)
         rec["decode_frac_hbm"] = bytes_layer / (rec["decode_corun_p50_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS

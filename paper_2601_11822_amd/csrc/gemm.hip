@@ -175,8 +175,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 // mod 8) cover a compact block of tiles: all row tiles of a few column tiles, served by that
 // XCD's L2.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int EPI, int NS>
-__global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
+template <int BM, int BN, int EPI, int NS, int OCC>
+__global__ __launch_bounds__(256, OCC) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
     constexpr int BK = 32;
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -340,9 +340,8 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs a, int m_tile
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS, int OCC>
 static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
-    constexpr int NS = (BM + BN) >= 512 ? 4 : 5;     // 4 x 32 KB or 5 x 24 KB of LDS
     const int m_tiles = (a.M + BM - 1) / BM;
     const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     const int total = m_tiles * n_tiles;
@@ -350,19 +349,19 @@ static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
     constexpr int lds = NS * (BM + BN) * 32 * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI, NS>,
+        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI, NS, OCC>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI, NS>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
+    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI, NS, OCC>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NS, int OCC>
 static void launch_direct(hipStream_t st, const GemmArgs &a) {
     switch (a.epi) {
-        case EPI_STORE: launch_direct_epi<BM, BN, EPI_STORE>(st, a); break;
-        case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL>(st, a); break;
-        default: launch_direct_epi<BM, BN, EPI_SWIGLU>(st, a); break;
+        case EPI_STORE: launch_direct_epi<BM, BN, EPI_STORE, NS, OCC>(st, a); break;
+        case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL, NS, OCC>(st, a); break;
+        default: launch_direct_epi<BM, BN, EPI_SWIGLU, NS, OCC>(st, a); break;
     }
 }
 
@@ -392,9 +391,9 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
         // the tile grid is a function of the problem shape only
         const long tiles256 = (long)((a.M + 255) / 256) * ((a.epi == EPI_SWIGLU ? 2 * a.N : a.N) / 256);
         if (tiles256 >= 256)
-            launch_direct<256, 256>(st, a);
+            launch_direct<256, 256, 4, 1>(st, a);   // 4 x 32 KB of LDS
         else
-            launch_direct<128, 256>(st, a);
+            launch_direct<128, 256, 5, 1>(st, a);   // 5 x 24 KB of LDS
     } else if (a.M >= 1024 && a.N >= 1024) {
         launch_tiled<256, 256>(st, a);
     } else {
