@@ -170,33 +170,22 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 // the younger loads that may still fly), meets the other waves at the barrier and reads tile
 // kt+1's step-0 fragments.  In both steps the first MFMAs are issued before the reads, so a wait
 // in front of a step is already satisfied and the barrier never sits between idle matrix cores.
-//
-// The flat workgroup id is remapped so that the workgroups resident on one XCD (ids congruent
-// mod 8) cover a compact block of tiles: all row tiles of a few column tiles, served by that
-// XCD's L2.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int EPI, int NS, int OCC>
-__global__ __launch_bounds__(256, OCC) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
+// One output tile: rows [bm, bm + BM), column tile nb (of width BN; BN/2 output columns for SwiGLU).
+template <int BM, int BN, int EPI, int NS, int NW>
+__device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm, const int nb, bf16_t *smem) {
     constexpr int BK = 32;
-    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int WGN = NW / 2;                      // waves: 2 along M x NW/2 along N
+    constexpr int WM = BM / 2, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int LA = BM / 64, LB = BN / 64;        // wave-wide loads per wave per stage
+    constexpr int LA = BM / (16 * NW), LB = BN / (16 * NW);   // wave-wide loads per wave per stage
     constexpr int STAGE = (BM + BN) * BK;            // elements per stage
     constexpr int D = NS - 1;                        // prefetch distance in K tiles
-    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int c32 = lane & 31, h = lane >> 5;
     const int M = a.M, N = a.N, K = a.K;
-
-    // XCD-aware tile order: xcd = id % 8 owns a contiguous run of column-major tiles
-    const int total = m_tiles * n_tiles;
-    const int per_xcd = (total + 7) >> 3;
-    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (t >= total) return;
-    const int bm = (t % m_tiles) * BM;
-    const int nb = t / m_tiles;
 
     const int lrow = lane >> 2;                                     // row within the 16-row group
     const int lchunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 3;       // element offset of the fetched chunk
@@ -272,7 +261,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_direct_kernel(GemmArgs a, int m
     constexpr int SL = 2 * TN * TM, LT = LA + LB, SP = SL / LT;
     auto k_loop = [&](auto wtag) {
         constexpr int W = decltype(wtag)::value;
-        constexpr int SHIFT = (W * SP) / 4;
+        constexpr int SHIFT = (W * SP) / NW;
         // loads of the current iteration already issued when the barrier of slot SL/2 is reached
         constexpr int EARLY = ((SL / 2 - 1 - SHIFT) / SP) + 1;
         for (int kt = 0; kt < nk; ++kt) {
@@ -297,7 +286,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_direct_kernel(GemmArgs a, int m
         case 0: k_loop(std::integral_constant<int, 0>{}); break;
         case 1: k_loop(std::integral_constant<int, 1>{}); break;
         case 2: k_loop(std::integral_constant<int, 2>{}); break;
-        default: k_loop(std::integral_constant<int, 3>{}); break;
+        case 3: k_loop(std::integral_constant<int, 3>{}); break;
+        case 4: k_loop(std::integral_constant<int, 4 % NW>{}); break;
+        case 5: k_loop(std::integral_constant<int, 5 % NW>{}); break;
+        case 6: k_loop(std::integral_constant<int, 6 % NW>{}); break;
+        default: k_loop(std::integral_constant<int, 7 % NW>{}); break;
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
@@ -340,7 +333,55 @@ __global__ __launch_bounds__(256, OCC) void gemm_direct_kernel(GemmArgs a, int m
     }
 }
 
-template <int BM, int BN, int EPI, int NS, int OCC>
+// The flat workgroup id is remapped so that the workgroups resident on one XCD (ids congruent
+// mod 8) own a contiguous run of column-major tiles: all row tiles of a few column tiles, served
+// by that XCD's L2.
+template <int BM, int BN, int EPI, int NS, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+    const int total = m_tiles * n_tiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (t >= total) return;
+    gemm_direct_tile<BM, BN, EPI, NS, NW>(a, (t % m_tiles) * BM, t / m_tiles, smem);
+}
+
+// Whole rounds of 256x256 tiles, then a last half round: when the 256x256 tiles do not divide by
+// the number of compute units, the first n_full workgroups (a multiple of the unit count) take
+// whole tiles and the remaining tiles are cut into their two 128-row halves, one workgroup each,
+// which are dispatched last.  The arithmetic of an output element does not depend on the tile
+// that holds it, so the schedule may follow the size of the partition.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_direct_mixed_kernel(GemmArgs a, int m_tiles, int n_full, int n_half) {
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+    const int id = blockIdx.x;
+    if (id < n_full) {
+        const int t = (id & 7) * (n_full >> 3) + (id >> 3);          // n_full is a multiple of 8
+        gemm_direct_tile<256, 256, EPI, 4, 4>(a, (t % m_tiles) * 256, t / m_tiles, smem);
+    } else {
+        const int j = id - n_full;
+        const int u = (j & 7) * ((n_half + 7) >> 3) + (j >> 3);
+        if (u >= n_half) return;
+        const int t = n_full + (u >> 1);
+        const int bm = (t % m_tiles) * 256 + (u & 1) * 128;
+        if (bm >= a.M) return;
+        gemm_direct_tile<128, 256, EPI, 5, 4>(a, bm, t / m_tiles, smem);
+    }
+}
+
+template <int EPI>
+static void launch_direct_mixed_epi(hipStream_t st, const GemmArgs &a, int m_tiles, int n_full, int n_half) {
+    constexpr int lds = 4 * 512 * 32 * 2;   // the larger of the two rings
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)gemm_direct_mixed_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    const int grid = n_full + ((n_half + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_direct_mixed_kernel<EPI>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_full, n_half);
+}
+
+template <int BM, int BN, int EPI, int NS, int NW>
 static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
     const int m_tiles = (a.M + BM - 1) / BM;
     const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
@@ -349,19 +390,19 @@ static void launch_direct_epi(hipStream_t st, const GemmArgs &a) {
     constexpr int lds = NS * (BM + BN) * 32 * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI, NS, OCC>,
+        (void)hipFuncSetAttribute((const void *)gemm_direct_kernel<BM, BN, EPI, NS, NW>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI, NS, OCC>), dim3(grid), dim3(256), lds, st, a, m_tiles, n_tiles);
+    hipLaunchKernelGGL((gemm_direct_kernel<BM, BN, EPI, NS, NW>), dim3(grid), dim3(64 * NW), lds, st, a, m_tiles, n_tiles);
 }
 
-template <int BM, int BN, int NS, int OCC>
+template <int BM, int BN, int NS, int NW>
 static void launch_direct(hipStream_t st, const GemmArgs &a) {
     switch (a.epi) {
-        case EPI_STORE: launch_direct_epi<BM, BN, EPI_STORE, NS, OCC>(st, a); break;
-        case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL, NS, OCC>(st, a); break;
-        default: launch_direct_epi<BM, BN, EPI_SWIGLU, NS, OCC>(st, a); break;
+        case EPI_STORE: launch_direct_epi<BM, BN, EPI_STORE, NS, NW>(st, a); break;
+        case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL, NS, NW>(st, a); break;
+        default: launch_direct_epi<BM, BN, EPI_SWIGLU, NS, NW>(st, a); break;
     }
 }
 
@@ -388,12 +429,22 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
     if (a.M <= 0 || a.N <= 0) return;
     const bool aligned = (a.K % 32 == 0) && a.K >= 32;
     if (aligned && a.M >= 512 && a.N >= 1024) {
-        // the tile grid is a function of the problem shape only
+        // tile shapes follow the problem shape; only the last-half-round schedule looks at the
+        // size of the partition
         const long tiles256 = (long)((a.M + 255) / 256) * ((a.epi == EPI_SWIGLU ? 2 * a.N : a.N) / 256);
-        if (tiles256 >= 256)
-            launch_direct<256, 256, 4, 1>(st, a);   // 4 x 32 KB of LDS
+        const int cus = a.cus > 0 ? a.cus : 256;
+        const int n_full = (int)(tiles256 / cus) * cus, rest = (int)tiles256 - n_full;
+        if (tiles256 >= 256 && n_full > 0 && n_full % 8 == 0 && rest > 0 && 2 * rest <= cus) {
+            const int m_tiles = (a.M + 255) / 256;
+            switch (a.epi) {
+                case EPI_STORE: launch_direct_mixed_epi<EPI_STORE>(st, a, m_tiles, n_full, 2 * rest); break;
+                case EPI_RESIDUAL: launch_direct_mixed_epi<EPI_RESIDUAL>(st, a, m_tiles, n_full, 2 * rest); break;
+                default: launch_direct_mixed_epi<EPI_SWIGLU>(st, a, m_tiles, n_full, 2 * rest); break;
+            }
+        } else if (tiles256 >= 256)
+            launch_direct<256, 256, 4, 4>(st, a);   // 4 x 32 KB of LDS
         else
-            launch_direct<128, 256, 5, 1>(st, a);   // 5 x 24 KB of LDS
+            launch_direct<128, 256, 5, 4>(st, a);   // 5 x 24 KB of LDS
     } else if (a.M >= 1024 && a.N >= 1024) {
         launch_tiled<256, 256>(st, a);
     } else {
@@ -402,80 +453,100 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Skinny kernel (M <= 64): the weights are streamed once from HBM straight into MFMA fragments,
-// no LDS staging.  Workgroup = 64 (virtual) weight rows x one K slice; its 4 waves split the
-// slice and are summed in wave order through LDS; the S slices of K are summed in slice order
+// Skinny kernel (M <= 64): bandwidth bound, so built for bytes in flight.  Both operands arrive in
+// MFMA fragment order -- the activations fragment-packed by their producer, the weights repacked
+// once when they are set -- so every load is one contiguous 1 KB per wave straight into the
+// registers that feed the matrix core: no LDS staging, and since only register loads are
+// outstanding they complete in order and the compiler's own wait counts are exact.
+//
+// Packed weights: [ceil(K/16) k blocks][ceil(N/64)*2 row tiles of 32][64 lanes][8], zero padded;
+// lane h*32 + r of block (kb, t) holds W[32t + r][16kb + 8h .. +8).  k-block major: the waves of
+// all workgroups advance through K together, so at any moment the chip reads a few contiguous
+// regions that spread evenly over the memory channels (row-tile-major streams would all sit at
+// the same offset within their 2^n-spaced rows and crowd the same channels).
+//
+// Workgroup = 64 (virtual) weight rows x one K slice; its 4 waves split the slice.  Each wave keeps
+// PD k-blocks (4 KB each: two weight and two activation fragments) in flight in a register ring;
+// two workgroups fit a CU, i.e. 8 waves x 32 KB in flight per CU.  Loads past the wave's range
+// re-fetch the last block (cache hits, never used), which keeps the ring's wait counts static.
+// The 4 waves are summed in wave order through LDS; the S slices of K are summed in slice order
 // by the epilogue kernel.  S depends on (N, K) only, so results never depend on the CU share.
-// Within a 64-wide K window lane half h covers k in [32h, 32h+32): 64 contiguous bytes/lane.
 // ---------------------------------------------------------------------------------------------
 static inline int skinny_virtual_n(int N, int epi) {
     return epi == EPI_SWIGLU ? ((N + 31) / 32) * 64 : ((N + 63) / 64) * 64;
 }
+static inline int skinny_kblocks(int K) { return (K + 15) / 16; }
 static inline int skinny_splits(int N, int K, int epi) {
     const int tiles = skinny_virtual_n(N, epi) / 64;
+    const int Kb = skinny_kblocks(K);
     int S = 1;
-    while (tiles * S < 256 && S < 16 && (K + 2 * S - 1) / (2 * S) >= 256) S *= 2;
+    // enough workgroups for two per CU, but at least 16 k-blocks per wave
+    while (tiles * S < RS_SKINNY_TARGET_WGS && S < 16 && Kb / (2 * S) >= 64) S *= 2;
     return S;
 }
-static inline int skinny_k_per_wg(int K, int S) {
-    const int per = (K + S - 1) / S;
-    return ((per + 255) / 256) * 256;  // 4 waves x whole 64-wide windows
+static inline int skinny_kb_per_wg(int K, int S) {
+    const int per = (skinny_kblocks(K) + S - 1) / S;
+    return ((per + 3) / 4) * 4;  // 4 waves
 }
 size_t skinny_partial_elems(int M, int N, int K, int epi) {
     return (size_t)skinny_splits(N, K, epi) * (size_t)M * (size_t)skinny_virtual_n(N, epi);
 }
+size_t packed_weight_elems(int N, int K) {
+    return (size_t)((N + 63) / 64) * 2 * (size_t)skinny_kblocks(K) * 512;
+}
 
-template <int EPI>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
-                                                          int k_per_wg, int Nv) {
-    // 64 KB: per wave two 8 KB weight slabs [64 rows][64 k] (rows of 128 B, chunk ^= (row>>1)&7);
-    // after the K loop the same bytes hold the waves' accumulators for the in-order reduction
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_sk[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int c32 = lane & 31, h = lane >> 5;
-    const int M = a.M, N = a.N, K = a.K;
-    const int kw = k_per_wg >> 2;
-    const int kb = blockIdx.y * k_per_wg + wave * kw;
-    const int ke = min(kb + kw, K);
-    const int nsteps = ke > kb ? (ke - kb + 63) >> 6 : 0;
-    bf16_t *slab = (bf16_t *)(smem_sk + wave * 16384);
-
-    // weight rows fetched by this lane in each of the 8 wave-wide DMA loads of a slab
-    const bf16_t *wrow[8];
-    int wchunk[8];
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-        const int row = 8 * g + (lane >> 3);
-        wchunk[g] = ((lane & 7) ^ ((row >> 1) & 7)) << 3;   // k offset of the chunk this lane stores
-        if (EPI == EPI_SWIGLU) {
-            const int f = min((int)blockIdx.x * 32 + (row & 31), N - 1);
-            wrow[g] = ((row >> 5) ? a.W2 : a.W) + (size_t)f * K;
+// One thread per 16-byte chunk of the packed matrix.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wp,
+                                                           int N, int K, int Kb, long n_chunks) {
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_chunks) return;
+    const int lane = (int)(idx & 63);
+    const long blk = idx >> 6;
+    const int Nt = ((N + 63) / 64) * 2;
+    const int t = (int)(blk % Nt), kb = (int)(blk / Nt);
+    const int row = 32 * t + (lane & 31), k0 = 16 * kb + 8 * (lane >> 5);
+    bf16x8 v = zero_bf16x8();
+    if (row < N) {
+        if (k0 + 8 <= K) {
+            v = ld_bf16x8(W + (size_t)row * K + k0);
         } else {
-            wrow[g] = a.W + (size_t)min((int)blockIdx.x * 64 + row, N - 1) * K;
+            for (int i = 0; i < 8; ++i)
+                if (k0 + i < K) v[i] = W[(size_t)row * K + k0 + i];
         }
     }
-    auto issue_w = [&](int k0, int stage) {
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            // a chunk past K is replaced by the window's first chunk (finite data; X is zero there)
-            const int ko = (k0 + wchunk[g] < K) ? wchunk[g] : 0;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wrow[g] + k0 + ko),
-                                             (__attribute__((address_space(3))) void *)(slab + stage * 4096 + g * 512),
-                                             16, 0, 0);
-        }
-    };
-    // activation fragments straight from the fragment-packed matrix: contiguous 1 KB per load
-    auto load_x = [&](int k0, bf16x8 (&xf)[2][4]) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int kb16 = (k0 >> 4) + s;
-            const bool kin = 16 * kb16 + 8 * h < K;
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-                xf[tm][s] = (kin && 32 * tm + c32 < M) ? ld_bf16x8(a.A + ((size_t)(kb16 * 2 + tm) * 64 + lane) * 8)
-                                                       : zero_bf16x8();
-        }
-    };
+    st_bf16x8(Wp + idx * 8, v);
+}
+
+void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K) {
+    const long n_chunks = (long)(packed_weight_elems(N, K) / 8);
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, W, Wp, N, K,
+                       skinny_kblocks(K), n_chunks);
+}
+
+template <int EPI, int PD>
+__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
+                                                             int kb_per_wg, int Kb, int Nv) {
+    // 64 KB: the waves' accumulators for the in-order reduction, [wave][tile][lane][16]
+    extern __shared__ __attribute__((aligned(1024))) float red[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int M = a.M;
+    const int kbw = kb_per_wg >> 2;
+    const int kb0 = __builtin_amdgcn_readfirstlane(blockIdx.y * kb_per_wg + wave * kbw);
+    const int nsteps = max(min(kb0 + kbw, Kb) - kb0, 0);
+    const int kb_last = Kb - 1;
+
+    // a.W / a.W2 are the packed matrices; row tile 0 / 1 of this workgroup
+    const bf16_t *w0, *w1;
+    const size_t wstride = (size_t)((a.N + 63) / 64) * 1024;   // elements per k block
+    if (EPI == EPI_SWIGLU) {
+        w0 = a.W + (size_t)blockIdx.x * 512 + lane * 8;
+        w1 = a.W2 + (size_t)blockIdx.x * 512 + lane * 8;
+    } else {
+        w0 = a.W + (size_t)blockIdx.x * 1024 + lane * 8;
+        w1 = w0 + 512;
+    }
+    const bf16_t *x = a.A + lane * 8;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -485,48 +556,38 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a, float *__r
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    bf16x8 xcur[2][4], xnext[2][4];
-    if (nsteps > 0) {
-        issue_w(kb, 0);
-        load_x(kb, xcur);
-    }
-    const int x7 = (c32 >> 1) & 7;
-    for (int i = 0; i < nsteps; ++i) {
-        const bool more = i + 1 < nsteps;
-        if (more) {
-            issue_w(kb + 64 * (i + 1), (i + 1) & 1);
-            load_x(kb + 64 * (i + 1), xnext);
-            // LDS-DMA loads and register loads each complete in order, but not with respect to one
-            // another: the younger (fast, L2-resident) activation loads may all be done while older
-            // weight DMAs still fly.  "At most 8 outstanding" is the largest count that still implies
-            // step i is complete: were a load of W(i) or X(i) pending, so were the 8 of its kind
-            // from step i+1, i.e. 16 in total.
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
-        const bf16_t *sl = slab + (i & 1) * 4096;
+    bf16x8 rw0[PD], rw1[PD], rx0[PD], rx1[PD];
+    auto load = [&](int p, int step) {
+        const size_t kb = (size_t)min(kb0 + step, kb_last);
+        rw0[p] = ld_bf16x8(w0 + kb * wstride);
+        rw1[p] = ld_bf16x8(w1 + kb * wstride);
+        rx0[p] = ld_bf16x8(x + kb * 1024);
+        rx1[p] = ld_bf16x8(x + kb * 1024 + 512);
+    };
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8 wf[2];
+    for (int p = 0; p < PD; ++p) load(p, p);
+    auto step = [&](int p) {
+        acc[0][0] = mfma32(rw0[p], rx0[p], acc[0][0]);
+        acc[0][1] = mfma32(rw0[p], rx1[p], acc[0][1]);
+        acc[1][0] = mfma32(rw1[p], rx0[p], acc[1][0]);
+        acc[1][1] = mfma32(rw1[p], rx1[p], acc[1][1]);
+    };
+    // whole rings: branch free, so the wait in front of each step is "all but the PD-1 younger steps"
+    int i = 0;
+    for (; i + PD <= nsteps; i += PD) {
 #pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
-                wf[tn] = *(const bf16x8 *)&sl[(32 * tn + c32) * 64 + (((2 * s + h) ^ x7) << 3)];
-#pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < 2; ++tm) acc[tn][tm] = mfma32(wf[tn], xcur[tm][s], acc[tn][tm]);
-        }
-        if (more) {
-#pragma unroll
-            for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) xcur[tm][s] = xnext[tm][s];
+        for (int p = 0; p < PD; ++p) {
+            step(p);
+            load(p, i + p + PD);
+            __builtin_amdgcn_sched_barrier(0);   // refill the ring slot at once: keeps the bytes in flight level
         }
     }
-    // in-order reduction of the 4 waves; each wave first overwrites only its own slab bytes
-    float *red = (float *)smem_sk;   // [wave][tile][lane][16]
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // the last, partial ring is already in flight
+    const int rem = nsteps - i;
+#pragma unroll
+    for (int p = 0; p < PD; ++p)
+        if (p < rem) step(p);
+    // in-order reduction of the 4 waves
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
@@ -588,25 +649,29 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
     *(bf16x4 *)dst = v;
 }
 
-void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
-    if (a.M <= 0 || a.N <= 0) return;
+template <int EPI>
+static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials) {
+    constexpr int PD = 8;
     const int Nv = skinny_virtual_n(a.N, a.epi);
     const int S = skinny_splits(a.N, a.K, a.epi);
-    const int kpw = skinny_k_per_wg(a.K, S);
-    dim3 grid(Nv / 64, S);
+    const int kbpw = skinny_kb_per_wg(a.K, S);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<EPI, PD>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+        attr_set = true;
+    }
     const int eblocks = (a.M * (a.N / 4) + 255) / 256;
+    hipLaunchKernelGGL((gemm_skinny_kernel<EPI, PD>), dim3(Nv / 64, S), dim3(256), 65536, st, a, partials, kbpw,
+                       skinny_kblocks(a.K), Nv);
+    hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
+}
+
+// a.A is fragment-packed, a.W / a.W2 are the packed weight matrices (launch_pack_weights).
+void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
+    if (a.M <= 0 || a.N <= 0) return;
     switch (a.epi) {
-        case EPI_STORE:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_STORE>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
-            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_STORE>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
-            break;
-        case EPI_RESIDUAL:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_RESIDUAL>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
-            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_RESIDUAL>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
-            break;
-        default:
-            hipLaunchKernelGGL(gemm_skinny_kernel<EPI_SWIGLU>, grid, dim3(256), 65536, st, a, partials, kpw, Nv);
-            hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_SWIGLU>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
-            break;
+        case EPI_STORE: launch_skinny_epi<EPI_STORE>(st, a, partials); break;
+        case EPI_RESIDUAL: launch_skinny_epi<EPI_RESIDUAL>(st, a, partials); break;
+        default: launch_skinny_epi<EPI_SWIGLU>(st, a, partials); break;
     }
 }

@@ -50,6 +50,7 @@ struct DecodeAttnArgs {
     float scale_log2;
     int out_packed;  // write `out` fragment-packed (B <= 64)
 };
+#define RS_SKINNY_TARGET_WGS 384  // the skinny GEMM splits K until it has about this many workgroups
 #define RS_DECODE_CHUNK 1024  // tokens per workgroup of the decode attention
 void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a);
 
@@ -66,13 +67,18 @@ struct GemmArgs {
     int M, N, K;
     int epi;
     int out_packed = 0;  // skinny path only: write `out` fragment-packed (it feeds another skinny GEMM)
+    int cus = 0;         // compute units of the launching stream's partition (0: the whole chip); scheduling only
 };
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 
 // Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through
 // `partials` (fp32, at least skinny_partial_elems(...) elements).  A must be fragment-packed.
+// a.W / a.W2 must be the fragment-packed copies made by launch_pack_weights (packed_weight_elems
+// elements each).
 size_t skinny_partial_elems(int M, int N, int K, int epi);
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
+size_t packed_weight_elems(int N, int K);
+void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
 
 // Counts workgroups per physical CU: hist[(xcc << 8) | (se << 5) | (sh << 4) | cu] += 1.
 void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);

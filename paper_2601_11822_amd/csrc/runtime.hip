@@ -74,6 +74,9 @@ struct rs_ctx {
     bool gpu = false;
     std::vector<rs_layer_weights> weights;
     std::vector<bool> have_weights;
+    // fragment-packed private copies of the five matrices, read by the decode side's skinny GEMMs
+    struct PackedLayer { bf16_t *wqkv = nullptr, *wo = nullptr, *wg = nullptr, *wu = nullptr, *wd = nullptr; };
+    std::vector<PackedLayer> packed;
     CosSin *rope = nullptr;
     int32_t *err_flag = nullptr;
     Workspace ws[2];
@@ -259,21 +262,25 @@ void tick(rs_ctx *c, int side, int i) {
 
 // The dense part after attention, shared by both passes.
 void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
-                        const bf16_t *x, bf16_t *y, int M, bool skinny) {
+                        const rs_ctx::PackedLayer &pl, const bf16_t *x, bf16_t *y, int M, bool skinny) {
     const rs_model_desc &m = c->m;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
-    auto gemm = [&](const GemmArgs &g) {
+    auto gemm = [&](GemmArgs g) {
+        g.cus = c->side[side].cus;
         if (skinny) launch_gemm_skinny(st, g, w.partials);
         else launch_gemm_tiled(st, g);
     };
     // on the skinny (decode) path every GEMM input is kept fragment-packed by its producer
-    gemm(GemmArgs{w.attn, (const bf16_t *)lw.wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
+    // ... and the weights are read from their packed copies
+    const bf16_t *wo = skinny ? pl.wo : (const bf16_t *)lw.wo, *wg = skinny ? pl.wg : (const bf16_t *)lw.wg;
+    const bf16_t *wu = skinny ? pl.wu : (const bf16_t *)lw.wu, *wd = skinny ? pl.wd : (const bf16_t *)lw.wd;
+    gemm(GemmArgs{w.attn, wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
     tick(c, side, 5);
     launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps, skinny);
     tick(c, side, 6);
-    gemm(GemmArgs{w.h, (const bf16_t *)lw.wg, (const bf16_t *)lw.wu, nullptr, w.act, M, f, d, EPI_SWIGLU, skinny ? 1 : 0});
+    gemm(GemmArgs{w.h, wg, wu, nullptr, w.act, M, f, d, EPI_SWIGLU, skinny ? 1 : 0});
     tick(c, side, 7);
-    gemm(GemmArgs{w.act, (const bf16_t *)lw.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
+    gemm(GemmArgs{w.act, wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
     tick(c, side, 8);
 }
 
@@ -305,7 +312,8 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     tick(c, RS_SIDE_PREFILL, 0);
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, T, d, m.rms_eps);
     tick(c, RS_SIDE_PREFILL, 1);
-    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, T, nqkv, d, EPI_STORE});
+    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, T, nqkv, d, EPI_STORE, 0,
+                                   c->side[RS_SIDE_PREFILL].cus});
     tick(c, RS_SIDE_PREFILL, 2);
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
@@ -315,7 +323,7 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
-    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
+    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
     HIP_TRY(hipGetLastError());
     return RS_OK;
 }
@@ -341,7 +349,8 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     tick(c, RS_SIDE_DECODE, 0);
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps, skinny);
     tick(c, RS_SIDE_DECODE, 1);
-    GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE};
+    GemmArgs g{w.h, skinny ? c->packed[layer].wqkv : (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE,
+               0, c->side[RS_SIDE_DECODE].cus};
     if (skinny) launch_gemm_skinny(st, g, w.partials);
     else launch_gemm_tiled(st, g);
     tick(c, RS_SIDE_DECODE, 2);
@@ -356,7 +365,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
                       (float)(1.4426950408889634 / std::sqrt((double)hd)), skinny ? 1 : 0};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
-    run_post_attention(c, RS_SIDE_DECODE, st, w, lw, (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
+    run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
     HIP_TRY(hipGetLastError());
     return RS_OK;
 }
@@ -403,6 +412,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     c->device = device;
     c->gpu = device != RS_HOST_ONLY;
     c->weights.resize(m.n_layers);
+    c->packed.resize(m.n_layers);
     c->have_weights.assign(m.n_layers, false);
     c->free_list.resize(pool->n_blocks);
     for (int i = 0; i < pool->n_blocks; ++i) c->free_list[i] = pool->n_blocks - 1 - i;  // pop -> 0,1,2,..
@@ -482,6 +492,9 @@ int32_t rs_destroy(rs_ctx *c) {
             for (auto &kv : c->side[s].pool) (void)hipStreamDestroy(kv.second);
             free_ws(c->ws[s]);
         }
+        for (auto &pl : c->packed)
+            for (bf16_t *q : {pl.wqkv, pl.wo, pl.wg, pl.wu, pl.wd})
+                if (q) (void)hipFree(q);
         if (c->rope) (void)hipFree(c->rope);
         if (c->err_flag) (void)hipFree(c->err_flag);
         if (c->d_ctx) (void)hipFree(c->d_ctx);
@@ -503,6 +516,22 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
     if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
     if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
+    if (c->gpu && c->lim.max_decode_batch > 0) {
+        // the decode side streams the matrices in MFMA fragment order: repack them once, here
+        HIP_TRY(hipSetDevice(c->device));
+        const rs_model_desc &m = c->m;
+        const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+        rs_ctx::PackedLayer &pl = c->packed[layer];
+        struct Item { bf16_t **dst; const void *src; int N, K; };
+        const Item items[5] = {{&pl.wqkv, w->wqkv, nqkv, d}, {&pl.wo, w->wo, d, qd}, {&pl.wg, w->wg, f, d},
+                               {&pl.wu, w->wu, f, d}, {&pl.wd, w->wd, d, f}};
+        for (const Item &it : items) {
+            if (!*it.dst) HIP_TRY(hipMalloc((void **)it.dst, packed_weight_elems(it.N, it.K) * sizeof(bf16_t)));
+            launch_pack_weights(nullptr, (const bf16_t *)it.src, *it.dst, it.N, it.K);
+        }
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipDeviceSynchronize());
+    }
     c->weights[layer] = *w;
     c->have_weights[layer] = true;
     return RS_OK;
