@@ -213,8 +213,7 @@ __global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
     const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     int n_keys = a.ctx_lens[b] + 1;
     const int col = hq * HD + d;
-    bf16_t *op = a.out_packed ? a.out + packed_chunk_offset(b, col) + (col & 7)
-                              : a.out + (size_t)b * a.Hq * HD + col;
+    bf16_t *op = a.out + packed_offset(b, col, packed_mt(a.B)) + (col & 7);   // feeds the output projection
     if (n_keys < 1) {
         *op = (bf16_t)0.f;
         return;
@@ -495,7 +494,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
         l_run += __shfl_xor(l_run, 32, 64);
         if (q_valid) {
             const float inv = 1.0f / l_run;
-            bf16_t *op = a.out + (size_t)(row0 + q_local) * (a.Hq * HD) + (size_t)hq * HD;
+            // the output feeds the output projection: fragment-packed operand layout
+            const int Mt = packed_mt(a.seq.cu[a.seq.n_req]);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -503,7 +503,8 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                     bf16x4 v;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(o[dt][4 * j + i] * inv);
-                    *(bf16x4 *)(op + 32 * dt + 8 * j + 4 * h) = v;
+                    const int col = hq * HD + 32 * dt + 8 * j + 4 * h;
+                    *(bf16x4 *)(a.out + packed_offset(row0 + q_local, col, Mt) + (col & 7)) = v;
                 }
         }
     }

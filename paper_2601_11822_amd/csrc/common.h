@@ -38,14 +38,18 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Fragment-packed layout of a skinny activation matrix X[M <= 64][K] (decode side only): the
-// 16 bytes that lane (h*32 + r) of a 32x32x16 MFMA column operand needs for rows 32*tm + r and
-// k in [16*kb + 8*h, +8) are stored contiguously in lane order, so that a wave-wide fragment
-// load is one contiguous 1 KB read.  Element offset of the 8-element chunk holding (m, k):
-__host__ __device__ __forceinline__ size_t packed_chunk_offset(int m, int k) {
-    const int kb = k >> 4, hh = (k >> 3) & 1, tm = m >> 5, r = m & 31;
-    return ((size_t)(kb * 2 + tm) * 64 + hh * 32 + r) * 8;
+// Fragment-packed layout of a GEMM operand X[M][K] (the GEMM inputs h, attn and act of both
+// sides, and the library's copies of the weight matrices): [K/16 k blocks][Mt row tiles of 32]
+// [64 lanes][8].  The 16 bytes that lane (h*32 + r) of a 32x32x16 MFMA operand needs for row
+// 32*t + r and k in [16*kb + 8*h, +8) sit in lane order, so a wave-wide fragment load is one
+// contiguous 1 KB read, and the (rows x 32 k) slab of a GEMM tile is two contiguous runs instead
+// of one 64-byte piece per 2K-byte-strided row (which crowds a few memory channels).
+// Element offset of the 8-element chunk holding (m, k):
+__host__ __device__ __forceinline__ size_t packed_offset(int m, int k, int Mt) {
+    return ((size_t)(k >> 4) * Mt + (m >> 5)) * 512 + (size_t)((((k >> 3) & 1) << 5) + (m & 31)) * 8;
 }
+// Row tiles of a packed activation matrix of M rows: at least the two tiles the skinny kernel reads.
+__host__ __device__ __forceinline__ int packed_mt(int M) { return M <= 64 ? 2 : (M + 31) >> 5; }
 
 // K pool layout inside one (block, kv head): [hd/32][4][16][8] = (32-wide dim group s, 8-wide
 // sub-chunk kh, permuted token row, 8 dims).  A 16x16x32 MFMA row operand for dim group s is then

@@ -2,45 +2,73 @@
 #include "kernels.h"
 
 // ---------------------------------------------------------------------------------------------
-// RMSNorm: one 256-thread workgroup per row.  The reduction tree depends on d only.
+// RMSNorm.  The output feeds a GEMM and is written in the fragment-packed operand layout, where
+// the 16-byte chunks of 8 consecutive rows (same k) are 128 contiguous bytes: a 256-thread
+// workgroup therefore takes R rows, 256/R threads per row, so that neighbouring threads complete
+// whole lines.  R = 8 for large M; R = 1 (one row per workgroup) when M is small and parallelism
+// matters more than write coalescing.  A row's reduction tree depends on d and R only, and R on M
+// only.
 // ---------------------------------------------------------------------------------------------
+template <int R, int NC>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__ x,
                                                       const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ out, int d, float eps, int packed) {
-    __shared__ float red[4];
-    const int row = blockIdx.x;
+                                                      bf16_t *__restrict__ out, int M, int d, float eps, int Mt) {
+    constexpr int TPR = 256 / R;   // threads per row
+    __shared__ float red[256 / 64][R];
     const int tid = threadIdx.x;
-    const bf16_t *xr = x + (size_t)row * d;
+    const int r = tid % R, t = tid / R;
+    const int row = blockIdx.x * R + r;
+    const bool valid = row < M;
+    const bf16_t *xr = x + (size_t)(valid ? row : M - 1) * d;
     const int nchunk = d >> 3;
+    // the thread's chunks t, t + TPR, ... stay in registers between the two passes (NC of them at most:
+    // the launcher picks NC >= nchunk / TPR); all loads are in flight at once
+    bf16x8 xv[NC];
     float ss = 0.f;
-    for (int c = tid; c < nchunk; c += 256) {
-        bf16x8 v = ld_bf16x8(xr + c * 8);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float f = (float)v[i];
+    for (int i = 0; i < NC; ++i) {
+        const int c = t + i * TPR;
+        xv[i] = c < nchunk ? ld_bf16x8(xr + c * 8) : zero_bf16x8();
+    }
+#pragma unroll
+    for (int i = 0; i < NC; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float f = (float)xv[i][e];
             ss += f * f;
         }
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    // lanes with the same (lane % R) hold the same row: butterfly over the other lane bits, then the 4 waves
+#pragma unroll
+    for (int o = 32; o >= R; o >>= 1) ss += __shfl_xor(ss, o, 64);
+    if ((tid & 63) < R) red[tid >> 6][tid & 63] = ss;
     __syncthreads();
-    float tot = (red[0] + red[1]) + (red[2] + red[3]);
-    float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    bf16_t *orow = out + (size_t)row * d;
-    for (int c = tid; c < nchunk; c += 256) {
-        bf16x8 v = ld_bf16x8(xr + c * 8);
-        bf16x8 gv = ld_bf16x8(g + c * 8);
+    const float tot = (red[0][r] + red[1][r]) + (red[2][r] + red[3][r]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    if (!valid) return;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = t + i * TPR;
+        if (c >= nchunk) break;
+        const bf16x8 gv = ld_bf16x8(g + c * 8);
         bf16x8 o;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = (bf16_t)((float)v[i] * inv * (float)gv[i]);
-        st_bf16x8(packed ? out + packed_chunk_offset(row, c * 8) : orow + c * 8, o);
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)xv[i][e] * inv * (float)gv[e]);
+        st_bf16x8(out + packed_offset(row, c * 8, Mt), o);
     }
 }
 
-void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
-                    float eps, bool packed) {
+void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d, float eps) {
     if (M <= 0) return;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, st, x, g, out, d, eps, packed ? 1 : 0);
+    const int nchunk = d >> 3, Mt = packed_mt(M);
+    // R and NC are functions of (M, d) only
+    if (M >= 512 && nchunk <= 16 * 32)
+        hipLaunchKernelGGL((rmsnorm_kernel<8, 16>), dim3((M + 7) / 8), dim3(256), 0, st, x, g, out, M, d, eps, Mt);
+    else if (M >= 512 && nchunk <= 32 * 32)
+        hipLaunchKernelGGL((rmsnorm_kernel<8, 32>), dim3((M + 7) / 8), dim3(256), 0, st, x, g, out, M, d, eps, Mt);
+    else if (nchunk <= 8 * 256)
+        hipLaunchKernelGGL((rmsnorm_kernel<1, 8>), dim3(M), dim3(256), 0, st, x, g, out, M, d, eps, Mt);
+    else
+        hipLaunchKernelGGL((rmsnorm_kernel<1, 32>), dim3(M), dim3(256), 0, st, x, g, out, M, d, eps, Mt);
 }
 
 // ---------------------------------------------------------------------------------------------

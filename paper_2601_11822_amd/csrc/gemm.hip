@@ -1,9 +1,11 @@
 // bf16 GEMMs out = epi(A[M,K] * W[N,K]^T) on the gfx950 matrix cores (fp32 accumulation).
 //
-// Both operands are K-contiguous, so a lane's 8-element MFMA fragment is one 16-byte load.
+// A lane's 8-element MFMA fragment is 8 consecutive k of one row: one 16-byte chunk, and the unit
+// of the fragment-packed operand layout (packed_offset) that the activations are always stored in.
 // The weight tile is the MFMA "row" operand and the activation tile the "column" operand:
 // a lane then owns 4 consecutive output columns of one output row, which makes the epilogues
 // (residual add, SwiGLU, bf16 pack) plain per-lane code with 8-byte stores.
+#include <algorithm>
 #include <type_traits>
 
 #include "kernels.h"
@@ -12,10 +14,15 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// 4 consecutive output columns (n % 4 == 0) of row m
+__device__ __forceinline__ void store_out4(const GemmArgs &a, int m, int n, bf16x4 v) {
+    bf16_t *dst = a.out_packed ? a.out + packed_offset(m, n, packed_mt(a.M)) + (n & 7) : a.out + (size_t)m * a.N + n;
+    *(bf16x4 *)dst = v;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Tiled kernel: BM x BN output tile per 256-thread workgroup (2x2 waves), BK = 64, operands
-// staged global -> registers -> LDS (16-byte chunks, chunk index XOR (row>>1)&7 against bank
+// (fragment-packed A, row-major W) staged global -> registers -> LDS (16-byte chunks, chunk index XOR (row>>1)&7 against bank
 // conflicts on the 64-bank LDS), next tile's global loads in flight during the MFMAs.  Every tail (M, N, K) is
 // handled by predicated zero-filled loads and predicated stores.
 //
@@ -42,12 +49,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     const bf16_t *pa[CA];
     const bf16_t *pb[CB];
     const int cc = tid & 7;  // chunk column (same for all of a thread's chunks)
+    const int Mt = packed_mt(M);
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
         const int r = (tid >> 3) + 32 * j;
         const int m = bm + r;
-        pa[j] = (m < M) ? a.A + (size_t)m * K + cc * 8 : nullptr;
+        pa[j] = (m < M) ? a.A + packed_offset(m, cc * 8, Mt) : nullptr;   // chunk (m, k0 + 8cc) for k0 = 0
     }
+    const size_t a_kmul = (size_t)Mt * 32;   // a step of 64 in k is 4 k blocks of Mt KB
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
         const int r = (tid >> 3) + 32 * j;  // row of the B tile
@@ -73,7 +82,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     auto gload = [&](int k0) {
         const bool kin = k0 + cc * 8 < K;
 #pragma unroll
-        for (int j = 0; j < CA; ++j) ra[j] = (kin && pa[j]) ? ld_bf16x8(pa[j] + k0) : zero_bf16x8();
+        for (int j = 0; j < CA; ++j) ra[j] = (kin && pa[j]) ? ld_bf16x8(pa[j] + k0 * a_kmul) : zero_bf16x8();
 #pragma unroll
         for (int j = 0; j < CB; ++j) rb[j] = (kin && pb[j]) ? ld_bf16x8(pb[j] + k0) : zero_bf16x8();
     };
@@ -128,7 +137,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         v[i] = (bf16_t)(silu_f(acc[2 * p][tm][4 * j + i]) * acc[2 * p + 1][tm][4 * j + i]);
-                    *(bf16x4 *)(a.out + (size_t)m * N + f) = v;
+                    store_out4(a, m, f, v);
                 }
         } else {
 #pragma unroll
@@ -146,24 +155,28 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[tn][tm][4 * j + i];
                     }
-                    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+                    store_out4(a, m, n, v);
                 }
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Direct kernel (K % 32 == 0): same tiling and epilogues as the tiled kernel, but the operand
-// tiles go global -> LDS with the 16-byte LDS-DMA load (no register staging) through a ring of
-// NS LDS stages of BK = 32, so that a K tile is requested NS-1 tiles (several microseconds of
-// MFMA work) before it is consumed: HBM latency is covered although only one wave runs per SIMD.
+// Direct kernel (K % 32 == 0): same tiling and epilogues as the tiled kernel, but both operands
+// are read in the fragment-packed layout (activations as their producers wrote them, weights from
+// the library's packed copies) and go global -> LDS with the 16-byte LDS-DMA load (no register
+// staging) through a ring of NS LDS stages of BK = 32, so that a K tile is requested NS-1 tiles
+// (several microseconds of MFMA work) before it is consumed: HBM latency is covered although only
+// one wave runs per SIMD.
 //
-// A wave-wide load fills 1 KB = 16 rows x 64 B.  The LDS has 64 four-byte banks, so four rows
-// span the banks once; 16 lanes reading one logical 16-byte chunk of 16 consecutive rows are
-// conflict free when the stored chunk index is chunk ^ ((row >> 2) & 3).  The swizzle is applied
-// by permuting which global chunk each lane fetches.  Rows past M or N are clamped to the last
-// valid row (their results are never stored); K tiles past the end re-fetch the last tile into a
-// stage nobody reads, which keeps the loop body branch free.
+// A wave-wide load moves one 1 KB fragment block (32 rows x 16 k), lane l fetching and storing
+// chunk l: the slab of a K tile is BM/32 + BN/32 contiguous kilobytes per k block, which spreads
+// over the memory channels (a row-major operand would give one 64-byte piece per 2K-byte-strided
+// row, crowding a few channels: the DMA fill rate of this tile walk measured 13 TB/s row-major
+// and 22 TB/s packed).  In LDS a block keeps the lane order, so a fragment read is 64 consecutive
+// 16-byte chunks: conflict free without a swizzle.  Row tiles past M or N are clamped to the last
+// tile (their results are never stored); K tiles past the end re-fetch the last tile into a stage
+// nobody reads, which keeps the loop body branch free.
 //
 // Per K tile (two MFMA steps, one barrier): the loads of tile kt+NS-1 trickle out between the
 // MFMAs; step 0 reads the step-1 fragments; step 1 waits until tile kt+1 has landed (vmcnt counts
@@ -178,51 +191,49 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     constexpr int WGN = NW / 2;                      // waves: 2 along M x NW/2 along N
     constexpr int WM = BM / 2, WN = BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int LA = BM / (16 * NW), LB = BN / (16 * NW);   // wave-wide loads per wave per stage
-    constexpr int STAGE = (BM + BN) * BK;            // elements per stage
+    constexpr int TA = BM / 32, TB = BN / 32;        // 32-row blocks per k block of the tile
+    constexpr int LA = 2 * TA / NW, LB = 2 * TB / NW;   // wave-wide loads per wave per stage
+    constexpr int STAGE = (BM + BN) * BK;            // elements per stage: [2][TA] A blocks, then [2][TB] B blocks
     constexpr int D = NS - 1;                        // prefetch distance in K tiles
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave / WGN, wn = wave % WGN;
     const int c32 = lane & 31, h = lane >> 5;
     const int M = a.M, N = a.N, K = a.K;
+    const int Mt = packed_mt(M), Nt = ((N + 63) / 64) * 2;   // row tiles per k block of A and of the weights
 
-    const int lrow = lane >> 2;                                     // row within the 16-row group
-    const int lchunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 3;       // element offset of the fetched chunk
     const bf16_t *pa[LA];
     const bf16_t *pb[LB];
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        const int r = (wave * LA + j) * 16 + lrow;
-        pa[j] = a.A + (size_t)min(bm + r, M - 1) * K + lchunk;
+        const int q = wave * LA + j, s = q / TA, t = q % TA;
+        pa[j] = a.A + ((size_t)s * Mt + min((bm >> 5) + t, Mt - 1)) * 512 + lane * 8;
     }
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
-        const int r = (wave * LB + j) * 16 + lrow;
-        if (EPI == EPI_SWIGLU) {
-            const int tt = r >> 5;
-            const int f = min(nb * (BN / 2) + (tt >> 1) * 32 + (r & 31), N - 1);
-            pb[j] = ((tt & 1) ? a.W2 : a.W) + (size_t)f * K + lchunk;
-        } else {
-            pb[j] = a.W + (size_t)min(nb * BN + r, N - 1) * K + lchunk;
-        }
+        const int q = wave * LB + j, s = q / TB, t = q % TB;
+        if (EPI == EPI_SWIGLU)   // blocks alternate: 32 gate rows, the 32 matching up rows
+            pb[j] = ((t & 1) ? a.Wp2 : a.Wp) + ((size_t)s * Nt + min(nb * (TB / 2) + (t >> 1), Nt - 1)) * 512 + lane * 8;
+        else
+            pb[j] = a.Wp + ((size_t)s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8;
     }
+    const size_t ksa = (size_t)Mt * 1024, ksb = (size_t)Nt * 1024;   // elements per K tile (2 k blocks)
     const int nk = K / BK;
     // loads [j0, j1) of the LA + LB wave-wide loads that bring K tile kt into its stage
     auto issue = [&](int kt, int j0, int j1) {
         const int stage = kt % NS;
-        const int k0 = min(kt, nk - 1) * BK;
+        const size_t kc = (size_t)min(kt, nk - 1);
         bf16_t *sa = smem + stage * STAGE;
         bf16_t *sb = sa + BM * BK;
 #pragma unroll
         for (int j = 0; j < LA + LB; ++j) {
             if (j < j0 || j >= j1) continue;
             if (j < LA)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + k0),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + kc * ksa),
                                                  (__attribute__((address_space(3))) void *)(sa + (wave * LA + j) * 512),
                                                  16, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j - LA] + k0),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j - LA] + kc * ksb),
                                                  (__attribute__((address_space(3))) void *)(sb + (wave * LB + j - LA) * 512),
                                                  16, 0, 0);
         }
@@ -236,17 +247,14 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int x3 = (c32 >> 2) & 3;
-    const int a_row = (wm * WM + c32) * BK, b_row = (wn * WN + c32) * BK;
     bf16x8 wf[2][TN], xf[2][TM];
     auto read_frags = [&](int set, int kt, int step) {
-        const bf16_t *sa = smem + (kt % NS) * STAGE;
+        const bf16_t *sa = smem + (kt % NS) * STAGE + lane * 8;
         const bf16_t *sb = sa + BM * BK;
-        const int co = ((2 * step + h) ^ x3) << 3;
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) wf[set][tn] = *(const bf16x8 *)&sb[b_row + tn * 32 * BK + co];
+        for (int tn = 0; tn < TN; ++tn) wf[set][tn] = *(const bf16x8 *)&sb[(step * TB + wn * TN + tn) * 512];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) xf[set][tm] = *(const bf16x8 *)&sa[a_row + tm * 32 * BK + co];
+        for (int tm = 0; tm < TM; ++tm) xf[set][tm] = *(const bf16x8 *)&sa[(step * TA + wm * TM + tm) * 512];
     };
 #pragma unroll
     for (int i = 0; i < D; ++i) issue(i, 0, LA + LB);
@@ -309,7 +317,7 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         v[i] = (bf16_t)(silu_f(acc[2 * p][tm][4 * j + i]) * acc[2 * p + 1][tm][4 * j + i]);
-                    *(bf16x4 *)(a.out + (size_t)m * N + f) = v;
+                    store_out4(a, m, f, v);
                 }
         } else {
 #pragma unroll
@@ -327,7 +335,7 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
 #pragma unroll
                         for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[tn][tm][4 * j + i];
                     }
-                    *(bf16x4 *)(a.out + (size_t)m * N + n) = v;
+                    store_out4(a, m, n, v);
                 }
         }
     }
@@ -425,26 +433,40 @@ static void launch_tiled(hipStream_t st, const GemmArgs &a) {
     }
 }
 
+// Tile shapes of the direct kernel and their cost per tile relative to a 256x256 tile (area over
+// measured relative efficiency).  The schedule with the fewest weighted rounds on the partition's
+// compute units wins; the arithmetic of an output element is the same in all of them.
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
     if (a.M <= 0 || a.N <= 0) return;
     const bool aligned = (a.K % 32 == 0) && a.K >= 32;
-    if (aligned && a.M >= 512 && a.N >= 1024) {
-        // tile shapes follow the problem shape; only the last-half-round schedule looks at the
-        // size of the partition
-        const long tiles256 = (long)((a.M + 255) / 256) * ((a.epi == EPI_SWIGLU ? 2 * a.N : a.N) / 256);
+    if (aligned && a.Wp && a.M >= 512 && a.N >= 1024) {
         const int cus = a.cus > 0 ? a.cus : 256;
-        const int n_full = (int)(tiles256 / cus) * cus, rest = (int)tiles256 - n_full;
-        if (tiles256 >= 256 && n_full > 0 && n_full % 8 == 0 && rest > 0 && 2 * rest <= cus) {
-            const int m_tiles = (a.M + 255) / 256;
-            switch (a.epi) {
-                case EPI_STORE: launch_direct_mixed_epi<EPI_STORE>(st, a, m_tiles, n_full, 2 * rest); break;
-                case EPI_RESIDUAL: launch_direct_mixed_epi<EPI_RESIDUAL>(st, a, m_tiles, n_full, 2 * rest); break;
-                default: launch_direct_mixed_epi<EPI_SWIGLU>(st, a, m_tiles, n_full, 2 * rest); break;
-            }
-        } else if (tiles256 >= 256)
+        const int nv = a.epi == EPI_SWIGLU ? 2 * a.N : a.N;
+        const int mt256 = (a.M + 255) / 256, mt128 = (a.M + 127) / 128;
+        const long t_full = (long)mt256 * ((nv + 255) / 256), t_half = (long)mt128 * ((nv + 255) / 256);
+        const long t_192 = (long)mt256 * ((a.N + 191) / 192);
+        auto rounds = [&](long t) { return (double)((t + cus - 1) / cus); };
+        constexpr double C_HALF = 0.59, C_192 = 0.79;
+        const double cost_full = rounds(t_full), cost_half = rounds(t_half) * C_HALF;
+        const double cost_192 = a.epi == EPI_SWIGLU ? 1e30 : rounds(t_192) * C_192;
+        const int n_full = (int)(t_full / cus) * cus, rest = (int)t_full - n_full;
+        const bool mixed_ok = n_full > 0 && n_full % 8 == 0 && rest > 0 && 2 * rest <= cus;
+        const double cost_mixed = mixed_ok ? n_full / cus + C_HALF : 1e30;
+        const double best = std::min(std::min(cost_full, cost_mixed), std::min(cost_half, cost_192));
+        if (best == cost_full) {
             launch_direct<256, 256, 4, 4>(st, a);   // 4 x 32 KB of LDS
-        else
+        } else if (best == cost_mixed) {
+            switch (a.epi) {
+                case EPI_STORE: launch_direct_mixed_epi<EPI_STORE>(st, a, mt256, n_full, 2 * rest); break;
+                case EPI_RESIDUAL: launch_direct_mixed_epi<EPI_RESIDUAL>(st, a, mt256, n_full, 2 * rest); break;
+                default: launch_direct_mixed_epi<EPI_SWIGLU>(st, a, mt256, n_full, 2 * rest); break;
+            }
+        } else if (best == cost_192) {
+            if (a.epi == EPI_STORE) launch_direct_epi<256, 192, EPI_STORE, 4, 4>(st, a);   // 4 x 28 KB
+            else launch_direct_epi<256, 192, EPI_RESIDUAL, 4, 4>(st, a);
+        } else {
             launch_direct<128, 256, 5, 4>(st, a);   // 5 x 24 KB of LDS
+        }
     } else if (a.M >= 1024 && a.N >= 1024) {
         launch_tiled<256, 256>(st, a);
     } else {
@@ -536,14 +558,14 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *
     const int nsteps = max(min(kb0 + kbw, Kb) - kb0, 0);
     const int kb_last = Kb - 1;
 
-    // a.W / a.W2 are the packed matrices; row tile 0 / 1 of this workgroup
+    // row tile 0 / 1 of this workgroup in the packed matrices
     const bf16_t *w0, *w1;
     const size_t wstride = (size_t)((a.N + 63) / 64) * 1024;   // elements per k block
     if (EPI == EPI_SWIGLU) {
-        w0 = a.W + (size_t)blockIdx.x * 512 + lane * 8;
-        w1 = a.W2 + (size_t)blockIdx.x * 512 + lane * 8;
+        w0 = a.Wp + (size_t)blockIdx.x * 512 + lane * 8;
+        w1 = a.Wp2 + (size_t)blockIdx.x * 512 + lane * 8;
     } else {
-        w0 = a.W + (size_t)blockIdx.x * 1024 + lane * 8;
+        w0 = a.Wp + (size_t)blockIdx.x * 1024 + lane * 8;
         w1 = w0 + 512;
     }
     const bf16_t *x = a.A + lane * 8;
@@ -645,8 +667,7 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
             for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[i];
         }
     }
-    bf16_t *dst = a.out_packed ? a.out + packed_chunk_offset(m, n) + (n & 7) : a.out + (size_t)m * N + n;
-    *(bf16x4 *)dst = v;
+    store_out4(a, m, n, v);
 }
 
 template <int EPI>
@@ -666,7 +687,6 @@ static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials
     hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
 }
 
-// a.A is fragment-packed, a.W / a.W2 are the packed weight matrices (launch_pack_weights).
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
     if (a.M <= 0 || a.N <= 0) return;
     switch (a.epi) {

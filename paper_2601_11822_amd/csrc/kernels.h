@@ -6,9 +6,8 @@
 #include "common.h"
 
 // out[m,:] = x[m,:] * rsqrt(mean(x[m,:]^2) + eps) * g      (bf16 in, fp32 math, bf16 out)
-// packed: write `out` in the fragment-packed layout (see packed_chunk_offset; M <= 64 only).
-void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d,
-                    float eps, bool packed = false);
+// x is row-major [M][d]; `out` is written fragment-packed (packed_offset with packed_mt(M) row tiles).
+void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *out, int M, int d, float eps);
 
 struct RopeKvArgs {
     bf16_t *qkv;            // [M][nqkv]; q part rotated in place
@@ -26,7 +25,7 @@ void launch_rope_kvwrite(hipStream_t st, const RopeKvArgs &a);
 struct PrefillAttnArgs {
     const bf16_t *q;  // [T][q_stride] (rotated)
     int q_stride;
-    bf16_t *out;  // [T][Hq*hd]
+    bf16_t *out;  // [T][Hq*hd], fragment-packed (packed_mt(T) row tiles)
     const bf16_t *k_pool, *v_pool;
     const int32_t *tables;
     int32_t *err_flag;
@@ -39,7 +38,7 @@ void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a);
 struct DecodeAttnArgs {
     const bf16_t *q;  // [B][q_stride]
     int q_stride;
-    bf16_t *out;  // [B][Hq*hd]
+    bf16_t *out;  // [B][Hq*hd], fragment-packed (packed_mt(B) row tiles)
     const bf16_t *k_pool, *v_pool;
     const int32_t *tables;
     const int32_t *ctx_lens;
@@ -48,7 +47,6 @@ struct DecodeAttnArgs {
     float *part_ml;  // [B][Hq][n_chunks][2]
     int B, Hq, Hkv, hd, max_blk, n_blocks, max_ctx, n_chunks;
     float scale_log2;
-    int out_packed;  // write `out` fragment-packed (B <= 64)
 };
 #define RS_SKINNY_TARGET_WGS 384  // the skinny GEMM splits K until it has about this many workgroups
 #define RS_DECODE_CHUNK 1024  // tokens per workgroup of the decode attention
@@ -58,23 +56,24 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
 
 // out[M,N] = epi(A[M,K] * W[N,K]^T).  EPI_RESIDUAL adds resid[M,N].  EPI_SWIGLU:
 // out[M,N] = silu(A*W^T) * (A*W2^T) with W, W2 both [N,K].
+// A is always fragment-packed (packed_offset, packed_mt(M) row tiles).  W / W2 are the caller's
+// row-major matrices (read by the tail-safe tiled kernel), Wp / Wp2 the library's fragment-packed
+// copies of the same matrices (launch_pack_weights; read by the direct and the skinny kernels).
 struct GemmArgs {
     const bf16_t *A;
-    const bf16_t *W;
-    const bf16_t *W2;
-    const bf16_t *resid;
-    bf16_t *out;
+    const bf16_t *W, *W2;
+    const bf16_t *Wp, *Wp2;
+    const bf16_t *resid;  // row-major [M][N]
+    bf16_t *out;          // row-major [M][N], or fragment-packed when it feeds another GEMM
     int M, N, K;
     int epi;
-    int out_packed = 0;  // skinny path only: write `out` fragment-packed (it feeds another skinny GEMM)
-    int cus = 0;         // compute units of the launching stream's partition (0: the whole chip); scheduling only
+    int out_packed = 0;
+    int cus = 0;  // compute units of the launching stream's partition (0: the whole chip); scheduling only
 };
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 
 // Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through
-// `partials` (fp32, at least skinny_partial_elems(...) elements).  A must be fragment-packed.
-// a.W / a.W2 must be the fragment-packed copies made by launch_pack_weights (packed_weight_elems
-// elements each).
+// `partials` (fp32, at least skinny_partial_elems(...) elements).  Reads A, Wp and Wp2.
 size_t skinny_partial_elems(int M, int N, int K, int epi);
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
 size_t packed_weight_elems(int N, int K);

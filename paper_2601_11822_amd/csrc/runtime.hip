@@ -74,13 +74,13 @@ struct rs_ctx {
     bool gpu = false;
     std::vector<rs_layer_weights> weights;
     std::vector<bool> have_weights;
-    // fragment-packed private copies of the five matrices, read by the decode side's skinny GEMMs
+    // fragment-packed private copies of the five matrices, read by the direct and the skinny GEMMs
     struct PackedLayer { bf16_t *wqkv = nullptr, *wo = nullptr, *wg = nullptr, *wu = nullptr, *wd = nullptr; };
     std::vector<PackedLayer> packed;
     CosSin *rope = nullptr;
     int32_t *err_flag = nullptr;
     Workspace ws[2];
-    bool decode_packed = false;  // the decode side's last layer call left h/attn/act fragment-packed
+    int last_rows[2] = {0, 0};   // rows of each side's last layer call: fixes the packed layout of h/attn/act
     Side side[2];
     bool over_alloc = true;
     bool kernel_timing = false;
@@ -139,14 +139,18 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     const size_t nqkv = qd + 2 * (size_t)m.n_kv_heads * m.head_dim, f = m.ffn_dim;
     w.rows = rows;
     if (rows <= 0) return RS_OK;
-    // the decode side keeps its GEMM inputs fragment-packed: always 64 rows x (width rounded to 16)
-    const size_t prow = decode ? std::max<size_t>(rows, 64) : rows;
-    auto r16 = [&](size_t v) { return decode ? (v + 15) / 16 * 16 : v; };
+    // GEMM inputs are kept fragment-packed: whole 32-row tiles x (width rounded to a k block of 16);
+    // zeroed once, so that the padding never holds a NaN pattern (producers write valid elements only)
+    const size_t prow = (size_t)packed_mt(rows) * 32;
+    auto r16 = [&](size_t v) { return (v + 15) / 16 * 16; };
     HIP_TRY(hipMalloc(&w.h, prow * r16(d) * 2));
+    HIP_TRY(hipMemset(w.h, 0, prow * r16(d) * 2));
     HIP_TRY(hipMalloc(&w.qkv, rows * nqkv * 2));
     HIP_TRY(hipMalloc(&w.attn, prow * r16(qd) * 2));
+    HIP_TRY(hipMemset(w.attn, 0, prow * r16(qd) * 2));
     HIP_TRY(hipMalloc(&w.x1, rows * d * 2));
     HIP_TRY(hipMalloc(&w.act, prow * r16(f) * 2));
+    HIP_TRY(hipMemset(w.act, 0, prow * r16(f) * 2));
     HIP_TRY(hipMalloc(&w.xbuf, rows * d * 2));
     if (decode) {
         const int Mmax = std::min(rows, 64);
@@ -270,17 +274,15 @@ void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
         if (skinny) launch_gemm_skinny(st, g, w.partials);
         else launch_gemm_tiled(st, g);
     };
-    // on the skinny (decode) path every GEMM input is kept fragment-packed by its producer
-    // ... and the weights are read from their packed copies
-    const bf16_t *wo = skinny ? pl.wo : (const bf16_t *)lw.wo, *wg = skinny ? pl.wg : (const bf16_t *)lw.wg;
-    const bf16_t *wu = skinny ? pl.wu : (const bf16_t *)lw.wu, *wd = skinny ? pl.wd : (const bf16_t *)lw.wd;
-    gemm(GemmArgs{w.attn, wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
+    // h, attn and act are fragment-packed by their producers; x1 and y are row-major
+    const bf16_t *wo = (const bf16_t *)lw.wo, *wg = (const bf16_t *)lw.wg, *wu = (const bf16_t *)lw.wu, *wd = (const bf16_t *)lw.wd;
+    gemm(GemmArgs{w.attn, wo, nullptr, pl.wo, nullptr, x, w.x1, M, d, qd, EPI_RESIDUAL});
     tick(c, side, 5);
-    launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps, skinny);
+    launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps);
     tick(c, side, 6);
-    gemm(GemmArgs{w.h, wg, wu, nullptr, w.act, M, f, d, EPI_SWIGLU, skinny ? 1 : 0});
+    gemm(GemmArgs{w.h, wg, wu, pl.wg, pl.wu, nullptr, w.act, M, f, d, EPI_SWIGLU, 1});
     tick(c, side, 7);
-    gemm(GemmArgs{w.act, wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
+    gemm(GemmArgs{w.act, wd, nullptr, pl.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
     tick(c, side, 8);
 }
 
@@ -310,10 +312,11 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
 
     tick(c, RS_SIDE_PREFILL, 0);
+    c->last_rows[RS_SIDE_PREFILL] = T;
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, T, d, m.rms_eps);
     tick(c, RS_SIDE_PREFILL, 1);
-    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, T, nqkv, d, EPI_STORE, 0,
-                                   c->side[RS_SIDE_PREFILL].cus});
+    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv,
+                                   T, nqkv, d, EPI_STORE, 0, c->side[RS_SIDE_PREFILL].cus});
     tick(c, RS_SIDE_PREFILL, 2);
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
@@ -344,12 +347,12 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
     const bool skinny = B <= 64;
-    c->decode_packed = skinny;
+    c->last_rows[RS_SIDE_DECODE] = B;
 
     tick(c, RS_SIDE_DECODE, 0);
-    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps, skinny);
+    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
     tick(c, RS_SIDE_DECODE, 1);
-    GemmArgs g{w.h, skinny ? c->packed[layer].wqkv : (const bf16_t *)lw.wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE,
+    GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE,
                0, c->side[RS_SIDE_DECODE].cus};
     if (skinny) launch_gemm_skinny(st, g, w.partials);
     else launch_gemm_tiled(st, g);
@@ -362,7 +365,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
                       B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
                       (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
-                      (float)(1.4426950408889634 / std::sqrt((double)hd)), skinny ? 1 : 0};
+                      (float)(1.4426950408889634 / std::sqrt((double)hd))};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
     run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
@@ -385,6 +388,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     if (m.head_dim != 64 && m.head_dim != 128) return fail(RS_ERR_BAD_ARG, "head_dim %d: only 64 and 128", m.head_dim);
     if (m.d_model < 8 || m.d_model % 8 || m.ffn_dim < 8 || m.ffn_dim % 8)
         return fail(RS_ERR_BAD_ARG, "d_model and ffn_dim must be positive multiples of 8");
+    if (m.d_model > 65536) return fail(RS_ERR_BAD_ARG, "d_model %d: at most 65536", m.d_model);
     if (m.n_kv_heads < 1 || m.n_q_heads < 1 || m.n_q_heads % m.n_kv_heads || m.n_q_heads / m.n_kv_heads > 16)
         return fail(RS_ERR_BAD_ARG, "need n_q_heads = G * n_kv_heads with 1 <= G <= 16");
     if (m.n_layers < 1 || m.max_pos < 1 || !(m.rope_base > 1.0f) || !(m.rms_eps >= 0.0f))
@@ -516,8 +520,8 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
     if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
     if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
-    if (c->gpu && c->lim.max_decode_batch > 0) {
-        // the decode side streams the matrices in MFMA fragment order: repack them once, here
+    if (c->gpu) {
+        // the GEMM kernels stream the matrices in MFMA fragment order: repack them once, here
         HIP_TRY(hipSetDevice(c->device));
         const rs_model_desc &m = c->m;
         const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
@@ -684,16 +688,18 @@ int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *ho
     }
     if (!src || (size_t)n_bytes > cap) return fail(RS_ERR_BAD_ARG, "workspace buffer %d holds %zu bytes", which, cap);
     if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
-    if (side == RS_SIDE_DECODE && c->decode_packed && (which == 0 || which == 2 || which == 4)) {
-        // undo the fragment-packed layout of the decode side's GEMM inputs: row-major out
+    if (which == 0 || which == 2 || which == 4) {
+        // undo the fragment-packed layout of the GEMM inputs: row-major out
         const int width = which == 0 ? m.d_model : which == 2 ? (int)qd : m.ffn_dim;
         const int rows = (int)((size_t)n_bytes / 2 / width);
-        if (rows > 64) return fail(RS_ERR_BAD_ARG, "packed buffers hold at most 64 rows");
-        std::vector<uint16_t> raw((size_t)64 * width);
+        const int Mt = packed_mt(c->last_rows[side]);
+        if (c->last_rows[side] < 1 || rows > c->last_rows[side])
+            return fail(RS_ERR_BAD_ARG, "the side's last layer call had %d rows", c->last_rows[side]);
+        std::vector<uint16_t> raw((size_t)Mt * 32 * ((width + 15) / 16 * 16));
         HIP_TRY(hipMemcpy(raw.data(), src, raw.size() * 2, hipMemcpyDeviceToHost));
         uint16_t *dst = (uint16_t *)host_out;
         for (int r = 0; r < rows; ++r)
-            for (int k = 0; k < width; ++k) dst[(size_t)r * width + k] = raw[packed_chunk_offset(r, k) + (k & 7)];
+            for (int k = 0; k < width; ++k) dst[(size_t)r * width + k] = raw[packed_offset(r, k, Mt) + (k & 7)];
         return RS_OK;
     }
     HIP_TRY(hipMemcpy(host_out, src, (size_t)n_bytes, hipMemcpyDeviceToHost));
