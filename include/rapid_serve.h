@@ -118,7 +118,12 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
                 const rs_profile *prof, int32_t device, rs_ctx **out);
 /* Waits for both sides, frees everything the library owns. */
 int32_t rs_destroy(rs_ctx *ctx);
-/* Registers (borrows) the weights of one layer. */
+/* Registers (borrows) the weights of one layer, and, on a GPU context, makes the library's own
+ * copy of the five matrices in the order its GEMM kernels read them (MFMA fragment order;
+ * device memory of about the same size, owned by the context and freed by rs_destroy; allocates
+ * and synchronises the device: a set-up call, not a hot-path call).  The caller's matrices must
+ * stay valid and unchanged while the context uses the layer; after changing one, call
+ * rs_set_weights again.  Errors: RS_ERR_BAD_ARG (null pointer, layer out of range), RS_ERR_HIP. */
 int32_t rs_set_weights(rs_ctx *ctx, int32_t layer, const rs_layer_weights *w);
 const char *rs_last_error(void);
 

@@ -192,3 +192,17 @@ def test_decode_batch_cap_and_fcfs_promotion():
     c.debug_complete_prefill(2)
     so = c.step()                              # 0 retires; 1 (older) is promoted before 2
     assert c.request_state(0) == 5 and c.request_state(1) == 4 and c.request_state(2) == 3
+
+
+def test_operand_layouts_shared_by_host_and_kernels(tmp_path):
+    """packed_offset / packed_mt / kpool_chunk_offset are bijections with the fragment structure the
+    kernels assume; checked on the host by a small program compiled against the kernels' own header."""
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "host_layout_check.hip")
+    exe = str(tmp_path / "host_layout_check")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O1", "-std=c++17", src, "-o", exe], check=True,
+                   stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
