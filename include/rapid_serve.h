@@ -200,6 +200,10 @@ int32_t rs_sync(rs_ctx *ctx, int32_t side);
  * the time from (side_begin, slot_begin) to (side_end, slot_end). */
 #define RS_MAX_MARKS 4096
 int32_t rs_mark(rs_ctx *ctx, int32_t side, int32_t slot);
+/* Non-blocking: *done_out = 1 if the work in front of the mark has completed, else 0.  For a
+ * host loop that keeps one side fed while it watches the other.  RS_ERR_STATE if the slot was
+ * never recorded. */
+int32_t rs_mark_done(rs_ctx *ctx, int32_t side, int32_t slot, int32_t *done_out);
 int32_t rs_elapsed_ms(rs_ctx *ctx, int32_t side_begin, int32_t slot_begin, int32_t side_end, int32_t slot_end,
                       float *ms_out);
 /* Per-kernel timing of layer calls.  While on, every layer call records an event between its

@@ -29,7 +29,7 @@ RS_CU_HIST_BINS = 4096
 EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_set_cu_split", "rs_get_cu_split",
-    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_elapsed_ms", "rs_set_kernel_timing", "rs_kernel_times",
+    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
 ]
 
@@ -260,6 +260,12 @@ class Context:
 
     def mark(self, side: int, slot: int):
         _check(self._lib.rs_mark(self._h, ctypes.c_int32(side), ctypes.c_int32(slot)))
+
+    def mark_done(self, side: int, slot: int) -> bool:
+        """True once the work enqueued in front of the mark has completed (non-blocking)."""
+        done = ctypes.c_int32(0)
+        _check(self._lib.rs_mark_done(self._h, ctypes.c_int32(side), ctypes.c_int32(slot), ctypes.byref(done)))
+        return bool(done.value)
 
     def elapsed_ms(self, side_begin: int, slot_begin: int, slot_end: int, side_end: Optional[int] = None) -> float:
         ms = ctypes.c_float(0)

@@ -112,11 +112,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
         bf16x8 kA[KS], kB[KS], vf[DT];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            kA[s] = ld_bf16x8(kp + 512 * s);
-            kB[s] = ld_bf16x8(kp + 512 * s + 64);
+            kA[s] = ld_bf16x8_stream(kp + 512 * s);
+            kB[s] = ld_bf16x8_stream(kp + 512 * s + 64);
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = ld_bf16x8(vp + dt * 256);
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = ld_bf16x8_stream(vp + dt * 256);
 
         f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll

@@ -581,8 +581,8 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *
     bf16x8 rw0[PD], rw1[PD], rx0[PD], rx1[PD];
     auto load = [&](int p, int step) {
         const size_t kb = (size_t)min(kb0 + step, kb_last);
-        rw0[p] = ld_bf16x8(w0 + kb * wstride);
-        rw1[p] = ld_bf16x8(w1 + kb * wstride);
+        rw0[p] = ld_bf16x8_stream(w0 + kb * wstride);
+        rw1[p] = ld_bf16x8_stream(w1 + kb * wstride);
         rx0[p] = ld_bf16x8(x + kb * 1024);
         rx1[p] = ld_bf16x8(x + kb * 1024 + 512);
     };

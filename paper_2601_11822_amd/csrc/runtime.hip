@@ -639,6 +639,17 @@ int32_t rs_mark(rs_ctx *c, int32_t side, int32_t slot) {
     return RS_OK;
 }
 
+int32_t rs_mark_done(rs_ctx *c, int32_t side, int32_t slot, int32_t *done_out) {
+    if (!c || !done_out || side < 0 || side > 1 || slot < 0 || slot >= RS_MAX_MARKS) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    hipEvent_t e = c->side[side].marks[slot];
+    if (!e) return fail(RS_ERR_STATE, "mark not recorded");
+    const hipError_t q = hipEventQuery(e);
+    if (q != hipSuccess && q != hipErrorNotReady) HIP_TRY(q);
+    *done_out = q == hipSuccess ? 1 : 0;
+    return RS_OK;
+}
+
 int32_t rs_elapsed_ms(rs_ctx *c, int32_t side_a, int32_t a, int32_t side_b, int32_t b, float *ms) {
     if (!c || !ms || side_a < 0 || side_a > 1 || side_b < 0 || side_b > 1 || a < 0 || b < 0 || a >= RS_MAX_MARKS ||
         b >= RS_MAX_MARKS)
