@@ -21,7 +21,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // =============================================================================================
 // Decode: one query token per request, keys gathered through the block table.
-// Workgroup = (1024-token chunk, kv head, request); its 4 waves take 256 tokens (16 blocks) each,
+// Workgroup = (512-token chunk, kv head, request); its 4 waves take 128 tokens (8 blocks) each,
 // two blocks per iteration.  The G = Hq/Hkv query heads that share the kv head are the (zero
 // padded) 16 columns of the MFMA tiles, so every K/V byte is fetched once per kv head, straight
 // from the pools into MFMA fragments with 16-byte loads (no LDS staging).
@@ -34,7 +34,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // product, and the matching V fragment V[block h>>1][d][8(h&1)..+8] is one 16-byte load.
 // =============================================================================================
 template <int HD>
-__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeAttnArgs a) {
+__global__ __launch_bounds__(256, 3) void decode_attn_kernel(DecodeAttnArgs a) {
     constexpr int KS = HD / 32;  // 16x16x32 steps over head_dim for S^T
     constexpr int DT = HD / 16;  // 16-row tiles of O^T
     extern __shared__ float smem_dec[];   // [4][HD][G] partial outputs, then [4][G] max, [4][G] sum

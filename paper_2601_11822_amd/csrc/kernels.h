@@ -49,7 +49,7 @@ struct DecodeAttnArgs {
     float scale_log2;
 };
 #define RS_SKINNY_TARGET_WGS 384  // the skinny GEMM splits K until it has about this many workgroups
-#define RS_DECODE_CHUNK 1024  // tokens per workgroup of the decode attention
+#define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention
 void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a);
 
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
