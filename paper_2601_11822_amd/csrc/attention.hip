@@ -7,6 +7,8 @@
 //
 // Both kernels evaluate S^T = K Q^T and O^T = V^T P^T, so that a lane owns one query column:
 // the running maximum and sum of the online softmax are per-lane scalars.
+#include <type_traits>
+
 #include "kernels.h"
 
 #define NEG_INF (-__builtin_huge_valf())
@@ -34,7 +36,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // product, and the matching V fragment V[block h>>1][d][8(h&1)..+8] is one 16-byte load.
 // =============================================================================================
 template <int HD>
-__global__ __launch_bounds__(256, 3) void decode_attn_kernel(DecodeAttnArgs a) {
+__global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a) {
     constexpr int KS = HD / 32;  // 16x16x32 steps over head_dim for S^T
     constexpr int DT = HD / 16;  // 16-row tiles of O^T
     extern __shared__ float smem_dec[];   // [4][HD][G] partial outputs, then [4][G] max, [4][G] sum
@@ -96,33 +98,38 @@ __global__ __launch_bounds__(256, 3) void decode_attn_kernel(DecodeAttnArgs a) {
     const bf16_t *v_head = a.v_pool + (size_t)hk * 16 * HD;
     const float sc = a.scale_log2;
 
-#pragma unroll
-    for (int it = 0; it < WT / 32; ++it) {
-        const int base = t0 + 32 * it;
-        if (base >= t1) break;
-        // the iteration's two block ids as wave-uniform scalars
+    // Two register buffers of one iteration's K and V fragments (32 tokens, 16 KB per wave): the loads
+    // of iteration it+1 are issued before iteration it is computed, so the wave always has bytes in
+    // flight.  The number of iterations is wave-uniform; each count gets its own straight-line copy
+    // of the schedule, which keeps the compiler's wait counts exact (a load issued under a branch
+    // would force a wait for everything at the join).
+    bf16x8 kA[2][KS], kB[2][KS], vf[2][DT];
+    auto issue = [&](int it, int buf) {
+        // the iteration's two block ids as wave-uniform scalars; blocks that are missing (past the
+        // context, or rejected) read block 0: valid memory whose contents are masked out in compute()
         const int b0 = __builtin_amdgcn_readlane(my_blk, 2 * it);
         const int b1 = __builtin_amdgcn_readlane(my_blk, 2 * it + 1);
-        const bool full = base + 32 <= n_keys && b0 >= 0 && b1 >= 0;   // uniform: every token valid
-        // blocks that are missing (past the context, or rejected) read block 0: valid memory whose
-        // contents are masked out below
         const size_t o0 = (size_t)max(b0, 0) * blk_stride, o1 = (size_t)max(b1, 0) * blk_stride;
         const bf16_t *kp = k_head + (k_second ? o1 : o0) + k_lane;
         const bf16_t *vp = v_head + (v_second ? o1 : o0) + v_lane;
-        bf16x8 kA[KS], kB[KS], vf[DT];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            kA[s] = ld_bf16x8_stream(kp + 512 * s);
-            kB[s] = ld_bf16x8_stream(kp + 512 * s + 64);
+            kA[buf][s] = ld_bf16x8_stream(kp + 512 * s);
+            kB[buf][s] = ld_bf16x8_stream(kp + 512 * s + 64);
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = ld_bf16x8_stream(vp + dt * 256);
-
+        for (int dt = 0; dt < DT; ++dt) vf[buf][dt] = ld_bf16x8_stream(vp + dt * 256);
+    };
+    auto compute = [&](int it, int buf) {
+        const int base = t0 + 32 * it;
+        const int b0 = __builtin_amdgcn_readlane(my_blk, 2 * it);
+        const int b1 = __builtin_amdgcn_readlane(my_blk, 2 * it + 1);
+        const bool full = base + 32 <= n_keys && b0 >= 0 && b1 >= 0;   // uniform: every token valid
         f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            sA = mfma16(kA[s], qf[s], sA);
-            sB = mfma16(kB[s], qf[s], sB);
+            sA = mfma16(kA[buf][s], qf[s], sA);
+            sB = mfma16(kB[buf][s], qf[s], sB);
         }
         // this lane's 8 scores are tokens tok0 .. tok0+7 (A: +0..3, B: +4..7) of its V block
         if (!full) {
@@ -140,10 +147,10 @@ __global__ __launch_bounds__(256, 3) void decode_attn_kernel(DecodeAttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
-                u32x4v raw = __builtin_bit_cast(u32x4v, vf[dt]);
+                u32x4v raw = __builtin_bit_cast(u32x4v, vf[buf][dt]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) raw[j] &= msk[j];
-                vf[dt] = __builtin_bit_cast(bf16x8, raw);
+                vf[buf][dt] = __builtin_bit_cast(bf16x8, raw);
             }
         }
         float m_tile = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3])));
@@ -170,7 +177,26 @@ __global__ __launch_bounds__(256, 3) void decode_attn_kernel(DecodeAttnArgs a) {
         }
         l_run += psum;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] = mfma16(vf[dt], pf, o[dt]);
+        for (int dt = 0; dt < DT; ++dt) o[dt] = mfma16(vf[buf][dt], pf, o[dt]);
+    };
+    auto run = [&](auto ntag) {
+        constexpr int N = decltype(ntag)::value;
+        issue(0, 0);
+#pragma unroll
+        for (int it = 0; it < N; ++it) {
+            if (it + 1 < N) issue(it + 1, (it + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);   // the next iteration's loads go out before this one's arithmetic
+            compute(it, it & 1);
+        }
+    };
+    static_assert(WT / 32 == 4, "one schedule per iteration count below");
+    const int nit = t1 > t0 ? (t1 - t0 + 31) >> 5 : 0;   // wave-uniform
+    switch (nit) {
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        default: break;
     }
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);

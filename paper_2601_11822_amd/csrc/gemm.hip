@@ -494,16 +494,19 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
 // The 4 waves are summed in wave order through LDS; the S slices of K are summed in slice order
 // by the epilogue kernel.  S depends on (N, K) only, so results never depend on the CU share.
 // ---------------------------------------------------------------------------------------------
+// RT = 32-row weight tiles per workgroup (and per wave: the 4 waves split K, not rows)
+#define RS_SKINNY_RT 2
 static inline int skinny_virtual_n(int N, int epi) {
-    return epi == EPI_SWIGLU ? ((N + 31) / 32) * 64 : ((N + 63) / 64) * 64;
+    constexpr int VT = 32 * RS_SKINNY_RT;   // virtual rows per workgroup; SwiGLU: half gate, half up
+    return epi == EPI_SWIGLU ? ((N + VT / 2 - 1) / (VT / 2)) * VT : ((N + VT - 1) / VT) * VT;
 }
 static inline int skinny_kblocks(int K) { return (K + 15) / 16; }
 static inline int skinny_splits(int N, int K, int epi) {
-    const int tiles = skinny_virtual_n(N, epi) / 64;
+    const int tiles = skinny_virtual_n(N, epi) / (32 * RS_SKINNY_RT);
     const int Kb = skinny_kblocks(K);
     int S = 1;
-    // enough workgroups for two per CU, but at least 16 k-blocks per wave
-    while (tiles * S < RS_SKINNY_TARGET_WGS && S < 16 && Kb / (2 * S) >= 64) S *= 2;
+    // enough workgroups for one per CU and more, but at least 8 k-blocks per wave
+    while (tiles * S < RS_SKINNY_TARGET_WGS && S < 16 && Kb / (2 * S) >= 32) S *= 2;
     return S;
 }
 static inline int skinny_kb_per_wg(int K, int S) {
@@ -545,10 +548,10 @@ void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int
                        skinny_kblocks(K), n_chunks);
 }
 
-template <int EPI, int PD>
-__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
-                                                             int kb_per_wg, int Kb, int Nv) {
-    // 64 KB: the waves' accumulators for the in-order reduction, [wave][tile][lane][16]
+template <int EPI, int RT, int PD>
+__global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void gemm_skinny_kernel(GemmArgs a, float *__restrict__ part,
+                                                          int kb_per_wg, int Kb, int Nv) {
+    // RT * 32 KB: the waves' accumulators for the in-order reduction, [wave][tile][lane][16]
     extern __shared__ __attribute__((aligned(1024))) float red[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c32 = lane & 31, h = lane >> 5;
@@ -558,41 +561,44 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *
     const int nsteps = max(min(kb0 + kbw, Kb) - kb0, 0);
     const int kb_last = Kb - 1;
 
-    // row tile 0 / 1 of this workgroup in the packed matrices
-    const bf16_t *w0, *w1;
-    const size_t wstride = (size_t)((a.N + 63) / 64) * 1024;   // elements per k block
-    if (EPI == EPI_SWIGLU) {
-        w0 = a.Wp + (size_t)blockIdx.x * 512 + lane * 8;
-        w1 = a.Wp2 + (size_t)blockIdx.x * 512 + lane * 8;
-    } else {
-        w0 = a.Wp + (size_t)blockIdx.x * 1024 + lane * 8;
-        w1 = w0 + 512;
+    // the workgroup's RT row tiles in the packed matrices.  SwiGLU: virtual tile t is gate (t even) or
+    // up (t odd) tile RT/2 * blockIdx.x + t/2, so gate and up of a feature sit 32 virtual columns apart
+    const int Nt = ((a.N + 63) / 64) * 2;
+    const size_t wstride = (size_t)Nt * 512, tstride = 512;   // elements per k block / per row tile
+    const bf16_t *w[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        if (EPI == EPI_SWIGLU)
+            w[t] = ((t & 1) ? a.Wp2 : a.Wp) + (size_t)min((RT / 2) * (int)blockIdx.x + (t >> 1), Nt - 1) * tstride + lane * 8;
+        else
+            w[t] = a.Wp + (size_t)min(RT * (int)blockIdx.x + t, Nt - 1) * tstride + lane * 8;
     }
     const bf16_t *x = a.A + lane * 8;
 
-    f32x16 acc[2][2];
+    f32x16 acc[RT][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    bf16x8 rw0[PD], rw1[PD], rx0[PD], rx1[PD];
+    bf16x8 rw[PD][RT], rx[PD][2];
     auto load = [&](int p, int step) {
         const size_t kb = (size_t)min(kb0 + step, kb_last);
-        rw0[p] = ld_bf16x8_stream(w0 + kb * wstride);
-        rw1[p] = ld_bf16x8_stream(w1 + kb * wstride);
-        rx0[p] = ld_bf16x8(x + kb * 1024);
-        rx1[p] = ld_bf16x8(x + kb * 1024 + 512);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) rw[p][t] = ld_bf16x8_stream(w[t] + kb * wstride);
+        rx[p][0] = ld_bf16x8(x + kb * 1024);
+        rx[p][1] = ld_bf16x8(x + kb * 1024 + 512);
     };
 #pragma unroll
     for (int p = 0; p < PD; ++p) load(p, p);
     auto step = [&](int p) {
-        acc[0][0] = mfma32(rw0[p], rx0[p], acc[0][0]);
-        acc[0][1] = mfma32(rw0[p], rx1[p], acc[0][1]);
-        acc[1][0] = mfma32(rw1[p], rx0[p], acc[1][0]);
-        acc[1][1] = mfma32(rw1[p], rx1[p], acc[1][1]);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            acc[t][0] = mfma32(rw[p][t], rx[p][0], acc[t][0]);
+            acc[t][1] = mfma32(rw[p][t], rx[p][1], acc[t][1]);
+        }
     };
     // whole rings: branch free, so the wait in front of each step is "all but the PD-1 younger steps"
     int i = 0;
@@ -611,26 +617,29 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmArgs a, float *
         if (p < rem) step(p);
     // in-order reduction of the 4 waves
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
+    for (int tn = 0; tn < RT; ++tn)
 #pragma unroll
         for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
-                *(f32x4 *)&red[((wave * 4 + tn * 2 + tm) * 64 + lane) * 16 + 4 * j] = v;
+                *(f32x4 *)&red[((wave * (2 * RT) + tn * 2 + tm) * 64 + lane) * 16 + 4 * j] = v;
             }
     __syncthreads();
-    // wave w finishes tile (tn, tm) = (w>>1, w&1): sum of the 4 waves in wave order
-    const int tn = wave >> 1, tm = wave & 1;
-    const int m = 32 * tm + c32;
-    if (m < M) {
-        float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * 64 + 32 * tn;
+    // wave w finishes tiles w, w + 4, ...: sum of the 4 waves in wave order
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            f32x4 v = *(const f32x4 *)&red[((0 * 4 + wave) * 64 + lane) * 16 + 4 * j];
+    for (int q = 0; q < (2 * RT) / 4; ++q) {
+        const int tile = wave + 4 * q, tn = tile >> 1, tm = tile & 1;
+        const int m = 32 * tm + c32;
+        if (m < M) {
+            float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * (32 * RT) + 32 * tn;
 #pragma unroll
-            for (int w = 1; w < 4; ++w) v += *(const f32x4 *)&red[((w * 4 + wave) * 64 + lane) * 16 + 4 * j];
-            *(f32x4 *)(dst + 8 * j + 4 * h) = v;
+            for (int j = 0; j < 4; ++j) {
+                f32x4 v = *(const f32x4 *)&red[((0 * (2 * RT) + tile) * 64 + lane) * 16 + 4 * j];
+#pragma unroll
+                for (int ww = 1; ww < 4; ++ww) v += *(const f32x4 *)&red[((ww * (2 * RT) + tile) * 64 + lane) * 16 + 4 * j];
+                *(f32x4 *)(dst + 8 * j + 4 * h) = v;
+            }
         }
     }
 }
@@ -672,17 +681,18 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
 
 template <int EPI>
 static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials) {
-    constexpr int PD = 8;
+    constexpr int RT = RS_SKINNY_RT, PD = 10;   // (RT + 2) * PD loads per wave in flight; at most 63 can be outstanding
+    constexpr int lds = RT * 32768;
     const int Nv = skinny_virtual_n(a.N, a.epi);
     const int S = skinny_splits(a.N, a.K, a.epi);
     const int kbpw = skinny_kb_per_wg(a.K, S);
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<EPI, PD>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<EPI, RT, PD>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
     const int eblocks = (a.M * (a.N / 4) + 255) / 256;
-    hipLaunchKernelGGL((gemm_skinny_kernel<EPI, PD>), dim3(Nv / 64, S), dim3(256), 65536, st, a, partials, kbpw,
+    hipLaunchKernelGGL((gemm_skinny_kernel<EPI, RT, PD>), dim3(Nv / (32 * RT), S), dim3(256), lds, st, a, partials, kbpw,
                        skinny_kblocks(a.K), Nv);
     hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
 }
