@@ -97,6 +97,26 @@ def enqueue_decode(r):
     r["ctx_obj"].decode_layer(0, r["xd"], r["yd"], r["cl"], r["dtab"], r["max_blk"], r["B"], r["max_ctx"])
 
 
+def enqueue_decode_graph(r):
+    c = r["ctx_obj"]
+    c.decode_layer_graph(0, r["xd"], r["yd"], r["cl"], r["dtab"], r["max_blk"], r["B"], c.max_context)
+
+
+def host_cost_us(fn, r, n=200):
+    """Mean host time of one enqueue call (the GPU is kept no more than a few steps behind)."""
+    c = r["ctx_obj"]
+    c.sync(1)
+    t = 0.0
+    for i in range(n):
+        t0 = time.perf_counter()
+        fn(r)
+        t += time.perf_counter() - t0
+        if i % 4 == 3:
+            c.sync(1)
+    c.sync(1)
+    return t / n * 1e6
+
+
 def run_alone(r, side, steps, warmup, kernel_times=False):
     fn = (lambda: enqueue_prefill(r)) if side == 0 else (lambda: enqueue_decode(r))
     return timing.run_alone(r["ctx_obj"], side, fn, steps, warmup, kernel_times)
@@ -214,6 +234,13 @@ def main():
     layer_p["frac_mfma"] = layer_p["tflops"] / MFMA_PEAK_TFLOPS
     layer_d = {"gbs": bytes_layer / (np.median(d256_bb) * 1e-3) / 1e9}
     layer_d["frac_hbm"] = layer_d["gbs"] / HBM_PEAK_GBS
+    # ---- the captured decode step (one graph launch instead of 14 kernel launches)
+    enqueue_decode_graph(r)
+    c.sync(1)
+    dg, _ = timing.run_alone(c, 1, lambda: enqueue_decode_graph(r), max(4 * K, 100), W)
+    graph = {"decode_ms_alone_256_graph": float(np.median(dg)), "decode_ms_alone_256_eager": float(np.median(d256_bb)),
+             "host_us_per_step_eager": host_cost_us(enqueue_decode, r), "host_us_per_step_graph": host_cost_us(enqueue_decode_graph, r)}
+    log("[bench] decode step as a graph: %s" % json.dumps(graph))
     if args.alone_only:
         # a plain copy of known size, so that HBM byte counters can be scaled against it
         for _ in range(3):
@@ -317,7 +344,7 @@ def main():
         "prefill_layer_alone_256": layer_p, "decode_layer_alone_256": layer_d,
         "prefill_kernels_ms_alone_256": dict(zip(names, map(float, kt_p))),
         "decode_kernels_ms_alone_256": dict(zip(names, map(float, kt_d))),
-        "roofline": roof, "roofline_decode": roof_d, "sweep": sweep,
+        "roofline": roof, "roofline_decode": roof_d, "decode_graph": graph, "sweep": sweep,
     }
     if not args.no_cpu_baseline:
         c.sync(0); c.sync(1)

@@ -167,6 +167,23 @@ int32_t rs_decode_layer(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_ou
                         const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
                         int32_t B, int32_t max_ctx);
 
+/* The same decode step, replayed from a captured HIP graph (section 4.5.2: decode steps are
+ * captured as graphs per batch size; section 4.5.3: the CU mask a graph was captured under stays
+ * with it).  The first call with a given (layer, pointers, max_blk, B, max_ctx_bucket, current
+ * decode stream) records rs_decode_layer's kernel sequence on the decode stream and instantiates
+ * it (set-up work: allocates); every call launches the instantiated graph on that stream, one
+ * runtime call instead of fourteen.  Pointers are part of the graph: the CONTENTS of x_in,
+ * ctx_lens and block_tables are read at replay, so a serving loop keeps them in place and updates
+ * them between steps.  max_ctx_bucket plays the role of max_ctx but is baked into the launch
+ * shape: a multiple of 512 (or the context limit of rs_init) that bounds ctx_lens[i]+1 for as
+ * long as the graph is reused, and block_tables rows must be long enough for it
+ * (RS_ERR_BAD_BLOCK otherwise).  After rs_set_cu_split the decode stream differs and a new graph
+ * is captured under the new mask.  At most 256 graphs are cached per context (RS_ERR_STATE);
+ * rs_destroy frees them.  Results are bit-identical to rs_decode_layer's. */
+int32_t rs_decode_layer_graph(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_out,
+                              const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
+                              int32_t B, int32_t max_ctx_bucket);
+
 /* ---- CU partitioning (sections 4.2, 4.5.3) -------------------------------------------------
  * Selects the masks for SUBSEQUENT enqueues.  Each count is 0 or a multiple of
  * RS_CU_GRANULE up to 256.  prefill+decode <= 256 gives disjoint masks (prefill takes mask
@@ -227,6 +244,9 @@ int32_t rs_debug_cu_histogram(rs_ctx *ctx, int32_t side, int32_t n_workgroups, i
  * GPU time.  n_bytes / time is the read bandwidth that partition can pull (section 3.3's
  * question, asked of this GPU).  Blocks until done. */
 int32_t rs_debug_stream_read(rs_ctx *ctx, int32_t side, const void *buf, int64_t n_bytes, float *ms_out);
+/* rs_debug_cu_histogram with the probe kernel replayed from a captured graph on the side's stream:
+ * shows whether a graph launch keeps the stream's CU mask. */
+int32_t rs_debug_cu_histogram_graph(rs_ctx *ctx, int32_t side, int32_t n_workgroups, int32_t *hist_out);
 
 /* Copies an intermediate activation buffer of a side's last layer call to host memory (after
  * waiting for that side): which = 0 first RMSNorm output [M,d]; 1 q|k|v with rotated q and k

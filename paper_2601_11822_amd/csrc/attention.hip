@@ -553,3 +553,9 @@ void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a) {
         hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(256), 4 * 64 * 64 * 2 + PREFILL_TAB_LDS * 4, st, a);
     }
 }
+
+void attention_kernels_init() {
+    (void)hipFuncSetAttribute((const void *)prefill_attn_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              4 * 64 * 128 * 2 + PREFILL_TAB_LDS * 4);
+}
+

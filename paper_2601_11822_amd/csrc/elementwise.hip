@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t *__restr
     for (; i + 256 * 7 < n16; i += stride) {
         u32x4_t v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[i + 256 * u];
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(&src[i + 256 * u]);   // streamed: read once
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u];
     }

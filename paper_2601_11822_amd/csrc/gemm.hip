@@ -681,7 +681,7 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
 
 template <int EPI>
 static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials) {
-    constexpr int RT = RS_SKINNY_RT, PD = 10;   // (RT + 2) * PD loads per wave in flight; at most 63 can be outstanding
+    constexpr int RT = RS_SKINNY_RT, PD = 10;   // (RT + 2) * PD loads per wave in flight; at most 63 can be outstanding (gemm_kernels_init uses the same pair)
     constexpr int lds = RT * 32768;
     const int Nv = skinny_virtual_n(a.N, a.epi);
     const int S = skinny_splits(a.N, a.K, a.epi);
@@ -705,3 +705,25 @@ void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
         default: launch_skinny_epi<EPI_SWIGLU>(st, a, partials); break;
     }
 }
+
+// Raises the dynamic-LDS limit of every kernel that needs more than the default, once, at context
+// creation: nothing but launches is then left for a call that may run under stream capture.
+void gemm_kernels_init() {
+    auto set = [](const void *f, int lds) { (void)hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds); };
+    constexpr int RT = RS_SKINNY_RT, PD = 10;
+    set((const void *)gemm_skinny_kernel<EPI_STORE, RT, PD>, RT * 32768);
+    set((const void *)gemm_skinny_kernel<EPI_RESIDUAL, RT, PD>, RT * 32768);
+    set((const void *)gemm_skinny_kernel<EPI_SWIGLU, RT, PD>, RT * 32768);
+    set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
+    set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
+    set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_STORE, 4, 4>, 131072);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_RESIDUAL, 4, 4>, 131072);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_SWIGLU, 4, 4>, 131072);
+    set((const void *)gemm_direct_kernel<128, 256, EPI_STORE, 5, 4>, 122880);
+    set((const void *)gemm_direct_kernel<128, 256, EPI_RESIDUAL, 5, 4>, 122880);
+    set((const void *)gemm_direct_kernel<128, 256, EPI_SWIGLU, 5, 4>, 122880);
+    set((const void *)gemm_direct_kernel<256, 192, EPI_STORE, 4, 4>, 114688);
+    set((const void *)gemm_direct_kernel<256, 192, EPI_RESIDUAL, 4, 4>, 114688);
+}
+

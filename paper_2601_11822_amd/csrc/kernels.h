@@ -84,3 +84,8 @@ void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);
 
 // Reads `bytes` (multiple of 16) once with coalesced 16-byte loads.
 void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups);
+
+// Called once per context creation (see gemm.hip).
+void gemm_kernels_init();
+void attention_kernels_init();
+

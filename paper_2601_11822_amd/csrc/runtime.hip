@@ -10,6 +10,7 @@
 #include <map>
 #include <string>
 #include <unordered_map>
+#include <tuple>
 #include <vector>
 
 #include "../../include/rapid_serve.h"
@@ -81,6 +82,18 @@ struct rs_ctx {
     int32_t *err_flag = nullptr;
     Workspace ws[2];
     int last_rows[2] = {0, 0};   // rows of each side's last layer call: fixes the packed layout of h/attn/act
+    // captured decode steps, keyed by everything a captured launch bakes in (rs_decode_layer_graph)
+    struct GraphKey {
+        int32_t layer, max_blk, B, max_ctx;
+        const void *x_in, *x_out, *ctx_lens, *tables;
+        hipStream_t stream;
+        bool operator<(const GraphKey &o) const {
+            return std::tie(layer, max_blk, B, max_ctx, x_in, x_out, ctx_lens, tables, stream) <
+                   std::tie(o.layer, o.max_blk, o.B, o.max_ctx, o.x_in, o.x_out, o.ctx_lens, o.tables, o.stream);
+        }
+    };
+    std::map<GraphKey, hipGraphExec_t> graphs;
+    bool capturing = false;      // a decode step is being recorded: no event records on the stream
     Side side[2];
     bool over_alloc = true;
     bool kernel_timing = false;
@@ -257,7 +270,7 @@ int32_t check_layer_call(rs_ctx *c, int side, int32_t layer, const void *x_in, v
 
 // With kernel timing on, records boundary `i` of the current layer call on the side's stream.
 void tick(rs_ctx *c, int side, int i) {
-    if (!c->kernel_timing) return;
+    if (!c->kernel_timing || c->capturing) return;
     Side &s = c->side[side];
     if (!s.kt[i] && hipEventCreate(&s.kt[i]) != hipSuccess) return;
     (void)hipEventRecord(s.kt[i], s.stream);
@@ -438,6 +451,8 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     int32_t rc;
     auto gpu_setup = [&]() -> int32_t {
         HIP_TRY(hipSetDevice(device));
+        gemm_kernels_init();
+        attention_kernels_init();
         // rotary table, angles in float64
         const int half = m.head_dim / 2;
         std::vector<CosSin> tab((size_t)m.max_pos * half);
@@ -496,6 +511,7 @@ int32_t rs_destroy(rs_ctx *c) {
             for (auto &kv : c->side[s].pool) (void)hipStreamDestroy(kv.second);
             free_ws(c->ws[s]);
         }
+        for (auto &kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
         for (auto &pl : c->packed)
             for (bf16_t *q : {pl.wqkv, pl.wo, pl.wg, pl.wu, pl.wd})
                 if (q) (void)hipFree(q);
@@ -584,6 +600,72 @@ int32_t rs_decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out,
     int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
     if (rc) return rc;
     return decode_layer(c, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
+}
+
+int32_t rs_decode_layer_graph(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
+                              const int32_t *block_tables, int32_t max_blk, int32_t B, int32_t max_ctx_bucket) {
+    int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
+    if (rc) return rc;
+    if (max_ctx_bucket < 1 || (max_ctx_bucket % RS_DECODE_CHUNK && max_ctx_bucket != c->lim.max_context))
+        return fail(RS_ERR_BAD_ARG, "max_ctx_bucket %d: a multiple of %d, or the context limit %d", max_ctx_bucket,
+                    RS_DECODE_CHUNK, c->lim.max_context);
+    hipStream_t st = c->side[RS_SIDE_DECODE].stream;
+    const rs_ctx::GraphKey key{layer, max_blk, B, max_ctx_bucket, x_in, x_out, ctx_lens, block_tables, st};
+    auto it = c->graphs.find(key);
+    if (it == c->graphs.end()) {
+        if (c->graphs.size() >= 256) return fail(RS_ERR_STATE, "256 captured decode steps are cached already");
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+        c->capturing = true;
+        rc = decode_layer(c, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx_bucket);
+        c->capturing = false;
+        const hipError_t e = hipStreamEndCapture(st, &graph);
+        if (rc) {
+            if (graph) (void)hipGraphDestroy(graph);
+            return rc;
+        }
+        HIP_TRY(e);
+        const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        HIP_TRY(ei);
+        it = c->graphs.emplace(key, exec).first;
+    }
+    c->last_rows[RS_SIDE_DECODE] = B;
+    HIP_TRY(hipGraphLaunch(it->second, st));
+    return RS_OK;
+}
+
+int32_t rs_debug_cu_histogram_graph(rs_ctx *c, int32_t side, int32_t n_workgroups, int32_t *hist_out) {
+    if (!c || !hist_out || side < 0 || side > 1 || n_workgroups < 1 || n_workgroups > (1 << 20))
+        return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    if (c->side[side].cus <= 0) return fail(RS_ERR_STATE, "side has no compute units");
+    hipStream_t st = c->side[side].stream;
+    int32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, RS_CU_HIST_BINS * sizeof(int32_t)));
+    auto run = [&]() -> int32_t {
+        HIP_TRY(hipMemset(d, 0, RS_CU_HIST_BINS * sizeof(int32_t)));   // outside the capture
+        HIP_TRY(hipStreamSynchronize(st));
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+        launch_cu_probe(st, d, n_workgroups);
+        HIP_TRY(hipStreamEndCapture(st, &graph));
+        const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        HIP_TRY(ei);
+        const hipError_t el = hipGraphLaunch(exec, st);
+        const hipError_t es = hipStreamSynchronize(st);
+        (void)hipGraphExecDestroy(exec);
+        HIP_TRY(el);
+        HIP_TRY(es);
+        HIP_TRY(hipMemcpy(hist_out, d, RS_CU_HIST_BINS * sizeof(int32_t), hipMemcpyDeviceToHost));
+        return RS_OK;
+    };
+    const int32_t rc = run();
+    (void)hipFree(d);
+    return rc;
 }
 
 int32_t rs_set_cu_split(rs_ctx *c, int32_t p, int32_t d) {
