@@ -40,8 +40,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 # what the same counter reads for the 1 GiB device copy that run ends with (reads x2.0, writes
 # x1.0); the summaries are under profiles/.  Valid for the default workload only.
 TRAFFIC_BYTES = {
-    "gateup": (377407 * 2.0 + 57344) * 1024.0,
-    "decode_attn": ((326737 + 1656) * 2.0 + 3173 + 512) * 1024.0,
+    "gateup": (377415 * 2.0 + 57344) * 1024.0,
+    "decode_attn": ((326434 + 2960) * 2.0 + 5739 + 512) * 1024.0,
 }
 
 
