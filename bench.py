@@ -132,7 +132,7 @@ def pct(a, q):
     return float(np.percentile(a, q)) if len(a) else float("nan")
 
 
-def cpu_baseline(r, budget_rows=(64, 192)):
+def cpu_baseline(r, budget_rows=(512, 1536)):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same
     workload: K/V of all T prompt rows plus the rest of the layer for a few sampled rows (two
     sample sizes give the per-row cost), and one decode step for a slice of the batch."""
@@ -156,8 +156,8 @@ def cpu_baseline(r, budget_rows=(64, 192)):
     per_row = (times[1] - times[0]) / (budget_rows[1] - budget_rows[0])
     fixed = max(times[0] - budget_rows[0] * per_row, 0.0)
     full = fixed + T * per_row
-    # decode: 8 of the 64 requests
-    nd = 8
+    # decode: 32 of the 64 requests
+    nd = 32
     ctx = r["ctx"][:nd]
     counts = [int(c_) + 1 for c_ in ctx]
     dt = S.identity_block_tables(counts)
