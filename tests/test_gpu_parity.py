@@ -122,11 +122,12 @@ def _fill_contexts(rig, ctx, tabs, stream0):
     Kc, Vc = L.new_cache(rig.n_blocks, fill=ORC_SENT)
     lens = [int(c) for c in ctx if c > 0]
     idx = [i for i, c in enumerate(ctx) if c > 0]
-    if lens:
-        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-        xb = S.hidden_states(int(cu[-1]), shape.d_model, stream=stream0)
-        rig.prefill(xb, cu, tabs[idx])
-        L.prefill(f32(xb), cu, tabs[idx], Kc, Vc)
+    for g in range(0, len(lens), rs.RS_MAX_PREFILL_REQS):      # a prefill call takes at most 64 prompts
+        gl, gi = lens[g:g + rs.RS_MAX_PREFILL_REQS], idx[g:g + rs.RS_MAX_PREFILL_REQS]
+        cu = np.concatenate([[0], np.cumsum(gl)]).astype(np.int32)
+        xb = S.hidden_states(int(cu[-1]), shape.d_model, stream=stream0 + 7 * (g // rs.RS_MAX_PREFILL_REQS))
+        rig.prefill(xb, cu, tabs[gi])
+        L.prefill(f32(xb), cu, tabs[gi], Kc, Vc)
     return Kc, Vc
 
 
@@ -165,6 +166,18 @@ def test_decode_edge_contexts_tiny():
 
 def test_decode_mid_gqa_several_chunks():
     _run_decode_parity(S.MID, [5, 127, 128, 640, 1100], stream=2)
+
+
+def test_decode_batch_spanning_both_token_tiles():
+    # 40 rows: the second 32-row tile of the skinny GEMMs is partly valid
+    ctx = [(37 * i) % 300 for i in range(40)]
+    _run_decode_parity(S.MID, ctx, stream=5)
+
+
+def test_decode_batch_over_64_takes_the_tiled_gemms():
+    # more than 64 rows leave the skinny path: packed activations with 3 row tiles, tiled GEMMs on the decode side
+    ctx = [(53 * i) % 260 for i in range(70)]
+    _run_decode_parity(S.MID, ctx, stream=6)
 
 
 @pytest.mark.parametrize("which", ["wo", "wd"])
