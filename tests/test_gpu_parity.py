@@ -361,3 +361,38 @@ def test_full_size_8b_layer_sampled_rows():
         assert np.array_equal(changed, want), "decode wrote K/V slots other than each request's next position"
     finally:
         rig.close()
+
+
+def test_70b_shaped_layer_sampled_rows():
+    """Llama-3-70B-shaped layer (d 8192, 64/8 heads, FFN 28672): the widest RMSNorm variant, GEMM
+    shapes with other tile counts and schedules than the 8B layer.  Prefill of two prompts (768 rows)
+    against sampled oracle rows and the whole K/V cache; one decode step of 16 requests."""
+    shape = S.LLAMA70B
+    lens = [500, 268]
+    T, B = sum(lens), 16
+    ctx = np.array([(97 * i + 40) % 1400 for i in range(B)], np.int32)
+    counts = [int(c) + 1 for c in ctx] + lens
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 16
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)))
+    dtab, ptab = tabs[:B], tabs[B:]
+    rig = Rig(shape, n_blocks, T, B, int(ctx.max()) + 1, sentinel=0x7FC1)
+    try:
+        L = rig.olayers[0]
+        xb = S.hidden_states(T, shape.d_model, stream=3)
+        x = f32(xb)
+        cu = [0, lens[0], T]
+        rig.ctx.set_cu_split(160, 96)
+        y_bits = rig.prefill(xb, cu, ptab)
+        rows = np.array([0, 1, 31, 32, 255, 256, 499, 500, 501, 511, 512, 700, 767], np.int32)
+        Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
+        y_ref = L.prefill(x, cu, ptab, Kc, Vc, rows=rows)
+        check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        check_tensor("70B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2)
+        kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
+        rig.load_pools_from_logical(kb, vb)
+        db = S.hidden_states(B, shape.d_model, stream=51)
+        yd = rig.decode(db, ctx, dtab)
+        yd_ref = L.decode(f32(db), ctx, dtab, f32(kb), f32(vb))
+        check_tensor("70B decode y, batch 16", f32(yd), yd_ref, f32(db), 2)
+    finally:
+        rig.close()
