@@ -251,7 +251,8 @@ int32_t rs_debug_cu_histogram_graph(rs_ctx *ctx, int32_t side, int32_t n_workgro
 /* Copies an intermediate activation buffer of a side's last layer call to host memory (after
  * waiting for that side): which = 0 first RMSNorm output [M,d]; 1 q|k|v with rotated q and k
  * [M,(Hq+2Hkv)hd]; 2 attention output [M,Hq*hd]; 3 hidden state after the attention residual
- * [M,d]; 4 silu(gate)*up [M,ffn].  All bf16, first n_bytes bytes.  For stage-by-stage checks. */
+ * [M,d]; 4 silu(gate)*up [M,ffn].  All bf16, row-major whatever the library's internal layout
+ * (n_bytes = whole rows, at most the rows of that call).  For stage-by-stage checks. */
 int32_t rs_debug_read_workspace(rs_ctx *ctx, int32_t side, int32_t which, void *host_out, int64_t n_bytes);
 
 /* ---- serving step (request flow of section 4.4, FCFS of 4.5.2, manager of 4.5.3) -------------
@@ -295,6 +296,10 @@ typedef struct {
 int32_t rs_submit(rs_ctx *ctx, int64_t req_id, int32_t prompt_len, int32_t output_len,
                   const void *prompt_hidden);
 int32_t rs_step(rs_ctx *ctx, const rs_step_in *in, rs_step_out *out);
+/* Request ids of the rows of the most recent rs_step's decode batch, in row order (row i of that
+ * step's decode_hidden / decode_out belongs to ids_out[i]).  Rows keep their relative order from
+ * step to step; finished requests drop out, newly promoted ones are appended in arrival order. */
+int32_t rs_decode_batch_ids(rs_ctx *ctx, int64_t *ids_out, int32_t cap, int32_t *n_out);
 /* State of a request: 0 WAITING, 1 PREFILL_READY, 2 PREFILLING, 3 PREFILL_DONE, 4 RUNNING,
  * 5 FINISHED; RS_ERR_BAD_ARG if unknown. */
 int32_t rs_request_state(rs_ctx *ctx, int64_t req_id);

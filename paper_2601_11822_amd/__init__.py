@@ -29,7 +29,7 @@ RS_CU_HIST_BINS = 4096
 EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_set_cu_split", "rs_get_cu_split",
-    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_set_kernel_timing", "rs_kernel_times",
+    "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
 ]
 
@@ -299,6 +299,13 @@ class Context:
         self._keep.append(prompt_hidden)
         _check(self._lib.rs_submit(self._h, ctypes.c_int64(req_id), ctypes.c_int32(prompt_len),
                                    ctypes.c_int32(output_len), _ptr(prompt_hidden)))
+
+    def decode_batch_ids(self) -> list:
+        """Request ids of the rows of the most recent step's decode batch."""
+        ids = (ctypes.c_int64 * 4096)()
+        n = ctypes.c_int32(0)
+        _check(self._lib.rs_decode_batch_ids(self._h, ids, ctypes.c_int32(4096), ctypes.byref(n)))
+        return [int(ids[i]) for i in range(n.value)]
 
     def step(self, decode_hidden=None, decode_out=None, wait_decode: bool = False) -> StepOut:
         si = StepIn(_ptr(decode_hidden), _ptr(decode_out), 1 if wait_decode else 0)

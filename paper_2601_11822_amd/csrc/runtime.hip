@@ -94,6 +94,7 @@ struct rs_ctx {
     };
     std::map<GraphKey, hipGraphExec_t> graphs;
     bool capturing = false;      // a decode step is being recorded: no event records on the stream
+    std::vector<int64_t> last_batch;   // request ids of the rows of the most recent rs_step's decode batch
     Side side[2];
     bool over_alloc = true;
     bool kernel_timing = false;
@@ -851,6 +852,14 @@ int32_t rs_submit(rs_ctx *c, int64_t req_id, int32_t prompt_len, int32_t output_
     return RS_OK;
 }
 
+int32_t rs_decode_batch_ids(rs_ctx *c, int64_t *ids_out, int32_t cap, int32_t *n_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !ids_out)) return fail(RS_ERR_BAD_ARG, "null argument");
+    if ((int)c->last_batch.size() > cap) return fail(RS_ERR_BAD_ARG, "id buffer of %d too small for %d rows", cap, (int)c->last_batch.size());
+    std::copy(c->last_batch.begin(), c->last_batch.end(), ids_out);
+    *n_out = (int32_t)c->last_batch.size();
+    return RS_OK;
+}
+
 int32_t rs_request_state(rs_ctx *c, int64_t req_id) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
     auto it = c->reqs.find(req_id);
@@ -945,6 +954,7 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
     out->decode_sum_ctx = sum_ctx;
 
     // 4. one decode step over the running batch
+    c->last_batch.assign(c->running.begin(), c->running.end());
     if (B > 0) {
         int max_ctx = 1;
         for (int64_t id : c->running) {

@@ -396,3 +396,61 @@ def test_70b_shaped_layer_sampled_rows():
         check_tensor("70B decode y, batch 16", f32(yd), yd_ref, f32(db), 2)
     finally:
         rig.close()
+
+
+def test_serving_steps_three_requests_async_matches_oracle():
+    """rs_submit / rs_step with requests arriving at different steps, prefills running beside decode
+    steps, steps enqueued without waiting (the host schedules step n+1 while step n runs) and a
+    measured-style profile steering the split: every decode row equals the oracle's stack for the
+    request rs_decode_batch_ids names, block growth included."""
+    shape = S.TINY
+    n_layers = 2
+    prof = rs.Profile([4], [1024], [64, 128, 192], [[[900, 500, 300]]], [[2000]], slo_us=600)
+    rig = Rig(shape, 40, 128, 4, 160, n_layers=n_layers, profile=prof)
+    try:
+        reqs = {1: (40, 4), 2: (70, 3), 3: (17, 5)}            # id -> (prompt tokens, tokens to generate)
+        prompts = {i: S.hidden_states(p, shape.d_model, stream=100 + i) for i, (p, _) in reqs.items()}
+        p_dev = {i: to_dev(b) for i, b in prompts.items()}
+        arrive = {0: [1, 2], 3: [3]}
+        d_out = torch.zeros((4, shape.d_model), dtype=torch.bfloat16, device="cuda")
+        # oracle state per request: block ids as the allocator hands them out are read back from the library
+        caches = {i: [L.new_cache(40) for L in rig.olayers] for i in reqs}
+        prefilled, ctx_len, checked = set(), {}, 0
+        splits = set()
+        for step in range(40):
+            for i in arrive.get(step, []):
+                rig.ctx.submit(i, reqs[i][0], reqs[i][1], p_dev[i])
+            x_bits = S.hidden_states(1, shape.d_model, stream=200 + step)
+            x_dev = to_dev(np.repeat(x_bits, 4, axis=0))        # the same input row for every request of the step
+            so = rig.ctx.step(x_dev, d_out, wait_decode=False)   # returns at once
+            splits.add((so.prefill_cus, so.decode_cus))
+            ids = rig.ctx.decode_batch_ids()
+            assert len(ids) == so.decode_batch
+            rig.ctx.sync(rs.RS_SIDE_DECODE)
+            got = f32(to_bits(d_out))
+            for row, i in enumerate(ids):
+                if i not in prefilled:                           # first decode step of i: its prefill has completed
+                    tabs = np.full((1, 10), -1, np.int32)
+                    blk = rig.ctx.kv_alloc(i, reqs[i][0])        # no growth: returns the ids the request owns
+                    tabs[0, :len(blk)] = blk
+                    x = f32(prompts[i])
+                    for l, L in enumerate(rig.olayers):
+                        x = L.prefill(x, [0, reqs[i][0]], tabs, *caches[i][l])
+                    prefilled.add(i); ctx_len[i] = reqs[i][0]
+                tabs = np.full((1, 10), -1, np.int32)
+                blk = rig.ctx.kv_alloc(i, ctx_len[i] + 1)        # the step grew the request to ctx+1 tokens already
+                tabs[0, :len(blk)] = blk
+                xr = f32(x_bits)
+                for l, L in enumerate(rig.olayers):
+                    xr = L.decode(xr, [ctx_len[i]], tabs, *caches[i][l])
+                e = residual_err(got[row:row + 1], xr, f32(x_bits), roundings=4)
+                assert e <= 1.5, (step, i, e)
+                ctx_len[i] += 1; checked += 1
+            if all(rig.ctx.request_state(i) == 5 for i in reqs) and step > 3:
+                break
+        assert checked == sum(o for _, o in reqs.values())
+        assert all(rig.ctx.request_state(i) == 5 for i in reqs) and rig.ctx.kv_num_free() == 40
+        assert len(splits) >= 2, splits                          # the manager did move the split
+        print("splits used:", sorted(splits))
+    finally:
+        rig.close()

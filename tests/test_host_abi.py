@@ -169,12 +169,13 @@ def test_request_flow_state_machine():
     c.debug_complete_prefill(11)
     so = c.step()                                                # 10 step 2, 11 step 1
     assert so.decode_batch == 2 and so.decode_sum_ctx == 101 + 60
+    assert c.decode_batch_ids() == [10, 11]                      # row order = promotion order
     assert c.request_state(12) == WAITING                        # 12 blocks all in use (7 + 4 + growth)
     assert (so.prefill_cus, so.decode_cus) == (0, 256)           # no prefill pending -> decode takes all
     so = c.step()                                                # 10 step 3, 11 step 2
     so = c.step()                                                # both retire, 12 gets blocks and starts
     assert so.n_finished == 2 and c.request_state(10) == FINISHED and c.request_state(11) == FINISHED
-    assert c.request_state(12) == PREFILLING and so.decode_batch == 0
+    assert c.request_state(12) == PREFILLING and so.decode_batch == 0 and c.decode_batch_ids() == []
     c.debug_complete_prefill(12)
     c.step(); c.step()
     so = c.step()
