@@ -513,8 +513,12 @@ static inline int skinny_kb_per_wg(int K, int S) {
     const int per = (skinny_kblocks(K) + S - 1) / S;
     return ((per + 3) / 4) * 4;  // 4 waves
 }
+static inline int shared_virtual_n(int N, int epi);
+static inline int shared_splits(int N, int K, int epi);
 size_t skinny_partial_elems(int M, int N, int K, int epi) {
-    return (size_t)skinny_splits(N, K, epi) * (size_t)M * (size_t)skinny_virtual_n(N, epi);
+    const size_t plain = (size_t)skinny_splits(N, K, epi) * (size_t)M * (size_t)skinny_virtual_n(N, epi);
+    const size_t shared = (size_t)shared_splits(N, K, epi) * (size_t)M * (size_t)shared_virtual_n(N, epi);
+    return std::max(plain, shared);
 }
 size_t packed_weight_elems(int N, int K) {
     return (size_t)((N + 63) / 64) * 2 * (size_t)skinny_kblocks(K) * 512;
@@ -644,6 +648,130 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void gemm_skinny_kernel(GemmA
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel, shared activations (used for the wide gate/up matrix).  A CU moves about 55 GB/s
+// through its vector memory path whether the bytes come from HBM or from L2 (measured: the plain
+// weight stream of gemm_skinny_kernel reaches 50 GB/s per CU, and 30 once every wave also fetches
+// its own activation fragments, which are as many bytes as the weights).  Here the 4 waves of a
+// workgroup take different rows over the SAME K slice, so the slice's activation k-blocks are
+// fetched once per workgroup into LDS (a quarter of the bytes) and read from there:
+//   * K is cut into chunks of CH k-blocks; the chunk's activations (CH x 2 KB) sit in one of two
+//     LDS slabs; while chunk c is computed each wave fetches its 8 pieces of chunk c+1's slab, one
+//     per step, through the same register ring as its weights (so all loads stay register loads,
+//     in order, exact wait counts) and stores them to the other slab when their ring slot comes
+//     up; one barrier per chunk (s_barrier after lgkmcnt(0): the weight ring is NOT drained);
+//   * no K split inside the workgroup, hence no LDS reduction: each wave writes its own 64 x 64
+//     partial tile; K is split S ways across workgroups, summed in slice order by the epilogue
+//     kernel as before (S depends on the shape only).
+// ---------------------------------------------------------------------------------------------
+#define RS_SHARED_CH 16
+static inline bool skinny_shared_applies(const GemmArgs &a) {
+    return a.epi == EPI_SWIGLU && a.N >= 4096 && skinny_kblocks(a.K) % (4 * RS_SHARED_CH) == 0;
+}
+static inline int shared_virtual_n(int N, int epi) {
+    return epi == EPI_SWIGLU ? ((N + 127) / 128) * 256 : ((N + 255) / 256) * 256;
+}
+static inline int shared_splits(int N, int K, int epi) {
+    const int tiles = shared_virtual_n(N, epi) / 256;
+    const int Kb = skinny_kblocks(K);
+    int S = 1;
+    while (tiles * S < 224 && S < 16 && Kb % (2 * S * RS_SHARED_CH) == 0 && Kb / (2 * S) >= 4 * RS_SHARED_CH) S *= 2;
+    return S;
+}
+
+template <int EPI, int CH>
+__global__ __launch_bounds__(256, 2) void gemm_skinny_shared_kernel(GemmArgs a, float *__restrict__ part, int kb_per_wg,
+                                                                     int Kb, int Nv) {
+    constexpr int PD = 8;                      // ring depth; divides CH, so ring slots are static in the unrolled chunk
+    static_assert(CH % PD == 0 && CH * 2 == 32, "4 waves x 8 pieces fill one slab");
+    extern __shared__ __attribute__((aligned(1024))) bf16_t slab[];   // [2][CH][2 token tiles][64 lanes][8]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c32 = lane & 31, h = lane >> 5;
+    const int M = a.M;
+    const int kb_begin = blockIdx.y * kb_per_wg;
+    const int nchunks = kb_per_wg / CH;
+    const int kb_last = Kb - 1;
+    const int Nt = ((a.N + 63) / 64) * 2;
+    const size_t wstride = (size_t)Nt * 512;
+    const bf16_t *w0, *w1;
+    if (EPI == EPI_SWIGLU) {   // wave w: gate tile and up tile of feature tile 4 * blockIdx.x + w
+        const int f = min(4 * (int)blockIdx.x + wave, Nt - 1);
+        w0 = a.Wp + (size_t)f * 512 + lane * 8;
+        w1 = a.Wp2 + (size_t)f * 512 + lane * 8;
+    } else {
+        w0 = a.Wp + (size_t)min(8 * (int)blockIdx.x + 2 * wave, Nt - 1) * 512 + lane * 8;
+        w1 = a.Wp + (size_t)min(8 * (int)blockIdx.x + 2 * wave + 1, Nt - 1) * 512 + lane * 8;
+    }
+    const bf16_t *x = a.A + lane * 8;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // piece q (0..31) of a chunk's slab = 1 KB = (k-block q/2, token tile q%2); wave w fetches pieces 8w .. 8w+7
+    auto x_piece = [&](int chunk, int j) {
+        const int q = 8 * wave + j;
+        const size_t kb = (size_t)min(kb_begin + chunk * CH + (q >> 1), kb_last);
+        return ld_bf16x8(x + kb * 1024 + (q & 1) * 512);
+    };
+    // chunk 0's slab, up front
+    {
+        bf16x8 t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = x_piece(0, j);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *(bf16x8 *)&slab[(8 * wave + j) * 512 + lane * 8] = t[j];
+    }
+    bf16x8 rw0[PD], rw1[PD], rxs[PD];
+    auto load_w = [&](int p, int step) {   // step counts k-blocks from kb_begin
+        const size_t kb = (size_t)min(kb_begin + step, kb_last);
+        rw0[p] = ld_bf16x8_stream(w0 + kb * wstride);
+        rw1[p] = ld_bf16x8_stream(w1 + kb * wstride);
+    };
+#pragma unroll
+    for (int p = 0; p < PD; ++p) load_w(p, p);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    for (int c = 0; c < nchunks; ++c) {
+        const bf16_t *cur = slab + (c & 1) * (CH * 1024) + lane * 8;
+        bf16_t *nxt = slab + ((c + 1) & 1) * (CH * 1024);
+#pragma unroll
+        for (int s = 0; s < CH; ++s) {
+            const int p = s % PD;
+            const bf16x8 x0 = *(const bf16x8 *)&cur[(2 * s) * 512], x1 = *(const bf16x8 *)&cur[(2 * s + 1) * 512];
+            acc[0][0] = mfma32(rw0[p], x0, acc[0][0]);
+            acc[0][1] = mfma32(rw0[p], x1, acc[0][1]);
+            acc[1][0] = mfma32(rw1[p], x0, acc[1][0]);
+            acc[1][1] = mfma32(rw1[p], x1, acc[1][1]);
+            // the piece of the next slab that was fetched into this slot PD steps ago
+            if (s >= PD && s - PD < 8) *(bf16x8 *)&nxt[(8 * wave + (s - PD)) * 512 + lane * 8] = rxs[p];
+            load_w(p, c * CH + s + PD);
+            if (s < 8) rxs[p] = x_piece(c + 1, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // every wave has read slab c and written its pieces of slab c+1; the weight loads stay in flight
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    // each wave owns its rows: partial tile straight from the accumulators
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm) {
+            const int m = 32 * tm + c32;
+            if (m >= M) continue;
+            float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * 256 + wave * 64 + 32 * tn;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
+                *(f32x4 *)(dst + 8 * j + 4 * h) = v;
+            }
+        }
+}
+
 // Sums the K slices in order and applies the epilogue; one thread per 4 output columns.
 template <int EPI>
 __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const float *__restrict__ part,
@@ -681,6 +809,15 @@ __global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const 
 
 template <int EPI>
 static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials) {
+    if (skinny_shared_applies(a)) {
+        constexpr int CH = RS_SHARED_CH, lds = 2 * CH * 2048;
+        const int Nv = shared_virtual_n(a.N, a.epi), S = shared_splits(a.N, a.K, a.epi);
+        const int kbpw = skinny_kblocks(a.K) / S;
+        hipLaunchKernelGGL((gemm_skinny_shared_kernel<EPI, CH>), dim3(Nv / 256, S), dim3(256), lds, st, a, partials, kbpw,
+                           skinny_kblocks(a.K), Nv);
+        hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3((a.M * (a.N / 4) + 255) / 256), dim3(256), 0, st, a, partials, S, Nv);
+        return;
+    }
     constexpr int RT = RS_SKINNY_RT, PD = 10;   // (RT + 2) * PD loads per wave in flight; at most 63 can be outstanding (gemm_kernels_init uses the same pair)
     constexpr int lds = RT * 32768;
     const int Nv = skinny_virtual_n(a.N, a.epi);
@@ -714,6 +851,7 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_kernel<EPI_STORE, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_kernel<EPI_RESIDUAL, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_kernel<EPI_SWIGLU, RT, PD>, RT * 32768);
+    set((const void *)gemm_skinny_shared_kernel<EPI_SWIGLU, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);
