@@ -666,7 +666,8 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void gemm_skinny_kernel(GemmA
 // ---------------------------------------------------------------------------------------------
 #define RS_SHARED_CH 16
 static inline bool skinny_shared_applies(const GemmArgs &a) {
-    return a.epi == EPI_SWIGLU && a.N >= 4096 && skinny_kblocks(a.K) % (4 * RS_SHARED_CH) == 0;
+    if (skinny_kblocks(a.K) % (4 * RS_SHARED_CH) != 0 || a.N < 4096) return false;
+    return a.epi == EPI_SWIGLU || (a.epi == EPI_RESIDUAL && a.K >= 8192);   // wide, or long enough in K to split 8 ways
 }
 static inline int shared_virtual_n(int N, int epi) {
     return epi == EPI_SWIGLU ? ((N + 127) / 128) * 256 : ((N + 255) / 256) * 256;
@@ -852,6 +853,7 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_kernel<EPI_RESIDUAL, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_kernel<EPI_SWIGLU, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_shared_kernel<EPI_SWIGLU, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
+    set((const void *)gemm_skinny_shared_kernel<EPI_RESIDUAL, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);
