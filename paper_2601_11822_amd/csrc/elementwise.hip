@@ -77,8 +77,71 @@ void launch_rmsnorm(hipStream_t st, const bf16_t *x, const bf16_t *g, bf16_t *ou
 // One workgroup per token row; work items of 8 elements are spread over the 256 threads.
 // A block id outside the pool, or a position outside the rotary table, is never dereferenced:
 // the item is skipped and the error flag raised.
+//
+// The V pool is transposed ([dim][slot]), so a single token touches one 2-byte element in each of
+// Hkv*hd different 32-byte sectors.  A decode row has no choice; a prompt does: workgroups past the
+// first M of a prefill launch each take one 16-token block of one prompt, gather its V values
+// token by token (a wave reads 256 contiguous bytes per token) and write whole [dim][16] rows, so
+// that a wave's stores cover one contiguous span.  The token-row workgroups of a prefill launch
+// then leave V alone.  The last, partly filled block of a prompt is written element by element:
+// its other slots belong to tokens that decode appends later and are not touched.
 // ---------------------------------------------------------------------------------------------
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+static __device__ void v_block_write(const RopeKvArgs &a, int vb) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // prompt and block within it
+    int req = 0, first = 0;
+    for (;; ++req) {
+        if (req >= a.seq.n_req) return;
+        const int nb = (a.seq.cu[req + 1] - a.seq.cu[req] + RS_BLOCK_TOKENS - 1) / RS_BLOCK_TOKENS;
+        if (vb < first + nb) break;
+        first += nb;
+    }
+    const int bi = vb - first;
+    const int len = min(a.seq.cu[req + 1] - a.seq.cu[req], a.max_pos);   // rows past the table are flagged by their own workgroup
+    const int nvalid = min(len - bi * RS_BLOCK_TOKENS, RS_BLOCK_TOKENS);
+    if (nvalid <= 0 || bi >= a.max_blk) return;
+    const int blk = a.tables[(size_t)req * a.max_blk + bi];
+    if ((unsigned)blk >= (unsigned)a.n_blocks) return;                   // flagged by the token rows
+    const int hd = a.hd, nqkv = (a.Hq + 2 * a.Hkv) * hd;
+    const bf16_t *row0 = a.qkv + (size_t)(a.seq.cu[req] + bi * RS_BLOCK_TOKENS) * nqkv + (a.Hq + a.Hkv) * hd;
+    for (int kvh = wave; kvh < a.Hkv; kvh += 4)
+        for (int dp = lane; dp < (hd >> 1); dp += 64) {
+            uint32_t w[RS_BLOCK_TOKENS];
+#pragma unroll
+            for (int t = 0; t < RS_BLOCK_TOKENS; ++t)
+                w[t] = t < nvalid ? *(const uint32_t *)(row0 + (size_t)t * nqkv + kvh * hd + 2 * dp) : 0u;
+            bf16_t *dst = a.v_pool + (((size_t)blk * a.Hkv + kvh) * hd + 2 * dp) * RS_BLOCK_TOKENS;
+            if (nvalid == RS_BLOCK_TOKENS) {
+                uint32_t ev[8], od[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    ev[j] = (w[2 * j] & 0xffffu) | (w[2 * j + 1] << 16);
+                    od[j] = (w[2 * j] >> 16) | (w[2 * j + 1] & 0xffff0000u);
+                }
+                u32x4_t *d4 = (u32x4_t *)dst;
+                d4[0] = u32x4_t{ev[0], ev[1], ev[2], ev[3]};
+                d4[1] = u32x4_t{ev[4], ev[5], ev[6], ev[7]};
+                d4[2] = u32x4_t{od[0], od[1], od[2], od[3]};
+                d4[3] = u32x4_t{od[4], od[5], od[6], od[7]};
+            } else {
+                uint16_t *d2 = (uint16_t *)dst;
+#pragma unroll
+                for (int t = 0; t < RS_BLOCK_TOKENS; ++t)
+                    if (t < nvalid) {
+                        d2[t] = (uint16_t)(w[t] & 0xffffu);
+                        d2[RS_BLOCK_TOKENS + t] = (uint16_t)(w[t] >> 16);
+                    }
+            }
+        }
+}
+
 __global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
+    if ((int)blockIdx.x >= a.M) {
+        v_block_write(a, (int)blockIdx.x - a.M);
+        return;
+    }
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
     int req, pos;
@@ -130,7 +193,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
             st_bf16x8(dst + kpool_chunk_offset(slot, half + c * 8), ohi);
         }
     }
-    if (blk_ok) {
+    if (blk_ok && a.ctx_lens) {
         const int n_v = a.Hkv * (hd >> 3);
         const bf16_t *vrow = rowp + (a.Hq + a.Hkv) * hd;
         for (int it = tid; it < n_v; it += 256) {
@@ -145,7 +208,11 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
 
 void launch_rope_kvwrite(hipStream_t st, const RopeKvArgs &a) {
     if (a.M <= 0) return;
-    hipLaunchKernelGGL(rope_kvwrite_kernel, dim3(a.M), dim3(256), 0, st, a);
+    int v_blocks = 0;   // prefill: one more workgroup per 16-token block of each prompt
+    if (!a.ctx_lens)
+        for (int r = 0; r < a.seq.n_req; ++r)
+            v_blocks += (a.seq.cu[r + 1] - a.seq.cu[r] + RS_BLOCK_TOKENS - 1) / RS_BLOCK_TOKENS;
+    hipLaunchKernelGGL(rope_kvwrite_kernel, dim3(a.M + v_blocks), dim3(256), 0, st, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -175,7 +242,6 @@ void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups) {
 // a CU partition can pull.  The XOR fold is compared with a value it cannot take for all-equal
 // input words, so nothing is stored.
 // ---------------------------------------------------------------------------------------------
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t *__restrict__ src, u32x4_t *sink, size_t n16) {
     size_t i = (size_t)blockIdx.x * 2048 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 2048;
