@@ -146,6 +146,22 @@ def layer_weights(shape: LayerShape, layer: int = 0, seed: int = SEED_WEIGHTS,
     }
 
 
+def head_weights(d_model: int, vocab: int, seed: int = SEED_WEIGHTS, stream: int = 4096) -> Dict[str, np.ndarray]:
+    """bf16 bit patterns of the token embedding [vocab, d_model] ~ N(0, 1) (the scale of the hidden
+    states the layer workloads use), the final RMSNorm gain 1 + N(0, 0.02) and the LM head
+    [vocab, d_model] ~ N(0, 0.02)."""
+    return {
+        "embed": normal_bf16((vocab, d_model), seed, stream + 0, 0.0, 1.0),
+        "final_norm": normal_bf16((d_model,), seed, stream + 1, 1.0, 0.02),
+        "lm_head": normal_bf16((vocab, d_model), seed, stream + 2, 0.0, 0.02),
+    }
+
+
+def prompt_tokens(n: int, vocab: int, stream: int = 0, seed: int = SEED_HIDDEN) -> np.ndarray:
+    """n token ids uniform over the vocabulary (int32)."""
+    return _rng(seed, 1 << 20 | stream).integers(0, vocab, size=n, dtype=np.int32)
+
+
 def hidden_states(n_rows: int, d_model: int, stream: int = 0, seed: int = SEED_HIDDEN) -> np.ndarray:
     """N(0,1) hidden states [n_rows, d_model] as bf16 bit patterns."""
     return normal_bf16((n_rows, d_model), seed, stream, 0.0, 1.0)
