@@ -291,6 +291,7 @@ typedef struct {
     int32_t n_finished;              /* requests retired in this step */
     int32_t n_waiting;               /* requests still without blocks */
     float decode_ms;                 /* GPU time of this step's decode work if wait_decode, else -1 */
+    int32_t n_preempted;             /* rs_step_tokens: running requests sent back to WAITING for want of blocks */
 } rs_step_out;
 
 int32_t rs_submit(rs_ctx *ctx, int64_t req_id, int32_t prompt_len, int32_t output_len,
@@ -306,6 +307,77 @@ int32_t rs_request_state(rs_ctx *ctx, int64_t req_id);
 /* Host-only contexts have no events: this marks a PREFILLING request's event as completed
  * (lets the state machine be exercised without a GPU).  RS_ERR_STATE on a GPU context. */
 int32_t rs_debug_complete_prefill(rs_ctx *ctx, int64_t req_id);
+
+/* ---- token boundary: what turns the layer stack into a generator -------------------------------
+ * The paper's request starts as a prompt and ends when generation ends (section 4.4); how tokens
+ * become hidden states and back is the usual Llama head: x = E[token]; logits = RMSNorm(x_last;
+ * g_final) W_lm^T; greedy choice = the lowest index among the maxima of the float32 logits.
+ *
+ * rs_set_head: embed and lm_head are device bf16 [vocab][d_model], final_norm device bf16
+ * [d_model]; all borrowed (must stay valid and unchanged; the library keeps a packed copy of
+ * lm_head, so a changed matrix needs another rs_set_head).  eos_token < 0: no end-of-sequence
+ * token.  RS_ERR_BAD_ARG for vocab < 1 or a null pointer.
+ *
+ * rs_embed: x_out[i][:] = E[tokens[i]][:] for n rows, enqueued on `side`'s stream.  tokens is a
+ * device pointer.  A token outside [0, vocab) is never dereferenced: its row is zero-filled and the
+ * next rs_sync returns RS_ERR_BAD_ARG.
+ *
+ * rs_lm_head_greedy: for the n rows of x (device bf16 [n][d_model], n <= the side's row limit)
+ * computes the logits and the greedy token, enqueued on `side`'s stream.  logits_out (device
+ * float32 [n][vocab]) and tokens_out (device int32 [n]) may each be null.  Uses the side's
+ * normalised-row workspace: not to be interleaved with a layer call on the same side from another
+ * thread. */
+typedef struct {
+    const void *embed;
+    const void *final_norm;
+    const void *lm_head;
+    int32_t vocab;
+    int32_t eos_token;
+} rs_head_weights;
+int32_t rs_set_head(rs_ctx *ctx, const rs_head_weights *w);
+int32_t rs_embed(rs_ctx *ctx, int32_t side, const int32_t *tokens, int32_t n, void *x_out);
+int32_t rs_lm_head_greedy(rs_ctx *ctx, int32_t side, const void *x, int32_t n, float *logits_out,
+                          int32_t *tokens_out);
+
+/* ---- closed-loop serving: the whole request life cycle (sections 4.4, 4.5.1, 4.5.2) -------------
+ * Same state machine, schedulers and manager as rs_submit / rs_step, but requests are token
+ * sequences and the loop closes on the device: a prompt's tokens are embedded, run through all
+ * layers on the prefill side, and the head's greedy choice on the last prompt row is the request's
+ * first output token; every decode step embeds each running request's latest token, runs all
+ * layers and chooses the next one.  Needs rs_set_head.  Do not mix with rs_submit / rs_step on one
+ * context.
+ *
+ * rs_submit_tokens: prompt_tokens is a HOST array, copied before the call returns.  The request
+ * produces at most max_new_tokens tokens and stops early after the end-of-sequence token (which is
+ * part of its output).  prompt_len + max_new_tokens must fit max_context and max_pos.
+ *
+ * rs_step_tokens: one scheduling step, as rs_step, with these additions.
+ *   - Sampled tokens reach the host by an asynchronous copy that the NEXT step looks at, so the
+ *     end-of-sequence token is noticed one step late unless wait_decode is set: the request then
+ *     runs one step too many, whose token is dropped (the scheduling of step n+1 never waits for
+ *     the results of step n).  Token counts are known in advance and are never overrun.
+ *   - When a running request cannot get the block its next token needs, the most recently
+ *     arrived request that holds blocks and is not being prefilled right now (possibly the
+ *     starved request itself) is preempted: its blocks are released, it returns to WAITING at
+ *     its original place in the arrival order, and its next prefill runs over prompt + tokens
+ *     generated so far (recomputation; nothing is swapped out).  n_preempted counts these.
+ *     RS_ERR_NO_BLOCKS if the starved request is the only block holder, or if the victim's
+ *     sequence no longer fits max_prefill_tokens.
+ *   - Blocks released in a step may still be written by a decode step that is in flight; a
+ *     prefill started afterwards is ordered behind that step on the device.
+ *
+ * rs_request_output: the tokens generated so far (host array), *finished_out = 1 once the request
+ * has produced its last token and the host has seen it.
+ *
+ * rs_debug_push_sampled: host-only contexts have no sampler; this queues the token that the
+ * request's next sampling event (its prefill, then each decode step) will yield.  Without a queued
+ * token the event yields token 0.  RS_ERR_STATE on a GPU context. */
+int32_t rs_submit_tokens(rs_ctx *ctx, int64_t req_id, const int32_t *prompt_tokens, int32_t prompt_len,
+                         int32_t max_new_tokens);
+int32_t rs_step_tokens(rs_ctx *ctx, int32_t wait_decode, rs_step_out *out);
+int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out,
+                          int32_t *finished_out);
+int32_t rs_debug_push_sampled(rs_ctx *ctx, int64_t req_id, int32_t token);
 
 #ifdef __cplusplus
 }

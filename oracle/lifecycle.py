@@ -1,0 +1,154 @@
+"""Exact definition of the closed-loop request life cycle (TEST INFRASTRUCTURE ONLY).
+
+Sections 4.4, 4.5.1 and 4.5.2 of the paper: a request first waits for KV blocks (the decode side
+owns the only cache manager and sizes a prompt's blocks from its length), its block ids go to the
+prefill side, which serves prompts first come first served and never chunks them; completion of
+the prefill is a notification, after which the request joins the running decode batch; blocks are
+released when the request ends or is preempted.
+
+Readings where the paper is silent:
+  * a prompt's prefill yields the request's first output token; every decode step one more;
+  * a request ends with its max_new-th token or with the end-of-sequence token, which it keeps;
+  * one prefill is in flight at a time; the decode batch is capped and filled in arrival order;
+  * when a running request's next token has no block, the most recently arrived request that
+    holds blocks and is not being prefilled at that moment (possibly the starved request itself)
+    is preempted: its blocks are released, it waits again at its original place in the arrival
+    order, and its next prefill covers prompt + tokens generated so far (recomputation); if the
+    starved request is the only block holder the pool is simply too small;
+  * here every sampled token is visible to the scheduler at the next step (no lag).
+
+The tokens themselves come from outside: `script[req]` is the sequence of tokens the request's
+successive sampling events yield (a missing entry yields 0).  Everything is integer and exact.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional, Tuple
+
+from .kv_alloc import KVAllocator, NoBlocks
+
+WAITING, PREFILL_READY, PREFILLING, PREFILL_DONE, RUNNING, FINISHED = range(6)
+
+
+class _Req:
+    def __init__(self, rid, prompt_len, max_new, script):
+        self.id, self.prompt_len, self.max_new = rid, prompt_len, max_new
+        self.script = list(script)
+        self.events = 0          # sampling events consumed
+        self.out: List[int] = []
+        self.state = WAITING
+        self.n_prefill = prompt_len
+        self.ctx = 0
+        self.complete = False
+        self.prefill_done = False
+
+
+class Lifecycle:
+    def __init__(self, n_blocks: int, max_batch: int, eos: int = -1,
+                 split: Optional[Callable[[int, int, bool], Tuple[int, int]]] = None):
+        self.alloc = KVAllocator(n_blocks)
+        self.max_batch, self.eos = max_batch, eos
+        self.split = split
+        self.reqs: Dict[int, _Req] = {}
+        self.arrival: List[int] = []
+        self.running: List[int] = []
+        self.prefilling: Optional[int] = None
+        self.last_tokens: List[int] = []   # requests whose decode-step token is still to be read
+
+    def submit(self, rid: int, prompt_len: int, max_new: int, script=()):
+        self.reqs[rid] = _Req(rid, prompt_len, max_new, script)
+        self.arrival.append(rid)
+
+    def complete_prefill(self, rid: int):
+        assert self.reqs[rid].state == PREFILLING
+        self.reqs[rid].prefill_done = True
+
+    def _sample(self, r: _Req):
+        tok = r.script[r.events] if r.events < len(r.script) else 0
+        r.events += 1
+        if r.complete:
+            return
+        r.out.append(tok)
+        if tok == self.eos or len(r.out) >= r.max_new:
+            r.complete = True
+
+    def _finish(self, r: _Req):
+        r.state = FINISHED
+        if r.id in self.alloc.owned:
+            self.alloc.release(r.id)
+
+    def step(self) -> dict:
+        o = dict(n_promoted=0, n_finished=0, n_preempted=0, prefill_started_req=-1, prefill_started_tokens=0)
+        for rid in self.last_tokens:                       # tokens of the previous decode step
+            self._sample(self.reqs[rid])
+        self.last_tokens = []
+        if self.prefilling is not None and self.reqs[self.prefilling].prefill_done:
+            r = self.reqs[self.prefilling]
+            r.prefill_done = False
+            r.state, r.ctx = PREFILL_DONE, r.n_prefill
+            self.prefilling = None
+            self._sample(r)
+            if r.complete:
+                self._finish(r)
+                o["n_finished"] += 1
+        for rid in list(self.running):
+            if self.reqs[rid].complete:
+                self._finish(self.reqs[rid])
+                self.running.remove(rid)
+                o["n_finished"] += 1
+        while self.arrival and self.reqs[self.arrival[0]].state == FINISHED:
+            self.arrival.pop(0)
+        for rid in self.arrival:
+            r = self.reqs[rid]
+            if r.state == PREFILL_DONE and len(self.running) < self.max_batch:
+                r.state = RUNNING
+                self.running.append(rid)
+                o["n_promoted"] += 1
+        for rid in self.arrival:
+            r = self.reqs[rid]
+            if r.state != WAITING:
+                continue
+            try:
+                self.alloc.alloc(rid, r.n_prefill)
+            except NoBlocks:
+                break
+            r.state = PREFILL_READY
+        while True:                                        # room for every running request's next token
+            stuck = None
+            for rid in self.running:
+                try:
+                    self.alloc.alloc(rid, self.reqs[rid].ctx + 1)
+                except NoBlocks:
+                    stuck = rid
+                    break
+            if stuck is None:
+                break
+            v = next(self.reqs[rid] for rid in reversed(self.arrival)
+                     if self.reqs[rid].state in (RUNNING, PREFILL_DONE, PREFILL_READY))
+            if v.id == stuck and all(not b for rid, b in self.alloc.owned.items() if rid != stuck):
+                raise NoBlocks()
+            if v.state == RUNNING:
+                self.running.remove(v.id)
+            self.alloc.release(v.id)
+            v.state, v.n_prefill, v.ctx = WAITING, v.prompt_len + len(v.out), 0
+            o["n_preempted"] += 1
+        o["n_waiting"] = sum(1 for rid in self.arrival if self.reqs[rid].state == WAITING)
+        nxt = None
+        if self.prefilling is None:
+            nxt = next((rid for rid in self.arrival if self.reqs[rid].state == PREFILL_READY), None)
+        pending = self.prefilling is not None or nxt is not None
+        o["decode_batch"] = len(self.running)
+        o["decode_sum_ctx"] = sum(self.reqs[rid].ctx for rid in self.running)
+        o["batch_ids"] = list(self.running)
+        p_cus = 256
+        if self.split is not None and (self.running or pending):
+            p_cus, d_cus = self.split(len(self.running), o["decode_sum_ctx"], pending)
+            o["split"] = (p_cus, d_cus)
+        for rid in self.running:                           # the decode step
+            self.reqs[rid].ctx += 1
+        self.last_tokens = list(self.running)
+        if nxt is not None and p_cus > 0:
+            r = self.reqs[nxt]
+            r.state = PREFILLING
+            self.prefilling = nxt
+            o["prefill_started_req"], o["prefill_started_tokens"] = nxt, r.n_prefill
+        return o

@@ -31,6 +31,8 @@ EXPORTS = [
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_set_cu_split", "rs_get_cu_split",
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
+    "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
+    "rs_debug_push_sampled",
 ]
 
 
@@ -78,7 +80,13 @@ class StepOut(ctypes.Structure):
     _fields_ = [("prefill_cus", ctypes.c_int32), ("decode_cus", ctypes.c_int32), ("decode_batch", ctypes.c_int32),
                 ("decode_sum_ctx", ctypes.c_int64), ("prefill_started_tokens", ctypes.c_int32),
                 ("prefill_started_req", ctypes.c_int64), ("n_promoted", ctypes.c_int32),
-                ("n_finished", ctypes.c_int32), ("n_waiting", ctypes.c_int32), ("decode_ms", ctypes.c_float)]
+                ("n_finished", ctypes.c_int32), ("n_waiting", ctypes.c_int32), ("decode_ms", ctypes.c_float),
+                ("n_preempted", ctypes.c_int32)]
+
+
+class HeadWeights(ctypes.Structure):
+    _fields_ = [("embed", ctypes.c_void_p), ("final_norm", ctypes.c_void_p), ("lm_head", ctypes.c_void_p),
+                ("vocab", ctypes.c_int32), ("eos_token", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -312,6 +320,41 @@ class Context:
         so = StepOut()
         _check(self._lib.rs_step(self._h, ctypes.byref(si), ctypes.byref(so)))
         return so
+
+    # -- token boundary and closed-loop serving
+    def set_head(self, embed, final_norm, lm_head, vocab: int, eos_token: int = -1):
+        self._keep.append((embed, final_norm, lm_head))
+        w = HeadWeights(_ptr(embed), _ptr(final_norm), _ptr(lm_head), vocab, eos_token)
+        _check(self._lib.rs_set_head(self._h, ctypes.byref(w)))
+
+    def embed(self, side: int, tokens, n: int, x_out):
+        _check(self._lib.rs_embed(self._h, ctypes.c_int32(side), _ptr(tokens), ctypes.c_int32(n), _ptr(x_out)))
+
+    def lm_head_greedy(self, side: int, x, n: int, logits_out=None, tokens_out=None):
+        _check(self._lib.rs_lm_head_greedy(self._h, ctypes.c_int32(side), _ptr(x), ctypes.c_int32(n), _ptr(logits_out),
+                                           _ptr(tokens_out)))
+
+    def submit_tokens(self, req_id: int, prompt_tokens, max_new_tokens: int):
+        t = _i32(prompt_tokens)
+        _check(self._lib.rs_submit_tokens(self._h, ctypes.c_int64(req_id), t.ctypes.data_as(_i32p), ctypes.c_int32(len(t)),
+                                          ctypes.c_int32(max_new_tokens)))
+
+    def step_tokens(self, wait_decode: bool = False) -> StepOut:
+        so = StepOut()
+        _check(self._lib.rs_step_tokens(self._h, ctypes.c_int32(1 if wait_decode else 0), ctypes.byref(so)))
+        return so
+
+    def request_output(self, req_id: int, cap: int = 1 << 16):
+        """(tokens generated so far, finished flag)."""
+        out = np.empty(cap, dtype=np.int32)
+        n = ctypes.c_int32(0)
+        fin = ctypes.c_int32(0)
+        _check(self._lib.rs_request_output(self._h, ctypes.c_int64(req_id), out.ctypes.data_as(_i32p), ctypes.c_int32(cap),
+                                           ctypes.byref(n), ctypes.byref(fin)))
+        return out[:n.value].copy(), bool(fin.value)
+
+    def debug_push_sampled(self, req_id: int, token: int):
+        _check(self._lib.rs_debug_push_sampled(self._h, ctypes.c_int64(req_id), ctypes.c_int32(token)))
 
     def request_state(self, req_id: int) -> int:
         return _check(self._lib.rs_request_state(self._h, ctypes.c_int64(req_id)))

@@ -835,6 +835,16 @@ static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials
     hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
 }
 
+void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *partials, int *S_out, int *Nv_out) {
+    constexpr int RT = RS_SKINNY_RT, PD = 10;
+    const int Nv = skinny_virtual_n(a.N, EPI_STORE), S = skinny_splits(a.N, a.K, EPI_STORE);
+    *S_out = S;
+    *Nv_out = Nv;
+    if (a.M <= 0 || a.N <= 0) return;
+    hipLaunchKernelGGL((gemm_skinny_kernel<EPI_STORE, RT, PD>), dim3(Nv / (32 * RT), S), dim3(256), RT * 32768, st, a, partials,
+                       skinny_kb_per_wg(a.K, S), skinny_kblocks(a.K), Nv);
+}
+
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
     if (a.M <= 0 || a.N <= 0) return;
     switch (a.epi) {

@@ -76,8 +76,31 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 // `partials` (fp32, at least skinny_partial_elems(...) elements).  Reads A, Wp and Wp2.
 size_t skinny_partial_elems(int M, int N, int K, int epi);
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
+// Main pass only (a.epi must be EPI_STORE): leaves part[s][m][n], s < *S_out K-slices, row stride
+// *Nv_out floats; the product's element (m, n) is the sum of its slices in slice order.
+void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *partials, int *S_out, int *Nv_out);
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
+
+struct EmbedArgs {
+    const int32_t *tokens;     // [n], or per-slot tokens when row_slot is given
+    const int32_t *row_slot;   // [n] or nullptr
+    const bf16_t *table;       // [vocab][d]
+    bf16_t *x;                 // [n][d] row-major
+    int32_t *err_flag;
+    int n, d, vocab;
+};
+void launch_embed(hipStream_t st, const EmbedArgs &a);
+
+struct HeadArgmaxArgs {
+    const float *part;         // [S][M][Nv] partial logits
+    float *logits;             // [M][N] or nullptr
+    int32_t *tokens;           // [M] or nullptr
+    const int32_t *row_slot;   // [M] or nullptr
+    int32_t *tok_by_slot;      // scattered copy of the tokens, or nullptr
+    int S, M, N, Nv;
+};
+void launch_head_argmax(hipStream_t st, const HeadArgmaxArgs &a);
 
 // Counts workgroups per physical CU: hist[(xcc << 8) | (se << 5) | (sh << 4) | cu] += 1.
 void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);

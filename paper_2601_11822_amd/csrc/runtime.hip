@@ -53,6 +53,14 @@ struct Request {
     int32_t generated = 0;  // decode steps taken
     hipEvent_t done = nullptr;
     bool host_done = false;
+    // closed-loop (token) requests
+    bool token_mode = false;
+    int slot = -1;                 // index of the request's current-token cell and prompt region on the device
+    std::vector<int32_t> toks;     // prompt, then every generated token the host has seen
+    int32_t n_prefill = 0;         // tokens the next prefill covers (prompt, plus generated ones after a preemption)
+    int32_t n_sampled = 0;         // sampling events enqueued so far (known without looking at any token)
+    bool complete = false;         // last token seen (end-of-sequence or the token limit)
+    std::deque<int32_t> injected;  // host-only contexts: tokens the next sampling events will yield
 };
 
 struct Side {
@@ -119,6 +127,29 @@ struct rs_ctx {
     hipEvent_t staged[2] = {nullptr, nullptr};
     hipEvent_t pstaged = nullptr;
     int stage_flip = 0;
+    // a decode step's end, alternating: a prefill that may reuse just-released blocks waits for the step
+    // enqueued before the release
+    hipEvent_t step_end[2] = {nullptr, nullptr};
+    int step_end_idx = 0;
+    bool step_end_valid[2] = {false, false};
+
+    // token boundary
+    rs_head_weights head{};
+    bool have_head = false;
+    bf16_t *packed_lm = nullptr;
+    float *head_part[2] = {nullptr, nullptr};
+    // closed-loop serving
+    int serving_mode = 0;            // 0 none yet, 1 hidden-state requests, 2 token requests
+    int n_slots = 0;
+    std::vector<int> free_slots;
+    int32_t *d_tok = nullptr;        // [n_slots] latest token of each live request
+    int32_t *d_prompts = nullptr;    // [n_slots][max_context] token sequences to prefill
+    int32_t *h_first = nullptr;      // pinned [n_slots]: the token a prefill chose
+    int32_t *d_rowslot = nullptr, *h_rowslot[2] = {nullptr, nullptr};
+    int32_t *d_sampled = nullptr, *h_sampled[2] = {nullptr, nullptr};
+    hipEvent_t sampled_ev[2] = {nullptr, nullptr};
+    std::vector<int64_t> inflight[2];   // request ids of the rows of a step whose tokens the host has not read yet
+    bool pending[2] = {false, false};
 };
 
 namespace {
@@ -387,6 +418,48 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     return RS_OK;
 }
 
+// Final RMSNorm + LM head + greedy choice for n rows of x, in groups of at most 64 rows (the
+// weight-streaming GEMM's limit).  The chosen tokens go to `tokens` (row order) and/or to
+// tok_by_slot[row_slot[row]].
+int32_t head_greedy(rs_ctx *c, int side, const bf16_t *x, int n, float *logits, int32_t *tokens,
+                    const int32_t *row_slot, int32_t *tok_by_slot) {
+    const rs_model_desc &m = c->m;
+    Workspace &w = c->ws[side];
+    hipStream_t st = c->side[side].stream;
+    const int d = m.d_model, V = c->head.vocab;
+    for (int g0 = 0; g0 < n; g0 += 64) {
+        const int mg = std::min(64, n - g0);
+        c->last_rows[side] = mg;
+        launch_rmsnorm(st, x + (size_t)g0 * d, (const bf16_t *)c->head.final_norm, w.h, mg, d, m.rms_eps);
+        GemmArgs g{w.h, (const bf16_t *)c->head.lm_head, nullptr, c->packed_lm, nullptr, nullptr, nullptr, mg, V, d, EPI_STORE,
+                   0, c->side[side].cus};
+        int S = 1, Nv = 0;
+        launch_gemm_skinny_partials(st, g, c->head_part[side], &S, &Nv);
+        HeadArgmaxArgs ha{c->head_part[side], logits ? logits + (size_t)g0 * V : nullptr, tokens ? tokens + g0 : nullptr,
+                          row_slot ? row_slot + g0 : nullptr, tok_by_slot, S, mg, V, Nv};
+        launch_head_argmax(st, ha);
+    }
+    HIP_TRY(hipGetLastError());
+    return RS_OK;
+}
+
+int32_t enter_mode(rs_ctx *c, int mode) {
+    if (c->serving_mode && c->serving_mode != mode)
+        return fail(RS_ERR_STATE, "hidden-state and token requests cannot be mixed on one context");
+    c->serving_mode = mode;
+    return RS_OK;
+}
+
+int32_t check_head_call(rs_ctx *c, int side, int n) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "side %d", side);
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context: no device work");
+    if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    if (c->side[side].cus <= 0 || !c->side[side].stream) return fail(RS_ERR_STATE, "side %d has no CUs", side);
+    if (n < 1 || n > c->ws[side].rows) return fail(RS_ERR_BAD_ARG, "%d rows, the side's workspace holds %d", n, c->ws[side].rows);
+    return RS_OK;
+}
+
 }  // namespace
 
 // ================================================================================ C ABI
@@ -435,6 +508,8 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     c->free_list.resize(pool->n_blocks);
     for (int i = 0; i < pool->n_blocks; ++i) c->free_list[i] = pool->n_blocks - 1 - i;  // pop -> 0,1,2,..
     c->max_blk_per_req = (limits->max_context + RS_KV_BLOCK - 1) / RS_KV_BLOCK;
+    c->n_slots = 4 * std::max(1, limits->max_decode_batch) + 64;
+    for (int i = c->n_slots - 1; i >= 0; --i) c->free_slots.push_back(i);
     if (prof) {
         c->have_prof = true;
         c->batch_edges.assign(prof->batch_edges, prof->batch_edges + prof->n_batch);
@@ -489,6 +564,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
         }
         HIP_TRY(hipHostMalloc(&c->h_ptab, (size_t)c->max_blk_per_req * sizeof(int32_t)));
         HIP_TRY(hipEventCreateWithFlags(&c->pstaged, hipEventDisableTiming));
+        for (int i = 0; i < 2; ++i) HIP_TRY(hipEventCreateWithFlags(&c->step_end[i], hipEventDisableTiming));
         return set_split(c, RS_TOTAL_CUS, RS_TOTAL_CUS);
     };
     rc = gpu_setup();
@@ -528,6 +604,16 @@ int32_t rs_destroy(rs_ctx *c) {
         }
         if (c->h_ptab) (void)hipHostFree(c->h_ptab);
         if (c->pstaged) (void)hipEventDestroy(c->pstaged);
+        for (int i = 0; i < 2; ++i) {
+            if (c->step_end[i]) (void)hipEventDestroy(c->step_end[i]);
+            if (c->head_part[i]) (void)hipFree(c->head_part[i]);
+            if (c->h_rowslot[i]) (void)hipHostFree(c->h_rowslot[i]);
+            if (c->h_sampled[i]) (void)hipHostFree(c->h_sampled[i]);
+            if (c->sampled_ev[i]) (void)hipEventDestroy(c->sampled_ev[i]);
+        }
+        for (void *q : {(void *)c->packed_lm, (void *)c->d_tok, (void *)c->d_prompts, (void *)c->d_rowslot, (void *)c->d_sampled})
+            if (q) (void)hipFree(q);
+        if (c->h_first) (void)hipHostFree(c->h_first);
     }
     delete c;
     return RS_OK;
@@ -556,6 +642,63 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     c->weights[layer] = *w;
     c->have_weights[layer] = true;
     return RS_OK;
+}
+
+int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
+    if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (w->vocab < 1) return fail(RS_ERR_BAD_ARG, "vocab %d", w->vocab);
+    if (c->gpu) {
+        if (!w->embed || !w->final_norm || !w->lm_head) return fail(RS_ERR_BAD_ARG, "null head pointer");
+        HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipDeviceSynchronize());   // the packed copy and the partial-sum buffers may be in use
+        const int d = c->m.d_model;
+        if (c->packed_lm) { (void)hipFree(c->packed_lm); c->packed_lm = nullptr; }
+        HIP_TRY(hipMalloc((void **)&c->packed_lm, packed_weight_elems(w->vocab, d) * sizeof(bf16_t)));
+        launch_pack_weights(nullptr, (const bf16_t *)w->lm_head, c->packed_lm, w->vocab, d);
+        for (int s = 0; s < 2; ++s) {
+            if (c->head_part[s]) { (void)hipFree(c->head_part[s]); c->head_part[s] = nullptr; }
+            if (c->ws[s].rows > 0)
+                HIP_TRY(hipMalloc((void **)&c->head_part[s], skinny_partial_elems(64, w->vocab, d, EPI_STORE) * sizeof(float)));
+        }
+        if (!c->d_tok) {
+            const size_t ns = (size_t)c->n_slots, mc = (size_t)c->lim.max_context, nb = std::max(1, c->lim.max_decode_batch);
+            HIP_TRY(hipMalloc((void **)&c->d_tok, ns * sizeof(int32_t)));
+            HIP_TRY(hipMemset(c->d_tok, 0, ns * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_prompts, ns * mc * sizeof(int32_t)));
+            HIP_TRY(hipHostMalloc((void **)&c->h_first, ns * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_rowslot, nb * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_sampled, nb * sizeof(int32_t)));
+            for (int i = 0; i < 2; ++i) {
+                HIP_TRY(hipHostMalloc((void **)&c->h_rowslot[i], nb * sizeof(int32_t)));
+                HIP_TRY(hipHostMalloc((void **)&c->h_sampled[i], nb * sizeof(int32_t)));
+                HIP_TRY(hipEventCreateWithFlags(&c->sampled_ev[i], hipEventDisableTiming));
+            }
+        }
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    c->head = *w;
+    c->have_head = true;
+    return RS_OK;
+}
+
+int32_t rs_embed(rs_ctx *c, int32_t side, const int32_t *tokens, int32_t n, void *x_out) {
+    int32_t rc = check_head_call(c, side, n);
+    if (rc) return rc;
+    if (!tokens || !x_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    HIP_TRY(hipSetDevice(c->device));
+    launch_embed(c->side[side].stream, EmbedArgs{tokens, nullptr, (const bf16_t *)c->head.embed, (bf16_t *)x_out, c->err_flag, n,
+                                                 c->m.d_model, c->head.vocab});
+    HIP_TRY(hipGetLastError());
+    return RS_OK;
+}
+
+int32_t rs_lm_head_greedy(rs_ctx *c, int32_t side, const void *x, int32_t n, float *logits_out, int32_t *tokens_out) {
+    int32_t rc = check_head_call(c, side, n);
+    if (rc) return rc;
+    if (!x) return fail(RS_ERR_BAD_ARG, "null x");
+    HIP_TRY(hipSetDevice(c->device));
+    return head_greedy(c, side, (const bf16_t *)x, n, logits_out, tokens_out, nullptr, nullptr);
 }
 
 int32_t rs_kv_alloc(rs_ctx *c, int64_t req_id, int32_t n_tokens_total, int32_t *block_ids_out, int32_t cap,
@@ -708,6 +851,7 @@ int32_t rs_sync(rs_ctx *c, int32_t side) {
     HIP_TRY(hipMemcpy(&flag, c->err_flag, sizeof flag, hipMemcpyDeviceToHost));
     if (flag) {
         HIP_TRY(hipMemset(c->err_flag, 0, sizeof flag));
+        if (flag & 4) return fail(RS_ERR_BAD_ARG, "a kernel met a token outside the vocabulary (flag %d)", flag);
         return fail(RS_ERR_BAD_BLOCK, "a kernel skipped an illegal block id, position or context length (flag %d)", flag);
     }
     return RS_OK;
@@ -842,6 +986,8 @@ int32_t rs_submit(rs_ctx *c, int64_t req_id, int32_t prompt_len, int32_t output_
     if (prompt_len + output_len > c->lim.max_context || prompt_len + output_len > c->m.max_pos)
         return fail(RS_ERR_BAD_ARG, "prompt+output %d exceeds max_context/max_pos", prompt_len + output_len);
     if (c->gpu && prompt_len > c->ws[RS_SIDE_PREFILL].rows) return fail(RS_ERR_BAD_ARG, "prompt longer than max_prefill_tokens");
+    int32_t mrc = enter_mode(c, 1);
+    if (mrc) return mrc;
     Request r{};
     r.id = req_id;
     r.prompt_len = prompt_len;
@@ -876,14 +1022,92 @@ int32_t rs_debug_complete_prefill(rs_ctx *c, int64_t req_id) {
     return RS_OK;
 }
 
-int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
-    if (!c || !in || !out) return fail(RS_ERR_BAD_ARG, "null argument");
-    if (c->gpu && (!in->decode_hidden || !in->decode_out)) return fail(RS_ERR_BAD_ARG, "null decode buffers");
+// ---- the serving step, for hidden-state requests (rs_step) and token requests (rs_step_tokens) ----
+namespace {
+
+int32_t out_count(const Request &r) { return (int32_t)r.toks.size() - r.prompt_len; }
+
+// A sampled token reaches the host: kept unless the request already has its last token.
+void accept_token(rs_ctx *c, Request &r, int32_t tok) {
+    if (r.complete) return;
+    r.toks.push_back(tok);
+    if ((c->head.eos_token >= 0 && tok == c->head.eos_token) || out_count(r) >= r.output_len) r.complete = true;
+}
+
+int32_t next_injected(Request &r) {
+    if (r.injected.empty()) return 0;
+    const int32_t t = r.injected.front();
+    r.injected.pop_front();
+    return t;
+}
+
+// Reads the tokens of the decode step staged in buffer f (its copy must have completed).
+void harvest(rs_ctx *c, int f) {
+    if (!c->pending[f]) return;
+    for (size_t i = 0; i < c->inflight[f].size(); ++i) {
+        Request &r = c->reqs[c->inflight[f][i]];
+        accept_token(c, r, c->gpu ? c->h_sampled[f][i] : next_injected(r));
+    }
+    c->pending[f] = false;
+    c->inflight[f].clear();
+}
+
+// Oldest first; with must = false only what has already arrived.
+int32_t harvest_ready(rs_ctx *c, bool must) {
+    const int order[2] = {c->stage_flip ^ 1, c->stage_flip};
+    for (int f : order) {
+        if (!c->pending[f]) continue;
+        if (c->gpu) {
+            if (must) HIP_TRY(hipEventSynchronize(c->sampled_ev[f]));
+            else {
+                hipError_t q = hipEventQuery(c->sampled_ev[f]);
+                if (q == hipErrorNotReady) return RS_OK;   // the newer one cannot be ready either
+                if (q != hipSuccess) return fail(RS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q));
+            }
+        }
+        harvest(c, f);
+    }
+    return RS_OK;
+}
+
+void release_request(rs_ctx *c, Request &r) {
+    r.state = FINISHED;
+    rs_kv_free(c, r.id);
+    if (r.done) { (void)hipEventDestroy(r.done); r.done = nullptr; }
+    if (r.slot >= 0) { c->free_slots.push_back(r.slot); r.slot = -1; }
+}
+
+bool wants_retire(const Request &r) {
+    return r.token_mode ? (r.complete || r.n_sampled >= r.output_len) : r.generated >= r.output_len;
+}
+
+int retire_finished(rs_ctx *c) {
+    int n = 0;
+    for (size_t i = 0; i < c->running.size();) {
+        Request &r = c->reqs[c->running[i]];
+        if (wants_retire(r)) {
+            release_request(c, r);
+            c->running.erase(c->running.begin() + i);
+            ++n;
+        } else {
+            ++i;
+        }
+    }
+    return n;
+}
+
+int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token_mode) {
     *out = rs_step_out{};
     out->prefill_started_req = -1;
     out->decode_ms = -1.f;
     const int maxB = c->lim.max_decode_batch;
+    if (c->gpu) HIP_TRY(hipSetDevice(c->device));
 
+    // 0. tokens of earlier steps that have reached the host
+    if (token_mode) {
+        int32_t rc = harvest_ready(c, false);
+        if (rc) return rc;
+    }
     // 1a. the prefill "notification": event completed -> PREFILL_DONE
     if (c->prefilling >= 0) {
         Request &r = c->reqs[c->prefilling];
@@ -895,23 +1119,17 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
         }
         if (done) {
             r.state = PREFILL_DONE;
-            r.ctx_len = r.prompt_len;
+            r.host_done = false;
+            r.ctx_len = token_mode ? r.n_prefill : r.prompt_len;
             c->prefilling = -1;
+            if (token_mode) {   // the prefill's own token
+                accept_token(c, r, c->gpu ? c->h_first[r.slot] : next_injected(r));
+                if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
+            }
         }
     }
     // 1b. retire requests that produced all their tokens
-    for (size_t i = 0; i < c->running.size();) {
-        Request &r = c->reqs[c->running[i]];
-        if (r.generated >= r.output_len) {
-            r.state = FINISHED;
-            rs_kv_free(c, r.id);
-            if (r.done) { (void)hipEventDestroy(r.done); r.done = nullptr; }
-            c->running.erase(c->running.begin() + i);
-            out->n_finished++;
-        } else {
-            ++i;
-        }
-    }
+    out->n_finished += retire_finished(c);
     while (!c->arrival.empty() && c->reqs[c->arrival.front()].state == FINISHED) c->arrival.pop_front();
     // 1c. promote finished prefills into the decode batch, FCFS
     for (int64_t id : c->arrival) {
@@ -922,17 +1140,59 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
             out->n_promoted++;
         }
     }
-    // 2. prompt blocks for waiting requests in arrival order (stop at the first that does not fit)
+    // 2. blocks for waiting requests in arrival order (stop at the first that does not fit)
     for (int64_t id : c->arrival) {
         Request &r = c->reqs[id];
         if (r.state != WAITING) continue;
-        if (kv_alloc(c, id, r.prompt_len, nullptr) != RS_OK) break;
+        if (kv_alloc(c, id, token_mode ? r.n_prefill : r.prompt_len, nullptr) != RS_OK) break;
         r.state = PREFILL_READY;
+    }
+
+    // 3. room for every running request's next token; in token mode a request that cannot grow
+    //    sends the most recently arrived running request back to WAITING (recomputation)
+    bool synced = false;
+    for (size_t i = 0; i < c->running.size();) {
+        Request &r = c->reqs[c->running[i]];
+        if (kv_alloc(c, r.id, r.ctx_len + 1, nullptr) == RS_OK) { ++i; continue; }
+        if (!token_mode)
+            return fail(RS_ERR_NO_BLOCKS, "no block to grow request %lld (hidden-state requests are not preempted)", (long long)r.id);
+        if (!synced) {   // the victim's sequence must be complete on the host; late tokens may also end requests
+            int32_t rc = harvest_ready(c, true);
+            if (rc) return rc;
+            out->n_finished += retire_finished(c);
+            synced = true;
+            i = 0;
+            continue;
+        }
+        Request *vp = nullptr;
+        for (auto it = c->arrival.rbegin(); it != c->arrival.rend() && !vp; ++it) {
+            Request &q = c->reqs[*it];
+            if (q.state == RUNNING || q.state == PREFILL_DONE || q.state == PREFILL_READY) vp = &q;
+        }
+        Request &v = *vp;   // exists: r itself is RUNNING
+        if (v.id == r.id) {
+            bool other = false;
+            for (auto &kv : c->owned) other = other || (kv.first != r.id && !kv.second.empty());
+            if (!other) return fail(RS_ERR_NO_BLOCKS, "request %lld alone does not fit the pool", (long long)r.id);
+        }
+        const int32_t n_all = (int32_t)v.toks.size();
+        if (c->gpu && n_all > c->ws[RS_SIDE_PREFILL].rows)
+            return fail(RS_ERR_NO_BLOCKS, "request %lld cannot be preempted: %d tokens exceed max_prefill_tokens", (long long)v.id, n_all);
+        if (c->gpu && n_all > v.prompt_len)   // generated tokens join the sequence to prefill (rare path: blocking copy)
+            HIP_TRY(hipMemcpy(c->d_prompts + (size_t)v.slot * c->lim.max_context + v.prompt_len, v.toks.data() + v.prompt_len,
+                              (size_t)(n_all - v.prompt_len) * sizeof(int32_t), hipMemcpyHostToDevice));
+        if (v.state == RUNNING) c->running.erase(std::find(c->running.begin(), c->running.end(), v.id));
+        rs_kv_free(c, v.id);
+        v.state = WAITING;
+        v.n_prefill = n_all;
+        v.ctx_len = 0;
+        out->n_preempted++;
+        i = 0;
     }
     for (int64_t id : c->arrival)
         if (c->reqs[id].state == WAITING) out->n_waiting++;
 
-    // 3. the split for this step
+    // 4. the split for this step
     int64_t next_prefill = -1;
     if (c->prefilling < 0)
         for (int64_t id : c->arrival)
@@ -953,37 +1213,60 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
     out->decode_batch = B;
     out->decode_sum_ctx = sum_ctx;
 
-    // 4. one decode step over the running batch
+    // a prefill started below may have been given blocks released above, which the decode step enqueued by
+    // the previous call may still write: it is ordered behind that step
+    const int prev_end = c->step_end_idx;
+
+    // 5. one decode step over the running batch
     c->last_batch.assign(c->running.begin(), c->running.end());
     if (B > 0) {
         int max_ctx = 1;
-        for (int64_t id : c->running) {
-            Request &r = c->reqs[id];
-            if (kv_alloc(c, id, r.ctx_len + 1, nullptr) != RS_OK)
-                return fail(RS_ERR_NO_BLOCKS, "no block to grow request %lld (preemption is not implemented)", (long long)id);
-            max_ctx = std::max(max_ctx, r.ctx_len + 1);
+        for (int64_t id : c->running) max_ctx = std::max(max_ctx, c->reqs[id].ctx_len + 1);
+        const int flip = c->stage_flip ^= 1;
+        if (token_mode && c->pending[flip]) {   // the staging buffers are about to be rewritten
+            if (c->gpu) HIP_TRY(hipEventSynchronize(c->sampled_ev[flip]));
+            harvest(c, flip);
         }
         if (c->gpu) {
-            const int flip = c->stage_flip ^= 1;
             HIP_TRY(hipEventSynchronize(c->staged[flip]));
             const int mb = c->max_blk_per_req;
             for (int i = 0; i < B; ++i) {
                 Request &r = c->reqs[c->running[i]];
                 c->h_ctx[flip][i] = r.ctx_len;
+                if (token_mode) c->h_rowslot[flip][i] = r.slot;
                 const std::vector<int32_t> &ids = c->owned[r.id];
                 for (int j = 0; j < mb; ++j) c->h_tab[flip][(size_t)i * mb + j] = j < (int)ids.size() ? ids[j] : -1;
             }
             hipStream_t st = c->side[RS_SIDE_DECODE].stream;
             HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
             HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+            if (token_mode)
+                HIP_TRY(hipMemcpyAsync(c->d_rowslot, c->h_rowslot[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
             HIP_TRY(hipEventRecord(c->staged[flip], st));
             if (in->wait_decode) { int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2); if (rc) return rc; }
+            Workspace &w = c->ws[RS_SIDE_DECODE];
+            const void *x_first = in->decode_hidden;
+            void *x_out = in->decode_out;
+            if (token_mode) {
+                launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag, B,
+                                           c->m.d_model, c->head.vocab});
+                x_first = w.xbuf;
+                x_out = w.xbuf;
+            }
             for (int l = 0; l < c->m.n_layers; ++l) {
                 if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                int32_t rc = decode_layer(c, l, l == 0 ? in->decode_hidden : in->decode_out, in->decode_out, c->d_ctx,
-                                          c->d_tab, mb, B, max_ctx);
+                int32_t rc = decode_layer(c, l, l == 0 ? x_first : (const void *)x_out, x_out, c->d_ctx, c->d_tab, mb, B, max_ctx);
                 if (rc) return rc;
             }
+            if (token_mode) {
+                int32_t rc = head_greedy(c, RS_SIDE_DECODE, w.xbuf, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
+                if (rc) return rc;
+                HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                HIP_TRY(hipEventRecord(c->sampled_ev[flip], st));
+            }
+            c->step_end_idx ^= 1;
+            HIP_TRY(hipEventRecord(c->step_end[c->step_end_idx], st));
+            c->step_end_valid[c->step_end_idx] = true;
             if (in->wait_decode) {
                 int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 1);
                 if (rc) return rc;
@@ -991,39 +1274,137 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
                 if (rc) return rc;
             }
         }
+        if (token_mode) {
+            c->inflight[flip].assign(c->running.begin(), c->running.end());
+            c->pending[flip] = true;
+        }
         for (int64_t id : c->running) {
             Request &r = c->reqs[id];
             r.ctx_len++;
             r.generated++;
+            r.n_sampled++;
+        }
+        if (token_mode && in->wait_decode) {
+            int32_t rc = harvest_ready(c, true);
+            if (rc) return rc;
         }
     }
 
-    // 5. start the next whole-prompt prefill if the prefill side is idle
+    // 6. start the next whole-prompt prefill if the prefill side is idle
     if (next_prefill >= 0 && c->side[RS_SIDE_PREFILL].cus > 0) {
         Request &r = c->reqs[next_prefill];
+        const int32_t n_tok = token_mode ? r.n_prefill : r.prompt_len;
         if (c->gpu) {
             const int mb = c->max_blk_per_req;
             HIP_TRY(hipEventSynchronize(c->pstaged));
             const std::vector<int32_t> &ids = c->owned[r.id];
             for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)ids.size() ? ids[j] : -1;
             hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+            if (c->step_end_valid[prev_end]) HIP_TRY(hipStreamWaitEvent(st, c->step_end[prev_end], 0));
             HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
             HIP_TRY(hipEventRecord(c->pstaged, st));
-            const int32_t cu[2] = {0, r.prompt_len};
+            const int32_t cu[2] = {0, n_tok};
             Workspace &w = c->ws[RS_SIDE_PREFILL];
+            const void *x_first = r.prompt_hidden;
+            if (token_mode) {
+                launch_embed(st, EmbedArgs{c->d_prompts + (size_t)r.slot * c->lim.max_context, nullptr, (const bf16_t *)c->head.embed,
+                                           w.xbuf, c->err_flag, n_tok, c->m.d_model, c->head.vocab});
+                x_first = w.xbuf;
+            }
             for (int l = 0; l < c->m.n_layers; ++l) {
                 if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                int32_t rc = prefill_layer(c, l, l == 0 ? r.prompt_hidden : (const void *)w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
+                int32_t rc = prefill_layer(c, l, l == 0 ? x_first : (const void *)w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
                 if (rc) return rc;
+            }
+            if (token_mode) {
+                int32_t rc = head_greedy(c, RS_SIDE_PREFILL, w.xbuf + (size_t)(n_tok - 1) * c->m.d_model, 1, nullptr, nullptr, nullptr,
+                                         c->d_tok + r.slot);
+                if (rc) return rc;
+                HIP_TRY(hipMemcpyAsync(c->h_first + r.slot, c->d_tok + r.slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
             }
             if (!r.done) HIP_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
             HIP_TRY(hipEventRecord(r.done, st));
         }
+        if (token_mode) r.n_sampled++;
         r.state = PREFILLING;
         c->prefilling = r.id;
         out->prefill_started_req = r.id;
-        out->prefill_started_tokens = r.prompt_len;
+        out->prefill_started_tokens = n_tok;
     }
+    return RS_OK;
+}
+
+}  // namespace
+
+int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
+    if (!c || !in || !out) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (c->gpu && (!in->decode_hidden || !in->decode_out)) return fail(RS_ERR_BAD_ARG, "null decode buffers");
+    int32_t rc = enter_mode(c, 1);
+    if (rc) return rc;
+    return serve_step(c, in, out, false);
+}
+
+int32_t rs_submit_tokens(rs_ctx *c, int64_t req_id, const int32_t *prompt_tokens, int32_t prompt_len, int32_t max_new_tokens) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    if (!prompt_tokens || prompt_len < 1 || max_new_tokens < 1) return fail(RS_ERR_BAD_ARG, "need a prompt and max_new_tokens >= 1");
+    if (c->reqs.count(req_id)) return fail(RS_ERR_BAD_ARG, "request %lld already known", (long long)req_id);
+    if (prompt_len + max_new_tokens > c->lim.max_context || prompt_len + max_new_tokens > c->m.max_pos)
+        return fail(RS_ERR_BAD_ARG, "prompt+output %d exceeds max_context/max_pos", prompt_len + max_new_tokens);
+    if (c->gpu && prompt_len > c->ws[RS_SIDE_PREFILL].rows) return fail(RS_ERR_BAD_ARG, "prompt longer than max_prefill_tokens");
+    for (int i = 0; i < prompt_len; ++i)
+        if (prompt_tokens[i] < 0 || prompt_tokens[i] >= c->head.vocab)
+            return fail(RS_ERR_BAD_ARG, "prompt token %d at %d outside the vocabulary of %d", prompt_tokens[i], i, c->head.vocab);
+    if (c->free_slots.empty()) return fail(RS_ERR_STATE, "too many live requests (%d)", c->n_slots);
+    int32_t rc = enter_mode(c, 2);
+    if (rc) return rc;
+    Request r{};
+    r.id = req_id;
+    r.prompt_len = prompt_len;
+    r.output_len = max_new_tokens;
+    r.token_mode = true;
+    r.n_prefill = prompt_len;
+    r.toks.assign(prompt_tokens, prompt_tokens + prompt_len);
+    r.slot = c->free_slots.back();
+    if (c->gpu) {
+        HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipMemcpy(c->d_prompts + (size_t)r.slot * c->lim.max_context, prompt_tokens, (size_t)prompt_len * sizeof(int32_t),
+                          hipMemcpyHostToDevice));
+    }
+    c->free_slots.pop_back();
+    c->reqs[req_id] = std::move(r);
+    c->arrival.push_back(req_id);
+    return RS_OK;
+}
+
+int32_t rs_step_tokens(rs_ctx *c, int32_t wait_decode, rs_step_out *out) {
+    if (!c || !out) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    int32_t rc = enter_mode(c, 2);
+    if (rc) return rc;
+    rs_step_in in{nullptr, nullptr, wait_decode};
+    return serve_step(c, &in, out, true);
+}
+
+int32_t rs_request_output(rs_ctx *c, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out, int32_t *finished_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !tokens_out)) return fail(RS_ERR_BAD_ARG, "null argument");
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
+    const Request &r = it->second;
+    const int32_t n = out_count(r);
+    if (n > cap) return fail(RS_ERR_BAD_ARG, "buffer of %d too small for %d tokens", cap, n);
+    std::copy(r.toks.begin() + r.prompt_len, r.toks.end(), tokens_out);
+    *n_out = n;
+    if (finished_out) *finished_out = r.complete ? 1 : 0;
+    return RS_OK;
+}
+
+int32_t rs_debug_push_sampled(rs_ctx *c, int64_t req_id, int32_t token) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->gpu) return fail(RS_ERR_STATE, "only for host-only contexts");
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
+    it->second.injected.push_back(token);
     return RS_OK;
 }
 

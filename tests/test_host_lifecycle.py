@@ -1,0 +1,198 @@
+"""Closed-loop request life cycle on the CPU: pins of the integer oracle (`oracle/lifecycle.py`), then
+the library's state machine (host-only context, sampled tokens injected) against it on random traces."""
+import numpy as np
+import pytest
+
+import paper_2601_11822_amd as rs
+import rs_synth as S
+from oracle.kv_alloc import NoBlocks
+from oracle.lifecycle import FINISHED, Lifecycle
+
+EOS = 7
+
+
+def _trace(seed, n_req=14, max_prompt=60, max_new=30, vocab=40):
+    g = np.random.default_rng(seed)
+    reqs = []
+    for i in range(n_req):
+        pl = int(g.integers(1, max_prompt + 1))
+        mn = int(g.integers(1, max_new + 1))
+        script = [int(t) for t in g.integers(0, vocab, size=mn + 4)]
+        reqs.append((100 + i, pl, mn, script, int(g.integers(0, 12)), ))
+    delays = [int(d) for d in g.integers(0, 3, size=400)]
+    return reqs, delays
+
+
+def _expected_output(script, max_new, eos):
+    out = []
+    for t in script:
+        out.append(t)
+        if t == eos or len(out) >= max_new:
+            break
+    return out
+
+
+def _drive(sim_submit, sim_step, sim_complete, reqs, delays, max_steps=2000):
+    """Submits each request at its arrival step, completes each prefill `delay` steps after it started."""
+    log, due = [], {}
+    todo = sorted(reqs, key=lambda r: r[4])
+    n_done, step = 0, 0
+    while n_done < len(reqs) and step < max_steps:
+        while todo and todo[0][4] <= step:
+            rid, pl, mn, script, _ = todo.pop(0)
+            sim_submit(rid, pl, mn, script)
+        for rid in [r for r, s in due.items() if s <= step]:
+            sim_complete(rid)
+            del due[rid]
+        o = sim_step()
+        log.append(o)
+        n_done += o["n_finished"]
+        if o["prefill_started_req"] >= 0:
+            due[o["prefill_started_req"]] = step + 1 + delays[step % len(delays)]
+        step += 1
+    assert n_done == len(reqs), "trace did not drain"
+    return log
+
+
+# ------------------------------------------------------------------------- pins of the oracle
+@pytest.mark.parametrize("n_blocks,seed", [(1000, 1), (12, 2), (8, 3), (7, 4)])
+def test_oracle_outputs_are_script_prefixes_and_blocks_return(n_blocks, seed):
+    reqs, delays = _trace(seed)
+    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS)
+    held_max = 0
+
+    def step():
+        nonlocal held_max
+        o = lc.step()
+        held_max = max(held_max, n_blocks - lc.alloc.n_free())
+        # every running request owns exactly the blocks its cached tokens need (ctx counts this step's token)
+        for rid in lc.running:
+            assert len(lc.alloc.owned[rid]) == -(-lc.reqs[rid].ctx // 16)
+        ids = [b for v in lc.alloc.owned.values() for b in v]
+        assert len(ids) == len(set(ids)) and len(ids) + lc.alloc.n_free() == n_blocks
+        assert o["decode_batch"] <= 4
+        return o
+
+    log = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), step, lc.complete_prefill, reqs, delays)
+    for rid, pl, mn, script, _ in reqs:
+        assert lc.reqs[rid].state == FINISHED
+        assert lc.reqs[rid].out == _expected_output(script, mn, EOS)
+    assert lc.alloc.n_free() == n_blocks and held_max <= n_blocks
+    n_pre = sum(o["n_preempted"] for o in log)
+    if n_blocks == 1000:
+        assert n_pre == 0
+        # ample pool: prompts are prefilled in arrival order, each exactly once, whole
+        started = [(o["prefill_started_req"], o["prefill_started_tokens"]) for o in log if o["prefill_started_req"] >= 0]
+        order = [r[0] for r in sorted(reqs, key=lambda r: (r[4], r[0]))]
+        assert [s[0] for s in started] == order
+        assert all(tok == next(r[1] for r in reqs if r[0] == rid) for rid, tok in started)
+    else:
+        assert n_pre > 0
+
+
+def test_oracle_preemption_worked_example():
+    # Pool of 4 blocks; A and B have 16-token prompts (1 block each) and produce 40 tokens each.
+    # Both need a 2nd block for their first decode token (position 16) -> pool full.  Prefills are
+    # serial, so A decodes from step 1 and B from step 2: A's context is 16 + k after step k.
+    # At step 17 A sits at position 32 and needs a 3rd block: A is starved, B (arrived last) is
+    # preempted.  By then B has taken decode steps 2..16: 1 (prefill) + 15 = 16 tokens, so its
+    # recomputation covers 16 + 16 = 32 tokens.
+    lc = Lifecycle(4, max_batch=4, eos=-1)
+    lc.submit(1, 16, 40, list(range(100, 140)))
+    lc.submit(2, 16, 40, list(range(200, 240)))
+    log, started = [], []
+    for _ in range(200):
+        o = lc.step()
+        log.append(o)
+        if o["prefill_started_req"] >= 0:
+            started.append((o["prefill_started_req"], o["prefill_started_tokens"]))
+            lc.complete_prefill(o["prefill_started_req"])
+        if lc.reqs[1].state == FINISHED and lc.reqs[2].state == FINISHED:
+            break
+    assert sum(o["n_preempted"] for o in log) == 1
+    assert started == [(1, 16), (2, 16), (2, 32)]
+    assert [i for i, o in enumerate(log) if o["n_preempted"]] == [17]
+    assert lc.reqs[1].out == list(range(100, 140)) and lc.reqs[2].out == list(range(200, 240))
+
+
+def test_oracle_pool_too_small_for_one_request():
+    lc = Lifecycle(2, max_batch=2)
+    lc.submit(1, 30, 20)
+    with pytest.raises(NoBlocks):
+        for _ in range(40):
+            o = lc.step()
+            if o["prefill_started_req"] >= 0:
+                lc.complete_prefill(1)
+
+
+# ------------------------------------------------------------------ the library against the oracle
+def _host_ctx(n_blocks, max_batch, eos):
+    c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=4096,
+                              max_decode_batch=max_batch, max_context=4096, device=rs.RS_HOST_ONLY)
+    c.set_head(None, None, None, vocab=64, eos_token=eos)
+    return c
+
+
+KEYS = ("n_promoted", "n_finished", "n_preempted", "n_waiting", "prefill_started_req", "prefill_started_tokens",
+        "decode_batch", "decode_sum_ctx")
+
+
+@pytest.mark.parametrize("n_blocks,seed", [(1000, 11), (12, 12), (8, 13), (7, 14), (9, 15)])
+def test_library_life_cycle_matches_oracle(n_blocks, seed):
+    reqs, delays = _trace(seed)
+    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS)
+    ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lc.complete_prefill, reqs, delays)
+
+    c = _host_ctx(n_blocks, 4, EOS)
+
+    def submit(rid, pl, mn, script):
+        c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
+        for t in script:
+            c.debug_push_sampled(rid, t)
+
+    def step():
+        so = c.step_tokens()
+        o = {k: getattr(so, k) for k in KEYS}
+        o["batch_ids"] = c.decode_batch_ids()
+        return o
+
+    got = _drive(submit, step, c.debug_complete_prefill, reqs, delays)
+    assert len(got) == len(ref)
+    for i, (a, b) in enumerate(zip(got, ref)):
+        for k in KEYS + ("batch_ids",):
+            assert a[k] == b[k], f"step {i}: {k}: library {a[k]} oracle {b[k]}"
+    for rid, pl, mn, script, _ in reqs:
+        toks, fin = c.request_output(rid)
+        assert fin and toks.tolist() == lc.reqs[rid].out
+        assert c.request_state(rid) == 5
+    assert c.kv_num_free() == n_blocks
+
+
+def test_library_token_requests_argument_checks():
+    c = _host_ctx(8, 2, EOS)
+    with pytest.raises(rs.RapidServeError):
+        c.submit_tokens(1, np.array([64], np.int32), 4)          # outside the vocabulary
+    with pytest.raises(rs.RapidServeError):
+        c.submit_tokens(1, np.zeros(4090, np.int32), 100)        # exceeds max_context
+    c.submit_tokens(1, np.array([1, 2, 3], np.int32), 4)
+    with pytest.raises(rs.RapidServeError):
+        c.submit_tokens(1, np.array([1], np.int32), 4)           # duplicate id
+    with pytest.raises(rs.RapidServeError) as e:
+        c.submit(2, 4, 4)                                        # hidden-state request on a token context
+    assert e.value.code == rs.RS_ERR_STATE
+    bare = rs.Context.from_shape(S.TINY, max_pos=128, n_blocks=8, max_prefill_tokens=64, max_decode_batch=2,
+                                 max_context=128, device=rs.RS_HOST_ONLY)
+    with pytest.raises(rs.RapidServeError) as e:
+        bare.submit_tokens(1, np.array([1], np.int32), 4)        # no head set
+    assert e.value.code == rs.RS_ERR_STATE
+
+
+def test_library_reports_a_pool_too_small_for_one_request():
+    c = _host_ctx(2, 2, -1)
+    c.submit_tokens(1, np.zeros(30, np.int32), 20)
+    with pytest.raises(rs.RapidServeError) as e:
+        for _ in range(40):
+            so = c.step_tokens()
+            if so.prefill_started_req >= 0:
+                c.debug_complete_prefill(1)
+    assert e.value.code == rs.RS_ERR_NO_BLOCKS
