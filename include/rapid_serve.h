@@ -260,7 +260,7 @@ int32_t rs_debug_read_workspace(rs_ctx *ctx, int32_t side, int32_t which, void *
  * blocks allocated, ids available to the prefill side) -> PREFILLING -> PREFILL_DONE (event
  * completed: the "notification") -> RUNNING (in the decode batch) -> FINISHED (blocks freed).
  *
- * rs_submit adds a request in arrival order.  prompt_hidden is device bf16
+ * rs_submit adds a request in arrival order (req_id >= 0, unique).  prompt_hidden is device bf16
  * [prompt_len, d_model] (there is no embedding on this path; hidden states are inputs).
  *
  * rs_step performs one scheduling step:
@@ -347,7 +347,7 @@ int32_t rs_lm_head_greedy(rs_ctx *ctx, int32_t side, const void *x, int32_t n, f
  * layers and chooses the next one.  Needs rs_set_head.  Do not mix with rs_submit / rs_step on one
  * context.
  *
- * rs_submit_tokens: prompt_tokens is a HOST array, copied before the call returns.  The request
+ * rs_submit_tokens: req_id >= 0, unique; prompt_tokens is a HOST array, copied before the call returns.  The request
  * produces at most max_new_tokens tokens and stops early after the end-of-sequence token (which is
  * part of its output).  prompt_len + max_new_tokens must fit max_context and max_pos.
  *
@@ -377,6 +377,9 @@ int32_t rs_submit_tokens(rs_ctx *ctx, int64_t req_id, const int32_t *prompt_toke
 int32_t rs_step_tokens(rs_ctx *ctx, int32_t wait_decode, rs_step_out *out);
 int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out,
                           int32_t *finished_out);
+/* Host-clock times in seconds since the context was created: [0] submission, [1] the moment the
+ * host saw the request's first token, [2] its latest token (0 while there is none). */
+int32_t rs_request_times(rs_ctx *ctx, int64_t req_id, double times_out[3]);
 int32_t rs_debug_push_sampled(rs_ctx *ctx, int64_t req_id, int32_t token);
 
 #ifdef __cplusplus

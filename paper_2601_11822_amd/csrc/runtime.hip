@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <chrono>
 #include <deque>
 #include <map>
 #include <string>
@@ -61,6 +62,7 @@ struct Request {
     int32_t n_sampled = 0;         // sampling events enqueued so far (known without looking at any token)
     bool complete = false;         // last token seen (end-of-sequence or the token limit)
     std::deque<int32_t> injected;  // host-only contexts: tokens the next sampling events will yield
+    double t_submit = 0, t_first = 0, t_last = 0;   // host clock: submission, first and latest token seen
 };
 
 struct Side {
@@ -133,6 +135,9 @@ struct rs_ctx {
     int step_end_idx = 0;
     bool step_end_valid[2] = {false, false};
 
+    std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
+    double now() const { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); }
+
     // token boundary
     rs_head_weights head{};
     bool have_head = false;
@@ -145,6 +150,7 @@ struct rs_ctx {
     int32_t *d_tok = nullptr;        // [n_slots] latest token of each live request
     int32_t *d_prompts = nullptr;    // [n_slots][max_context] token sequences to prefill
     int32_t *h_first = nullptr;      // pinned [n_slots]: the token a prefill chose
+    hipStream_t copy_stream = nullptr;   // non-blocking: token uploads must not wait for the partitions' work
     int32_t *d_rowslot = nullptr, *h_rowslot[2] = {nullptr, nullptr};
     int32_t *d_sampled = nullptr, *h_sampled[2] = {nullptr, nullptr};
     hipEvent_t sampled_ev[2] = {nullptr, nullptr};
@@ -614,6 +620,7 @@ int32_t rs_destroy(rs_ctx *c) {
         for (void *q : {(void *)c->packed_lm, (void *)c->d_tok, (void *)c->d_prompts, (void *)c->d_rowslot, (void *)c->d_sampled})
             if (q) (void)hipFree(q);
         if (c->h_first) (void)hipHostFree(c->h_first);
+        if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     }
     delete c;
     return RS_OK;
@@ -662,6 +669,7 @@ int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
         }
         if (!c->d_tok) {
             const size_t ns = (size_t)c->n_slots, mc = (size_t)c->lim.max_context, nb = std::max(1, c->lim.max_decode_batch);
+            HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
             HIP_TRY(hipMalloc((void **)&c->d_tok, ns * sizeof(int32_t)));
             HIP_TRY(hipMemset(c->d_tok, 0, ns * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&c->d_prompts, ns * mc * sizeof(int32_t)));
@@ -980,6 +988,7 @@ int32_t rs_debug_cu_histogram(rs_ctx *c, int32_t side, int32_t n_workgroups, int
 
 int32_t rs_submit(rs_ctx *c, int64_t req_id, int32_t prompt_len, int32_t output_len, const void *prompt_hidden) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (req_id < 0) return fail(RS_ERR_BAD_ARG, "request ids are non-negative");
     if (prompt_len < 1 || output_len < 1) return fail(RS_ERR_BAD_ARG, "prompt_len and output_len must be >= 1");
     if (c->gpu && !prompt_hidden) return fail(RS_ERR_BAD_ARG, "null prompt_hidden");
     if (c->reqs.count(req_id)) return fail(RS_ERR_BAD_ARG, "request %lld already known", (long long)req_id);
@@ -1031,6 +1040,8 @@ int32_t out_count(const Request &r) { return (int32_t)r.toks.size() - r.prompt_l
 void accept_token(rs_ctx *c, Request &r, int32_t tok) {
     if (r.complete) return;
     r.toks.push_back(tok);
+    r.t_last = c->now();
+    if (out_count(r) == 1) r.t_first = r.t_last;
     if ((c->head.eos_token >= 0 && tok == c->head.eos_token) || out_count(r) >= r.output_len) r.complete = true;
 }
 
@@ -1178,9 +1189,11 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         const int32_t n_all = (int32_t)v.toks.size();
         if (c->gpu && n_all > c->ws[RS_SIDE_PREFILL].rows)
             return fail(RS_ERR_NO_BLOCKS, "request %lld cannot be preempted: %d tokens exceed max_prefill_tokens", (long long)v.id, n_all);
-        if (c->gpu && n_all > v.prompt_len)   // generated tokens join the sequence to prefill (rare path: blocking copy)
-            HIP_TRY(hipMemcpy(c->d_prompts + (size_t)v.slot * c->lim.max_context + v.prompt_len, v.toks.data() + v.prompt_len,
-                              (size_t)(n_all - v.prompt_len) * sizeof(int32_t), hipMemcpyHostToDevice));
+        if (c->gpu && n_all > v.prompt_len) {   // generated tokens join the sequence to prefill
+            HIP_TRY(hipMemcpyAsync(c->d_prompts + (size_t)v.slot * c->lim.max_context + v.prompt_len, v.toks.data() + v.prompt_len,
+                                   (size_t)(n_all - v.prompt_len) * sizeof(int32_t), hipMemcpyHostToDevice, c->copy_stream));
+            HIP_TRY(hipStreamSynchronize(c->copy_stream));
+        }
         if (v.state == RUNNING) c->running.erase(std::find(c->running.begin(), c->running.end(), v.id));
         rs_kv_free(c, v.id);
         v.state = WAITING;
@@ -1347,6 +1360,7 @@ int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
 int32_t rs_submit_tokens(rs_ctx *c, int64_t req_id, const int32_t *prompt_tokens, int32_t prompt_len, int32_t max_new_tokens) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
     if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    if (req_id < 0) return fail(RS_ERR_BAD_ARG, "request ids are non-negative");
     if (!prompt_tokens || prompt_len < 1 || max_new_tokens < 1) return fail(RS_ERR_BAD_ARG, "need a prompt and max_new_tokens >= 1");
     if (c->reqs.count(req_id)) return fail(RS_ERR_BAD_ARG, "request %lld already known", (long long)req_id);
     if (prompt_len + max_new_tokens > c->lim.max_context || prompt_len + max_new_tokens > c->m.max_pos)
@@ -1365,11 +1379,15 @@ int32_t rs_submit_tokens(rs_ctx *c, int64_t req_id, const int32_t *prompt_tokens
     r.token_mode = true;
     r.n_prefill = prompt_len;
     r.toks.assign(prompt_tokens, prompt_tokens + prompt_len);
+    r.t_submit = c->now();
     r.slot = c->free_slots.back();
     if (c->gpu) {
         HIP_TRY(hipSetDevice(c->device));
-        HIP_TRY(hipMemcpy(c->d_prompts + (size_t)r.slot * c->lim.max_context, prompt_tokens, (size_t)prompt_len * sizeof(int32_t),
-                          hipMemcpyHostToDevice));
+        // on a stream of its own that does not synchronise with others: a plain blocking copy would wait
+        // for whatever prefill is in flight and hold up the caller's step loop for that long
+        HIP_TRY(hipMemcpyAsync(c->d_prompts + (size_t)r.slot * c->lim.max_context, prompt_tokens,
+                               (size_t)prompt_len * sizeof(int32_t), hipMemcpyHostToDevice, c->copy_stream));
+        HIP_TRY(hipStreamSynchronize(c->copy_stream));
     }
     c->free_slots.pop_back();
     c->reqs[req_id] = std::move(r);
@@ -1396,6 +1414,16 @@ int32_t rs_request_output(rs_ctx *c, int64_t req_id, int32_t *tokens_out, int32_
     std::copy(r.toks.begin() + r.prompt_len, r.toks.end(), tokens_out);
     *n_out = n;
     if (finished_out) *finished_out = r.complete ? 1 : 0;
+    return RS_OK;
+}
+
+int32_t rs_request_times(rs_ctx *c, int64_t req_id, double times_out[3]) {
+    if (!c || !times_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
+    times_out[0] = it->second.t_submit;
+    times_out[1] = it->second.t_first;
+    times_out[2] = it->second.t_last;
     return RS_OK;
 }
 

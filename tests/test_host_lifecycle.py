@@ -174,6 +174,8 @@ def test_library_token_requests_argument_checks():
         c.submit_tokens(1, np.array([64], np.int32), 4)          # outside the vocabulary
     with pytest.raises(rs.RapidServeError):
         c.submit_tokens(1, np.zeros(4090, np.int32), 100)        # exceeds max_context
+    with pytest.raises(rs.RapidServeError):
+        c.submit_tokens(-1, np.array([1], np.int32), 4)          # ids are non-negative
     c.submit_tokens(1, np.array([1, 2, 3], np.int32), 4)
     with pytest.raises(rs.RapidServeError):
         c.submit_tokens(1, np.array([1], np.int32), 4)           # duplicate id
