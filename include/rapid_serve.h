@@ -382,6 +382,36 @@ int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int3
 int32_t rs_request_times(rs_ctx *ctx, int64_t req_id, double times_out[3]);
 int32_t rs_debug_push_sampled(rs_ctx *ctx, int64_t req_id, int32_t token);
 
+/* ---- engine: the two asynchronous sides of section 4.4 as two threads ---------------------------
+ * rs_engine_start spawns a decode thread and a prefill thread inside the library and returns.
+ *   decode thread : owns the request table, the only KV allocator (section 4.5.1), the manager and
+ *                   the decode partition; runs the rs_step_tokens loop without ever waiting for a
+ *                   prefill;
+ *   prefill thread: owns the prefill partition; takes requests whose blocks are allocated, first
+ *                   come first served, runs each whole prompt and waits for it (only this thread
+ *                   blocks on prefill work), then sends the notification.
+ * The threads share no lock: three bounded single-producer / single-consumer rings carry
+ * submissions (application -> decode), block ids (decode -> prefill) and notifications
+ * (prefill -> decode); the CU count of the prefill partition is published by the manager and picked
+ * up by the prefill thread at its next prompt (work in flight keeps the mask it started with).
+ * Several prompts may be queued on the prefill thread at once.
+ *
+ * While the engine runs: rs_submit_tokens (any application thread), rs_request_output,
+ * rs_request_times, rs_request_state and rs_engine_stats are the calls to use; rs_step,
+ * rs_step_tokens and the layer calls are refused or must not be made.  Results are published by
+ * the decode thread with release stores and read here with acquire loads: a reader never sees a
+ * token count ahead of the tokens.  Host-only contexts: queue a request's sampled tokens with
+ * rs_debug_push_sampled BEFORE submitting it.
+ *
+ * rs_engine_stop(drain != 0) returns after every submitted request has finished; with drain == 0
+ * it stops after the step in progress (unfinished requests stay unfinished and the context can then
+ * only be inspected and destroyed).  It reports the first error an engine thread met, as does
+ * rs_engine_stats.  stats_out: [0] submitted, [1] finished, [2] decode-thread iterations,
+ * [3] preemptions. */
+int32_t rs_engine_start(rs_ctx *ctx);
+int32_t rs_engine_stop(rs_ctx *ctx, int32_t drain);
+int32_t rs_engine_stats(rs_ctx *ctx, int64_t stats_out[4]);
+
 #ifdef __cplusplus
 }
 #endif

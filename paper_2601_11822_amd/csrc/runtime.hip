@@ -2,6 +2,10 @@
 // resource manager, layer drivers and the serving step.  Declarations and their contract are
 // in include/rapid_serve.h.
 #include <algorithm>
+#include <atomic>
+#include <memory>
+#include <mutex>
+#include <thread>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -45,6 +49,54 @@ struct Workspace {
 
 enum ReqState { WAITING = 0, PREFILL_READY, PREFILLING, PREFILL_DONE, RUNNING, FINISHED };
 
+// Bounded single-producer / single-consumer ring: the only coupling between the engine's threads
+// (section 4.4: the two sides exchange requests and notifications, never locks).
+template <class T, size_t N>
+struct SpscRing {
+    std::atomic<size_t> head{0}, tail{0};   // head: next slot to pop (consumer's), tail: next to fill (producer's)
+    T buf[N];
+    bool push(const T &v) {
+        const size_t t = tail.load(std::memory_order_relaxed);
+        if (t - head.load(std::memory_order_acquire) == N) return false;
+        buf[t % N] = v;
+        tail.store(t + 1, std::memory_order_release);
+        return true;
+    }
+    bool pop(T &v) {
+        const size_t h = head.load(std::memory_order_relaxed);
+        if (h == tail.load(std::memory_order_acquire)) return false;
+        v = buf[h % N];
+        head.store(h + 1, std::memory_order_release);
+        return true;
+    }
+    bool empty() const { return head.load(std::memory_order_acquire) == tail.load(std::memory_order_acquire); }
+};
+
+// What the application reads of an engine request: written by the decode thread only, every field
+// published with release stores (tokens first, then their count).
+struct Result {
+    int32_t max_new = 0;
+    std::unique_ptr<int32_t[]> toks;
+    std::atomic<int32_t> n{0}, finished{0}, state{WAITING};
+    std::atomic<double> t_submit{0}, t_first{0}, t_last{0};
+};
+struct SubmitMsg {          // application -> decode thread ("waiting" queue)
+    int64_t id;
+    int32_t prompt_len, max_new;
+    std::vector<int32_t> *toks, *script;   // owned by the message
+    Result *res;
+    double t_submit;
+};
+struct PrefillMsg {         // decode thread -> prefill thread: blocks are allocated, here are their ids
+    int64_t id;
+    int32_t slot, n_tok, wait_idx;
+    std::vector<int32_t> *blocks;          // owned by the message
+};
+struct DoneMsg {            // prefill thread -> decode thread: the notification (no KV moves)
+    int64_t id;
+    int32_t token, rc;
+};
+
 struct Request {
     int64_t id;
     int32_t prompt_len, output_len;
@@ -63,6 +115,7 @@ struct Request {
     bool complete = false;         // last token seen (end-of-sequence or the token limit)
     std::deque<int32_t> injected;  // host-only contexts: tokens the next sampling events will yield
     double t_submit = 0, t_first = 0, t_last = 0;   // host clock: submission, first and latest token seen
+    Result *res = nullptr;         // engine requests: where the application looks
 };
 
 struct Side {
@@ -156,6 +209,23 @@ struct rs_ctx {
     hipEvent_t sampled_ev[2] = {nullptr, nullptr};
     std::vector<int64_t> inflight[2];   // request ids of the rows of a step whose tokens the host has not read yet
     bool pending[2] = {false, false};
+
+    // engine: a decode thread (owns the request table, the allocator and the decode side) and a prefill
+    // thread (owns the prefill side), coupled by three rings
+    bool engine = false;                 // threads running; set and cleared by the application thread
+    bool engine_ever = false;
+    std::thread th_decode, th_prefill;
+    std::atomic<bool> stop{false}, stop_prefill{false}, drain{false};
+    SpscRing<SubmitMsg, 4096> sub_q;     // producer side serialised by sub_mu (several application threads)
+    SpscRing<PrefillMsg, 4096> pre_q;
+    SpscRing<DoneMsg, 4096> fin_q;
+    std::mutex sub_mu, res_mu;
+    std::unordered_map<int64_t, std::unique_ptr<Result>> results;            // under res_mu
+    std::unordered_map<int64_t, std::vector<int32_t>> pre_scripts;           // under res_mu
+    std::string eng_err;                                                     // under res_mu
+    std::atomic<int32_t> prefill_cus_pub{RS_TOTAL_CUS}, eng_rc{0};
+    std::atomic<int64_t> eng_steps{0}, eng_finished{0}, eng_preempted{0}, eng_submitted{0};
+    int n_prefill_inflight = 0;          // decode thread only
 };
 
 namespace {
@@ -270,26 +340,40 @@ int32_t kv_alloc(rs_ctx *c, int64_t req_id, int32_t n_tokens, const std::vector<
     return RS_OK;
 }
 
+// One side's CU count and the stream masked to it.
+int32_t set_side(rs_ctx *c, int s, int cus) {
+    Side &sd = c->side[s];
+    if (c->gpu && cus > 0) {
+        hipStream_t st;
+        int32_t rc = get_stream(c, s, cus, &st);
+        if (rc) return rc;
+        if (st != sd.stream && sd.stream) {
+            // later work of this side is ordered after what the old stream still holds
+            HIP_TRY(hipEventRecord(sd.order, sd.stream));
+            HIP_TRY(hipStreamWaitEvent(st, sd.order, 0));
+        }
+        sd.stream = st;
+    }
+    sd.cus = cus;
+    return RS_OK;
+}
+
 int32_t set_split(rs_ctx *c, int32_t p, int32_t d) {
     auto legal = [](int v) { return v >= 0 && v <= RS_TOTAL_CUS && v % RS_CU_GRANULE == 0; };
     if (!legal(p) || !legal(d)) return fail(RS_ERR_BAD_SPLIT, "split (%d,%d): counts must be multiples of %d in [0,256]", p, d, RS_CU_GRANULE);
     const bool over = (p == RS_TOTAL_CUS && d == RS_TOTAL_CUS);
     if (!over && p + d > RS_TOTAL_CUS) return fail(RS_ERR_BAD_SPLIT, "split (%d,%d) overlaps; only (256,256) may", p, d);
+    if (c->engine) {   // the prefill side belongs to the prefill thread: it picks the published count up at its next prompt
+        int32_t rc = set_side(c, RS_SIDE_DECODE, d);
+        if (rc) return rc;
+        c->prefill_cus_pub.store(p, std::memory_order_release);
+        c->over_alloc = over;
+        return RS_OK;
+    }
     const int want[2] = {p, d};
     for (int s = 0; s < 2; ++s) {
-        Side &sd = c->side[s];
-        if (c->gpu && want[s] > 0) {
-            hipStream_t st;
-            int32_t rc = get_stream(c, s, want[s], &st);
-            if (rc) return rc;
-            if (st != sd.stream && sd.stream) {
-                // later work of this side is ordered after what the old stream still holds
-                HIP_TRY(hipEventRecord(sd.order, sd.stream));
-                HIP_TRY(hipStreamWaitEvent(st, sd.order, 0));
-            }
-            sd.stream = st;
-        }
-        sd.cus = want[s];
+        int32_t rc = set_side(c, s, want[s]);
+        if (rc) return rc;
     }
     c->over_alloc = over;
     return RS_OK;
@@ -580,6 +664,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
 
 int32_t rs_destroy(rs_ctx *c) {
     if (!c) return RS_OK;
+    if (c->engine) (void)rs_engine_stop(c, 0);
     if (c->gpu) {
         (void)hipSetDevice(c->device);
         (void)hipDeviceSynchronize();
@@ -1017,6 +1102,12 @@ int32_t rs_decode_batch_ids(rs_ctx *c, int64_t *ids_out, int32_t cap, int32_t *n
 
 int32_t rs_request_state(rs_ctx *c, int64_t req_id) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->engine_ever) {
+        std::lock_guard<std::mutex> lr(c->res_mu);
+        auto ir = c->results.find(req_id);
+        if (ir == c->results.end()) return fail(RS_ERR_BAD_ARG, "unknown request");
+        return ir->second->state.load(std::memory_order_acquire);
+    }
     auto it = c->reqs.find(req_id);
     if (it == c->reqs.end()) return fail(RS_ERR_BAD_ARG, "unknown request");
     return it->second.state;
@@ -1036,6 +1127,11 @@ namespace {
 
 int32_t out_count(const Request &r) { return (int32_t)r.toks.size() - r.prompt_len; }
 
+void set_state(Request &r, int st) {
+    r.state = st;
+    if (r.res) r.res->state.store(st, std::memory_order_release);
+}
+
 // A sampled token reaches the host: kept unless the request already has its last token.
 void accept_token(rs_ctx *c, Request &r, int32_t tok) {
     if (r.complete) return;
@@ -1043,6 +1139,14 @@ void accept_token(rs_ctx *c, Request &r, int32_t tok) {
     r.t_last = c->now();
     if (out_count(r) == 1) r.t_first = r.t_last;
     if ((c->head.eos_token >= 0 && tok == c->head.eos_token) || out_count(r) >= r.output_len) r.complete = true;
+    if (r.res) {   // token, then times, then the count that makes them visible, then the end flag
+        const int32_t n = out_count(r);
+        r.res->toks[n - 1] = tok;
+        r.res->t_last.store(r.t_last, std::memory_order_relaxed);
+        if (n == 1) r.res->t_first.store(r.t_first, std::memory_order_relaxed);
+        r.res->n.store(n, std::memory_order_release);
+        if (r.complete) r.res->finished.store(1, std::memory_order_release);
+    }
 }
 
 int32_t next_injected(Request &r) {
@@ -1082,7 +1186,7 @@ int32_t harvest_ready(rs_ctx *c, bool must) {
 }
 
 void release_request(rs_ctx *c, Request &r) {
-    r.state = FINISHED;
+    set_state(r, FINISHED);
     rs_kv_free(c, r.id);
     if (r.done) { (void)hipEventDestroy(r.done); r.done = nullptr; }
     if (r.slot >= 0) { c->free_slots.push_back(r.slot); r.slot = -1; }
@@ -1120,7 +1224,18 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         if (rc) return rc;
     }
     // 1a. the prefill "notification": event completed -> PREFILL_DONE
-    if (c->prefilling >= 0) {
+    if (c->engine) {
+        DoneMsg dm;
+        while (c->fin_q.pop(dm)) {
+            c->n_prefill_inflight--;
+            if (dm.rc) return fail(dm.rc, "the prefill thread failed on request %lld", (long long)dm.id);
+            Request &r = c->reqs[dm.id];
+            set_state(r, PREFILL_DONE);
+            r.ctx_len = r.n_prefill;
+            accept_token(c, r, c->gpu ? dm.token : next_injected(r));
+            if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
+        }
+    } else if (c->prefilling >= 0) {
         Request &r = c->reqs[c->prefilling];
         bool done = r.host_done;
         if (c->gpu) {
@@ -1129,7 +1244,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             else if (q != hipErrorNotReady) return fail(RS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q));
         }
         if (done) {
-            r.state = PREFILL_DONE;
+            set_state(r, PREFILL_DONE);
             r.host_done = false;
             r.ctx_len = token_mode ? r.n_prefill : r.prompt_len;
             c->prefilling = -1;
@@ -1146,7 +1261,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     for (int64_t id : c->arrival) {
         Request &r = c->reqs[id];
         if (r.state == PREFILL_DONE && (int)c->running.size() < maxB) {
-            r.state = RUNNING;
+            set_state(r, RUNNING);
             c->running.push_back(id);
             out->n_promoted++;
         }
@@ -1156,7 +1271,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         Request &r = c->reqs[id];
         if (r.state != WAITING) continue;
         if (kv_alloc(c, id, token_mode ? r.n_prefill : r.prompt_len, nullptr) != RS_OK) break;
-        r.state = PREFILL_READY;
+        set_state(r, PREFILL_READY);
     }
 
     // 3. room for every running request's next token; in token mode a request that cannot grow
@@ -1196,7 +1311,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         }
         if (v.state == RUNNING) c->running.erase(std::find(c->running.begin(), c->running.end(), v.id));
         rs_kv_free(c, v.id);
-        v.state = WAITING;
+        set_state(v, WAITING);
         v.n_prefill = n_all;
         v.ctx_len = 0;
         out->n_preempted++;
@@ -1210,13 +1325,13 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     if (c->prefilling < 0)
         for (int64_t id : c->arrival)
             if (c->reqs[id].state == PREFILL_READY) { next_prefill = id; break; }
-    const bool prefill_pending = c->prefilling >= 0 || next_prefill >= 0;
+    const bool prefill_pending = c->prefilling >= 0 || next_prefill >= 0 || c->n_prefill_inflight > 0;
     const int B = (int)c->running.size();
     int64_t sum_ctx = 0;
     for (int64_t id : c->running) sum_ctx += c->reqs[id].ctx_len;
     int32_t p, d;
     choose_split(c, B, sum_ctx, prefill_pending, &p, &d);
-    if (B == 0 && !prefill_pending) { p = c->side[0].cus; d = c->side[1].cus; }
+    if (B == 0 && !prefill_pending) { p = c->engine ? c->prefill_cus_pub.load() : c->side[0].cus; d = c->side[1].cus; }
     else {
         int32_t rc = set_split(c, p, d);
         if (rc) return rc;
@@ -1303,6 +1418,22 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         }
     }
 
+    // 6. engine: every request whose blocks are allocated goes to the prefill thread, in arrival order
+    if (c->engine) {
+        if (p > 0)
+            for (int64_t id : c->arrival) {
+                Request &r = c->reqs[id];
+                if (r.state != PREFILL_READY) continue;
+                PrefillMsg pm{id, r.slot, r.n_prefill, c->step_end_valid[prev_end] ? prev_end : -1,
+                              new std::vector<int32_t>(c->owned[id])};
+                if (!c->pre_q.push(pm)) { delete pm.blocks; break; }   // ring full: next step
+                r.n_sampled++;
+                set_state(r, PREFILLING);
+                c->n_prefill_inflight++;
+                if (out->prefill_started_req < 0) { out->prefill_started_req = id; out->prefill_started_tokens = r.n_prefill; }
+            }
+        return RS_OK;
+    }
     // 6. start the next whole-prompt prefill if the prefill side is idle
     if (next_prefill >= 0 && c->side[RS_SIDE_PREFILL].cus > 0) {
         Request &r = c->reqs[next_prefill];
@@ -1339,7 +1470,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             HIP_TRY(hipEventRecord(r.done, st));
         }
         if (token_mode) r.n_sampled++;
-        r.state = PREFILLING;
+        set_state(r, PREFILLING);
         c->prefilling = r.id;
         out->prefill_started_req = r.id;
         out->prefill_started_tokens = n_tok;
@@ -1349,9 +1480,177 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
 
 }  // namespace
 
+// ---- the two-thread engine (section 4.4) -------------------------------------------------------
+namespace {
+
+// Prefill thread: one whole prompt on the prefill side, then wait for it (this thread only).
+int32_t engine_run_prompt(rs_ctx *c, const PrefillMsg &m, int32_t *token) {
+    int32_t rc = set_side(c, RS_SIDE_PREFILL, c->prefill_cus_pub.load(std::memory_order_acquire));
+    if (rc) return rc;
+    if (c->side[RS_SIDE_PREFILL].cus <= 0) return fail(RS_ERR_STATE, "a prompt was handed over while the prefill side has no CUs");
+    const int mb = c->max_blk_per_req;
+    hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+    for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)m.blocks->size() ? (*m.blocks)[j] : -1;
+    // blocks released by the decode thread may still be written by the decode step it had in flight
+    if (m.wait_idx >= 0) HIP_TRY(hipStreamWaitEvent(st, c->step_end[m.wait_idx], 0));
+    HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    const int32_t cu[2] = {0, m.n_tok};
+    Workspace &w = c->ws[RS_SIDE_PREFILL];
+    launch_embed(st, EmbedArgs{c->d_prompts + (size_t)m.slot * c->lim.max_context, nullptr, (const bf16_t *)c->head.embed, w.xbuf,
+                               c->err_flag, m.n_tok, c->m.d_model, c->head.vocab});
+    for (int l = 0; l < c->m.n_layers; ++l) {
+        if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+        rc = prefill_layer(c, l, w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
+        if (rc) return rc;
+    }
+    rc = head_greedy(c, RS_SIDE_PREFILL, w.xbuf + (size_t)(m.n_tok - 1) * c->m.d_model, 1, nullptr, nullptr, nullptr, c->d_tok + m.slot);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(c->h_first + m.slot, c->d_tok + m.slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    *token = c->h_first[m.slot];
+    return RS_OK;
+}
+
+void engine_fail(rs_ctx *c, int32_t rc) {
+    std::lock_guard<std::mutex> lk(c->res_mu);
+    if (!c->eng_rc.load()) {
+        c->eng_err = g_err;
+        c->eng_rc.store(rc);
+    }
+}
+
+void prefill_main(rs_ctx *c) {
+    if (c->gpu) (void)hipSetDevice(c->device);
+    for (;;) {
+        PrefillMsg m;
+        if (!c->pre_q.pop(m)) {
+            if (c->stop_prefill.load(std::memory_order_acquire)) break;
+            std::this_thread::sleep_for(std::chrono::microseconds(50));
+            continue;
+        }
+        int32_t token = 0, rc = RS_OK;
+        if (c->gpu) rc = engine_run_prompt(c, m, &token);
+        if (rc) engine_fail(c, rc);
+        delete m.blocks;
+        while (!c->fin_q.push(DoneMsg{m.id, token, rc})) std::this_thread::yield();
+    }
+}
+
+// Decode thread: a new request enters the table ("waiting" queue of the decode side).
+int32_t engine_admit(rs_ctx *c, const SubmitMsg &m) {
+    std::unique_ptr<std::vector<int32_t>> toks(m.toks), script(m.script);
+    Request r{};
+    r.id = m.id;
+    r.prompt_len = m.prompt_len;
+    r.output_len = m.max_new;
+    r.token_mode = true;
+    r.n_prefill = m.prompt_len;
+    r.toks = std::move(*toks);
+    r.t_submit = m.t_submit;
+    r.res = m.res;
+    if (script) r.injected.assign(script->begin(), script->end());
+    if (c->free_slots.empty()) return fail(RS_ERR_STATE, "no request slot for %lld", (long long)m.id);   // submit keeps within n_slots
+    r.slot = c->free_slots.back();
+    c->free_slots.pop_back();
+    if (c->gpu) {
+        HIP_TRY(hipMemcpyAsync(c->d_prompts + (size_t)r.slot * c->lim.max_context, r.toks.data(), (size_t)r.prompt_len * sizeof(int32_t),
+                               hipMemcpyHostToDevice, c->copy_stream));
+        HIP_TRY(hipStreamSynchronize(c->copy_stream));
+    }
+    c->reqs[m.id] = std::move(r);
+    c->arrival.push_back(m.id);
+    return RS_OK;
+}
+
+void decode_main(rs_ctx *c) {
+    if (c->gpu) (void)hipSetDevice(c->device);
+    rs_step_in in{nullptr, nullptr, 0};
+    rs_step_out out;
+    for (;;) {
+        int32_t rc = RS_OK;
+        SubmitMsg sm;
+        while (!rc && c->sub_q.pop(sm)) rc = engine_admit(c, sm);
+        if (!rc) rc = serve_step(c, &in, &out, true);
+        if (rc) { engine_fail(c, rc); break; }
+        c->eng_steps.fetch_add(1, std::memory_order_relaxed);
+        c->eng_finished.fetch_add(out.n_finished, std::memory_order_release);
+        c->eng_preempted.fetch_add(out.n_preempted, std::memory_order_relaxed);
+        if (c->stop.load(std::memory_order_acquire)) {
+            const bool idle = c->arrival.empty() && c->n_prefill_inflight == 0 && c->sub_q.empty() && !c->pending[0] && !c->pending[1];
+            if (!c->drain.load() || idle) break;
+        }
+        if (out.decode_batch == 0) std::this_thread::sleep_for(std::chrono::microseconds(50));
+    }
+    (void)harvest_ready(c, true);   // tokens of the last steps
+}
+
+}  // namespace
+
+int32_t rs_engine_start(rs_ctx *c) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->engine) return fail(RS_ERR_STATE, "the engine is already running");
+    if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    if (!c->arrival.empty()) return fail(RS_ERR_STATE, "requests are live on this context");
+    int32_t rc = enter_mode(c, 2);
+    if (rc) return rc;
+    if (c->gpu) {
+        HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    c->stop.store(false);
+    c->stop_prefill.store(false);
+    c->drain.store(false);
+    c->eng_rc.store(0);
+    c->prefill_cus_pub.store(c->side[RS_SIDE_PREFILL].cus);
+    c->engine = true;
+    c->engine_ever = true;
+    c->th_prefill = std::thread(prefill_main, c);
+    c->th_decode = std::thread(decode_main, c);
+    return RS_OK;
+}
+
+int32_t rs_engine_stop(rs_ctx *c, int32_t drain) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (!c->engine) return fail(RS_ERR_STATE, "the engine is not running");
+    c->drain.store(drain != 0);
+    c->stop.store(true, std::memory_order_release);
+    c->th_decode.join();
+    c->stop_prefill.store(true, std::memory_order_release);
+    c->th_prefill.join();
+    PrefillMsg pm;
+    while (c->pre_q.pop(pm)) delete pm.blocks;
+    SubmitMsg sm;
+    while (c->sub_q.pop(sm)) { delete sm.toks; delete sm.script; }
+    DoneMsg dm;
+    while (c->fin_q.pop(dm)) {}
+    c->engine = false;
+    if (c->gpu) HIP_TRY(hipDeviceSynchronize());
+    const int32_t rc = c->eng_rc.load();
+    if (rc) {
+        std::lock_guard<std::mutex> lk(c->res_mu);
+        return fail(rc, "engine thread: %s", c->eng_err.c_str());
+    }
+    return RS_OK;
+}
+
+int32_t rs_engine_stats(rs_ctx *c, int64_t stats_out[4]) {
+    if (!c || !stats_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    stats_out[0] = c->eng_submitted.load();
+    stats_out[1] = c->eng_finished.load(std::memory_order_acquire);
+    stats_out[2] = c->eng_steps.load();
+    stats_out[3] = c->eng_preempted.load();
+    const int32_t rc = c->eng_rc.load();
+    if (rc) {
+        std::lock_guard<std::mutex> lk(c->res_mu);
+        return fail(rc, "engine thread: %s", c->eng_err.c_str());
+    }
+    return RS_OK;
+}
+
 int32_t rs_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out) {
     if (!c || !in || !out) return fail(RS_ERR_BAD_ARG, "null argument");
     if (c->gpu && (!in->decode_hidden || !in->decode_out)) return fail(RS_ERR_BAD_ARG, "null decode buffers");
+    if (c->engine) return fail(RS_ERR_STATE, "the engine's threads drive this context");
     int32_t rc = enter_mode(c, 1);
     if (rc) return rc;
     return serve_step(c, in, out, false);
@@ -1369,6 +1668,40 @@ int32_t rs_submit_tokens(rs_ctx *c, int64_t req_id, const int32_t *prompt_tokens
     for (int i = 0; i < prompt_len; ++i)
         if (prompt_tokens[i] < 0 || prompt_tokens[i] >= c->head.vocab)
             return fail(RS_ERR_BAD_ARG, "prompt token %d at %d outside the vocabulary of %d", prompt_tokens[i], i, c->head.vocab);
+    if (c->engine) {
+        std::lock_guard<std::mutex> lk(c->sub_mu);   // among application threads only
+        if (c->eng_submitted.load() - c->eng_finished.load(std::memory_order_acquire) >= c->n_slots)
+            return fail(RS_ERR_STATE, "too many live requests (%d)", c->n_slots);
+        Result *res;
+        std::vector<int32_t> *script = nullptr;
+        {
+            std::lock_guard<std::mutex> lr(c->res_mu);
+            if (c->results.count(req_id)) return fail(RS_ERR_BAD_ARG, "request %lld already known", (long long)req_id);
+            auto up = std::make_unique<Result>();
+            up->max_new = max_new_tokens;
+            up->toks.reset(new int32_t[max_new_tokens]);
+            up->t_submit.store(c->now());
+            res = up.get();
+            c->results[req_id] = std::move(up);
+            auto ps = c->pre_scripts.find(req_id);
+            if (ps != c->pre_scripts.end()) {
+                script = new std::vector<int32_t>(std::move(ps->second));
+                c->pre_scripts.erase(ps);
+            }
+        }
+        SubmitMsg m{req_id, prompt_len, max_new_tokens, new std::vector<int32_t>(prompt_tokens, prompt_tokens + prompt_len), script, res,
+                    res->t_submit.load()};
+        if (!c->sub_q.push(m)) {
+            delete m.toks;
+            delete m.script;
+            std::lock_guard<std::mutex> lr(c->res_mu);
+            c->results.erase(req_id);
+            return fail(RS_ERR_STATE, "submission queue full");
+        }
+        c->eng_submitted.fetch_add(1);
+        return RS_OK;
+    }
+    if (c->engine_ever) return fail(RS_ERR_STATE, "this context was driven by the engine: start it again to submit");
     if (c->free_slots.empty()) return fail(RS_ERR_STATE, "too many live requests (%d)", c->n_slots);
     int32_t rc = enter_mode(c, 2);
     if (rc) return rc;
@@ -1398,6 +1731,7 @@ int32_t rs_submit_tokens(rs_ctx *c, int64_t req_id, const int32_t *prompt_tokens
 int32_t rs_step_tokens(rs_ctx *c, int32_t wait_decode, rs_step_out *out) {
     if (!c || !out) return fail(RS_ERR_BAD_ARG, "null argument");
     if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
+    if (c->engine) return fail(RS_ERR_STATE, "the engine's threads drive this context");
     int32_t rc = enter_mode(c, 2);
     if (rc) return rc;
     rs_step_in in{nullptr, nullptr, wait_decode};
@@ -1406,6 +1740,22 @@ int32_t rs_step_tokens(rs_ctx *c, int32_t wait_decode, rs_step_out *out) {
 
 int32_t rs_request_output(rs_ctx *c, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out, int32_t *finished_out) {
     if (!c || !n_out || cap < 0 || (cap > 0 && !tokens_out)) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (c->engine_ever) {
+        Result *res = nullptr;
+        {
+            std::lock_guard<std::mutex> lr(c->res_mu);
+            auto ir = c->results.find(req_id);
+            if (ir != c->results.end()) res = ir->second.get();
+        }
+        if (!res) return fail(RS_ERR_BAD_ARG, "unknown token request");
+        const int32_t fin = res->finished.load(std::memory_order_acquire);   // before the count: a set flag means the count is final
+        const int32_t n = res->n.load(std::memory_order_acquire);
+        if (n > cap) return fail(RS_ERR_BAD_ARG, "buffer of %d too small for %d tokens", cap, n);
+        std::copy(res->toks.get(), res->toks.get() + n, tokens_out);
+        *n_out = n;
+        if (finished_out) *finished_out = fin;
+        return RS_OK;
+    }
     auto it = c->reqs.find(req_id);
     if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
     const Request &r = it->second;
@@ -1419,6 +1769,16 @@ int32_t rs_request_output(rs_ctx *c, int64_t req_id, int32_t *tokens_out, int32_
 
 int32_t rs_request_times(rs_ctx *c, int64_t req_id, double times_out[3]) {
     if (!c || !times_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (c->engine_ever) {
+        std::lock_guard<std::mutex> lr(c->res_mu);
+        auto ir = c->results.find(req_id);
+        if (ir == c->results.end()) return fail(RS_ERR_BAD_ARG, "unknown token request");
+        (void)ir->second->n.load(std::memory_order_acquire);
+        times_out[0] = ir->second->t_submit.load();
+        times_out[1] = ir->second->t_first.load();
+        times_out[2] = ir->second->t_last.load();
+        return RS_OK;
+    }
     auto it = c->reqs.find(req_id);
     if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
     times_out[0] = it->second.t_submit;
@@ -1430,6 +1790,12 @@ int32_t rs_request_times(rs_ctx *c, int64_t req_id, double times_out[3]) {
 int32_t rs_debug_push_sampled(rs_ctx *c, int64_t req_id, int32_t token) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
     if (c->gpu) return fail(RS_ERR_STATE, "only for host-only contexts");
+    if (c->engine) {   // the table belongs to the decode thread: the script travels with the submission
+        std::lock_guard<std::mutex> lr(c->res_mu);
+        if (c->results.count(req_id)) return fail(RS_ERR_STATE, "with the engine running, queue a request's tokens before submitting it");
+        c->pre_scripts[req_id].push_back(token);
+        return RS_OK;
+    }
     auto it = c->reqs.find(req_id);
     if (it == c->reqs.end() || !it->second.token_mode) return fail(RS_ERR_BAD_ARG, "unknown token request");
     it->second.injected.push_back(token);

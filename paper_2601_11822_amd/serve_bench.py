@@ -14,6 +14,10 @@ the preemption count, for one policy:
                        offline profiler first on a one-layer rig of the same shape)
     --policy over      no profile: both partitions see every CU whenever both have work
 
+With --engine the library's own decode and prefill threads drive the loop (rs_engine_start) and
+the script only submits and polls; per-request inter-token latency is then (last - first token
+time) / (tokens - 1).
+
     python -m paper_2601_11822_amd.serve_bench --layers 32 --requests 48 --rate 8 --policy over
 """
 from __future__ import annotations
@@ -114,6 +118,53 @@ def serve(c: Context, work, wait_decode: bool, time_limit: float):
     return steps, wall
 
 
+def serve_engine(c: Context, work, time_limit: float):
+    """The same arrival process against the library's own two threads (rs_engine_start)."""
+    todo = list(work)
+    c.engine_start()
+    t0 = time.perf_counter()
+    t_log = 0.0
+    try:
+        while True:
+            now = time.perf_counter() - t0
+            while todo and todo[0][1] <= now:
+                rid, _, prompt, n_out = todo.pop(0)
+                c.submit_tokens(rid, prompt, n_out)
+            st = c.engine_stats()
+            if not todo and st["finished"] >= len(work):
+                break
+            if now > time_limit:
+                raise RuntimeError(f"time limit: {st}")
+            if now - t_log > 2.0:
+                _log(f"[serve] t={now:.1f}s {st}")
+                t_log = now
+            time.sleep(0.0005 if not todo else min(0.0005, max(0.0, todo[0][1] - now)))
+        wall = time.perf_counter() - t0
+    finally:
+        c.engine_stop(drain=False)
+    return c.engine_stats(), wall
+
+
+def summarise_engine(c: Context, work, stats, wall: float):
+    ttft, itl, n_gen, n_prompt = [], [], 0, 0
+    for rid, t_arr, prompt, n_out in work:
+        toks, fin = c.request_output(rid)
+        assert fin and len(toks) == n_out, f"request {rid}: {len(toks)} of {n_out} tokens"
+        ts, tf, tl = c.request_times(rid)
+        ttft.append(tf - ts)
+        if n_out > 1:
+            itl.append((tl - tf) / (n_out - 1))
+        n_gen += len(toks)
+        n_prompt += len(prompt)
+    return {
+        "requests": len(work), "wall_s": wall, "generated_tokens": n_gen, "prompt_tokens": n_prompt,
+        "generated_tok_per_s": n_gen / wall, "prompt_tok_per_s": n_prompt / wall,
+        "ttft_ms_p50": float(np.percentile(ttft, 50) * 1e3), "ttft_ms_p95": float(np.percentile(ttft, 95) * 1e3),
+        "request_mean_itl_ms_p50": float(np.percentile(itl, 50) * 1e3), "request_mean_itl_ms_p95": float(np.percentile(itl, 95) * 1e3),
+        "decode_thread_iterations": int(stats["iterations"]), "preemptions": int(stats["preempted"]),
+    }
+
+
 def summarise(c: Context, work, steps, wall: float):
     ttft, n_gen, n_prompt = [], 0, 0
     for rid, t_arr, prompt, n_out in work:
@@ -169,6 +220,7 @@ def main(argv=None):
     ap.add_argument("--profile", default=None, help="JSON written by the profiler, or 'measure'")
     ap.add_argument("--slo-ms", type=float, default=50.0)
     ap.add_argument("--wait-decode", action="store_true", help="wait for each decode step (exact per-step GPU times)")
+    ap.add_argument("--engine", action="store_true", help="let the library's two threads drive (rs_engine_start)")
     ap.add_argument("--time-limit", type=float, default=120.0)
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--out", default=None)
@@ -201,10 +253,14 @@ def main(argv=None):
     while not c.step_tokens(wait_decode=True).n_finished:
         if time.time() - t_settle > 30:
             raise RuntimeError("the settling request did not finish")
-    steps, wall = serve(c, work, a.wait_decode, a.time_limit)
-    rec = summarise(c, work, steps, wall)
+    if a.engine:
+        stats, wall = serve_engine(c, work, a.time_limit)
+        rec = summarise_engine(c, work, stats, wall)
+    else:
+        steps, wall = serve(c, work, a.wait_decode, a.time_limit)
+        rec = summarise(c, work, steps, wall)
     rec.update({"policy": a.policy, "shape": shape.name, "layers": a.layers, "rate_per_s": a.rate, "slo_ms": a.slo_ms,
-                "wait_decode": bool(a.wait_decode), "max_batch_cap": a.max_batch, "data": "synthetic"})
+                "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "data": "synthetic"})
     line = json.dumps(rec)
     print(line, flush=True)
     if a.out:

@@ -241,3 +241,53 @@ def test_closed_loop_with_preemption_matches_oracle():
         assert frac >= 0.9 and rig.ctx.kv_num_free() == 6
     finally:
         rig.close()
+
+
+# ------------------------------------------------------------------------------ two-thread engine
+def _serve_engine(rig, requests, timeout_s=60.0):
+    import time
+    c = rig.ctx
+    c.engine_start()
+    try:
+        for rid, prompt, mn, arr in sorted(requests, key=lambda r: r[3]):
+            time.sleep(0.002 * arr)          # staggered arrivals
+            c.submit_tokens(rid, prompt, mn)
+        t0 = time.time()
+        while c.engine_stats()["finished"] < len(requests):
+            assert time.time() - t0 < timeout_s, f"engine stalled: {c.engine_stats()}"
+            time.sleep(0.001)
+    finally:
+        c.engine_stop(drain=True)
+    st = c.engine_stats()
+    outs = {}
+    for rid, *_ in requests:
+        toks, fin = c.request_output(rid)
+        assert fin
+        outs[rid] = toks.tolist()
+    return outs, st
+
+
+@pytest.mark.parametrize("n_blocks", [64, 6])
+def test_engine_generation_matches_oracle(n_blocks):
+    shape, n_layers, vocab = S.TINY, 2, 1000
+    if n_blocks == 64:
+        prompts = [(1, 37, 12, 0), (2, 5, 20, 0), (3, 64, 9, 2), (4, 16, 1, 3), (5, 23, 16, 6)]
+    else:   # two sequences growing to 60 tokens each need 8 blocks: one is recomputed
+        prompts = [(1, 20, 40, 0), (2, 20, 40, 0)]
+    requests = [(rid, S.prompt_tokens(pl, vocab, rid), mn, arr) for rid, pl, mn, arr in prompts]
+    hb = S.head_weights(shape.d_model, vocab)
+    wbits = [S.layer_weights(shape, l) for l in range(n_layers)]
+    free, _ = lm.OracleModel(shape, wbits, hb, 4).generate(requests[1][1], np.arange(4, dtype=np.int32), 20)
+    eos = free[5] if n_blocks == 64 else -1
+    rig = Rig(shape, n_blocks=n_blocks, max_prefill_tokens=128, max_decode_batch=4, max_context=128, n_layers=n_layers,
+              with_oracle=False)
+    try:
+        hd = {k: to_dev(v) for k, v in hb.items()}
+        rig.ctx.set_head(hd["embed"], hd["final_norm"], hd["lm_head"], vocab, eos)
+        outs, st = _serve_engine(rig, requests)
+        frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, eos, requests, outs)
+        print(f"  engine, pool {n_blocks}: {st}; {frac:.2%} of generated tokens equal the oracle's choice", flush=True)
+        assert frac >= 0.9 and rig.ctx.kv_num_free() == n_blocks
+        assert (st["preempted"] >= 1) == (n_blocks == 6)
+    finally:
+        rig.close()

@@ -198,3 +198,88 @@ def test_library_reports_a_pool_too_small_for_one_request():
             if so.prefill_started_req >= 0:
                 c.debug_complete_prefill(1)
     assert e.value.code == rs.RS_ERR_NO_BLOCKS
+
+
+# ------------------------------------------------------------------ the two-thread engine (host-only)
+def _engine_run(n_blocks, seed, n_req=14, threads=1):
+    import threading
+    import time
+    reqs, _ = _trace(seed, n_req=n_req)
+    c = _host_ctx(n_blocks, 4, EOS)
+    c.engine_start()
+    try:
+        def submit_some(part):
+            for rid, pl, mn, script, _ in part:
+                for t in script:
+                    c.debug_push_sampled(rid, t)
+                c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
+        parts = [reqs[i::threads] for i in range(threads)]
+        ts = [threading.Thread(target=submit_some, args=(p,)) for p in parts]
+        for t in ts:
+            t.start()
+        # poll while it runs: a reader must never see a count ahead of its tokens (every visible token is final)
+        seen = {}
+        t0 = time.time()
+        while c.engine_stats()["finished"] < len(reqs) and time.time() - t0 < 30:
+            for rid, *_ in reqs:
+                try:
+                    toks, fin = c.request_output(rid)
+                except rs.RapidServeError:
+                    continue   # not submitted yet
+                prev = seen.get(rid, [])
+                assert toks.tolist()[:len(prev)] == prev
+                seen[rid] = toks.tolist()
+        for t in ts:
+            t.join()
+    finally:
+        c.engine_stop(drain=True)
+    st = c.engine_stats()
+    assert st["submitted"] == st["finished"] == len(reqs)
+    for rid, pl, mn, script, _ in reqs:
+        toks, fin = c.request_output(rid)
+        assert fin and toks.tolist() == _expected_output(script, mn, EOS)
+        assert c.request_state(rid) == 5
+        ts_, tf, tl = c.request_times(rid)
+        assert 0 < ts_ <= tf <= tl
+    assert c.kv_num_free() == n_blocks
+    return st
+
+
+@pytest.mark.parametrize("n_blocks,seed,threads", [(1000, 21, 1), (8, 22, 1), (7, 23, 3), (12, 24, 2)])
+def test_engine_threads_produce_the_scripted_outputs(n_blocks, seed, threads):
+    st = _engine_run(n_blocks, seed, threads=threads)
+    if n_blocks == 1000:
+        assert st["preempted"] == 0
+
+
+def test_engine_refuses_direct_stepping_and_restarts():
+    c = _host_ctx(64, 4, EOS)
+    c.engine_start()
+    with pytest.raises(rs.RapidServeError) as e:
+        c.step_tokens()
+    assert e.value.code == rs.RS_ERR_STATE
+    with pytest.raises(rs.RapidServeError):
+        c.engine_start()
+    c.debug_push_sampled(5, 3)
+    c.debug_push_sampled(5, EOS)
+    c.submit_tokens(5, np.zeros(9, np.int32), 10)
+    c.engine_stop(drain=True)
+    toks, fin = c.request_output(5)
+    assert fin and toks.tolist() == [3, EOS]
+    with pytest.raises(rs.RapidServeError):
+        c.engine_stop()
+    c.engine_start()                         # a drained engine can be started again
+    c.submit_tokens(6, np.zeros(4, np.int32), 2)
+    c.engine_stop(drain=True)
+    toks, fin = c.request_output(6)
+    assert fin and toks.tolist() == [0, 0]
+    c.destroy()
+
+
+def test_engine_reports_a_pool_too_small():
+    c = _host_ctx(2, 2, -1)
+    c.engine_start()
+    c.submit_tokens(1, np.zeros(30, np.int32), 20)
+    with pytest.raises(rs.RapidServeError) as e:
+        c.engine_stop(drain=True)
+    assert e.value.code == rs.RS_ERR_NO_BLOCKS
