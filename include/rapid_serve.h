@@ -272,7 +272,9 @@ int32_t rs_debug_read_workspace(rs_ctx *ctx, int32_t side, int32_t which, void *
  *      request's blocks as needed), with decode_hidden (device bf16 [>=batch, d_model]) as
  *      the step's input rows;
  *   5. if the prefill side is idle and a request is PREFILL_READY, enqueues its whole prompt
- *      over all n_layers on the prefill side and records its completion event.
+ *      over all n_layers on the prefill side and records its completion event (rs_step_tokens
+ *      takes, in arrival order, as many whole prompts as fit max_prefill_tokens, at most
+ *      RS_MAX_PREFILL_REQS, into that one pass; a prompt is never split).
  * Never blocks on the GPU except when `wait_decode` is non-zero (then it waits for this
  * step's decode work, which is what a caller measuring inter-token latency wants). */
 typedef struct {
@@ -292,6 +294,8 @@ typedef struct {
     int32_t n_waiting;               /* requests still without blocks */
     float decode_ms;                 /* GPU time of this step's decode work if wait_decode, else -1 */
     int32_t n_preempted;             /* rs_step_tokens: running requests sent back to WAITING for want of blocks */
+    int32_t prefill_started_count;   /* prompts in the prefill pass that was started (prefill_started_req is the first,
+                                        prefill_started_tokens their total) */
 } rs_step_out;
 
 int32_t rs_submit(rs_ctx *ctx, int64_t req_id, int32_t prompt_len, int32_t output_len,

@@ -9,7 +9,9 @@ released when the request ends or is preempted.
 Readings where the paper is silent:
   * a prompt's prefill yields the request's first output token; every decode step one more;
   * a request ends with its max_new-th token or with the end-of-sequence token, which it keeps;
-  * one prefill is in flight at a time; the decode batch is capped and filled in arrival order;
+  * one prefill pass is in flight at a time; it takes, in arrival order, as many whole prompts as
+    fit the prefill token budget (at least one, never part of one); the decode batch is capped and
+    filled in arrival order;
   * when a running request's next token has no block, the most recently arrived request that
     holds blocks and is not being prefilled at that moment (possibly the starved request itself)
     is preempted: its blocks are released, it waits again at its original place in the arrival
@@ -39,19 +41,21 @@ class _Req:
         self.n_prefill = prompt_len
         self.ctx = 0
         self.complete = False
-        self.prefill_done = False
 
 
 class Lifecycle:
     def __init__(self, n_blocks: int, max_batch: int, eos: int = -1,
-                 split: Optional[Callable[[int, int, bool], Tuple[int, int]]] = None):
+                 split: Optional[Callable[[int, int, bool], Tuple[int, int]]] = None,
+                 max_prefill_tokens: int = 1 << 30, max_prefill_reqs: int = 64):
+        self.max_prefill_tokens, self.max_prefill_reqs = max_prefill_tokens, max_prefill_reqs
         self.alloc = KVAllocator(n_blocks)
         self.max_batch, self.eos = max_batch, eos
         self.split = split
         self.reqs: Dict[int, _Req] = {}
         self.arrival: List[int] = []
         self.running: List[int] = []
-        self.prefilling: Optional[int] = None
+        self.prefilling: List[int] = []      # the prompts of the pass in flight
+        self.pass_done = False
         self.last_tokens: List[int] = []   # requests whose decode-step token is still to be read
 
     def submit(self, rid: int, prompt_len: int, max_new: int, script=()):
@@ -59,8 +63,9 @@ class Lifecycle:
         self.arrival.append(rid)
 
     def complete_prefill(self, rid: int):
-        assert self.reqs[rid].state == PREFILLING
-        self.reqs[rid].prefill_done = True
+        """The pass that contains rid has finished."""
+        assert self.reqs[rid].state == PREFILLING and rid in self.prefilling
+        self.pass_done = True
 
     def _sample(self, r: _Req):
         tok = r.script[r.events] if r.events < len(r.script) else 0
@@ -81,15 +86,16 @@ class Lifecycle:
         for rid in self.last_tokens:                       # tokens of the previous decode step
             self._sample(self.reqs[rid])
         self.last_tokens = []
-        if self.prefilling is not None and self.reqs[self.prefilling].prefill_done:
-            r = self.reqs[self.prefilling]
-            r.prefill_done = False
-            r.state, r.ctx = PREFILL_DONE, r.n_prefill
-            self.prefilling = None
-            self._sample(r)
-            if r.complete:
-                self._finish(r)
-                o["n_finished"] += 1
+        if self.prefilling and self.pass_done:
+            self.pass_done = False
+            for rid in self.prefilling:
+                r = self.reqs[rid]
+                r.state, r.ctx = PREFILL_DONE, r.n_prefill
+                self._sample(r)
+                if r.complete:
+                    self._finish(r)
+                    o["n_finished"] += 1
+            self.prefilling = []
         for rid in list(self.running):
             if self.reqs[rid].complete:
                 self._finish(self.reqs[rid])
@@ -132,10 +138,18 @@ class Lifecycle:
             v.state, v.n_prefill, v.ctx = WAITING, v.prompt_len + len(v.out), 0
             o["n_preempted"] += 1
         o["n_waiting"] = sum(1 for rid in self.arrival if self.reqs[rid].state == WAITING)
-        nxt = None
-        if self.prefilling is None:
-            nxt = next((rid for rid in self.arrival if self.reqs[rid].state == PREFILL_READY), None)
-        pending = self.prefilling is not None or nxt is not None
+        nxt: List[int] = []
+        if not self.prefilling:
+            total = 0
+            for rid in self.arrival:
+                r = self.reqs[rid]
+                if r.state != PREFILL_READY:
+                    continue
+                if nxt and (total + r.n_prefill > self.max_prefill_tokens or len(nxt) >= self.max_prefill_reqs):
+                    break
+                nxt.append(rid)
+                total += r.n_prefill
+        pending = bool(self.prefilling) or bool(nxt)
         o["decode_batch"] = len(self.running)
         o["decode_sum_ctx"] = sum(self.reqs[rid].ctx for rid in self.running)
         o["batch_ids"] = list(self.running)
@@ -146,9 +160,13 @@ class Lifecycle:
         for rid in self.running:                           # the decode step
             self.reqs[rid].ctx += 1
         self.last_tokens = list(self.running)
-        if nxt is not None and p_cus > 0:
-            r = self.reqs[nxt]
-            r.state = PREFILLING
+        o["prefill_started_count"] = 0
+        if nxt and p_cus > 0:
+            for rid in nxt:
+                self.reqs[rid].state = PREFILLING
             self.prefilling = nxt
-            o["prefill_started_req"], o["prefill_started_tokens"] = nxt, r.n_prefill
+            o["prefill_started_req"] = nxt[0]
+            o["prefill_started_tokens"] = sum(self.reqs[rid].n_prefill for rid in nxt)
+            o["prefill_started_count"] = len(nxt)
+            o["prefill_started_ids"] = list(nxt)
         return o

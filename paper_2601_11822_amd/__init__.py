@@ -81,7 +81,7 @@ class StepOut(ctypes.Structure):
                 ("decode_sum_ctx", ctypes.c_int64), ("prefill_started_tokens", ctypes.c_int32),
                 ("prefill_started_req", ctypes.c_int64), ("n_promoted", ctypes.c_int32),
                 ("n_finished", ctypes.c_int32), ("n_waiting", ctypes.c_int32), ("decode_ms", ctypes.c_float),
-                ("n_preempted", ctypes.c_int32)]
+                ("n_preempted", ctypes.c_int32), ("prefill_started_count", ctypes.c_int32)]
 
 
 class HeadWeights(ctypes.Structure):

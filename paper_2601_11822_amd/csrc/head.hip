@@ -10,7 +10,14 @@
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
     const int row = blockIdx.x;
-    const int tok = a.tokens[a.row_slot ? a.row_slot[row] : row];
+    int tok;
+    if (a.slots) {
+        int q = 0;
+        while (q + 1 < a.seq.n_req && row >= a.seq.cu[q + 1]) ++q;
+        tok = a.tokens[(size_t)a.slots[q] * a.slot_stride + (row - a.seq.cu[q])];
+    } else {
+        tok = a.tokens[a.row_slot ? a.row_slot[row] : row];
+    }
     const bool ok = (unsigned)tok < (unsigned)a.vocab;
     if (!ok && threadIdx.x == 0) atomicOr(a.err_flag, 4);
     const bf16_t *src = a.table + (size_t)(ok ? tok : 0) * a.d;
@@ -21,6 +28,17 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
 void launch_embed(hipStream_t st, const EmbedArgs &a) {
     if (a.n <= 0) return;
     hipLaunchKernelGGL(embed_kernel, dim3(a.n), dim3(256), 0, st, a);
+}
+
+__global__ __launch_bounds__(256) void gather_last_rows_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ out, int d, SeqInfo seq) {
+    const int q = blockIdx.x;
+    const bf16_t *src = x + (size_t)(seq.cu[q + 1] - 1) * d;
+    for (int c = threadIdx.x; c < (d >> 3); c += 256) st_bf16x8(out + (size_t)q * d + c * 8, ld_bf16x8(src + c * 8));
+}
+
+void launch_gather_last_rows(hipStream_t st, const bf16_t *x, bf16_t *out, int d, const SeqInfo &seq) {
+    if (seq.n_req <= 0) return;
+    hipLaunchKernelGGL(gather_last_rows_kernel, dim3(seq.n_req), dim3(256), 0, st, x, out, d, seq);
 }
 
 // ---------------------------------------------------------------------------------------------

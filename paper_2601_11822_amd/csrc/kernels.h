@@ -83,14 +83,21 @@ size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
 
 struct EmbedArgs {
-    const int32_t *tokens;     // [n], or per-slot tokens when row_slot is given
+    const int32_t *tokens;     // [n], or per-slot tokens when row_slot is given, or slot regions when slots is given
     const int32_t *row_slot;   // [n] or nullptr
     const bf16_t *table;       // [vocab][d]
     bf16_t *x;                 // [n][d] row-major
     int32_t *err_flag;
     int n, d, vocab;
+    // several whole prompts in one call: row r of prompt q (seq.cu delimits them) is token
+    // tokens[slots[q] * slot_stride + (r - seq.cu[q])]
+    const int32_t *slots = nullptr;
+    int slot_stride = 0;
+    SeqInfo seq{};
 };
 void launch_embed(hipStream_t st, const EmbedArgs &a);
+// out[q][:] = x[seq.cu[q+1] - 1][:]: the last row of each prompt, for the LM head.
+void launch_gather_last_rows(hipStream_t st, const bf16_t *x, bf16_t *out, int d, const SeqInfo &seq);
 
 struct HeadArgmaxArgs {
     const float *part;         // [S][M][Nv] partial logits

@@ -69,6 +69,11 @@ struct SpscRing {
         head.store(h + 1, std::memory_order_release);
         return true;
     }
+    // consumer only: the element pop would return, without taking it
+    const T *front() const {
+        const size_t h = head.load(std::memory_order_relaxed);
+        return h == tail.load(std::memory_order_acquire) ? nullptr : &buf[h % N];
+    }
     bool empty() const { return head.load(std::memory_order_acquire) == tail.load(std::memory_order_acquire); }
 };
 
@@ -175,7 +180,9 @@ struct rs_ctx {
     std::deque<int64_t> arrival;  // FCFS order of all live requests
     std::unordered_map<int64_t, Request> reqs;
     std::vector<int64_t> running;  // decode batch, in promotion order
-    int64_t prefilling = -1;
+    std::vector<int64_t> prefill_ids;   // the prompts of the prefill pass in flight (one pass at a time)
+    bool prefill_host_done = false;     // host-only contexts: rs_debug_complete_prefill
+    hipEvent_t prefill_ev = nullptr;    // end of that pass
     int32_t max_blk_per_req = 0;
     int32_t *d_ctx = nullptr, *d_tab = nullptr, *d_ptab = nullptr;   // device staging
     int32_t *h_ctx[2] = {nullptr, nullptr}, *h_tab[2] = {nullptr, nullptr}, *h_ptab = nullptr;
@@ -204,6 +211,8 @@ struct rs_ctx {
     int32_t *d_prompts = nullptr;    // [n_slots][max_context] token sequences to prefill
     int32_t *h_first = nullptr;      // pinned [n_slots]: the token a prefill chose
     hipStream_t copy_stream = nullptr;   // non-blocking: token uploads must not wait for the partitions' work
+    int32_t *d_pslots = nullptr, *h_pslots = nullptr;   // request slots of the prompts of a prefill pass
+    int32_t *d_pfirst = nullptr, *h_pfirst = nullptr;   // the tokens that pass chose, prompt order
     int32_t *d_rowslot = nullptr, *h_rowslot[2] = {nullptr, nullptr};
     int32_t *d_sampled = nullptr, *h_sampled[2] = {nullptr, nullptr};
     hipEvent_t sampled_ev[2] = {nullptr, nullptr};
@@ -646,13 +655,14 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
         const size_t tab_elems = nb * c->max_blk_per_req;
         HIP_TRY(hipMalloc(&c->d_ctx, nb * sizeof(int32_t)));
         HIP_TRY(hipMalloc(&c->d_tab, tab_elems * sizeof(int32_t)));
-        HIP_TRY(hipMalloc(&c->d_ptab, (size_t)c->max_blk_per_req * sizeof(int32_t)));
+        HIP_TRY(hipMalloc(&c->d_ptab, (size_t)RS_MAX_PREFILL_REQS * c->max_blk_per_req * sizeof(int32_t)));
+        HIP_TRY(hipEventCreateWithFlags(&c->prefill_ev, hipEventDisableTiming));
         for (int i = 0; i < 2; ++i) {
             HIP_TRY(hipHostMalloc(&c->h_ctx[i], nb * sizeof(int32_t)));
             HIP_TRY(hipHostMalloc(&c->h_tab[i], tab_elems * sizeof(int32_t)));
             HIP_TRY(hipEventCreateWithFlags(&c->staged[i], hipEventDisableTiming));
         }
-        HIP_TRY(hipHostMalloc(&c->h_ptab, (size_t)c->max_blk_per_req * sizeof(int32_t)));
+        HIP_TRY(hipHostMalloc(&c->h_ptab, (size_t)RS_MAX_PREFILL_REQS * c->max_blk_per_req * sizeof(int32_t)));
         HIP_TRY(hipEventCreateWithFlags(&c->pstaged, hipEventDisableTiming));
         for (int i = 0; i < 2; ++i) HIP_TRY(hipEventCreateWithFlags(&c->step_end[i], hipEventDisableTiming));
         return set_split(c, RS_TOTAL_CUS, RS_TOTAL_CUS);
@@ -702,9 +712,13 @@ int32_t rs_destroy(rs_ctx *c) {
             if (c->h_sampled[i]) (void)hipHostFree(c->h_sampled[i]);
             if (c->sampled_ev[i]) (void)hipEventDestroy(c->sampled_ev[i]);
         }
-        for (void *q : {(void *)c->packed_lm, (void *)c->d_tok, (void *)c->d_prompts, (void *)c->d_rowslot, (void *)c->d_sampled})
+        for (void *q : {(void *)c->packed_lm, (void *)c->d_tok, (void *)c->d_prompts, (void *)c->d_rowslot, (void *)c->d_sampled,
+                        (void *)c->d_pslots, (void *)c->d_pfirst})
             if (q) (void)hipFree(q);
         if (c->h_first) (void)hipHostFree(c->h_first);
+        if (c->h_pslots) (void)hipHostFree(c->h_pslots);
+        if (c->h_pfirst) (void)hipHostFree(c->h_pfirst);
+        if (c->prefill_ev) (void)hipEventDestroy(c->prefill_ev);
         if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     }
     delete c;
@@ -759,6 +773,10 @@ int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
             HIP_TRY(hipMemset(c->d_tok, 0, ns * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&c->d_prompts, ns * mc * sizeof(int32_t)));
             HIP_TRY(hipHostMalloc((void **)&c->h_first, ns * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_pslots, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_pfirst, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
+            HIP_TRY(hipHostMalloc((void **)&c->h_pslots, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
+            HIP_TRY(hipHostMalloc((void **)&c->h_pfirst, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&c->d_rowslot, nb * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&c->d_sampled, nb * sizeof(int32_t)));
             for (int i = 0; i < 2; ++i) {
@@ -1118,7 +1136,7 @@ int32_t rs_debug_complete_prefill(rs_ctx *c, int64_t req_id) {
     if (c->gpu) return fail(RS_ERR_STATE, "only for host-only contexts");
     auto it = c->reqs.find(req_id);
     if (it == c->reqs.end() || it->second.state != PREFILLING) return fail(RS_ERR_STATE, "request is not prefilling");
-    it->second.host_done = true;
+    c->prefill_host_done = true;   // the whole pass the request is part of
     return RS_OK;
 }
 
@@ -1211,6 +1229,52 @@ int retire_finished(rs_ctx *c) {
     return n;
 }
 
+// One prefill pass over several whole token prompts on the prefill side's current stream: block tables and
+// slots staged, embedding, every layer, then the head on each prompt's last row.  The chosen tokens are in
+// c->h_pfirst[0..n) (prompt order) once the stream has reached the end of what is enqueued here; each
+// request's token cell is written too.
+struct PromptItem {
+    int32_t slot, n_tok;
+    const std::vector<int32_t> *blocks;
+};
+int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wait_for) {
+    const int mb = c->max_blk_per_req;
+    hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+    Workspace &w = c->ws[RS_SIDE_PREFILL];
+    HIP_TRY(hipEventSynchronize(c->pstaged));   // the staging buffers' previous contents have been copied
+    int32_t cu[RS_MAX_PREFILL_REQS + 1];
+    cu[0] = 0;
+    SeqInfo seq{};
+    seq.n_req = n;
+    for (int q = 0; q < n; ++q) {
+        cu[q + 1] = cu[q] + items[q].n_tok;
+        c->h_pslots[q] = items[q].slot;
+        const std::vector<int32_t> &ids = *items[q].blocks;
+        for (int j = 0; j < mb; ++j) c->h_ptab[(size_t)q * mb + j] = j < (int)ids.size() ? ids[j] : -1;
+    }
+    for (int q = 0; q <= n; ++q) seq.cu[q] = cu[q];
+    const int T = cu[n];
+    if (wait_for) HIP_TRY(hipStreamWaitEvent(st, wait_for, 0));
+    HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, (size_t)n * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(c->pstaged, st));
+    EmbedArgs ea{c->d_prompts, nullptr, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag, T, c->m.d_model, c->head.vocab};
+    ea.slots = c->d_pslots;
+    ea.slot_stride = c->lim.max_context;
+    ea.seq = seq;
+    launch_embed(st, ea);
+    for (int l = 0; l < c->m.n_layers; ++l) {
+        if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+        int32_t rc = prefill_layer(c, l, w.xbuf, w.xbuf, cu, n, c->d_ptab, mb);
+        if (rc) return rc;
+    }
+    launch_gather_last_rows(st, w.xbuf, w.x1, c->m.d_model, seq);   // x1 is free once the layers are enqueued
+    int32_t rc = head_greedy(c, RS_SIDE_PREFILL, w.x1, n, nullptr, c->d_pfirst, c->d_pslots, c->d_tok);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(c->h_pfirst, c->d_pfirst, n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    return RS_OK;
+}
+
 int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token_mode) {
     *out = rs_step_out{};
     out->prefill_started_req = -1;
@@ -1235,23 +1299,25 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             accept_token(c, r, c->gpu ? dm.token : next_injected(r));
             if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
         }
-    } else if (c->prefilling >= 0) {
-        Request &r = c->reqs[c->prefilling];
-        bool done = r.host_done;
+    } else if (!c->prefill_ids.empty()) {
+        bool done = c->prefill_host_done;
         if (c->gpu) {
-            hipError_t q = hipEventQuery(r.done);
+            hipError_t q = hipEventQuery(c->prefill_ev);
             if (q == hipSuccess) done = true;
             else if (q != hipErrorNotReady) return fail(RS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q));
         }
         if (done) {
-            set_state(r, PREFILL_DONE);
-            r.host_done = false;
-            r.ctx_len = token_mode ? r.n_prefill : r.prompt_len;
-            c->prefilling = -1;
-            if (token_mode) {   // the prefill's own token
-                accept_token(c, r, c->gpu ? c->h_first[r.slot] : next_injected(r));
-                if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
+            c->prefill_host_done = false;
+            for (size_t i = 0; i < c->prefill_ids.size(); ++i) {
+                Request &r = c->reqs[c->prefill_ids[i]];
+                set_state(r, PREFILL_DONE);
+                r.ctx_len = token_mode ? r.n_prefill : r.prompt_len;
+                if (token_mode) {   // the prefill's own token
+                    accept_token(c, r, c->gpu ? c->h_pfirst[i] : next_injected(r));
+                    if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
+                }
             }
+            c->prefill_ids.clear();
         }
     }
     // 1b. retire requests that produced all their tokens
@@ -1322,10 +1388,10 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
 
     // 4. the split for this step
     int64_t next_prefill = -1;
-    if (c->prefilling < 0)
+    if (c->prefill_ids.empty())
         for (int64_t id : c->arrival)
             if (c->reqs[id].state == PREFILL_READY) { next_prefill = id; break; }
-    const bool prefill_pending = c->prefilling >= 0 || next_prefill >= 0 || c->n_prefill_inflight > 0;
+    const bool prefill_pending = !c->prefill_ids.empty() || next_prefill >= 0 || c->n_prefill_inflight > 0;
     const int B = (int)c->running.size();
     int64_t sum_ctx = 0;
     for (int64_t id : c->running) sum_ctx += c->reqs[id].ctx_len;
@@ -1430,50 +1496,61 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 r.n_sampled++;
                 set_state(r, PREFILLING);
                 c->n_prefill_inflight++;
-                if (out->prefill_started_req < 0) { out->prefill_started_req = id; out->prefill_started_tokens = r.n_prefill; }
+                if (out->prefill_started_req < 0) out->prefill_started_req = id;
+                out->prefill_started_tokens += r.n_prefill;
+                out->prefill_started_count++;
             }
         return RS_OK;
     }
-    // 6. start the next whole-prompt prefill if the prefill side is idle
+    // 6. start the next prefill pass if the prefill side is idle: whole prompts in arrival order, as many as
+    //    fit the prefill workspace (token requests; a hidden-state request runs alone)
     if (next_prefill >= 0 && c->side[RS_SIDE_PREFILL].cus > 0) {
-        Request &r = c->reqs[next_prefill];
-        const int32_t n_tok = token_mode ? r.n_prefill : r.prompt_len;
-        if (c->gpu) {
-            const int mb = c->max_blk_per_req;
-            HIP_TRY(hipEventSynchronize(c->pstaged));
-            const std::vector<int32_t> &ids = c->owned[r.id];
-            for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)ids.size() ? ids[j] : -1;
-            hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
-            if (c->step_end_valid[prev_end]) HIP_TRY(hipStreamWaitEvent(st, c->step_end[prev_end], 0));
-            HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
-            HIP_TRY(hipEventRecord(c->pstaged, st));
-            const int32_t cu[2] = {0, n_tok};
-            Workspace &w = c->ws[RS_SIDE_PREFILL];
-            const void *x_first = r.prompt_hidden;
-            if (token_mode) {
-                launch_embed(st, EmbedArgs{c->d_prompts + (size_t)r.slot * c->lim.max_context, nullptr, (const bf16_t *)c->head.embed,
-                                           w.xbuf, c->err_flag, n_tok, c->m.d_model, c->head.vocab});
-                x_first = w.xbuf;
-            }
-            for (int l = 0; l < c->m.n_layers; ++l) {
-                if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                int32_t rc = prefill_layer(c, l, l == 0 ? x_first : (const void *)w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
-                if (rc) return rc;
-            }
-            if (token_mode) {
-                int32_t rc = head_greedy(c, RS_SIDE_PREFILL, w.xbuf + (size_t)(n_tok - 1) * c->m.d_model, 1, nullptr, nullptr, nullptr,
-                                         c->d_tok + r.slot);
-                if (rc) return rc;
-                HIP_TRY(hipMemcpyAsync(c->h_first + r.slot, c->d_tok + r.slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-            }
-            if (!r.done) HIP_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
-            HIP_TRY(hipEventRecord(r.done, st));
+        std::vector<int64_t> ids;
+        int32_t total = 0;
+        for (int64_t id : c->arrival) {
+            Request &r = c->reqs[id];
+            if (r.state != PREFILL_READY) continue;
+            const int32_t n_tok = token_mode ? r.n_prefill : r.prompt_len;
+            if (!ids.empty() && (!token_mode || total + n_tok > c->lim.max_prefill_tokens || (int)ids.size() >= RS_MAX_PREFILL_REQS)) break;
+            ids.push_back(id);
+            total += n_tok;
         }
-        if (token_mode) r.n_sampled++;
-        set_state(r, PREFILLING);
-        c->prefilling = r.id;
-        out->prefill_started_req = r.id;
-        out->prefill_started_tokens = n_tok;
+        if (c->gpu) {
+            hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+            hipEvent_t wait_for = c->step_end_valid[prev_end] ? c->step_end[prev_end] : nullptr;
+            if (token_mode) {
+                std::vector<PromptItem> items;
+                for (int64_t id : ids) items.push_back(PromptItem{c->reqs[id].slot, c->reqs[id].n_prefill, &c->owned[id]});
+                int32_t rc = enqueue_prompts(c, items.data(), (int)items.size(), wait_for);
+                if (rc) return rc;
+            } else {
+                Request &r = c->reqs[ids[0]];
+                const int mb = c->max_blk_per_req;
+                HIP_TRY(hipEventSynchronize(c->pstaged));
+                const std::vector<int32_t> &bl = c->owned[r.id];
+                for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)bl.size() ? bl[j] : -1;
+                if (wait_for) HIP_TRY(hipStreamWaitEvent(st, wait_for, 0));
+                HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipEventRecord(c->pstaged, st));
+                const int32_t cu[2] = {0, r.prompt_len};
+                Workspace &w = c->ws[RS_SIDE_PREFILL];
+                for (int l = 0; l < c->m.n_layers; ++l) {
+                    if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+                    int32_t rc = prefill_layer(c, l, l == 0 ? r.prompt_hidden : (const void *)w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
+                    if (rc) return rc;
+                }
+            }
+            HIP_TRY(hipEventRecord(c->prefill_ev, st));
+        }
+        for (int64_t id : ids) {
+            Request &r = c->reqs[id];
+            if (token_mode) r.n_sampled++;
+            set_state(r, PREFILLING);
+        }
+        c->prefill_ids = ids;
+        out->prefill_started_req = ids[0];
+        out->prefill_started_tokens = total;
+        out->prefill_started_count = (int32_t)ids.size();
     }
     return RS_OK;
 }
@@ -1483,31 +1560,21 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
 // ---- the two-thread engine (section 4.4) -------------------------------------------------------
 namespace {
 
-// Prefill thread: one whole prompt on the prefill side, then wait for it (this thread only).
-int32_t engine_run_prompt(rs_ctx *c, const PrefillMsg &m, int32_t *token) {
+// Prefill thread: one pass over the prompts it has taken, then wait for it (this thread only).
+int32_t engine_run_prompts(rs_ctx *c, const std::vector<PrefillMsg> &ms) {
     int32_t rc = set_side(c, RS_SIDE_PREFILL, c->prefill_cus_pub.load(std::memory_order_acquire));
     if (rc) return rc;
     if (c->side[RS_SIDE_PREFILL].cus <= 0) return fail(RS_ERR_STATE, "a prompt was handed over while the prefill side has no CUs");
-    const int mb = c->max_blk_per_req;
-    hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
-    for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)m.blocks->size() ? (*m.blocks)[j] : -1;
-    // blocks released by the decode thread may still be written by the decode step it had in flight
-    if (m.wait_idx >= 0) HIP_TRY(hipStreamWaitEvent(st, c->step_end[m.wait_idx], 0));
-    HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    const int32_t cu[2] = {0, m.n_tok};
-    Workspace &w = c->ws[RS_SIDE_PREFILL];
-    launch_embed(st, EmbedArgs{c->d_prompts + (size_t)m.slot * c->lim.max_context, nullptr, (const bf16_t *)c->head.embed, w.xbuf,
-                               c->err_flag, m.n_tok, c->m.d_model, c->head.vocab});
-    for (int l = 0; l < c->m.n_layers; ++l) {
-        if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-        rc = prefill_layer(c, l, w.xbuf, w.xbuf, cu, 1, c->d_ptab, mb);
-        if (rc) return rc;
+    std::vector<PromptItem> items;
+    int wait_idx = -1;
+    for (const PrefillMsg &m : ms) {
+        items.push_back(PromptItem{m.slot, m.n_tok, m.blocks});
+        if (m.wait_idx >= 0) wait_idx = m.wait_idx;   // the newest message names the newest decode step to stay behind
     }
-    rc = head_greedy(c, RS_SIDE_PREFILL, w.xbuf + (size_t)(m.n_tok - 1) * c->m.d_model, 1, nullptr, nullptr, nullptr, c->d_tok + m.slot);
+    // blocks released by the decode thread may still be written by the decode step it had in flight
+    rc = enqueue_prompts(c, items.data(), (int)items.size(), wait_idx >= 0 ? c->step_end[wait_idx] : nullptr);
     if (rc) return rc;
-    HIP_TRY(hipMemcpyAsync(c->h_first + m.slot, c->d_tok + m.slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
-    *token = c->h_first[m.slot];
+    HIP_TRY(hipStreamSynchronize(c->side[RS_SIDE_PREFILL].stream));
     return RS_OK;
 }
 
@@ -1521,6 +1588,7 @@ void engine_fail(rs_ctx *c, int32_t rc) {
 
 void prefill_main(rs_ctx *c) {
     if (c->gpu) (void)hipSetDevice(c->device);
+    std::vector<PrefillMsg> ms;
     for (;;) {
         PrefillMsg m;
         if (!c->pre_q.pop(m)) {
@@ -1528,11 +1596,23 @@ void prefill_main(rs_ctx *c) {
             std::this_thread::sleep_for(std::chrono::microseconds(50));
             continue;
         }
-        int32_t token = 0, rc = RS_OK;
-        if (c->gpu) rc = engine_run_prompt(c, m, &token);
+        // first come first served, never chunked: as many whole prompts, in order, as fit the workspace
+        ms.assign(1, m);
+        int32_t total = m.n_tok;
+        for (const PrefillMsg *nx; (nx = c->pre_q.front()) != nullptr;) {
+            if (total + nx->n_tok > c->lim.max_prefill_tokens || (int)ms.size() >= RS_MAX_PREFILL_REQS) break;
+            total += nx->n_tok;
+            (void)c->pre_q.pop(m);
+            ms.push_back(m);
+        }
+        int32_t rc = RS_OK;
+        if (c->gpu) rc = engine_run_prompts(c, ms);
         if (rc) engine_fail(c, rc);
-        delete m.blocks;
-        while (!c->fin_q.push(DoneMsg{m.id, token, rc})) std::this_thread::yield();
+        for (size_t i = 0; i < ms.size(); ++i) {
+            delete ms[i].blocks;
+            const DoneMsg dm{ms[i].id, (c->gpu && !rc) ? c->h_pfirst[i] : 0, rc};
+            while (!c->fin_q.push(dm)) std::this_thread::yield();
+        }
     }
 }
 

@@ -82,21 +82,23 @@ def test_oracle_outputs_are_script_prefixes_and_blocks_return(n_blocks, seed):
     if n_blocks == 1000:
         assert n_pre == 0
         # ample pool: prompts are prefilled in arrival order, each exactly once, whole
-        started = [(o["prefill_started_req"], o["prefill_started_tokens"]) for o in log if o["prefill_started_req"] >= 0]
-        order = [r[0] for r in sorted(reqs, key=lambda r: (r[4], r[0]))]
-        assert [s[0] for s in started] == order
-        assert all(tok == next(r[1] for r in reqs if r[0] == rid) for rid, tok in started)
+        passes = [o for o in log if o["prefill_started_req"] >= 0]
+        order = [r[0] for r in sorted(reqs, key=lambda r: r[4])]
+        assert [rid for o in passes for rid in o["prefill_started_ids"]] == order
+        plen = {r[0]: r[1] for r in reqs}
+        assert all(o["prefill_started_tokens"] == sum(plen[rid] for rid in o["prefill_started_ids"]) for o in passes)
+        assert any(o["prefill_started_count"] > 1 for o in passes)
     else:
         assert n_pre > 0
 
 
 def test_oracle_preemption_worked_example():
     # Pool of 4 blocks; A and B have 16-token prompts (1 block each) and produce 40 tokens each.
-    # Both need a 2nd block for their first decode token (position 16) -> pool full.  Prefills are
-    # serial, so A decodes from step 1 and B from step 2: A's context is 16 + k after step k.
-    # At step 17 A sits at position 32 and needs a 3rd block: A is starved, B (arrived last) is
-    # preempted.  By then B has taken decode steps 2..16: 1 (prefill) + 15 = 16 tokens, so its
-    # recomputation covers 16 + 16 = 32 tokens.
+    # They arrive together, so one prefill pass covers both (32 tokens) and they decode in lock
+    # step from step 1: context 16 + k after step k.  Both need a 2nd block for their first decode
+    # token (position 16) -> pool full.  At step 17 both sit at position 32 and need a 3rd block:
+    # A (first in line) is starved, B (arrived last) is preempted.  By then B has 1 (prefill) + 16
+    # (steps 1..16) = 17 tokens, so its recomputation covers 16 + 17 = 33 tokens.
     lc = Lifecycle(4, max_batch=4, eos=-1)
     lc.submit(1, 16, 40, list(range(100, 140)))
     lc.submit(2, 16, 40, list(range(200, 240)))
@@ -105,12 +107,12 @@ def test_oracle_preemption_worked_example():
         o = lc.step()
         log.append(o)
         if o["prefill_started_req"] >= 0:
-            started.append((o["prefill_started_req"], o["prefill_started_tokens"]))
+            started.append((o["prefill_started_req"], o["prefill_started_tokens"], o["prefill_started_count"]))
             lc.complete_prefill(o["prefill_started_req"])
         if lc.reqs[1].state == FINISHED and lc.reqs[2].state == FINISHED:
             break
     assert sum(o["n_preempted"] for o in log) == 1
-    assert started == [(1, 16), (2, 16), (2, 32)]
+    assert started == [(1, 32, 2), (2, 33, 1)]
     assert [i for i, o in enumerate(log) if o["n_preempted"]] == [17]
     assert lc.reqs[1].out == list(range(100, 140)) and lc.reqs[2].out == list(range(200, 240))
 
@@ -126,24 +128,28 @@ def test_oracle_pool_too_small_for_one_request():
 
 
 # ------------------------------------------------------------------ the library against the oracle
-def _host_ctx(n_blocks, max_batch, eos):
-    c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=4096,
+def _host_ctx(n_blocks, max_batch, eos, max_prefill=4096):
+    c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=max_prefill,
                               max_decode_batch=max_batch, max_context=4096, device=rs.RS_HOST_ONLY)
     c.set_head(None, None, None, vocab=64, eos_token=eos)
     return c
 
 
 KEYS = ("n_promoted", "n_finished", "n_preempted", "n_waiting", "prefill_started_req", "prefill_started_tokens",
-        "decode_batch", "decode_sum_ctx")
+        "prefill_started_count", "decode_batch", "decode_sum_ctx")
 
 
-@pytest.mark.parametrize("n_blocks,seed", [(1000, 11), (12, 12), (8, 13), (7, 14), (9, 15)])
-def test_library_life_cycle_matches_oracle(n_blocks, seed):
+@pytest.mark.parametrize("n_blocks,seed,budget", [(1000, 11, 4096), (12, 12, 4096), (8, 13, 4096), (7, 14, 100), (9, 15, 120),
+                                                  (1000, 16, 100)])
+def test_library_life_cycle_matches_oracle(n_blocks, seed, budget):
     reqs, delays = _trace(seed)
-    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS)
+    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS, max_prefill_tokens=budget)
     ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lc.complete_prefill, reqs, delays)
+    if budget < 4096:   # the budget binds somewhere, and is never exceeded by a pass of several prompts
+        assert all(o["prefill_started_tokens"] <= budget for o in ref if o["prefill_started_count"] > 1)
+        assert any(o["prefill_started_count"] > 1 for o in ref)
 
-    c = _host_ctx(n_blocks, 4, EOS)
+    c = _host_ctx(n_blocks, 4, EOS, budget)
 
     def submit(rid, pl, mn, script):
         c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
