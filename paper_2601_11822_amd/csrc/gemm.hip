@@ -185,8 +185,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 // in front of a step is already satisfied and the barrier never sits between idle matrix cores.
 // ---------------------------------------------------------------------------------------------
 // One output tile: rows [bm, bm + BM), column tile nb (of width BN; BN/2 output columns for SwiGLU).
-template <int BM, int BN, int EPI, int NS, int NW>
-__device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm, const int nb, bf16_t *smem) {
+// PARTIAL: the tile covers K tiles [kt0, kt0 + nk_part) only and stores its raw float32 sums to
+// part[z][m][n] (row stride N), for an epilogue pass that adds the slices in order.
+template <int BM, int BN, int EPI, int NS, int NW, bool PARTIAL = false>
+__device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm, const int nb, bf16_t *smem,
+                                                 const int kt0 = 0, const int nk_part = 0, float *part = nullptr, const int z = 0) {
     constexpr int BK = 32;
     constexpr int WGN = NW / 2;                      // waves: 2 along M x NW/2 along N
     constexpr int WM = BM / 2, WN = BN / WGN;
@@ -218,11 +221,11 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
             pb[j] = a.Wp + ((size_t)s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8;
     }
     const size_t ksa = (size_t)Mt * 1024, ksb = (size_t)Nt * 1024;   // elements per K tile (2 k blocks)
-    const int nk = K / BK;
+    const int nk = PARTIAL ? nk_part : K / BK;
     // loads [j0, j1) of the LA + LB wave-wide loads that bring K tile kt into its stage
     auto issue = [&](int kt, int j0, int j1) {
         const int stage = kt % NS;
-        const size_t kc = (size_t)min(kt, nk - 1);
+        const size_t kc = (size_t)(kt0 + min(kt, nk - 1));
         bf16_t *sa = smem + stage * STAGE;
         bf16_t *sb = sa + BM * BK;
 #pragma unroll
@@ -302,6 +305,23 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
+    if (PARTIAL) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = bm + wm * WM + 32 * tm + c32;
+            if (m >= M) continue;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = nb * BN + wn * WN + 32 * tn + 8 * j + 4 * h;
+                    if (n >= N) continue;
+                    f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
+                    *(f32x4 *)(part + ((size_t)z * M + m) * N + n) = v;
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int m = bm + wm * WM + 32 * tm + c32;
@@ -377,6 +397,43 @@ __global__ __launch_bounds__(256) void gemm_direct_mixed_kernel(GemmArgs a, int 
     }
 }
 
+// Few output tiles and a long K (the projections back to d_model at a few hundred rows): the K range is
+// cut into S slices, one workgroup per (tile, slice), and skinny_epilogue_kernel adds the slices in order
+// and applies the epilogue.  S follows from (M, N, K) alone, so results do not depend on the CU share.
+__global__ __launch_bounds__(256) void gemm_direct_splitk_kernel(GemmArgs a, int m_tiles, int n_tiles, int nk_per, float *part) {
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+    const int tiles = m_tiles * n_tiles;
+    const int z = blockIdx.x / tiles, t = blockIdx.x % tiles;
+    const int nk_total = a.K / 32;
+    const int kt0 = z * nk_per;
+    gemm_direct_tile<128, 256, EPI_STORE, 5, 4, true>(a, (t % m_tiles) * 128, t / m_tiles, smem, kt0, min(nk_per, nk_total - kt0), part, z);
+}
+
+static inline int direct_splits(int M, int N, int K) {
+    const long tiles = (long)((M + 127) / 128) * ((N + 255) / 256);
+    const int nk = K / 32;
+    int S = 1;
+    // until about half of a whole chip's compute units have a workgroup; at least 16 K tiles per slice
+    while (tiles * S * 2 <= 256 && S < 8 && nk / (S * 2) >= 16) S *= 2;
+    return S;
+}
+size_t direct_partial_elems(int M, int N, int K) { return (size_t)direct_splits(M, N, K) * (size_t)M * (size_t)N; }
+
+template <int EPI>
+__global__ __launch_bounds__(256) void skinny_epilogue_kernel(GemmArgs a, const float *__restrict__ part, int S, int Nv);
+
+static void launch_direct_splitk(hipStream_t st, const GemmArgs &a, int S) {
+    const int m_tiles = (a.M + 127) / 128, n_tiles = (a.N + 255) / 256;
+    const int nk_total = a.K / 32, nk_per = (nk_total + S - 1) / S;
+    constexpr int lds = 5 * (128 + 256) * 32 * 2;
+    hipLaunchKernelGGL(gemm_direct_splitk_kernel, dim3(m_tiles * n_tiles * S), dim3(256), lds, st, a, m_tiles, n_tiles, nk_per, a.partials);
+    const int eblocks = (a.M * (a.N / 4) + 255) / 256;
+    if (a.epi == EPI_RESIDUAL)
+        hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_RESIDUAL>, dim3(eblocks), dim3(256), 0, st, a, a.partials, S, a.N);
+    else
+        hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_STORE>, dim3(eblocks), dim3(256), 0, st, a, a.partials, S, a.N);
+}
+
 template <int EPI>
 static void launch_direct_mixed_epi(hipStream_t st, const GemmArgs &a, int m_tiles, int n_full, int n_half) {
     constexpr int lds = 4 * 512 * 32 * 2;   // the larger of the two rings
@@ -439,7 +496,14 @@ static void launch_tiled(hipStream_t st, const GemmArgs &a) {
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
     if (a.M <= 0 || a.N <= 0) return;
     const bool aligned = (a.K % 32 == 0) && a.K >= 32;
-    if (aligned && a.Wp && a.M >= 512 && a.N >= 1024) {
+    if (aligned && a.Wp && a.M > 64 && a.N >= 1024) {
+        if (a.epi != EPI_SWIGLU && a.partials && a.N % 4 == 0) {
+            const int S = direct_splits(a.M, a.N, a.K);
+            if (S > 1 && direct_partial_elems(a.M, a.N, a.K) <= a.partial_cap) {
+                launch_direct_splitk(st, a, S);
+                return;
+            }
+        }
         const int cus = a.cus > 0 ? a.cus : 256;
         const int nv = a.epi == EPI_SWIGLU ? 2 * a.N : a.N;
         const int mt256 = (a.M + 255) / 256, mt128 = (a.M + 127) / 128;
@@ -864,6 +928,7 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_kernel<EPI_SWIGLU, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_shared_kernel<EPI_SWIGLU, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_skinny_shared_kernel<EPI_RESIDUAL, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
+    set((const void *)gemm_direct_splitk_kernel, 5 * (128 + 256) * 32 * 2);
     set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);

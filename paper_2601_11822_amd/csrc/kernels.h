@@ -69,7 +69,12 @@ struct GemmArgs {
     int epi;
     int out_packed = 0;
     int cus = 0;  // compute units of the launching stream's partition (0: the whole chip); scheduling only
+    // float32 scratch for launch_gemm_tiled's K-sliced path (few tiles, long K); without it that path is not taken
+    float *partials = nullptr;
+    size_t partial_cap = 0;   // elements
 };
+// Upper bound of what the K-sliced path of launch_gemm_tiled needs, for any M: S * M * N <= this.
+#define RS_DIRECT_PARTIAL_ELEMS ((size_t)10 << 20)
 void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 
 // Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through

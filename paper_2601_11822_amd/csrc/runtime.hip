@@ -44,6 +44,7 @@ int32_t fail(int32_t code, const char *fmt, ...) {
 struct Workspace {
     bf16_t *h = nullptr, *qkv = nullptr, *attn = nullptr, *x1 = nullptr, *act = nullptr, *xbuf = nullptr;
     float *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
+    size_t partial_cap = 0;
     int rows = 0;
 };
 
@@ -282,14 +283,17 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     HIP_TRY(hipMalloc(&w.act, prow * r16(f) * 2));
     HIP_TRY(hipMemset(w.act, 0, prow * r16(f) * 2));
     HIP_TRY(hipMalloc(&w.xbuf, rows * d * 2));
-    if (decode) {
+    {
         const int Mmax = std::min(rows, 64);
-        size_t pe = 0;
+        size_t pe = decode ? 0 : RS_DIRECT_PARTIAL_ELEMS;   // prefill: also the K-sliced path of the large-tile GEMM
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)nqkv, (int)d, EPI_STORE));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)f, EPI_RESIDUAL));
         HIP_TRY(hipMalloc(&w.partials, pe * sizeof(float)));
+        w.partial_cap = pe;
+    }
+    if (decode) {
         const size_t nch = (c->lim.max_context + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
         HIP_TRY(hipMalloc(&w.part_o, (size_t)rows * m.n_q_heads * nch * m.head_dim * sizeof(float)));
         HIP_TRY(hipMalloc(&w.part_ml, (size_t)rows * m.n_q_heads * nch * 2 * sizeof(float)));
@@ -415,6 +419,8 @@ void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
     auto gemm = [&](GemmArgs g) {
         g.cus = c->side[side].cus;
+        g.partials = w.partials;
+        g.partial_cap = w.partial_cap;
         if (skinny) launch_gemm_skinny(st, g, w.partials);
         else launch_gemm_tiled(st, g);
     };
@@ -459,8 +465,12 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     c->last_rows[RS_SIDE_PREFILL] = T;
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, T, d, m.rms_eps);
     tick(c, RS_SIDE_PREFILL, 1);
-    launch_gemm_tiled(st, GemmArgs{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv,
-                                   T, nqkv, d, EPI_STORE, 0, c->side[RS_SIDE_PREFILL].cus});
+    // a pass of at most 64 rows is bound by reading the weights once: it takes the weight-streaming kernels
+    const bool skinny = T <= 64;
+    GemmArgs gq{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv,
+                T, nqkv, d, EPI_STORE, 0, c->side[RS_SIDE_PREFILL].cus, w.partials, w.partial_cap};
+    if (skinny) launch_gemm_skinny(st, gq, w.partials);
+    else launch_gemm_tiled(st, gq);
     tick(c, RS_SIDE_PREFILL, 2);
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
@@ -470,7 +480,7 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
-    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, false);
+    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny);
     HIP_TRY(hipGetLastError());
     return RS_OK;
 }
