@@ -291,3 +291,27 @@ def test_engine_generation_matches_oracle(n_blocks):
         assert (st["preempted"] >= 1) == (n_blocks == 6)
     finally:
         rig.close()
+
+
+def test_closed_loop_8b_shaped_layer_and_edge_prompts():
+    """One Llama-3-8B-shaped layer with a 32000-token vocabulary: prompts of 1 token, of 20 tokens (the pass
+    takes the weight-streaming GEMMs), of 70 tokens (large-tile GEMMs with a sliced K range) and of exactly
+    max_prefill_tokens, generated through the engine and checked token by token against the oracle."""
+    shape, n_layers, vocab = S.LLAMA8B, 1, 32000
+    prompts = [(1, 70, 5, 0), (2, 20, 5, 0), (3, 1, 4, 1), (4, 96, 3, 2)]
+    requests = [(rid, S.prompt_tokens(pl, vocab, rid), mn, arr) for rid, pl, mn, arr in prompts]
+    hb = S.head_weights(shape.d_model, vocab)
+    wbits = [S.layer_weights(shape, 0)]
+    rig = Rig(shape, n_blocks=32, max_prefill_tokens=96, max_decode_batch=4, max_context=128, n_layers=n_layers,
+              with_oracle=False)
+    try:
+        hd = {k: to_dev(v) for k, v in hb.items()}
+        rig.ctx.set_head(hd["embed"], hd["final_norm"], hd["lm_head"], vocab, -1)
+        with pytest.raises(rs.RapidServeError):
+            rig.ctx.submit_tokens(9, S.prompt_tokens(97, vocab, 9), 2)     # longer than max_prefill_tokens
+        outs, st = _serve_engine(rig, requests)
+        frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, -1, requests, outs)
+        print(f"  8B-shaped layer: {st}; {frac:.2%} of generated tokens equal the oracle's choice", flush=True)
+        assert frac >= 0.8 and rig.ctx.kv_num_free() == 32
+    finally:
+        rig.close()
