@@ -285,7 +285,7 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     HIP_TRY(hipMalloc(&w.xbuf, rows * d * 2));
     {
         const int Mmax = std::min(rows, 64);
-        size_t pe = decode ? 0 : RS_DIRECT_PARTIAL_ELEMS;   // prefill: also the K-sliced path of the large-tile GEMM
+        size_t pe = rows > 64 ? RS_DIRECT_PARTIAL_ELEMS : 0;   // more than 64 rows: also the K-sliced path of the large-tile GEMM
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)nqkv, (int)d, EPI_STORE));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
@@ -507,7 +507,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
     tick(c, RS_SIDE_DECODE, 1);
     GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE,
-               0, c->side[RS_SIDE_DECODE].cus};
+               0, c->side[RS_SIDE_DECODE].cus, w.partials, w.partial_cap};
     if (skinny) launch_gemm_skinny(st, g, w.partials);
     else launch_gemm_tiled(st, g);
     tick(c, RS_SIDE_DECODE, 2);

@@ -183,6 +183,13 @@ def test_decode_batch_over_64_takes_the_tiled_gemms():
     _run_decode_parity(S.MID, ctx, stream=6)
 
 
+def test_decode_batch_130_wide_takes_the_large_tile_gemms_with_sliced_k():
+    # 130 rows on the wide shape: the decode side's GEMMs are the large-tile kernel (second 128-row tile almost
+    # empty), the output and down projections with their K range sliced
+    ctx = [(29 * i) % 61 for i in range(130)]
+    _run_decode_parity(S.WIDE, ctx, stream=8)
+
+
 @pytest.mark.parametrize("which", ["wo", "wd"])
 def test_decode_mid_loud_output_projection(which):
     _run_decode_parity(S.MID, [40, 513, 700], stream=4, **{which + "_std": 0.2})
