@@ -434,6 +434,16 @@ static void launch_direct_splitk(hipStream_t st, const GemmArgs &a, int S) {
         hipLaunchKernelGGL(skinny_epilogue_kernel<EPI_STORE>, dim3(eblocks), dim3(256), 0, st, a, a.partials, S, a.N);
 }
 
+// Main pass of the large-tile kernel only, whole K in one slice: part[m][n] (row stride N) holds the float32
+// sums.  False (nothing launched) when the shape is not one the kernel takes.
+bool launch_gemm_direct_partials(hipStream_t st, const GemmArgs &a, float *part) {
+    if (!(a.K % 32 == 0 && a.K >= 32 && a.Wp && a.M >= 1 && a.N >= 1024 && a.N % 4 == 0)) return false;
+    const int m_tiles = (a.M + 127) / 128, n_tiles = (a.N + 255) / 256;
+    constexpr int lds = 5 * (128 + 256) * 32 * 2;
+    hipLaunchKernelGGL(gemm_direct_splitk_kernel, dim3(m_tiles * n_tiles), dim3(256), lds, st, a, m_tiles, n_tiles, a.K / 32, part);
+    return true;
+}
+
 template <int EPI>
 static void launch_direct_mixed_epi(hipStream_t st, const GemmArgs &a, int m_tiles, int n_full, int n_half) {
     constexpr int lds = 4 * 512 * 32 * 2;   // the larger of the two rings

@@ -48,6 +48,8 @@ struct Workspace {
     int rows = 0;
 };
 
+constexpr int RS_HEAD_GROUP = 256;
+
 enum ReqState { WAITING = 0, PREFILL_READY, PREFILLING, PREFILL_DONE, RUNNING, FINISHED };
 
 // Bounded single-producer / single-consumer ring: the only coupling between the engine's threads
@@ -204,6 +206,7 @@ struct rs_ctx {
     bool have_head = false;
     bf16_t *packed_lm = nullptr;
     float *head_part[2] = {nullptr, nullptr};
+    int head_group[2] = {64, 64};     // rows per pass of the LM head over its weights
     // closed-loop serving
     int serving_mode = 0;            // 0 none yet, 1 hidden-state requests, 2 token requests
     int n_slots = 0;
@@ -536,14 +539,21 @@ int32_t head_greedy(rs_ctx *c, int side, const bf16_t *x, int n, float *logits, 
     Workspace &w = c->ws[side];
     hipStream_t st = c->side[side].stream;
     const int d = m.d_model, V = c->head.vocab;
-    for (int g0 = 0; g0 < n; g0 += 64) {
-        const int mg = std::min(64, n - g0);
+    // one pass over the weights per group of rows: the large-tile kernel (up to RS_HEAD_GROUP rows; with K only
+    // d_model deep and a very wide N it also beats the weight-streaming kernel at a few rows: 243 against 249 us
+    // at one row, 259 against 299 us at 64 rows for a 128256 x 4096 head), else the weight-streaming kernel (64 rows)
+    const int group = c->head_group[side];
+    for (int g0 = 0; g0 < n; g0 += group) {
+        const int mg = std::min(group, n - g0);
         c->last_rows[side] = mg;
         launch_rmsnorm(st, x + (size_t)g0 * d, (const bf16_t *)c->head.final_norm, w.h, mg, d, m.rms_eps);
         GemmArgs g{w.h, (const bf16_t *)c->head.lm_head, nullptr, c->packed_lm, nullptr, nullptr, nullptr, mg, V, d, EPI_STORE,
                    0, c->side[side].cus};
-        int S = 1, Nv = 0;
-        launch_gemm_skinny_partials(st, g, c->head_part[side], &S, &Nv);
+        int S = 1, Nv = V;
+        if (!launch_gemm_direct_partials(st, g, c->head_part[side])) {
+            if (mg > 64) return fail(RS_ERR_STATE, "head group of %d rows without the large-tile kernel", mg);
+            launch_gemm_skinny_partials(st, g, c->head_part[side], &S, &Nv);
+        }
         HeadArgmaxArgs ha{c->head_part[side], logits ? logits + (size_t)g0 * V : nullptr, tokens ? tokens + g0 : nullptr,
                           row_slot ? row_slot + g0 : nullptr, tok_by_slot, S, mg, V, Nv};
         launch_head_argmax(st, ha);
@@ -773,8 +783,13 @@ int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
         launch_pack_weights(nullptr, (const bf16_t *)w->lm_head, c->packed_lm, w->vocab, d);
         for (int s = 0; s < 2; ++s) {
             if (c->head_part[s]) { (void)hipFree(c->head_part[s]); c->head_part[s] = nullptr; }
-            if (c->ws[s].rows > 0)
-                HIP_TRY(hipMalloc((void **)&c->head_part[s], skinny_partial_elems(64, w->vocab, d, EPI_STORE) * sizeof(float)));
+            if (c->ws[s].rows > 0) {
+                // more than 64 rows per call and a shape the large-tile kernel takes: groups of up to 256 rows
+                const bool big = c->ws[s].rows > 64 && d % 32 == 0 && w->vocab >= 1024 && w->vocab % 4 == 0;
+                c->head_group[s] = big ? std::min(c->ws[s].rows, RS_HEAD_GROUP) : 64;
+                const size_t elems = std::max(skinny_partial_elems(64, w->vocab, d, EPI_STORE), (size_t)c->head_group[s] * w->vocab);
+                HIP_TRY(hipMalloc((void **)&c->head_part[s], elems * sizeof(float)));
+            }
         }
         if (!c->d_tok) {
             const size_t ns = (size_t)c->n_slots, mc = (size_t)c->lim.max_context, nb = std::max(1, c->lim.max_decode_batch);
