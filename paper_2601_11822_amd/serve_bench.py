@@ -232,7 +232,8 @@ def main(argv=None):
         if not a.profile:
             ap.error("--policy manager needs --profile")
         if a.profile == "measure":
-            be, ce, dc = [16, a.max_batch], [32768, 131072], [64, 96, 128, 160, 192]
+            be = sorted({b for b in (16, 32, 64, 128, 256) if b < a.max_batch} | {a.max_batch})
+            ce, dc = [32768, 131072], [32, 64, 96, 128, 160, 192]
             rig = profiler.Rig(shape, be, ce, prefill_tokens=2048, max_context=a.max_prompt + a.max_out)
             d = profiler.profile(rig, be, ce, dc, a.layers, steps=6, warmup=2)
             rig.c.destroy()
