@@ -483,3 +483,47 @@ def test_serving_steps_three_requests_async_matches_oracle():
         print("splits used:", sorted(splits))
     finally:
         rig.close()
+
+
+def test_long_context_decode_and_16k_prefill_mid_shape():
+    """The long-context configuration's sizes on the mid shape: decode over contexts up to 32767 cached tokens
+    (64 attention chunks, directly written cache, same bits on both sides) and a whole 16384-token prompt
+    (128 query tiles), sampled rows against the oracle."""
+    shape = S.MID
+    ctx = np.array([8191, 8192, 20000, 32767, 3, 513], np.int32)
+    B = len(ctx)
+    T = 16384
+    counts = [int(c) + 1 for c in ctx] + [T]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 7
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)), stream=9)
+    dtab, ptab = tabs[:B], tabs[B:B + 1]
+    rig = Rig(shape, n_blocks, T, B, 32768, sentinel=0x7FC1)
+    try:
+        L = rig.olayers[0]
+        kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim, stream=3)
+        rig.load_pools_from_logical(kb, vb)
+        Kc, Vc = f32(kb), f32(vb)
+        db = S.hidden_states(B, shape.d_model, stream=61)
+        yd = rig.decode(db, ctx, dtab)
+        yd_ref, taps = L.decode(f32(db), ctx, dtab, Kc, Vc, taps=True)
+        check_tensor("long-context decode attention out", f32(rig.ctx.debug_read_workspace(rs.RS_SIDE_DECODE, 2, (B, shape.q_dim))),
+                     taps["attn"])
+        check_tensor("long-context decode y", f32(yd), yd_ref, f32(db), 2)
+        # the 16384-token prompt overwrites its own blocks only (snapshot after the decode step's appends)
+        kb, vb = rig.k_bits_logical(), rig.v_bits_logical()
+        xb = S.hidden_states(T, shape.d_model, stream=62)
+        y_bits = rig.prefill(xb, [0, T], ptab)
+        rng = np.random.default_rng(5)
+        rows = np.unique(np.concatenate([[0, 1, 127, 128, 8191, 8192, 16382, 16383], rng.integers(0, T, 24)])).astype(np.int32)
+        Kp, Vp = L.new_cache(n_blocks, fill=ORC_SENT)
+        y_ref = L.prefill(f32(xb), [0, T], ptab, Kp, Vp, rows=rows)
+        check_tensor("16K prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2)
+        # K/V written by the prompt: exactly its blocks, contents to tolerance
+        kg, vg = rig.k_bits_logical(), rig.v_bits_logical()
+        mine = np.zeros(n_blocks, bool)
+        mine[ptab[0, :S.blocks_for(T)]] = True
+        assert np.array_equal(kg[~mine], kb[~mine]) and np.array_equal(vg[~mine], vb[~mine])
+        assert rel_err(f32(kg[mine]).reshape(-1, shape.head_dim), Kp[mine].reshape(-1, shape.head_dim)) <= TOL
+        assert rel_err(f32(vg[mine]).reshape(-1, shape.head_dim), Vp[mine].reshape(-1, shape.head_dim)) <= TOL
+    finally:
+        rig.close()
