@@ -125,6 +125,13 @@ int32_t rs_destroy(rs_ctx *ctx);
  * stay valid and unchanged while the context uses the layer; after changing one, call
  * rs_set_weights again.  Errors: RS_ERR_BAD_ARG (null pointer, layer out of range), RS_ERR_HIP. */
 int32_t rs_set_weights(rs_ctx *ctx, int32_t layer, const rs_layer_weights *w);
+/* Declares that the five matrices given to rs_set_weights for `layer` will not be read again: the
+ * library keeps only its packed copies and the caller may free or reuse that memory (the two gain
+ * vectors stay borrowed).  This halves the weight footprint of a large model: a 70B-shaped stack is
+ * 137 GB packed.  RS_ERR_STATE if the shape can still reach the generic GEMM kernel, which reads the
+ * caller's row-major matrices (some K not a multiple of 32, or some N below 1024); nothing changes
+ * then.  Waits for the device to be idle. */
+int32_t rs_release_source_weights(rs_ctx *ctx, int32_t layer);
 const char *rs_last_error(void);
 
 /* ---- KV cache manager (section 4.5.1; request flow, section 4.4) ------------------------

@@ -32,7 +32,7 @@ EXPORTS = [
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
-    "rs_debug_push_sampled", "rs_request_times", "rs_engine_start", "rs_engine_stop", "rs_engine_stats",
+    "rs_debug_push_sampled", "rs_request_times", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights",
 ]
 
 
@@ -161,6 +161,7 @@ class Context:
         self._prof = profile
         pd = profile.desc() if profile is not None else None
         self._keep = [k_pool, v_pool]
+        self._keep_layers = []
         self.n_layers = n_layers
         self.max_context = max_context
         _check(self._lib.rs_init(ctypes.byref(m), ctypes.byref(p), ctypes.byref(lim),
@@ -185,9 +186,18 @@ class Context:
 
     # -- weights
     def set_weights(self, layer: int, g1, wqkv, wo, g2, wg, wu, wd):
-        self._keep.append((g1, wqkv, wo, g2, wg, wu, wd))
+        while len(self._keep_layers) <= layer:
+            self._keep_layers.append(None)
+        self._keep_layers[layer] = (g1, wqkv, wo, g2, wg, wu, wd)   # the library borrows them
         w = LayerWeights(*[_ptr(t) for t in (g1, wqkv, wo, g2, wg, wu, wd)])
         _check(self._lib.rs_set_weights(self._h, ctypes.c_int32(layer), ctypes.byref(w)))
+
+    def release_source_weights(self, layer: int):
+        """The five matrices given to set_weights(layer) may be freed afterwards (packed copies remain)."""
+        _check(self._lib.rs_release_source_weights(self._h, ctypes.c_int32(layer)))
+        if layer < len(self._keep_layers):
+            g1, _, _, g2, _, _, _ = self._keep_layers[layer]
+            self._keep_layers[layer] = (g1, None, None, g2, None, None, None)
 
     # -- allocator
     def kv_alloc(self, req_id: int, n_tokens_total: int, cap: int = 1 << 16) -> np.ndarray:

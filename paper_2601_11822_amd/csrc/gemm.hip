@@ -503,15 +503,15 @@ static void launch_tiled(hipStream_t st, const GemmArgs &a) {
 // Tile shapes of the direct kernel and their cost per tile relative to a 256x256 tile (area over
 // measured relative efficiency).  The schedule with the fewest weighted rounds on the partition's
 // compute units wins; the arithmetic of an output element is the same in all of them.
-void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
-    if (a.M <= 0 || a.N <= 0) return;
+bool launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
+    if (a.M <= 0 || a.N <= 0) return true;
     const bool aligned = (a.K % 32 == 0) && a.K >= 32;
     if (aligned && a.Wp && a.M > 64 && a.N >= 1024) {
         if (a.epi != EPI_SWIGLU && a.partials && a.N % 4 == 0) {
             const int S = direct_splits(a.M, a.N, a.K);
             if (S > 1 && direct_partial_elems(a.M, a.N, a.K) <= a.partial_cap) {
                 launch_direct_splitk(st, a, S);
-                return;
+                return true;
             }
         }
         const int cus = a.cus > 0 ? a.cus : 256;
@@ -541,11 +541,13 @@ void launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
         } else {
             launch_direct<128, 256, 5, 4>(st, a);   // 5 x 24 KB of LDS
         }
-    } else if (a.M >= 1024 && a.N >= 1024) {
-        launch_tiled<256, 256>(st, a);
     } else {
-        launch_tiled<128, 128>(st, a);
+        // the generic kernel reads the caller's row-major matrices: refuse when they have been released
+        if (!a.W || (a.epi == EPI_SWIGLU && !a.W2)) return false;
+        if (a.M >= 1024 && a.N >= 1024) launch_tiled<256, 256>(st, a);
+        else launch_tiled<128, 128>(st, a);
     }
+    return true;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -75,7 +75,8 @@ struct GemmArgs {
 };
 // Upper bound of what the K-sliced path of launch_gemm_tiled needs, for any M: S * M * N <= this.
 #define RS_DIRECT_PARTIAL_ELEMS ((size_t)10 << 20)
-void launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
+// false (nothing launched): the shape needs the generic kernel, which reads a.W / a.W2, and they are null
+bool launch_gemm_tiled(hipStream_t st, const GemmArgs &a);
 
 // Skinny variant for M <= 64 (decode): weight-streaming, deterministic split-K through
 // `partials` (fp32, at least skinny_partial_elems(...) elements).  Reads A, Wp and Wp2.

@@ -416,8 +416,9 @@ void tick(rs_ctx *c, int side, int i) {
 }
 
 // The dense part after attention, shared by both passes.
-void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
+bool run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
                         const rs_ctx::PackedLayer &pl, const bf16_t *x, bf16_t *y, int M, bool skinny) {
+    bool released_needed = false;   // a GEMM needed row-major weights the caller has released
     const rs_model_desc &m = c->m;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
     auto gemm = [&](GemmArgs g) {
@@ -425,7 +426,7 @@ void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
         g.partials = w.partials;
         g.partial_cap = w.partial_cap;
         if (skinny) launch_gemm_skinny(st, g, w.partials);
-        else launch_gemm_tiled(st, g);
+        else if (!launch_gemm_tiled(st, g)) released_needed = true;
     };
     // h, attn and act are fragment-packed by their producers; x1 and y are row-major
     const bf16_t *wo = (const bf16_t *)lw.wo, *wg = (const bf16_t *)lw.wg, *wu = (const bf16_t *)lw.wu, *wd = (const bf16_t *)lw.wd;
@@ -437,6 +438,7 @@ void run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
     tick(c, side, 7);
     gemm(GemmArgs{w.act, wd, nullptr, pl.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
     tick(c, side, 8);
+    return !released_needed;
 }
 
 int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu,
@@ -472,8 +474,9 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     const bool skinny = T <= 64;
     GemmArgs gq{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv,
                 T, nqkv, d, EPI_STORE, 0, c->side[RS_SIDE_PREFILL].cus, w.partials, w.partial_cap};
+    bool ok = true;
     if (skinny) launch_gemm_skinny(st, gq, w.partials);
-    else launch_gemm_tiled(st, gq);
+    else ok = launch_gemm_tiled(st, gq);
     tick(c, RS_SIDE_PREFILL, 2);
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
@@ -483,8 +486,9 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
-    run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny);
+    ok = run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny) && ok;
     HIP_TRY(hipGetLastError());
+    if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this pass needs the row-major matrices that were released", layer);
     return RS_OK;
 }
 
@@ -511,8 +515,9 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     tick(c, RS_SIDE_DECODE, 1);
     GemmArgs g{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv, B, nqkv, d, EPI_STORE,
                0, c->side[RS_SIDE_DECODE].cus, w.partials, w.partial_cap};
+    bool ok = true;
     if (skinny) launch_gemm_skinny(st, g, w.partials);
-    else launch_gemm_tiled(st, g);
+    else ok = launch_gemm_tiled(st, g);
     tick(c, RS_SIDE_DECODE, 2);
     SeqInfo none{};
     RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, ctx_lens, c->err_flag, B, m.n_q_heads, m.n_kv_heads, hd,
@@ -525,8 +530,9 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
                       (float)(1.4426950408889634 / std::sqrt((double)hd))};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
-    run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny);
+    ok = run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny) && ok;
     HIP_TRY(hipGetLastError());
+    if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this step needs the row-major matrices that were released", layer);
     return RS_OK;
 }
 
@@ -767,6 +773,26 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     }
     c->weights[layer] = *w;
     c->have_weights[layer] = true;
+    return RS_OK;
+}
+
+int32_t rs_release_source_weights(rs_ctx *c, int32_t layer) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
+    if (!c->have_weights[layer]) return fail(RS_ERR_STATE, "weights of layer %d not set", layer);
+    const rs_model_desc &m = c->m;
+    const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+    // every pass of more than 64 rows must qualify for the large-tile kernel (K a multiple of 32, N >= 1024);
+    // passes of up to 64 rows always take the weight-streaming kernel: both read the packed copies only
+    const bool packed_only = d % 32 == 0 && qd % 32 == 0 && f % 32 == 0 && nqkv >= 1024 && d >= 1024 && f >= 1024;
+    if (!packed_only)
+        return fail(RS_ERR_STATE, "this shape still reads the caller's matrices (generic GEMM kernel for K %% 32 != 0 or N < 1024)");
+    if (c->gpu) {
+        HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    rs_layer_weights &w = c->weights[layer];
+    w.wqkv = w.wo = w.wg = w.wu = w.wd = nullptr;
     return RS_OK;
 }
 

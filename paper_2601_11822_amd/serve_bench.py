@@ -53,7 +53,7 @@ def make_workload(n: int, rate: float, prompt_mean: float, prompt_sd: float, out
 
 
 def build_model(shape, n_layers: int, vocab: int, n_blocks: int, max_prefill: int, max_batch: int, max_context: int,
-                profile, device: int = 0):
+                profile, device: int = 0, release: bool = False):
     import torch
     dev = torch.device(f"cuda:{device}")
     g = torch.Generator(device=dev)
@@ -69,6 +69,9 @@ def build_model(shape, n_layers: int, vocab: int, n_blocks: int, max_prefill: in
     for l in range(n_layers):
         w = (rnd(d, mean=1.0), rnd(shape.qkv_dim, d), rnd(d, shape.q_dim), rnd(d, mean=1.0), rnd(f, d), rnd(f, d), rnd(d, f))
         c.set_weights(l, *w)
+        if release:   # the library keeps packed copies only: a 70B-shaped stack then fits one GPU beside its KV pool
+            c.release_source_weights(l)
+            w = (w[0], w[3])
         keep.append(w)
     head = (rnd(vocab, d, std=1.0), rnd(d, mean=1.0), rnd(vocab, d))
     c.set_head(*head, vocab, -1)
@@ -220,6 +223,7 @@ def main(argv=None):
     ap.add_argument("--profile", default=None, help="JSON written by the profiler, or 'measure'")
     ap.add_argument("--slo-ms", type=float, default=50.0)
     ap.add_argument("--wait-decode", action="store_true", help="wait for each decode step (exact per-step GPU times)")
+    ap.add_argument("--release-weights", action="store_true", help="free each layer's row-major matrices after packing")
     ap.add_argument("--engine", action="store_true", help="let the library's two threads drive (rs_engine_start)")
     ap.add_argument("--time-limit", type=float, default=120.0)
     ap.add_argument("--seed", type=int, default=4)
@@ -244,7 +248,8 @@ def main(argv=None):
     work = make_workload(a.requests, a.rate, a.prompt_mean, a.prompt_sd, a.out_mean, a.out_sd, (32, a.max_prompt),
                          (16, a.max_out), a.vocab, a.seed)
     t0 = time.time()
-    c, keep = build_model(shape, a.layers, a.vocab, a.kv_tokens // 16, a.max_prompt, a.max_batch, a.max_prompt + a.max_out, prof)
+    c, keep = build_model(shape, a.layers, a.vocab, a.kv_tokens // 16, a.max_prompt, a.max_batch, a.max_prompt + a.max_out, prof,
+                          release=a.release_weights)
     _log(f"[serve] model of {a.layers} layers built in {time.time() - t0:.1f}s; {a.requests} requests over "
          f"{work[-1][1]:.1f}s, {sum(len(w[2]) for w in work)} prompt tokens, {sum(w[3] for w in work)} to generate")
     # one throw-away request settles lazy runtime work (first launches, masked streams)

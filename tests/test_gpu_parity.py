@@ -527,3 +527,34 @@ def test_long_context_decode_and_16k_prefill_mid_shape():
         assert rel_err(f32(vg[mine]).reshape(-1, shape.head_dim), Vp[mine].reshape(-1, shape.head_dim)) <= TOL
     finally:
         rig.close()
+
+
+def test_released_source_weights_are_not_read_again():
+    """Wide shape (every GEMM qualifies for the packed-operand kernels): after rs_release_source_weights the
+    caller's matrices are overwritten with NaN patterns; prefill (short and long pass) and decode still match."""
+    shape = S.WIDE
+    lens = [150, 40]
+    cu, T, n_blocks, tabs, xb = _prefill_case(shape, lens, stream=11)
+    rig = Rig(shape, n_blocks + 4, 256, 4, 256)
+    try:
+        rig.ctx.release_source_weights(0)
+        for k in ("wqkv", "wo", "wg", "wu", "wd"):
+            rig.wdev[0][k].view(torch.int16).fill_(0x7FC1)
+        torch.cuda.synchronize()
+        L = rig.olayers[0]
+        Kc, Vc = L.new_cache(n_blocks + 4, fill=ORC_SENT)
+        y = rig.prefill(xb, cu, tabs)
+        y_ref = L.prefill(f32(xb), cu, tabs, Kc, Vc)
+        check_tensor("prefill y after release (190 rows)", f32(y), y_ref, f32(xb), 2)
+        xs = S.hidden_states(40, shape.d_model, stream=12)
+        one = tabs[1:2]
+        ys = rig.prefill(xs, [0, 40], one)
+        ys_ref = L.prefill(f32(xs), [0, 40], one, Kc, Vc)
+        check_tensor("prefill y after release (40 rows)", f32(ys), ys_ref, f32(xs), 2)
+        db = S.hidden_states(2, shape.d_model, stream=13)
+        ctx = np.array([150, 40], np.int32)
+        yd = rig.decode(db, ctx, tabs)     # positions 150 and 40 fall inside the prompts' last blocks
+        yd_ref = L.decode(f32(db), ctx, tabs, Kc, Vc)
+        check_tensor("decode y after release", f32(yd), yd_ref, f32(db), 2)
+    finally:
+        rig.close()

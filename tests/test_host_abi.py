@@ -207,3 +207,19 @@ def test_operand_layouts_shared_by_host_and_kernels(tmp_path):
                    stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
+
+
+def test_release_source_weights_only_where_the_packed_copies_suffice():
+    c = host_ctx(shape=S.LLAMA8B)
+    with pytest.raises(rs.RapidServeError) as e:
+        c.release_source_weights(0)                      # weights not set yet
+    assert e.value.code == rs.RS_ERR_STATE
+    c.set_weights(0, 1, 1, 1, 1, 1, 1, 1)
+    c.release_source_weights(0)
+    with pytest.raises(rs.RapidServeError):
+        c.release_source_weights(3)                      # layer out of range
+    t = host_ctx(shape=S.TINY)                           # N < 1024: the generic kernel still reads them
+    t.set_weights(0, 1, 1, 1, 1, 1, 1, 1)
+    with pytest.raises(rs.RapidServeError) as e:
+        t.release_source_weights(0)
+    assert e.value.code == rs.RS_ERR_STATE
