@@ -146,6 +146,20 @@ def layer_weights(shape: LayerShape, layer: int = 0, seed: int = SEED_WEIGHTS,
     }
 
 
+def moe_weights(shape: LayerShape, n_experts: int, layer: int = 0, seed: int = SEED_WEIGHTS, std: float = 0.02,
+                router_std: float = 0.1) -> Dict[str, np.ndarray]:
+    """bf16 bit patterns of a sparse feed-forward block: router [E, d] ~ N(0, router_std) (wide enough that
+    most tokens have a clear top two), per-expert wg / wu [E, F, d] and wd [E, d, F] ~ N(0, std)."""
+    d, f = shape.d_model, shape.ffn_dim
+    base = 8192 + layer * 16
+    return {
+        "router": normal_bf16((n_experts, d), seed, base + 0, 0.0, router_std),
+        "wg": normal_bf16((n_experts, f, d), seed, base + 1, 0.0, std),
+        "wu": normal_bf16((n_experts, f, d), seed, base + 2, 0.0, std),
+        "wd": normal_bf16((n_experts, d, f), seed, base + 3, 0.0, std),
+    }
+
+
 def head_weights(d_model: int, vocab: int, seed: int = SEED_WEIGHTS, stream: int = 4096) -> Dict[str, np.ndarray]:
     """bf16 bit patterns of the token embedding [vocab, d_model] ~ N(0, 1) (the scale of the hidden
     states the layer workloads use), the final RMSNorm gain 1 + N(0, 0.02) and the LM head
