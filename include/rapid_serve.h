@@ -125,6 +125,28 @@ int32_t rs_destroy(rs_ctx *ctx);
  * stay valid and unchanged while the context uses the layer; after changing one, call
  * rs_set_weights again.  Errors: RS_ERR_BAD_ARG (null pointer, layer out of range), RS_ERR_HIP. */
 int32_t rs_set_weights(rs_ctx *ctx, int32_t layer, const rs_layer_weights *w);
+/* Sparse (mixture-of-experts) feed-forward block for `layer`, as in the mixture-of-experts model the
+ * paper evaluates next to the dense one (section 5): router logits h W_r^T over n_experts experts,
+ * the two largest per row (lower index first on ties), weights = softmax over those two logits,
+ * output = x1 + w0 FFN_e0(h) + w1 FFN_e1(h) with each expert a SwiGLU block of the model's ffn_dim.
+ * router: device bf16 [n_experts][d_model]; wg, wu: [n_experts][ffn_dim][d_model]; wd:
+ * [n_experts][d_model][ffn_dim].  The router stays borrowed; the experts' matrices are packed during
+ * the call and may be freed when it returns.  A layer with a sparse block may pass null wg / wu / wd to rs_set_weights; once set,
+ * the sparse block replaces the dense one in rs_prefill_layer / rs_decode_layer and everything built
+ * on them.  Needs d_model and ffn_dim multiples of 32 and >= 1024, 2 <= n_experts <= 16, top_k = 2
+ * (RS_ERR_BAD_ARG otherwise).  Both projections run as grouped GEMMs over 128-row tiles, one expert
+ * per tile.  rs_debug_read_moe_routing waits for the side and returns the experts and weights the
+ * last layer call on it chose for its first n_rows rows ([n_rows][2] each, host arrays). */
+typedef struct {
+    const void *router;
+    const void *wg;
+    const void *wu;
+    const void *wd;
+    int32_t n_experts;
+    int32_t top_k;
+} rs_moe_weights;
+int32_t rs_set_moe_weights(rs_ctx *ctx, int32_t layer, const rs_moe_weights *w);
+int32_t rs_debug_read_moe_routing(rs_ctx *ctx, int32_t side, int32_t n_rows, int32_t *experts_out, float *weights_out);
 /* Declares that the five matrices given to rs_set_weights for `layer` will not be read again: the
  * library keeps only its packed copies and the caller may free or reuse that memory (the two gain
  * vectors stay borrowed).  This halves the weight footprint of a large model: a 70B-shaped stack is

@@ -32,7 +32,7 @@ EXPORTS = [
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
-    "rs_debug_push_sampled", "rs_request_times", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights",
+    "rs_debug_push_sampled", "rs_request_times", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
 ]
 
 
@@ -82,6 +82,11 @@ class StepOut(ctypes.Structure):
                 ("prefill_started_req", ctypes.c_int64), ("n_promoted", ctypes.c_int32),
                 ("n_finished", ctypes.c_int32), ("n_waiting", ctypes.c_int32), ("decode_ms", ctypes.c_float),
                 ("n_preempted", ctypes.c_int32), ("prefill_started_count", ctypes.c_int32)]
+
+
+class MoeWeights(ctypes.Structure):
+    _fields_ = [("router", ctypes.c_void_p), ("wg", ctypes.c_void_p), ("wu", ctypes.c_void_p), ("wd", ctypes.c_void_p),
+                ("n_experts", ctypes.c_int32), ("top_k", ctypes.c_int32)]
 
 
 class HeadWeights(ctypes.Structure):
@@ -191,6 +196,18 @@ class Context:
         self._keep_layers[layer] = (g1, wqkv, wo, g2, wg, wu, wd)   # the library borrows them
         w = LayerWeights(*[_ptr(t) for t in (g1, wqkv, wo, g2, wg, wu, wd)])
         _check(self._lib.rs_set_weights(self._h, ctypes.c_int32(layer), ctypes.byref(w)))
+
+    def set_moe_weights(self, layer: int, router, wg, wu, wd, n_experts: int, top_k: int = 2):
+        self._keep.append(router)   # the experts' matrices are packed during the call and not referenced afterwards
+        w = MoeWeights(_ptr(router), _ptr(wg), _ptr(wu), _ptr(wd), n_experts, top_k)
+        _check(self._lib.rs_set_moe_weights(self._h, ctypes.c_int32(layer), ctypes.byref(w)))
+
+    def debug_read_moe_routing(self, side: int, n_rows: int):
+        sel = np.empty((n_rows, 2), dtype=np.int32)
+        wt = np.empty((n_rows, 2), dtype=np.float32)
+        _check(self._lib.rs_debug_read_moe_routing(self._h, ctypes.c_int32(side), ctypes.c_int32(n_rows),
+                                                   sel.ctypes.data_as(_i32p), wt.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
+        return sel, wt
 
     def release_source_weights(self, layer: int):
         """The five matrices given to set_weights(layer) may be freed afterwards (packed copies remain)."""

@@ -205,6 +205,13 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     const int M = a.M, N = a.N, K = a.K;
     const int Mt = packed_mt(M), Nt = ((N + 63) / 64) * 2;   // row tiles per k block of A and of the weights
 
+    const bf16_t *wp = a.Wp, *wp2 = a.Wp2;
+    if (a.tile_expert) {   // grouped: this 128-row tile multiplies one expert's matrices, or is not in use
+        const int e = a.tile_expert[bm >> 7];
+        if (e < 0) return;
+        wp += (size_t)e * a.expert_stride;
+        if (EPI == EPI_SWIGLU) wp2 += (size_t)e * a.expert_stride;
+    }
     const bf16_t *pa[LA];
     const bf16_t *pb[LB];
 #pragma unroll
@@ -216,9 +223,9 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     for (int j = 0; j < LB; ++j) {
         const int q = wave * LB + j, s = q / TB, t = q % TB;
         if (EPI == EPI_SWIGLU)   // blocks alternate: 32 gate rows, the 32 matching up rows
-            pb[j] = ((t & 1) ? a.Wp2 : a.Wp) + ((size_t)s * Nt + min(nb * (TB / 2) + (t >> 1), Nt - 1)) * 512 + lane * 8;
+            pb[j] = ((t & 1) ? wp2 : wp) + ((size_t)s * Nt + min(nb * (TB / 2) + (t >> 1), Nt - 1)) * 512 + lane * 8;
         else
-            pb[j] = a.Wp + ((size_t)s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8;
+            pb[j] = wp + ((size_t)s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8;
     }
     const size_t ksa = (size_t)Mt * 1024, ksb = (size_t)Nt * 1024;   // elements per K tile (2 k blocks)
     const int nk = PARTIAL ? nk_part : K / BK;
@@ -479,6 +486,14 @@ static void launch_direct(hipStream_t st, const GemmArgs &a) {
         case EPI_RESIDUAL: launch_direct_epi<BM, BN, EPI_RESIDUAL, NS, NW>(st, a); break;
         default: launch_direct_epi<BM, BN, EPI_SWIGLU, NS, NW>(st, a); break;
     }
+}
+
+bool launch_gemm_grouped(hipStream_t st, const GemmArgs &a) {
+    if (!(a.K % 32 == 0 && a.K >= 32 && a.Wp && a.N >= 1024 && a.M % 128 == 0 && a.tile_expert)) return false;
+    if (a.epi == EPI_SWIGLU) launch_direct_epi<128, 256, EPI_SWIGLU, 5, 4>(st, a);
+    else if (a.epi == EPI_STORE) launch_direct_epi<128, 256, EPI_STORE, 5, 4>(st, a);
+    else return false;
+    return true;
 }
 
 template <int BM, int BN>

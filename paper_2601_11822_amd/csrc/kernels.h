@@ -72,6 +72,10 @@ struct GemmArgs {
     // float32 scratch for launch_gemm_tiled's K-sliced path (few tiles, long K); without it that path is not taken
     float *partials = nullptr;
     size_t partial_cap = 0;   // elements
+    // grouped form (launch_gemm_grouped): the expert whose weights each 128-row tile multiplies (-1: skip the
+    // tile), and the distance in elements between consecutive experts' packed matrices (Wp and Wp2 alike)
+    const int32_t *tile_expert = nullptr;
+    size_t expert_stride = 0;
 };
 // Upper bound of what the K-sliced path of launch_gemm_tiled needs, for any M: S * M * N <= this.
 #define RS_DIRECT_PARTIAL_ELEMS ((size_t)10 << 20)
@@ -88,6 +92,28 @@ void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *parti
 bool launch_gemm_direct_partials(hipStream_t st, const GemmArgs &a, float *part);
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
+
+// Grouped GEMM over 128-row tiles that each belong to one expert: STORE or SWIGLU epilogue, a.M = the padded
+// row capacity (a multiple of 128), a.tile_expert and a.expert_stride set.  Needs K % 32 == 0 and N >= 1024.
+bool launch_gemm_grouped(hipStream_t st, const GemmArgs &a);
+
+#define RS_MOE_MAX_EXPERTS 16
+struct MoeArgs {
+    const bf16_t *h;        // normalised rows, fragment-packed with packed_mt(M) row tiles
+    const bf16_t *router;   // [E][d] row-major
+    int32_t *sel;           // [M][2] experts of each row
+    float *wt;              // [M][2] their weights
+    int32_t *pos;           // [M][2] grouped row of each assignment
+    int32_t *src;           // [Mg_cap] source row of each grouped row, -1 for padding
+    int32_t *tile_expert;   // [Mg_cap / 128]
+    bf16_t *a_g;            // gathered rows, fragment-packed with Mg_cap / 32 row tiles
+    const bf16_t *out_g;    // [Mg_cap][d] expert outputs, row-major
+    const bf16_t *x1;       // [M][d]
+    bf16_t *y;              // [M][d]
+    int M, d, E, Mg_cap;
+};
+void launch_moe_route_and_gather(hipStream_t st, const MoeArgs &a);
+void launch_moe_combine(hipStream_t st, const MoeArgs &a);
 
 struct EmbedArgs {
     const int32_t *tokens;     // [n], or per-slot tokens when row_slot is given, or slot regions when slots is given

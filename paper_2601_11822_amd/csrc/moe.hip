@@ -1,0 +1,124 @@
+// Sparse (mixture-of-experts) feed-forward block around the grouped form of the large-tile GEMM:
+// route each row to its two experts, lay the (row, expert) assignments out expert by expert in
+// whole 128-row tiles, gather the normalised rows into that order, run gate/up and down once over
+// all tiles (each tile reads its own expert's weights), and add the two weighted results back.
+#include "kernels.h"
+
+// ---------------------------------------------------------------------------------------------
+// Router: logits of row m = h[m] . Wr[e] for the E experts (h fragment-packed, Wr row-major), then
+// the two largest (lower index first on ties) and the softmax over those two.  One workgroup per row.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
+    __shared__ float red[4][RS_MOE_MAX_EXPERTS];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const int Mt = packed_mt(a.M);
+    float acc[RS_MOE_MAX_EXPERTS];
+#pragma unroll
+    for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) acc[e] = 0.f;
+    for (int c = tid; c < (a.d >> 3); c += 256) {
+        const bf16x8 hv = ld_bf16x8(a.h + packed_offset(m, c * 8, Mt));
+#pragma unroll
+        for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) {
+            if (e >= a.E) break;
+            const bf16x8 wv = ld_bf16x8(a.router + (size_t)e * a.d + c * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[e] += (float)hv[i] * (float)wv[i];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) {
+        const float s = wave_sum(acc[e]);
+        if ((tid & 63) == 0) red[tid >> 6][e] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float lg[RS_MOE_MAX_EXPERTS];
+        for (int e = 0; e < a.E; ++e) lg[e] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+        int e0 = 0;
+        for (int e = 1; e < a.E; ++e)
+            if (lg[e] > lg[e0]) e0 = e;
+        int e1 = -1;
+        for (int e = 0; e < a.E; ++e)
+            if (e != e0 && (e1 < 0 || lg[e] > lg[e1])) e1 = e;
+        const float eb = expf(lg[e1] - lg[e0]);
+        a.sel[2 * m] = e0;
+        a.sel[2 * m + 1] = e1;
+        a.wt[2 * m] = 1.0f / (1.0f + eb);
+        a.wt[2 * m + 1] = eb / (1.0f + eb);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plan (one workgroup): per-expert counts, each expert's segment padded to whole 128-row tiles,
+// the expert of every tile (-1 past the last used tile), the source row of every grouped row
+// (-1 for padding) and the grouped position of every assignment.  The order of rows inside a
+// segment is arbitrary (an atomic cursor): a row's result does not depend on where it sits.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void moe_plan_kernel(MoeArgs a) {
+    __shared__ int cnt[RS_MOE_MAX_EXPERTS], off[RS_MOE_MAX_EXPERTS], cur[RS_MOE_MAX_EXPERTS];
+    const int tid = threadIdx.x;
+    if (tid < RS_MOE_MAX_EXPERTS) cnt[tid] = cur[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < 2 * a.M; i += 1024) atomicAdd(&cnt[a.sel[i]], 1);
+    for (int i = tid; i < a.Mg_cap; i += 1024) a.src[i] = -1;
+    __syncthreads();
+    if (tid == 0) {
+        int t = 0;
+        for (int e = 0; e < a.E; ++e) {
+            off[e] = t * 128;
+            const int nt = (cnt[e] + 127) >> 7;
+            for (int j = 0; j < nt; ++j) a.tile_expert[t + j] = e;
+            t += nt;
+        }
+        for (int j = t; j < a.Mg_cap / 128; ++j) a.tile_expert[j] = -1;
+    }
+    __syncthreads();
+    for (int i = tid; i < 2 * a.M; i += 1024) {
+        const int e = a.sel[i];
+        const int p = off[e] + atomicAdd(&cur[e], 1);
+        a.pos[i] = p;
+        a.src[p] = i >> 1;
+    }
+}
+
+// Gathered, fragment-packed GEMM input: grouped row g takes the chunks of its source row (zeros for padding).
+__global__ __launch_bounds__(256) void moe_gather_kernel(MoeArgs a) {
+    const int chunks = a.d >> 3;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)a.Mg_cap * chunks) return;
+    // consecutive threads take consecutive rows of one k chunk: whole 128-byte lines on the writing side
+    const int g = (int)(idx % a.Mg_cap), c = (int)(idx / a.Mg_cap);
+    if (a.tile_expert[g >> 7] < 0) return;   // tile not in use: the GEMMs skip it too
+    const int s = a.src[g];
+    const bf16x8 v = s >= 0 ? ld_bf16x8(a.h + packed_offset(s, c * 8, packed_mt(a.M))) : zero_bf16x8();
+    st_bf16x8(a.a_g + packed_offset(g, c * 8, a.Mg_cap >> 5), v);
+}
+
+// y[m] = x1[m] + w0 * out[pos0] + w1 * out[pos1], float32 arithmetic.  One workgroup per row.
+__global__ __launch_bounds__(256) void moe_combine_kernel(MoeArgs a) {
+    const int m = blockIdx.x;
+    const float w0 = a.wt[2 * m], w1 = a.wt[2 * m + 1];
+    const bf16_t *o0 = a.out_g + (size_t)a.pos[2 * m] * a.d, *o1 = a.out_g + (size_t)a.pos[2 * m + 1] * a.d;
+    const bf16_t *xr = a.x1 + (size_t)m * a.d;
+    bf16_t *yr = a.y + (size_t)m * a.d;
+    for (int c = threadIdx.x; c < (a.d >> 3); c += 256) {
+        const bf16x8 x = ld_bf16x8(xr + c * 8), p = ld_bf16x8(o0 + c * 8), q = ld_bf16x8(o1 + c * 8);
+        bf16x8 r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = (bf16_t)((float)x[i] + (w0 * (float)p[i] + w1 * (float)q[i]));
+        st_bf16x8(yr + c * 8, r);
+    }
+}
+
+void launch_moe_route_and_gather(hipStream_t st, const MoeArgs &a) {
+    if (a.M <= 0) return;
+    hipLaunchKernelGGL(moe_router_kernel, dim3(a.M), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(moe_plan_kernel, dim3(1), dim3(1024), 0, st, a);
+    const long n = (long)a.Mg_cap * (a.d >> 3);
+    hipLaunchKernelGGL(moe_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+}
+
+void launch_moe_combine(hipStream_t st, const MoeArgs &a) {
+    if (a.M <= 0) return;
+    hipLaunchKernelGGL(moe_combine_kernel, dim3(a.M), dim3(256), 0, st, a);
+}

@@ -46,6 +46,11 @@ struct Workspace {
     float *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
     size_t partial_cap = 0;
     int rows = 0;
+    // sparse feed-forward block (allocated by the first rs_set_moe_weights)
+    int32_t *m_sel = nullptr, *m_pos = nullptr, *m_src = nullptr, *m_tile = nullptr;
+    float *m_wt = nullptr;
+    bf16_t *m_a = nullptr, *m_act = nullptr, *m_out = nullptr;
+    int m_cap = 0;   // grouped row capacity (a multiple of 128)
 };
 
 constexpr int RS_HEAD_GROUP = 256;
@@ -149,6 +154,10 @@ struct rs_ctx {
     // fragment-packed private copies of the five matrices, read by the direct and the skinny GEMMs
     struct PackedLayer { bf16_t *wqkv = nullptr, *wo = nullptr, *wg = nullptr, *wu = nullptr, *wd = nullptr; };
     std::vector<PackedLayer> packed;
+    // sparse feed-forward block of a layer: the experts' matrices packed back to back (stride elements apart)
+    struct MoeLayer { int E = 0; const bf16_t *router = nullptr; bf16_t *wg = nullptr, *wu = nullptr, *wd = nullptr;
+                      size_t stride_gu = 0, stride_d = 0; };
+    std::vector<MoeLayer> moe;
     CosSin *rope = nullptr;
     int32_t *err_flag = nullptr;
     Workspace ws[2];
@@ -305,7 +314,8 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
 }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml};
+    void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml,
+                    w.m_sel, w.m_pos, w.m_src, w.m_tile, w.m_wt, w.m_a, w.m_act, w.m_out};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     w = Workspace{};
@@ -417,7 +427,7 @@ void tick(rs_ctx *c, int side, int i) {
 
 // The dense part after attention, shared by both passes.
 bool run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const rs_layer_weights &lw,
-                        const rs_ctx::PackedLayer &pl, const bf16_t *x, bf16_t *y, int M, bool skinny) {
+                        const rs_ctx::PackedLayer &pl, const rs_ctx::MoeLayer &ml, const bf16_t *x, bf16_t *y, int M, bool skinny) {
     bool released_needed = false;   // a GEMM needed row-major weights the caller has released
     const rs_model_desc &m = c->m;
     const int d = m.d_model, qd = m.n_q_heads * m.head_dim, f = m.ffn_dim;
@@ -434,6 +444,24 @@ bool run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
     tick(c, side, 5);
     launch_rmsnorm(st, w.x1, (const bf16_t *)lw.g2, w.h, M, d, m.rms_eps);
     tick(c, side, 6);
+    if (ml.E > 0) {
+        // sparse block: route, gather expert by expert, two grouped GEMMs over all tiles, weighted sum
+        const int cap = std::min(w.m_cap, ((2 * M + 127 * ml.E + 127) / 128) * 128);
+        MoeArgs ma{w.h, ml.router, w.m_sel, w.m_wt, w.m_pos, w.m_src, w.m_tile, w.m_a, w.m_out, w.x1, y, M, d, ml.E, cap};
+        launch_moe_route_and_gather(st, ma);
+        GemmArgs gu{w.m_a, nullptr, nullptr, ml.wg, ml.wu, nullptr, w.m_act, cap, f, d, EPI_SWIGLU, 1, c->side[side].cus};
+        gu.tile_expert = w.m_tile;
+        gu.expert_stride = ml.stride_gu;
+        bool ok = launch_gemm_grouped(st, gu);
+        tick(c, side, 7);
+        GemmArgs gd{w.m_act, nullptr, nullptr, ml.wd, nullptr, nullptr, w.m_out, cap, d, f, EPI_STORE, 0, c->side[side].cus};
+        gd.tile_expert = w.m_tile;
+        gd.expert_stride = ml.stride_d;
+        ok = launch_gemm_grouped(st, gd) && ok;
+        launch_moe_combine(st, ma);
+        tick(c, side, 8);
+        return ok && !released_needed;
+    }
     gemm(GemmArgs{w.h, wg, wu, pl.wg, pl.wu, nullptr, w.act, M, f, d, EPI_SWIGLU, 1});
     tick(c, side, 7);
     gemm(GemmArgs{w.act, wd, nullptr, pl.wd, nullptr, w.x1, y, M, d, f, EPI_RESIDUAL});
@@ -460,6 +488,8 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     if (longest > m.max_pos) return fail(RS_ERR_BAD_ARG, "prompt of %d tokens exceeds max_pos %d", longest, m.max_pos);
     if ((longest + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk)
         return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for %d tokens", max_blk, longest);
+    if (!c->packed[layer].wg && c->moe[layer].E == 0)
+        return fail(RS_ERR_STATE, "layer %d has no feed-forward weights (dense ones in rs_set_weights, or rs_set_moe_weights)", layer);
     const rs_layer_weights &lw = c->weights[layer];
     hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
     const int d = m.d_model, hd = m.head_dim, qd = m.n_q_heads * hd, nqkv = qd + 2 * m.n_kv_heads * hd;
@@ -486,7 +516,7 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
-    ok = run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny) && ok;
+    ok = run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], c->moe[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny) && ok;
     HIP_TRY(hipGetLastError());
     if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this pass needs the row-major matrices that were released", layer);
     return RS_OK;
@@ -502,6 +532,8 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
         return fail(RS_ERR_BAD_ARG, "max_ctx %d outside [1, min(%d,%d)]", max_ctx, c->lim.max_context, m.max_pos);
     if ((max_ctx + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk)
         return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for context %d", max_blk, max_ctx);
+    if (!c->packed[layer].wg && c->moe[layer].E == 0)
+        return fail(RS_ERR_STATE, "layer %d has no feed-forward weights (dense ones in rs_set_weights, or rs_set_moe_weights)", layer);
     const rs_layer_weights &lw = c->weights[layer];
     hipStream_t st = c->side[RS_SIDE_DECODE].stream;
     const int d = m.d_model, hd = m.head_dim, qd = m.n_q_heads * hd, nqkv = qd + 2 * m.n_kv_heads * hd;
@@ -530,7 +562,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
                       (float)(1.4426950408889634 / std::sqrt((double)hd))};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
-    ok = run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny) && ok;
+    ok = run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], c->moe[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny) && ok;
     HIP_TRY(hipGetLastError());
     if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this step needs the row-major matrices that were released", layer);
     return RS_OK;
@@ -629,6 +661,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     c->gpu = device != RS_HOST_ONLY;
     c->weights.resize(m.n_layers);
     c->packed.resize(m.n_layers);
+    c->moe.resize(m.n_layers);
     c->have_weights.assign(m.n_layers, false);
     c->free_list.resize(pool->n_blocks);
     for (int i = 0; i < pool->n_blocks; ++i) c->free_list[i] = pool->n_blocks - 1 - i;  // pop -> 0,1,2,..
@@ -719,6 +752,9 @@ int32_t rs_destroy(rs_ctx *c) {
         for (auto &pl : c->packed)
             for (bf16_t *q : {pl.wqkv, pl.wo, pl.wg, pl.wu, pl.wd})
                 if (q) (void)hipFree(q);
+        for (auto &ml : c->moe)
+            for (bf16_t *q : {ml.wg, ml.wu, ml.wd})
+                if (q) (void)hipFree(q);
         if (c->rope) (void)hipFree(c->rope);
         if (c->err_flag) (void)hipFree(c->err_flag);
         if (c->d_ctx) (void)hipFree(c->d_ctx);
@@ -754,7 +790,9 @@ int32_t rs_destroy(rs_ctx *c) {
 int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
     if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
-    if (!w->g1 || !w->wqkv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
+    if (!w->g1 || !w->wqkv || !w->wo || !w->g2) return fail(RS_ERR_BAD_ARG, "null weight pointer");
+    const bool dense_ffn = w->wg || w->wu || w->wd;   // all three null: the layer's feed-forward block is a sparse one (rs_set_moe_weights)
+    if (dense_ffn && (!w->wg || !w->wu || !w->wd)) return fail(RS_ERR_BAD_ARG, "null weight pointer");
     if (c->gpu) {
         // the GEMM kernels stream the matrices in MFMA fragment order: repack them once, here
         HIP_TRY(hipSetDevice(c->device));
@@ -765,6 +803,7 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
         const Item items[5] = {{&pl.wqkv, w->wqkv, nqkv, d}, {&pl.wo, w->wo, d, qd}, {&pl.wg, w->wg, f, d},
                                {&pl.wu, w->wu, f, d}, {&pl.wd, w->wd, d, f}};
         for (const Item &it : items) {
+            if (!it.src) continue;
             if (!*it.dst) HIP_TRY(hipMalloc((void **)it.dst, packed_weight_elems(it.N, it.K) * sizeof(bf16_t)));
             launch_pack_weights(nullptr, (const bf16_t *)it.src, *it.dst, it.N, it.K);
         }
@@ -773,6 +812,74 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     }
     c->weights[layer] = *w;
     c->have_weights[layer] = true;
+    return RS_OK;
+}
+
+int32_t rs_set_moe_weights(rs_ctx *c, int32_t layer, const rs_moe_weights *w) {
+    if (!c || !w) return fail(RS_ERR_BAD_ARG, "null argument");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(RS_ERR_BAD_ARG, "layer %d out of range", layer);
+    if (w->n_experts < 2 || w->n_experts > RS_MOE_MAX_EXPERTS) return fail(RS_ERR_BAD_ARG, "n_experts %d: 2 to %d", w->n_experts, RS_MOE_MAX_EXPERTS);
+    if (w->top_k != 2) return fail(RS_ERR_BAD_ARG, "top_k %d: only 2", w->top_k);
+    const rs_model_desc &m = c->m;
+    const int d = m.d_model, f = m.ffn_dim, E = w->n_experts;
+    // both products run as grouped large-tile GEMMs
+    if (d % 32 || f % 32 || d < 1024 || f < 1024)
+        return fail(RS_ERR_BAD_ARG, "the sparse block needs d_model and ffn_dim to be multiples of 32 and at least 1024");
+    rs_ctx::MoeLayer &ml = c->moe[layer];
+    if (c->gpu) {
+        if (!w->router || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
+        HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipDeviceSynchronize());
+        ml.stride_gu = packed_weight_elems(f, d);
+        ml.stride_d = packed_weight_elems(d, f);
+        if (ml.E != E) {
+            for (bf16_t **q : {&ml.wg, &ml.wu, &ml.wd})
+                if (*q) { (void)hipFree(*q); *q = nullptr; }
+        }
+        if (!ml.wg) {
+            HIP_TRY(hipMalloc((void **)&ml.wg, ml.stride_gu * E * sizeof(bf16_t)));
+            HIP_TRY(hipMalloc((void **)&ml.wu, ml.stride_gu * E * sizeof(bf16_t)));
+            HIP_TRY(hipMalloc((void **)&ml.wd, ml.stride_d * E * sizeof(bf16_t)));
+        }
+        for (int e = 0; e < E; ++e) {
+            launch_pack_weights(nullptr, (const bf16_t *)w->wg + (size_t)e * f * d, ml.wg + e * ml.stride_gu, f, d);
+            launch_pack_weights(nullptr, (const bf16_t *)w->wu + (size_t)e * f * d, ml.wu + e * ml.stride_gu, f, d);
+            launch_pack_weights(nullptr, (const bf16_t *)w->wd + (size_t)e * d * f, ml.wd + e * ml.stride_d, d, f);
+        }
+        // per-side buffers of the grouped layout, sized for the side's row limit
+        for (int s = 0; s < 2; ++s) {
+            Workspace &ws = c->ws[s];
+            const int cap = ((2 * ws.rows + 127 * RS_MOE_MAX_EXPERTS + 127) / 128) * 128;
+            if (ws.rows <= 0 || ws.m_cap >= cap) continue;
+            ws.m_cap = cap;
+            HIP_TRY(hipMalloc((void **)&ws.m_sel, (size_t)ws.rows * 2 * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_pos, (size_t)ws.rows * 2 * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_wt, (size_t)ws.rows * 2 * sizeof(float)));
+            HIP_TRY(hipMalloc((void **)&ws.m_src, (size_t)cap * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_tile, (size_t)(cap / 128) * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_a, (size_t)cap * d * sizeof(bf16_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_act, (size_t)cap * f * sizeof(bf16_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_out, (size_t)cap * d * sizeof(bf16_t)));
+            HIP_TRY(hipMemset(ws.m_a, 0, (size_t)cap * d * sizeof(bf16_t)));
+            HIP_TRY(hipMemset(ws.m_act, 0, (size_t)cap * f * sizeof(bf16_t)));
+        }
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    ml.router = (const bf16_t *)w->router;
+    ml.E = E;
+    return RS_OK;
+}
+
+int32_t rs_debug_read_moe_routing(rs_ctx *c, int32_t side, int32_t n_rows, int32_t *experts_out, float *weights_out) {
+    if (!c || side < 0 || side > 1 || !experts_out || !weights_out) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    Workspace &w = c->ws[side];
+    if (!w.m_sel || n_rows < 1 || n_rows > w.rows) return fail(RS_ERR_BAD_ARG, "no routing of %d rows to read", n_rows);
+    HIP_TRY(hipSetDevice(c->device));
+    if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
+    HIP_TRY(hipMemcpy(experts_out, w.m_sel, (size_t)n_rows * 2 * sizeof(int32_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(weights_out, w.m_wt, (size_t)n_rows * 2 * sizeof(float), hipMemcpyDeviceToHost));
     return RS_OK;
 }
 

@@ -1,0 +1,123 @@
+"""GPU parity of the sparse (mixture-of-experts) feed-forward block through the C ABI against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import moe
+import paper_2601_11822_amd as rs
+import rs_synth as S
+from tests.gpu_util import TOL, Rig, check_cache_against_oracle, check_tensor, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+f32 = S.bf16_bits_to_f32
+ORC_SENT = np.float32(-777.0)
+
+
+def _moe_rig(shape, n_experts, n_blocks, max_prefill, max_batch, max_context):
+    rig = Rig(shape, n_blocks, max_prefill, max_batch, max_context, with_oracle=False)
+    mw = S.moe_weights(shape, n_experts)
+    md = {k: to_dev(v) for k, v in mw.items()}
+    rig.ctx.set_moe_weights(0, md["router"], md["wg"], md["wu"], md["wd"], n_experts)
+    rig._keep.append(md)
+    return rig, mw, moe.OracleMoELayer(shape, rig.wbits[0], mw)
+
+
+def _check_routing(side, rig, L, mw, x1_ref, M):
+    """The routing is a floating-point decision: the library's experts must be near-maximal under the oracle's
+    logits, equal to the oracle's wherever those are decisive, and its weights the softmax of the two."""
+    sel_g, wt_g = rig.ctx.debug_read_moe_routing(side, M)
+    h2 = oracle.rmsnorm(x1_ref, L.g2, L.shape.rms_eps)
+    lg = moe.router_logits(h2, mw["router"])
+    sel_o, _ = moe.top2(lg)
+    srt = np.sort(lg, axis=1)
+    slack = 2 * TOL * np.max(np.abs(lg), axis=1)
+    for k in range(2):
+        assert np.all(lg[np.arange(M), sel_g[:, k]] >= srt[:, -2] - slack), "an expert outside the top two was chosen"
+    assert np.all(sel_g[:, 0] != sel_g[:, 1])
+    decisive = ((srt[:, -1] - srt[:, -2]) > slack) & ((srt[:, -2] - srt[:, -3]) > slack)
+    assert np.array_equal(sel_g[decisive], sel_o[decisive])
+    two = lg[np.arange(M)[:, None], sel_g].astype(np.float64)
+    p = np.exp(two - two.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    assert np.abs(wt_g - p).max() <= TOL
+    print(f"  routing: {np.mean((sel_g == sel_o).all(axis=1)):.2%} of rows as the oracle, {decisive.mean():.2%} decisive; "
+          f"rows per expert {np.bincount(sel_g.ravel(), minlength=mw['router'].shape[0]).tolist()}", flush=True)
+    return sel_g, p.astype(np.float32)
+
+
+@pytest.mark.parametrize("lens", [[150, 50], [700], [3]])
+def test_moe_prefill_matches_oracle(lens):
+    shape, E = S.WIDE, 8
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    n_blocks = sum(S.blocks_for(n) for n in lens) + 3
+    tabs = S.shuffled_block_tables(lens, n_blocks, stream=21)
+    xb = S.hidden_states(T, shape.d_model, stream=21)
+    rig, mw, L = _moe_rig(shape, E, n_blocks, T, 2, max(lens) + 1)
+    try:
+        y_bits = rig.prefill(xb, cu, tabs)
+        Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
+        x = f32(xb)
+        _, x1_ref, _, _ = L.prefill(x, cu, tabs, Kc, Vc)
+        check_tensor("x1", f32(rig.ctx.debug_read_workspace(rs.RS_SIDE_PREFILL, 3, (T, shape.d_model))), x1_ref, x, 1)
+        sel, wt = _check_routing(rs.RS_SIDE_PREFILL, rig, L, mw, x1_ref, T)
+        Kc2, Vc2 = L.new_cache(n_blocks, fill=ORC_SENT)
+        y_ref, _, _, _ = L.prefill(x, cu, tabs, Kc2, Vc2, sel=sel, wt=wt)     # the oracle under the library's routing
+        check_tensor("y (sparse block)", f32(y_bits), y_ref, x, 2)
+        check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("ctx", [[37], [5, 64, 100, 17, 33], list(range(1, 71))])
+def test_moe_decode_matches_oracle(ctx):
+    shape, E = S.WIDE, 8
+    ctx = np.asarray(ctx, np.int32)
+    B = len(ctx)
+    counts = [int(c) + 1 for c in ctx]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 3
+    tabs = S.shuffled_block_tables(counts, n_blocks, stream=22)
+    rig, mw, L = _moe_rig(shape, E, n_blocks, max(int(ctx.sum()), 1), B, int(ctx.max()) + 1)
+    try:
+        # fill the contexts through the library's own prefill, in groups of at most 64 prompts
+        Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
+        for g0 in range(0, B, 64):
+            lens = [int(c) for c in ctx[g0:g0 + 64]]
+            cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            xb = S.hidden_states(int(cu[-1]), shape.d_model, stream=40 + g0)
+            rig.prefill(xb, cu, tabs[g0:g0 + 64])
+            L.prefill(f32(xb), cu, tabs[g0:g0 + 64], Kc, Vc)
+        db = S.hidden_states(B, shape.d_model, stream=50)
+        yd = rig.decode(db, ctx, tabs)
+        x = f32(db)
+        Kt, Vt = Kc.copy(), Vc.copy()
+        _, x1_ref, _, _ = L.decode(x, ctx, tabs, Kt, Vt)
+        sel, wt = _check_routing(rs.RS_SIDE_DECODE, rig, L, mw, x1_ref, B)
+        y_ref, _, _, _ = L.decode(x, ctx, tabs, Kc, Vc, sel=sel, wt=wt)
+        check_tensor("decode y (sparse block)", f32(yd), y_ref, x, 2)
+    finally:
+        rig.close()
+
+
+def test_moe_argument_checks():
+    rig = Rig(S.TINY, 8, 16, 2, 32, with_oracle=False)
+    try:
+        mw = {k: to_dev(v) for k, v in S.moe_weights(S.TINY, 4).items()}
+        with pytest.raises(rs.RapidServeError) as e:
+            rig.ctx.set_moe_weights(0, mw["router"], mw["wg"], mw["wu"], mw["wd"], 4)     # d_model < 1024
+        assert e.value.code == rs.RS_ERR_BAD_ARG
+    finally:
+        rig.close()
+    rig = Rig(S.WIDE, 8, 16, 2, 32, with_oracle=False)
+    try:
+        mw = {k: to_dev(v) for k, v in S.moe_weights(S.WIDE, 2).items()}
+        with pytest.raises(rs.RapidServeError):
+            rig.ctx.set_moe_weights(0, mw["router"], mw["wg"], mw["wu"], mw["wd"], 2, top_k=1)
+        with pytest.raises(rs.RapidServeError):
+            rig.ctx.set_moe_weights(0, mw["router"], mw["wg"], mw["wu"], mw["wd"], 17)
+        with pytest.raises(rs.RapidServeError):
+            rig.ctx.set_moe_weights(1, mw["router"], mw["wg"], mw["wu"], mw["wd"], 2)      # layer out of range
+        rig.ctx.set_moe_weights(0, mw["router"], mw["wg"], mw["wu"], mw["wd"], 2)          # two experts: both always chosen
+    finally:
+        rig.close()
