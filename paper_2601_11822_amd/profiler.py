@@ -46,7 +46,7 @@ class Rig:
     """Weights, KV pools and activations of one layer, sized for the largest profiled load."""
 
     def __init__(self, shape, batch_edges: Sequence[int], ctx_edges: Sequence[int], prefill_tokens: int,
-                 max_context: int, device: int = 0):
+                 max_context: int, device: int = 0, experts: int = 0):
         import torch
         import rs_synth as S
         self.S, self.torch, self.shape = S, torch, shape
@@ -75,6 +75,11 @@ class Rig:
                                     max_decode_batch=self.max_batch, max_context=max_context, device=device)
         self.c.set_weights(0, w["g1"], w["wqkv"], w["wo"], w["g2"], w["wg"], w["wu"], w["wd"])
         self._w = w
+        if experts:   # sparse feed-forward block (random weights: only the timing matters here)
+            d, f = shape.d_model, shape.ffn_dim
+            rnd = lambda *sh, std=0.02: (torch.randn(sh, generator=g, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+            self._router = rnd(experts, d, std=0.1)
+            self.c.set_moe_weights(0, self._router, rnd(experts, f, d), rnd(experts, f, d), rnd(experts, d, f), experts)
         self.xp = to_dev(S.hidden_states(prefill_tokens, shape.d_model, stream=0))
         self.yp = torch.empty_like(self.xp)
         self.xd = to_dev(S.hidden_states(self.max_batch, shape.d_model, stream=50))

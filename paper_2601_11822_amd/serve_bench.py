@@ -53,7 +53,7 @@ def make_workload(n: int, rate: float, prompt_mean: float, prompt_sd: float, out
 
 
 def build_model(shape, n_layers: int, vocab: int, n_blocks: int, max_prefill: int, max_batch: int, max_context: int,
-                profile, device: int = 0, release: bool = False):
+                profile, device: int = 0, release: bool = False, experts: int = 0):
     import torch
     dev = torch.device(f"cuda:{device}")
     g = torch.Generator(device=dev)
@@ -67,6 +67,13 @@ def build_model(shape, n_layers: int, vocab: int, n_blocks: int, max_prefill: in
     rnd = lambda *s, std=0.02, mean=0.0: (torch.randn(s, generator=g, device=dev, dtype=torch.float32) * std + mean).to(torch.bfloat16)
     keep = [k_pool, v_pool]
     for l in range(n_layers):
+        if experts:   # sparse feed-forward block: the experts' matrices are packed during the call and dropped here
+            w = (rnd(d, mean=1.0), rnd(shape.qkv_dim, d), rnd(d, shape.q_dim), rnd(d, mean=1.0), None, None, None)
+            c.set_weights(l, *w)
+            router = rnd(experts, d, std=0.1)
+            c.set_moe_weights(l, router, rnd(experts, f, d), rnd(experts, f, d), rnd(experts, d, f), experts)
+            keep.append((w, router))
+            continue
         w = (rnd(d, mean=1.0), rnd(shape.qkv_dim, d), rnd(d, shape.q_dim), rnd(d, mean=1.0), rnd(f, d), rnd(f, d), rnd(d, f))
         c.set_weights(l, *w)
         if release:   # the library keeps packed copies only: a 70B-shaped stack then fits one GPU beside its KV pool
@@ -223,6 +230,7 @@ def main(argv=None):
     ap.add_argument("--profile", default=None, help="JSON written by the profiler, or 'measure'")
     ap.add_argument("--slo-ms", type=float, default=50.0)
     ap.add_argument("--wait-decode", action="store_true", help="wait for each decode step (exact per-step GPU times)")
+    ap.add_argument("--experts", type=int, default=0, help="sparse feed-forward block with this many experts (two per token)")
     ap.add_argument("--release-weights", action="store_true", help="free each layer's row-major matrices after packing")
     ap.add_argument("--engine", action="store_true", help="let the library's two threads drive (rs_engine_start)")
     ap.add_argument("--time-limit", type=float, default=120.0)
@@ -238,7 +246,7 @@ def main(argv=None):
         if a.profile == "measure":
             be = sorted({b for b in (16, 32, 64, 128, 256) if b < a.max_batch} | {a.max_batch})
             ce, dc = [32768, 131072], [32, 64, 96, 128, 160, 192]
-            rig = profiler.Rig(shape, be, ce, prefill_tokens=2048, max_context=a.max_prompt + a.max_out)
+            rig = profiler.Rig(shape, be, ce, prefill_tokens=2048, max_context=a.max_prompt + a.max_out, experts=a.experts)
             d = profiler.profile(rig, be, ce, dc, a.layers, steps=6, warmup=2)
             rig.c.destroy()
             del rig
@@ -249,7 +257,7 @@ def main(argv=None):
                          (16, a.max_out), a.vocab, a.seed)
     t0 = time.time()
     c, keep = build_model(shape, a.layers, a.vocab, a.kv_tokens // 16, a.max_prompt, a.max_batch, a.max_prompt + a.max_out, prof,
-                          release=a.release_weights)
+                          release=a.release_weights, experts=a.experts)
     _log(f"[serve] model of {a.layers} layers built in {time.time() - t0:.1f}s; {a.requests} requests over "
          f"{work[-1][1]:.1f}s, {sum(len(w[2]) for w in work)} prompt tokens, {sum(w[3] for w in work)} to generate")
     # one throw-away request settles lazy runtime work (first launches, masked streams)
@@ -266,7 +274,7 @@ def main(argv=None):
         steps, wall = serve(c, work, a.wait_decode, a.time_limit)
         rec = summarise(c, work, steps, wall)
     rec.update({"policy": a.policy, "shape": shape.name, "layers": a.layers, "rate_per_s": a.rate, "slo_ms": a.slo_ms,
-                "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "data": "synthetic"})
+                "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "experts": a.experts, "data": "synthetic"})
     line = json.dumps(rec)
     print(line, flush=True)
     if a.out:
