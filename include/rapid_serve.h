@@ -290,7 +290,9 @@ int32_t rs_debug_read_workspace(rs_ctx *ctx, int32_t side, int32_t which, void *
  * completed: the "notification") -> RUNNING (in the decode batch) -> FINISHED (blocks freed).
  *
  * rs_submit adds a request in arrival order (req_id >= 0, unique).  prompt_hidden is device bf16
- * [prompt_len, d_model] (there is no embedding on this path; hidden states are inputs).
+ * [prompt_len, d_model] (hidden states are this path's inputs; rs_submit_tokens / rs_step_tokens
+ * below take token ids).  A decode step that cannot get a block for a request's next token fails
+ * with RS_ERR_NO_BLOCKS: the library cannot recompute a hidden-state request, so none is preempted.
  *
  * rs_step performs one scheduling step:
  *   1. promotes requests whose prefill event has completed into the decode batch (FCFS,
@@ -431,7 +433,9 @@ int32_t rs_debug_push_sampled(rs_ctx *ctx, int64_t req_id, int32_t token);
  *
  * While the engine runs: rs_submit_tokens (any application thread), rs_request_output,
  * rs_request_times, rs_request_state and rs_engine_stats are the calls to use; rs_step,
- * rs_step_tokens and the layer calls are refused or must not be made.  Results are published by
+ * rs_step_tokens and the layer calls are refused or must not be made, and the allocator and
+ * split calls (rs_kv_alloc, rs_kv_free, rs_kv_num_free, rs_set_cu_split, rs_sync, ...) read or
+ * change state the engine's threads own: call them only while it is stopped.  Results are published by
  * the decode thread with release stores and read here with acquire loads: a reader never sees a
  * token count ahead of the tokens.  Host-only contexts: queue a request's sampled tokens with
  * rs_debug_push_sampled BEFORE submitting it.
