@@ -938,6 +938,17 @@ void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *parti
 
 void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials) {
     if (a.M <= 0 || a.N <= 0) return;
+    // A residual projection too short in K for the shared-activation kernel (the attention output projection)
+    // has few, short K ranges per wave in the streaming kernel; the K-sliced large-tile kernel serves it better
+    // on a partition (8B layer, 64 rows: 27 -> 21 us on 128 CUs, equal on 256).  A function of the shape alone.
+    if (a.epi == EPI_RESIDUAL && !skinny_shared_applies(a) && a.K % 32 == 0 && a.K >= 512 && a.Wp && a.N >= 1024 && a.N % 4 == 0 &&
+        a.partials == partials && a.partial_cap > 0) {
+        const int S = direct_splits(a.M, a.N, a.K);
+        if (S > 1 && direct_partial_elems(a.M, a.N, a.K) <= a.partial_cap) {
+            launch_direct_splitk(st, a, S);
+            return;
+        }
+    }
     switch (a.epi) {
         case EPI_STORE: launch_skinny_epi<EPI_STORE>(st, a, partials); break;
         case EPI_RESIDUAL: launch_skinny_epi<EPI_RESIDUAL>(st, a, partials); break;
