@@ -174,6 +174,42 @@ def test_library_life_cycle_matches_oracle(n_blocks, seed, budget):
     assert c.kv_num_free() == n_blocks
 
 
+@pytest.mark.parametrize("seed", range(100, 130))
+def test_library_life_cycle_matches_oracle_random_pools(seed):
+    """Thirty more traces with pool size, batch cap, prefill budget and request count drawn from the seed."""
+    g = np.random.default_rng(seed)
+    n_blocks = int(g.integers(6, 40))
+    max_batch = int(g.integers(1, 7))
+    budget = int(g.choice([64, 100, 160, 4096]))
+    reqs, delays = _trace(seed, n_req=int(g.integers(3, 25)), max_prompt=min(60, budget), max_new=30)
+    lc = Lifecycle(n_blocks, max_batch=max_batch, eos=EOS, max_prefill_tokens=budget)
+    ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lc.complete_prefill, reqs, delays)
+    c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=budget, max_decode_batch=max_batch,
+                              max_context=4096, device=rs.RS_HOST_ONLY)
+    c.set_head(None, None, None, vocab=64, eos_token=EOS)
+
+    def submit(rid, pl, mn, script):
+        c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
+        for t in script:
+            c.debug_push_sampled(rid, t)
+
+    def step():
+        so = c.step_tokens()
+        o = {k: getattr(so, k) for k in KEYS}
+        o["batch_ids"] = c.decode_batch_ids()
+        return o
+
+    got = _drive(submit, step, c.debug_complete_prefill, reqs, delays)
+    assert len(got) == len(ref)
+    for i, (a, b) in enumerate(zip(got, ref)):
+        for k in KEYS + ("batch_ids",):
+            assert a[k] == b[k], f"step {i}: {k}: library {a[k]} oracle {b[k]}"
+    for rid, pl, mn, script, _ in reqs:
+        toks, fin = c.request_output(rid)
+        assert fin and toks.tolist() == lc.reqs[rid].out == _expected_output(script, mn, EOS)
+    assert c.kv_num_free() == n_blocks
+
+
 def test_library_token_requests_argument_checks():
     c = _host_ctx(8, 2, EOS)
     with pytest.raises(rs.RapidServeError):
