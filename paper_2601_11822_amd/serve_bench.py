@@ -223,12 +223,17 @@ def main(argv=None):
     ap.add_argument("--out-mean", type=float, default=128.0)
     ap.add_argument("--out-sd", type=float, default=64.0)
     ap.add_argument("--max-prompt", type=int, default=8192)
+    ap.add_argument("--min-prompt", type=int, default=32)
     ap.add_argument("--max-out", type=int, default=1024)
     ap.add_argument("--max-batch", type=int, default=64)
     ap.add_argument("--kv-tokens", type=int, default=262144, help="KV pool size in tokens")
     ap.add_argument("--policy", choices=("manager", "over"), default="over")
     ap.add_argument("--profile", default=None, help="JSON written by the profiler, or 'measure'")
     ap.add_argument("--slo-ms", type=float, default=50.0)
+    ap.add_argument("--profile-ctx-edges", default="32768,131072",
+                    help="with --profile measure: bucket edges of the batch's total cached tokens")
+    ap.add_argument("--profile-prefill-tokens", type=int, default=2048,
+                    help="with --profile measure: size of the prefill pass that runs beside the measured decode steps")
     ap.add_argument("--wait-decode", action="store_true", help="wait for each decode step (exact per-step GPU times)")
     ap.add_argument("--experts", type=int, default=0, help="sparse feed-forward block with this many experts (two per token)")
     ap.add_argument("--release-weights", action="store_true", help="free each layer's row-major matrices after packing")
@@ -245,15 +250,16 @@ def main(argv=None):
             ap.error("--policy manager needs --profile")
         if a.profile == "measure":
             be = sorted({b for b in (16, 32, 64, 128, 256) if b < a.max_batch} | {a.max_batch})
-            ce, dc = [32768, 131072], [32, 64, 96, 128, 160, 192]
-            rig = profiler.Rig(shape, be, ce, prefill_tokens=2048, max_context=a.max_prompt + a.max_out, experts=a.experts)
+            ce, dc = sorted(int(x) for x in a.profile_ctx_edges.split(",")), [32, 64, 96, 128, 160, 192]
+            rig = profiler.Rig(shape, be, ce, prefill_tokens=a.profile_prefill_tokens, max_context=a.max_prompt + a.max_out,
+                               experts=a.experts)
             d = profiler.profile(rig, be, ce, dc, a.layers, steps=6, warmup=2)
             rig.c.destroy()
             del rig
         else:
             d = json.load(open(a.profile))
         prof = profiler.load_profile(d, int(a.slo_ms * 1000))
-    work = make_workload(a.requests, a.rate, a.prompt_mean, a.prompt_sd, a.out_mean, a.out_sd, (32, a.max_prompt),
+    work = make_workload(a.requests, a.rate, a.prompt_mean, a.prompt_sd, a.out_mean, a.out_sd, (a.min_prompt, a.max_prompt),
                          (16, a.max_out), a.vocab, a.seed)
     t0 = time.time()
     c, keep = build_model(shape, a.layers, a.vocab, a.kv_tokens // 16, a.max_prompt, a.max_batch, a.max_prompt + a.max_out, prof,
