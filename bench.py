@@ -54,7 +54,7 @@ def build_rig(args):
     import paper_2601_11822_amd as rs
     import rs_synth as S
 
-    shape = S.LLAMA8B
+    shape = S.SHAPES[getattr(args, "shape", "llama3-8b-layer")]
     T, B = args.prefill_tokens, args.decode_batch
     ctx = S.uniform_context_lengths(B, args.ctx_lo, args.ctx_hi)
     counts = [int(c) + 1 for c in ctx] + [T]
@@ -184,6 +184,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--shape", default="llama3-8b-layer", choices=("llama3-8b-layer", "llama3-70b-layer"),
+                    help="layer shape; the headline metric is quoted on the default")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
     ap.add_argument("--decode-batch", type=int, default=64)
     ap.add_argument("--ctx-lo", type=int, default=512)
@@ -208,7 +210,7 @@ def main():
     kv_tok_bytes = 2 * shape.n_kv_heads * shape.head_dim * 2
     attn_bytes = float((r["ctx"].astype(np.int64) + 1).sum()) * kv_tok_bytes
     bytes_layer = 2.0 * P + attn_bytes + B * kv_tok_bytes
-    default_workload = (T, B, args.ctx_lo, args.ctx_hi) == (2048, 64, 512, 4096)
+    default_workload = (args.shape, T, B, args.ctx_lo, args.ctx_hi) == ("llama3-8b-layer", 2048, 64, 512, 4096)
     probe = torch.empty(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB, read by the bandwidth probe
     probe.fill_(1.0)
 
@@ -329,7 +331,7 @@ def main():
         "value": head["prefill_tok_s_corun"], "unit": "tok/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": head["prefill_corun_ms"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"llama3-8b-shaped layer: prefill 1x{T} tokens co-running with decode batch {B}, "
+        "config": {"workload": f"{args.shape.replace('-layer', '')}-shaped layer: prefill 1x{T} tokens co-running with decode batch {B}, "
                                f"contexts U[{args.ctx_lo},{args.ctx_hi}], 16-token blocks, "
                                f"split {head['prefill_cus']}/{head['decode_cus']} CUs",
                    "prefill_tokens": T, "decode_batch": B, "sum_ctx": int(r["ctx"].sum()),
