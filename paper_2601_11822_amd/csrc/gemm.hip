@@ -488,10 +488,38 @@ static void launch_direct(hipStream_t st, const GemmArgs &a) {
     }
 }
 
+// Grouped GEMM (one weight matrix per 128-row tile, tile_expert[]).  The work list that follows the tile
+// table (tile_expert[n] = number of units, then one code per unit: 2 * tile + 1 for two neighbouring tiles of
+// one expert taken as one 256x256 tile, the cheaper shape per row, 2 * tile for a single 128x256 tile) names
+// the tiles in use, so the workgroups with work come first in every column tile and the rest leave at once.
+// The arithmetic of an output element does not depend on the tile that holds it.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_grouped_kernel(GemmArgs a, int n_tiles) {
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+    const int n128 = a.M >> 7;   // most units there can be
+    const int total = n128 * n_tiles;
+    const int per_xcd = (total + 7) >> 3;
+    const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (t >= total) return;
+    const int u = t % n128, nb = t / n128;
+    const int32_t *units = a.tile_expert + n128;
+    if (u >= __builtin_amdgcn_readfirstlane(units[0])) return;
+    const int code = __builtin_amdgcn_readfirstlane(units[1 + u]);
+    if (code & 1) gemm_direct_tile<256, 256, EPI, 4, 4>(a, (code >> 1) * 128, nb, smem);
+    else gemm_direct_tile<128, 256, EPI, 5, 4>(a, (code >> 1) * 128, nb, smem);
+}
+
+template <int EPI>
+static void launch_grouped_epi(hipStream_t st, const GemmArgs &a) {
+    const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + 127) / 128 : (a.N + 255) / 256;
+    const int grid = (((a.M >> 7) * n_tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_grouped_kernel<EPI>), dim3(grid), dim3(256), 131072, st, a, n_tiles);
+}
+
 bool launch_gemm_grouped(hipStream_t st, const GemmArgs &a) {
     if (!(a.K % 32 == 0 && a.K >= 32 && a.Wp && a.N >= 1024 && a.M % 128 == 0 && a.tile_expert)) return false;
-    if (a.epi == EPI_SWIGLU) launch_direct_epi<128, 256, EPI_SWIGLU, 5, 4>(st, a);
-    else if (a.epi == EPI_STORE) launch_direct_epi<128, 256, EPI_STORE, 5, 4>(st, a);
+    if (a.epi == EPI_SWIGLU) launch_grouped_epi<EPI_SWIGLU>(st, a);
+    else if (a.epi == EPI_STORE) launch_grouped_epi<EPI_STORE>(st, a);
     else return false;
     return true;
 }
@@ -967,6 +995,8 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_shared_kernel<EPI_SWIGLU, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_skinny_shared_kernel<EPI_RESIDUAL, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_direct_splitk_kernel, 5 * (128 + 256) * 32 * 2);
+    set((const void *)gemm_grouped_kernel<EPI_STORE>, 131072);
+    set((const void *)gemm_grouped_kernel<EPI_SWIGLU>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
     set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);

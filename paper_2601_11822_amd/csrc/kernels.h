@@ -94,10 +94,15 @@ size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
 
 // Grouped GEMM over 128-row tiles that each belong to one expert: STORE or SWIGLU epilogue, a.M = the padded
-// row capacity (a multiple of 128), a.tile_expert and a.expert_stride set.  Needs K % 32 == 0 and N >= 1024.
+// row capacity (a multiple of 128), a.expert_stride and a.tile_expert set, the latter followed by the work list
+// that moe_plan_kernel writes behind the a.M / 128 tile entries.  Needs K % 32 == 0 and N >= 1024.
 bool launch_gemm_grouped(hipStream_t st, const GemmArgs &a);
 
 #define RS_MOE_MAX_EXPERTS 16
+// Rows of the grouped (expert-major) layout that M rows with two experts each can need: every expert's segment
+// is padded to whole 128-row tiles, and a segment of two or more tiles may be preceded by one idle tile so that
+// it starts on a 256-row boundary.
+static inline int moe_row_cap(int M, int E) { return ((2 * M + 255 * E + 127) / 128) * 128; }
 struct MoeArgs {
     const bf16_t *h;        // normalised rows, fragment-packed with packed_mt(M) row tiles
     const bf16_t *router;   // [E][d] row-major
@@ -105,7 +110,7 @@ struct MoeArgs {
     float *wt;              // [M][2] their weights
     int32_t *pos;           // [M][2] grouped row of each assignment
     int32_t *src;           // [Mg_cap] source row of each grouped row, -1 for padding
-    int32_t *tile_expert;   // [Mg_cap / 128]
+    int32_t *tile_expert;   // [2 * (Mg_cap / 128) + 1]: expert of each tile, then the grouped GEMM's work list
     bf16_t *a_g;            // gathered rows, fragment-packed with Mg_cap / 32 row tiles
     const bf16_t *out_g;    // [Mg_cap][d] expert outputs, row-major
     const bf16_t *x1;       // [M][d]

@@ -49,8 +49,9 @@ __global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Plan (one workgroup): per-expert counts, each expert's segment padded to whole 128-row tiles,
-// the expert of every tile (-1 past the last used tile), the source row of every grouped row
+// Plan (one workgroup): per-expert counts, each expert's segment padded to whole 128-row tiles (a
+// segment of two or more tiles starts on a 256-row boundary, after an idle tile if need be, so that
+// the grouped GEMM can take its tiles in pairs), the expert of every tile (-1 for a tile not in use), the source row of every grouped row
 // (-1 for padding) and the grouped position of every assignment.  The order of rows inside a
 // segment is arbitrary (an atomic cursor): a row's result does not depend on where it sits.
 // ---------------------------------------------------------------------------------------------
@@ -65,12 +66,26 @@ __global__ __launch_bounds__(1024) void moe_plan_kernel(MoeArgs a) {
     if (tid == 0) {
         int t = 0;
         for (int e = 0; e < a.E; ++e) {
-            off[e] = t * 128;
             const int nt = (cnt[e] + 127) >> 7;
+            if (nt >= 2 && (t & 1)) a.tile_expert[t++] = -1;   // longer segments start on a 256-row boundary
+            off[e] = t * 128;
             for (int j = 0; j < nt; ++j) a.tile_expert[t + j] = e;
             t += nt;
         }
-        for (int j = t; j < a.Mg_cap / 128; ++j) a.tile_expert[j] = -1;
+        const int n128 = a.Mg_cap / 128;
+        for (int j = t; j < n128; ++j) a.tile_expert[j] = -1;
+        // the grouped GEMM's work list, behind the tile table: aligned pairs of one expert, else single tiles
+        int32_t *units = a.tile_expert + n128;
+        int nu = 0;
+        for (int e = 0, j = 0; e < a.E; ++e) {
+            const int nt = (cnt[e] + 127) >> 7;
+            if (nt >= 2 && (j & 1)) ++j;
+            int k = 0;
+            for (; k + 2 <= nt && !((j + k) & 1); k += 2) units[1 + nu++] = 2 * (j + k) + 1;
+            for (; k < nt; ++k) units[1 + nu++] = 2 * (j + k);
+            j += nt;
+        }
+        units[0] = nu;
     }
     __syncthreads();
     for (int i = tid; i < 2 * a.M; i += 1024) {

@@ -446,7 +446,7 @@ bool run_post_attention(rs_ctx *c, int side, hipStream_t st, Workspace &w, const
     tick(c, side, 6);
     if (ml.E > 0) {
         // sparse block: route, gather expert by expert, two grouped GEMMs over all tiles, weighted sum
-        const int cap = std::min(w.m_cap, ((2 * M + 127 * ml.E + 127) / 128) * 128);
+        const int cap = std::min(w.m_cap, moe_row_cap(M, ml.E));
         MoeArgs ma{w.h, ml.router, w.m_sel, w.m_wt, w.m_pos, w.m_src, w.m_tile, w.m_a, w.m_out, w.x1, y, M, d, ml.E, cap};
         launch_moe_route_and_gather(st, ma);
         GemmArgs gu{w.m_a, nullptr, nullptr, ml.wg, ml.wu, nullptr, w.m_act, cap, f, d, EPI_SWIGLU, 1, c->side[side].cus};
@@ -849,14 +849,14 @@ int32_t rs_set_moe_weights(rs_ctx *c, int32_t layer, const rs_moe_weights *w) {
         // per-side buffers of the grouped layout, sized for the side's row limit
         for (int s = 0; s < 2; ++s) {
             Workspace &ws = c->ws[s];
-            const int cap = ((2 * ws.rows + 127 * RS_MOE_MAX_EXPERTS + 127) / 128) * 128;
+            const int cap = moe_row_cap(ws.rows, RS_MOE_MAX_EXPERTS);
             if (ws.rows <= 0 || ws.m_cap >= cap) continue;
             ws.m_cap = cap;
             HIP_TRY(hipMalloc((void **)&ws.m_sel, (size_t)ws.rows * 2 * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&ws.m_pos, (size_t)ws.rows * 2 * sizeof(int32_t)));
             HIP_TRY(hipMalloc((void **)&ws.m_wt, (size_t)ws.rows * 2 * sizeof(float)));
             HIP_TRY(hipMalloc((void **)&ws.m_src, (size_t)cap * sizeof(int32_t)));
-            HIP_TRY(hipMalloc((void **)&ws.m_tile, (size_t)(cap / 128) * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&ws.m_tile, (size_t)(2 * (cap / 128) + 1) * sizeof(int32_t)));   // tile table + work list
             HIP_TRY(hipMalloc((void **)&ws.m_a, (size_t)cap * d * sizeof(bf16_t)));
             HIP_TRY(hipMalloc((void **)&ws.m_act, (size_t)cap * f * sizeof(bf16_t)));
             HIP_TRY(hipMalloc((void **)&ws.m_out, (size_t)cap * d * sizeof(bf16_t)));
