@@ -46,7 +46,9 @@ def _check_routing(side, rig, L, mw, x1_ref, M):
     return sel_g, p.astype(np.float32)
 
 
-@pytest.mark.parametrize("lens", [[150, 50], [700], [3]])
+# [700]: experts of one and two 128-row tiles (single tiles, aligned pairs, idle alignment tiles);
+# [1100, 450]: about 390 rows per expert, segments of three and four tiles (pairs followed by a single tile)
+@pytest.mark.parametrize("lens", [[150, 50], [700], [3], [1100, 450]])
 def test_moe_prefill_matches_oracle(lens):
     shape, E = S.WIDE, 8
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
