@@ -326,7 +326,32 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
     // this thread's chunks of a key tile: K chunk j = (row (tid+256j)/CPR, 16-byte column kc),
     // V chunk j = (dim (tid+256j)>>3, block vcc>>1, 8-token half vcc&1)
     const int kc = tid % CPR, vcc = tid & 7;
+    // head_dim 128: a thread's four K chunks are the same (token slot, dims) of the tile's four blocks and its four V
+    // chunks are four dims, 32 apart, of one block, so a whole tile needs four wave-uniform block ids for K, one
+    // per-lane id for V and addresses that differ by constants
+    const uint32_t k_thread_off = (uint32_t)kpool_chunk_offset((tid / CPR) & 15, kc * 8);
+    const uint32_t v_thread_off = (uint32_t)((tid >> 3) * 16 + (vcc & 1) * 8);
     auto load_regs = [&](int kv0) {
+        if (HD == 128 && kv0 + 64 <= len && (kv0 >> 4) + 4 <= PREFILL_TAB_LDS) {
+            const int b0 = kv0 >> 4;
+            int blk[4];
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                blk[j] = __builtin_amdgcn_readfirstlane(s_tab[b0 + j]);
+                ok = ok && (unsigned)blk[j] < (unsigned)a.n_blocks;
+            }
+            if (ok) {   // uniform; a tile with a bad block id takes the checked path below, which reports it
+#pragma unroll
+                for (int j = 0; j < NKC; ++j)
+                    rk[j] = ld_bf16x8(a.k_pool + ((size_t)blk[j] * a.Hkv + hk) * 16 * HD + k_thread_off);
+                const int bv = s_tab[b0 + (vcc >> 1)];
+                const bf16_t *vp = a.v_pool + ((size_t)bv * a.Hkv + hk) * 16 * HD + v_thread_off;
+#pragma unroll
+                for (int j = 0; j < NVC; ++j) rv[j] = ld_bf16x8(vp + j * (32 * 16));
+                return;
+            }
+        }
         if (kv0 + 64 <= len) {   // whole tile inside the prompt (uniform): no per-element checks
 #pragma unroll
             for (int j = 0; j < NKC; ++j) {
