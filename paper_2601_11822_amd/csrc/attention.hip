@@ -318,7 +318,17 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
     const float sc = a.scale_log2;
     const int n_blk = (len + 15) >> 4;
     for (int i = tid; i < min(n_blk, PREFILL_TAB_LDS); i += 256) s_tab[i] = tab[i];
-    auto block_of = [&](int bi) { return bi < PREFILL_TAB_LDS ? s_tab[bi] : tab[bi]; };
+    // (two separate loads: a pointer chosen between the LDS copy and the table would become a generic-address
+    // load, which waits for every outstanding LDS and global access)
+    auto block_of = [&](int bi) {
+        int b = s_tab[min(bi, PREFILL_TAB_LDS - 1)];
+        if (bi >= PREFILL_TAB_LDS) {
+            int g = tab[bi];
+            asm volatile("" : "+v"(g));   // pins the global load to this branch: the two loads must not be merged
+            b = g;
+        }
+        return b;
+    };
 
     auto kswz = [](int r, int cc) { return HD == 128 ? (cc ^ (r & 15)) : (cc ^ ((r >> 1) & 7)); };
 
