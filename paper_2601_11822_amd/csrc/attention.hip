@@ -283,8 +283,9 @@ void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
 // one barrier per key tile.  The prompt's block ids are copied to LDS once, so a key tile costs one
 // memory round trip (pool) instead of two chained ones (table, then pool).
 // LDS chunk indices are XOR-swizzled for the 64-bank LDS (K rows: chunk ^ row&15 at head_dim 128,
-// chunk ^ (row>>1)&7 at 64; V rows: chunk ^ (d>>1)&7 and the two 8-byte halves of a chunk swapped
-// when d&16).
+// chunk ^ (row>>1)&7 at 64; V rows: chunk ^ (d>>1)&7).  A V row keeps each 16-token block as the four-token
+// pieces 0-3, 8-11, 4-7, 12-15: the eight tokens a lane contributes to one P V step (4h..4h+3 and 8+4h..) are
+// then one 16-byte chunk, read straight into the MFMA operand.
 // =============================================================================================
 template <int HD>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a) {
@@ -429,18 +430,17 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
 #pragma unroll
         for (int j = 0; j < NVC; ++j) {
             const int c = tid + 256 * j;
-            const int d = c >> 3, cc = c & 7;
-            bf16x8 v = rv[j];
-            if (d & 16) {
-                bf16x8 w;
+            const int d = c >> 3, blk = (c & 7) >> 1, half = c & 1;
+            const int x = (d >> 1) & 7;
+            // tokens 8 half + (0..3) and 8 half + (4..7) of the block: pieces half and 2 + half of its row
+            bf16x4 lo, hi;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    w[i] = v[4 + i];
-                    w[4 + i] = v[i];
-                }
-                v = w;
+            for (int i = 0; i < 4; ++i) {
+                lo[i] = rv[j][i];
+                hi[i] = rv[j][4 + i];
             }
-            *(bf16x8 *)&vs[d * 64 + ((cc ^ ((d >> 1) & 7)) << 3)] = v;
+            *(bf16x4 *)&vs[d * 64 + (((2 * blk) ^ x) << 3) + 4 * half] = lo;
+            *(bf16x4 *)&vs[d * 64 + (((2 * blk + 1) ^ x) << 3) + 4 * half] = hi;
         }
     };
 
@@ -482,14 +482,26 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                 const bf16_t *vs = Vs + (kt & 1) * HD * 64;
                 f32x16 st[2];
 #pragma unroll
-                for (int t2 = 0; t2 < 2; ++t2) {
+                for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) st[t2][i] = 0.f;
-                    const int row = 32 * t2 + c32;
+                {
+                    // K fragment i = (key half i & 1, head_dim step i >> 1), read four fragments ahead of its MFMA; the
+                    // two score tiles alternate, each still summed over the steps in order
+                    constexpr int NQK = 2 * KS, R = 4;
+                    auto kread = [&](int i) {
+                        const int row = 32 * (i & 1) + c32;
+                        return *(const bf16x8 *)&ks[row * HD + (kswz(row, 2 * (i >> 1) + h) << 3)];
+                    };
+                    bf16x8 kf[R];
 #pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        const bf16x8 kf = *(const bf16x8 *)&ks[row * HD + (kswz(row, 2 * s + h) << 3)];
-                        st[t2] = mfma32(kf, qf[s], st[t2]);
+                    for (int i = 0; i < R; ++i) kf[i] = kread(i);
+#pragma unroll
+                    for (int i = 0; i < NQK; ++i) {
+                        st[i & 1] = mfma32(kf[i % R], qf[i >> 1], st[i & 1]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (i + R < NQK) kf[i % R] = kread(i + R);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
                 if (kv0 + 63 > wave_q_min) {   // only tiles that touch the diagonal need the mask
@@ -535,16 +547,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
                         const int d = 32 * dt + c32;
-                        const int hs = (h ^ ((d >> 4) & 1)) << 2;
-                        const int x = (d >> 1) & 7;
-                        const bf16x4 lo = *(const bf16x4 *)&vs[d * 64 + (((2 * blk4) ^ x) << 3) + hs];
-                        const bf16x4 hi = *(const bf16x4 *)&vs[d * 64 + (((2 * blk4 + 1) ^ x) << 3) + hs];
-                        bf16x8 vf;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            vf[i] = lo[i];
-                            vf[4 + i] = hi[i];
-                        }
+                        const bf16x8 vf = *(const bf16x8 *)&vs[d * 64 + (((2 * blk4 + h) ^ ((d >> 1) & 7)) << 3)];
                         o[dt] = mfma32(vf, pf, o[dt]);
                     }
                 }
