@@ -282,10 +282,10 @@ void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
 // LDS buffers: the next key tile's global loads are in flight while the current one is multiplied,
 // one barrier per key tile.  The prompt's block ids are copied to LDS once, so a key tile costs one
 // memory round trip (pool) instead of two chained ones (table, then pool).
-// LDS chunk indices are XOR-swizzled for the 64-bank LDS (K rows: chunk ^ row&15 at head_dim 128,
-// chunk ^ (row>>1)&7 at 64; V rows: chunk ^ (d>>1)&7).  A V row keeps each 16-token block as the four-token
-// pieces 0-3, 8-11, 4-7, 12-15: the eight tokens a lane contributes to one P V step (4h..4h+3 and 8+4h..) are
-// then one 16-byte chunk, read straight into the MFMA operand.
+// The K tile sits in LDS as its four blocks in the pool's own order and the V tile as [block][8-token half][dim]:
+// the 16 lanes of a fragment read are then 16 consecutive 16-byte chunks (no bank conflicts, no swizzle), every
+// read address is a per-lane base plus a constant, and a whole tile comes in by LDS-DMA (global -> LDS, no
+// staging registers, no LDS stores).
 // =============================================================================================
 template <int HD>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a) {
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
     constexpr int KS = HD / 16;   // 32x32x16 steps over head_dim
     constexpr int DT = HD / 32;   // 32-row tiles of O^T
     constexpr int NKC = (64 * CPR) / 256, NVC = (HD * 8) / 256;  // chunks per thread per tile
-    extern __shared__ __attribute__((aligned(16))) bf16_t smem_attn[];
+    extern __shared__ __attribute__((aligned(1024))) bf16_t smem_attn[];
     bf16_t *Ks = smem_attn;                 // [2][64 * HD]
     bf16_t *Vs = smem_attn + 2 * 64 * HD;   // [2][HD * 64]
     int32_t *s_tab = (int32_t *)(smem_attn + 4 * 64 * HD);   // [PREFILL_TAB_LDS] block ids of this prompt
@@ -331,18 +331,18 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
         return b;
     };
 
-    auto kswz = [](int r, int cc) { return HD == 128 ? (cc ^ (r & 15)) : (cc ^ ((r >> 1) & 7)); };
+    // K tile in LDS: the four blocks one after the other, each in the pool's own order (element offset of row r, 16-byte column cc)
+    auto klds = [](int r, int cc) { return (r >> 4) * (16 * HD) + kpool_chunk_offset(r & 15, cc * 8); };
 
-    bf16x8 rk[NKC], rv[NVC];
-    // this thread's chunks of a key tile: K chunk j = (row (tid+256j)/CPR, 16-byte column kc),
-    // V chunk j = (dim (tid+256j)>>3, block vcc>>1, 8-token half vcc&1)
-    const int kc = tid % CPR, vcc = tid & 7;
-    // head_dim 128: a thread's four K chunks are the same (token slot, dims) of the tile's four blocks and its four V
-    // chunks are four dims, 32 apart, of one block, so a whole tile needs four wave-uniform block ids for K, one
-    // per-lane id for V and addresses that differ by constants
-    const uint32_t k_thread_off = (uint32_t)kpool_chunk_offset((tid / CPR) & 15, kc * 8);
-    const uint32_t v_thread_off = (uint32_t)((tid >> 3) * 16 + (vcc & 1) * 8);
-    auto load_regs = [&](int kv0) {
+    // this thread's chunks of a key tile on the checked path: K chunk j = (row c/CPR, 16-byte column c%CPR),
+    // V chunk j = (dim c>>3, block (c&7)>>1, 8-token half c&1), c = tid + 256 j
+    // V tile in LDS: per block the 8-token halves apart, [block][half][dim][8 tokens]: the 16 lanes of a fragment read
+    // (16 dims, one half) are 16 consecutive 16-byte chunks
+    auto vlds = [](int blk, int half, int d) { return blk * (16 * HD) + half * (8 * HD) + d * 8; };
+    // Brings key tile [kv0, kv0 + 64) into LDS buffer buf (nobody reads that buffer before the next barrier).
+    auto load_tile = [&](int kv0, int buf) {
+        bf16_t *ks = Ks + buf * 64 * HD;
+        bf16_t *vs = Vs + buf * HD * 64;
         if (HD == 128 && kv0 + 64 <= len && (kv0 >> 4) + 4 <= PREFILL_TAB_LDS) {
             const int b0 = kv0 >> 4;
             int blk[4];
@@ -353,36 +353,29 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                 ok = ok && (unsigned)blk[j] < (unsigned)a.n_blocks;
             }
             if (ok) {   // uniform; a tile with a bad block id takes the checked path below, which reports it
+                // Whole tile by LDS-DMA (global -> LDS, 16 bytes per lane, lane l's bytes land at the window's
+                // base + 16 l; no registers): wave w copies block w.  K keeps the pool's order (4 KB straight);
+                // V's 16-byte chunk (dim d, half) goes to [half][d], so a lane fetches chunk (64 i + l, half).
+                const int w = __builtin_amdgcn_readfirstlane(wave);
+                const int bw = w == 0 ? blk[0] : w == 1 ? blk[1] : w == 2 ? blk[2] : blk[3];
+                const size_t head = ((size_t)bw * a.Hkv + hk) * 16 * HD;
+                const bf16_t *ksrc = a.k_pool + head + lane * 8;
+                const bf16_t *vsrc = a.v_pool + head + lane * 16;
+                bf16_t *kdst = ks + w * (16 * HD), *vdst = vs + w * (16 * HD);
 #pragma unroll
-                for (int j = 0; j < NKC; ++j)
-                    rk[j] = ld_bf16x8(a.k_pool + ((size_t)blk[j] * a.Hkv + hk) * 16 * HD + k_thread_off);
-                const int bv = s_tab[b0 + (vcc >> 1)];
-                const bf16_t *vp = a.v_pool + ((size_t)bv * a.Hkv + hk) * 16 * HD + v_thread_off;
+                for (int j = 0; j < 4; ++j)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ksrc + j * 512),
+                                                     (__attribute__((address_space(3))) void *)(kdst + j * 512), 16, 0, 0);
 #pragma unroll
-                for (int j = 0; j < NVC; ++j) rv[j] = ld_bf16x8(vp + j * (32 * 16));
+                for (int j = 0; j < 4; ++j)   // j = 2 * half + i
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(vsrc + (j & 1) * (64 * 16) + (j >> 1) * 8),
+                        (__attribute__((address_space(3))) void *)(vdst + (j >> 1) * (8 * HD) + (j & 1) * 512), 16, 0, 0);
                 return;
             }
         }
-        if (kv0 + 64 <= len) {   // whole tile inside the prompt (uniform): no per-element checks
-#pragma unroll
-            for (int j = 0; j < NKC; ++j) {
-                const int r = (tid + 256 * j) / CPR;
-                const int blk = block_of((kv0 + r) >> 4);
-                const bool ok = (unsigned)blk < (unsigned)a.n_blocks;
-                if (!ok && kc == 0 && (r & 15) == 0) atomicOr(a.err_flag, 2);
-                rk[j] = ok ? ld_bf16x8(a.k_pool + ((size_t)blk * a.Hkv + hk) * 16 * HD + kpool_chunk_offset(r & 15, kc * 8))
-                           : zero_bf16x8();
-            }
-#pragma unroll
-            for (int j = 0; j < NVC; ++j) {
-                const int d = (tid + 256 * j) >> 3;
-                const int blk = block_of((kv0 >> 4) + (vcc >> 1));
-                const bool ok = (unsigned)blk < (unsigned)a.n_blocks;
-                rv[j] = ok ? ld_bf16x8(a.v_pool + (((size_t)blk * a.Hkv + hk) * HD + d) * 16 + (vcc & 1) * 8)
-                           : zero_bf16x8();
-            }
-            return;
-        }
+        // checked path (a ragged last tile, a bad block id, head_dim 64): through registers
+        bf16x8 rk[NKC], rv[NVC];
 #pragma unroll
         for (int j = 0; j < NKC; ++j) {
             const int c = tid + 256 * j;
@@ -417,30 +410,15 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
             }
             rv[j] = v;
         }
-    };
-    auto store_lds = [&](int buf) {
-        bf16_t *ks = Ks + buf * 64 * HD;
-        bf16_t *vs = Vs + buf * HD * 64;
 #pragma unroll
         for (int j = 0; j < NKC; ++j) {
             const int c = tid + 256 * j;
-            const int r = c / CPR, cc = c % CPR;
-            *(bf16x8 *)&ks[r * HD + (kswz(r, cc) << 3)] = rk[j];
+            *(bf16x8 *)&ks[klds(c / CPR, c % CPR)] = rk[j];
         }
 #pragma unroll
         for (int j = 0; j < NVC; ++j) {
             const int c = tid + 256 * j;
-            const int d = c >> 3, blk = (c & 7) >> 1, half = c & 1;
-            const int x = (d >> 1) & 7;
-            // tokens 8 half + (0..3) and 8 half + (4..7) of the block: pieces half and 2 + half of its row
-            bf16x4 lo, hi;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo[i] = rv[j][i];
-                hi[i] = rv[j][4 + i];
-            }
-            *(bf16x4 *)&vs[d * 64 + (((2 * blk) ^ x) << 3) + 4 * half] = lo;
-            *(bf16x4 *)&vs[d * 64 + (((2 * blk + 1) ^ x) << 3) + 4 * half] = hi;
+            *(bf16x8 *)&vs[vlds((c & 7) >> 1, c & 1, c >> 3)] = rv[j];
         }
     };
 
@@ -470,13 +448,13 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
             for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
 
         __syncthreads();   // s_tab visible; the previous tile's last reads done before buffer 0 is refilled
-        load_regs(0);
-        store_lds(0);
+        load_tile(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS-DMA loads have landed
         __syncthreads();
         for (int kt = 0; kt < n_kv_tiles; ++kt) {
             const int kv0 = kt * 64;
             const bool more = kt + 1 < n_kv_tiles;
-            if (more) load_regs(kv0 + 64);
+            if (more) load_tile(kv0 + 64, (kt + 1) & 1);
             if (kv0 <= wave_q_max) {
                 const bf16_t *ks = Ks + (kt & 1) * 64 * HD;
                 const bf16_t *vs = Vs + (kt & 1) * HD * 64;
@@ -489,10 +467,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                     // K fragment i = (key half i & 1, head_dim step i >> 1), read four fragments ahead of its MFMA; the
                     // two score tiles alternate, each still summed over the steps in order
                     constexpr int NQK = 2 * KS, R = 4;
-                    auto kread = [&](int i) {
-                        const int row = 32 * (i & 1) + c32;
-                        return *(const bf16x8 *)&ks[row * HD + (kswz(row, 2 * (i >> 1) + h) << 3)];
-                    };
+                    auto kread = [&](int i) { return *(const bf16x8 *)&ks[klds(32 * (i & 1) + c32, 2 * (i >> 1) + h)]; };
                     bf16x8 kf[R];
 #pragma unroll
                     for (int i = 0; i < R; ++i) kf[i] = kread(i);
@@ -541,18 +516,29 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                 l_run += psum;
 #pragma unroll
                 for (int blk4 = 0; blk4 < 4; ++blk4) {  // one 16-token block per MFMA step
+                    // The score registers give lane half h the block's tokens 4h..4h+3 and 8+4h..8+4h+3.  The two
+                    // half-waves (same query column) trade their middle pieces, h = 0 then holds tokens 0-7 and
+                    // h = 1 tokens 8-15: the contraction slices of V's own layout, 16 bytes per (dim, half).
                     bf16x8 pf;
 #pragma unroll
                     for (int t = 0; t < 8; ++t) pf[t] = (bf16_t)st[blk4 >> 1][8 * (blk4 & 1) + t];
+                    typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
+                    u32x4p pr4 = __builtin_bit_cast(u32x4p, pf);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {   // upper half-wave of word u <-> lower half-wave of word u + 2
+                        const auto sw = __builtin_amdgcn_permlane32_swap(pr4[u], pr4[u + 2], false, false);
+                        pr4[u] = sw[0];
+                        pr4[u + 2] = sw[1];
+                    }
+                    pf = __builtin_bit_cast(bf16x8, pr4);
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        const int d = 32 * dt + c32;
-                        const bf16x8 vf = *(const bf16x8 *)&vs[d * 64 + (((2 * blk4 + h) ^ ((d >> 1) & 7)) << 3)];
+                        const bf16x8 vf = *(const bf16x8 *)&vs[vlds(blk4, h, 32 * dt + c32)];
                         o[dt] = mfma32(vf, pf, o[dt]);
                     }
                 }
             }
-            if (more) store_lds((kt + 1) & 1);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS-DMA loads have landed
             __syncthreads();
         }
         l_run += __shfl_xor(l_run, 32, 64);
