@@ -529,6 +529,30 @@ def test_long_context_decode_and_16k_prefill_mid_shape():
         rig.close()
 
 
+def test_prefill_prompt_longer_than_the_kernel_s_lds_block_table_mid_shape():
+    """A 33000-token prompt: more blocks (2063) than the 2048 ids the prefill attention kernel keeps in LDS, so the
+    last key tiles take their block ids from the table in global memory, and a ragged last tile.  Sampled rows
+    against the oracle, rows around the 32768-token boundary among them."""
+    shape = S.MID
+    T = 33000
+    n_blocks = S.blocks_for(T) + 5
+    ptab = S.shuffled_block_tables([T], n_blocks, max_blk=S.blocks_for(T), stream=14)
+    rig = Rig(shape, n_blocks, T, 1, 33024)
+    try:
+        L = rig.olayers[0]
+        xb = S.hidden_states(T, shape.d_model, stream=63)
+        y_bits = rig.prefill(xb, [0, T], ptab)
+        rng = np.random.default_rng(6)
+        rows = np.unique(np.concatenate([[0, 63, 32703, 32767, 32768, 32769, 32831, 32832, 32960, 32998, 32999],
+                                         rng.integers(0, T, 16)])).astype(np.int32)
+        Kp, Vp = L.new_cache(n_blocks, fill=ORC_SENT)
+        y_ref = L.prefill(f32(xb), [0, T], ptab, Kp, Vp, rows=rows)
+        check_tensor("33000-token prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2)
+        check_cache_against_oracle(rig, Kp, Vp, ORC_SENT)
+    finally:
+        rig.close()
+
+
 def test_released_source_weights_are_not_read_again():
     """Wide shape (every GEMM qualifies for the packed-operand kernels): after rs_release_source_weights the
     caller's matrices are overwritten with NaN patterns; prefill (short and long pass) and decode still match."""
