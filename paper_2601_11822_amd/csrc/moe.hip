@@ -6,17 +6,25 @@
 
 // ---------------------------------------------------------------------------------------------
 // Router: logits of row m = h[m] . Wr[e] for the E experts (h fragment-packed, Wr row-major), then
-// the two largest (lower index first on ties) and the softmax over those two.  One workgroup per row.
+// the two largest (lower index first on ties) and the softmax over those two.  One workgroup per R
+// consecutive rows, 256 / R threads per row.  R = 8 for long passes: in the packed layout the same
+// 16-byte chunk of 8 consecutive rows is one 128-byte line, so the 8 threads that share a chunk index
+// read whole lines (a row on its own touches 8 times the bytes it uses); R = 1 for short ones, where
+// the number of workgroups and the short loop matter more.
 // ---------------------------------------------------------------------------------------------
+template <int R>
 __global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
-    __shared__ float red[4][RS_MOE_MAX_EXPERTS];
-    const int m = blockIdx.x, tid = threadIdx.x;
+    __shared__ float red[4][R][RS_MOE_MAX_EXPERTS];
+    const int tid = threadIdx.x;
+    const int r = tid % R, t = tid / R;   // row within the group, thread within the row
+    const int m = blockIdx.x * R + r;
     const int Mt = packed_mt(a.M);
+    const int mc = min(m, a.M - 1);
     float acc[RS_MOE_MAX_EXPERTS];
 #pragma unroll
     for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) acc[e] = 0.f;
-    for (int c = tid; c < (a.d >> 3); c += 256) {
-        const bf16x8 hv = ld_bf16x8(a.h + packed_offset(m, c * 8, Mt));
+    for (int c = t; c < (a.d >> 3); c += 256 / R) {
+        const bf16x8 hv = ld_bf16x8(a.h + packed_offset(mc, c * 8, Mt));
 #pragma unroll
         for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) {
             if (e >= a.E) break;
@@ -25,15 +33,18 @@ __global__ __launch_bounds__(256) void moe_router_kernel(MoeArgs a) {
             for (int i = 0; i < 8; ++i) acc[e] += (float)hv[i] * (float)wv[i];
         }
     }
+    // lanes with equal (lane % R) hold the same row: butterfly over the other lane bits, then the 4 waves
 #pragma unroll
     for (int e = 0; e < RS_MOE_MAX_EXPERTS; ++e) {
-        const float s = wave_sum(acc[e]);
-        if ((tid & 63) == 0) red[tid >> 6][e] = s;
+        float v = acc[e];
+#pragma unroll
+        for (int o = 32; o >= R; o >>= 1) v += __shfl_xor(v, o, 64);
+        if ((tid & 63) < R) red[tid >> 6][r][e] = v;
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid < R && m < a.M) {
         float lg[RS_MOE_MAX_EXPERTS];
-        for (int e = 0; e < a.E; ++e) lg[e] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+        for (int e = 0; e < a.E; ++e) lg[e] = (red[0][r][e] + red[1][r][e]) + (red[2][r][e] + red[3][r][e]);
         int e0 = 0;
         for (int e = 1; e < a.E; ++e)
             if (lg[e] > lg[e0]) e0 = e;
@@ -127,7 +138,10 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(MoeArgs a) {
 
 void launch_moe_route_and_gather(hipStream_t st, const MoeArgs &a) {
     if (a.M <= 0) return;
-    hipLaunchKernelGGL(moe_router_kernel, dim3(a.M), dim3(256), 0, st, a);
+    if (a.M >= 512)   // a function of the row count alone
+        hipLaunchKernelGGL(moe_router_kernel<8>, dim3((a.M + 7) / 8), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(moe_router_kernel<1>, dim3(a.M), dim3(256), 0, st, a);
     hipLaunchKernelGGL(moe_plan_kernel, dim3(1), dim3(1024), 0, st, a);
     const long n = (long)a.Mg_cap * (a.d >> 3);
     hipLaunchKernelGGL(moe_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
