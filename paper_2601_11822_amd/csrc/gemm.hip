@@ -746,7 +746,7 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void gemm_skinny_kernel(GemmA
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
-                *(f32x4 *)&red[((wave * (2 * RT) + tn * 2 + tm) * 64 + lane) * 16 + 4 * j] = v;
+                *(f32x4 *)&red[(((wave * (2 * RT) + tn * 2 + tm) * 4 + j) * 64 + lane) * 4] = v;   // lanes 16 bytes apart: no bank conflicts
             }
     __syncthreads();
     // wave w finishes tiles w, w + 4, ...: sum of the 4 waves in wave order
@@ -758,9 +758,9 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void gemm_skinny_kernel(GemmA
             float *dst = part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * (32 * RT) + 32 * tn;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                f32x4 v = *(const f32x4 *)&red[((0 * (2 * RT) + tile) * 64 + lane) * 16 + 4 * j];
+                f32x4 v = *(const f32x4 *)&red[(((0 * (2 * RT) + tile) * 4 + j) * 64 + lane) * 4];
 #pragma unroll
-                for (int ww = 1; ww < 4; ++ww) v += *(const f32x4 *)&red[((ww * (2 * RT) + tile) * 64 + lane) * 16 + 4 * j];
+                for (int ww = 1; ww < 4; ++ww) v += *(const f32x4 *)&red[(((ww * (2 * RT) + tile) * 4 + j) * 64 + lane) * 4];
                 *(f32x4 *)(dst + 8 * j + 4 * h) = v;
             }
         }
