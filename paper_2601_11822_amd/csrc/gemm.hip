@@ -954,7 +954,22 @@ static void launch_skinny_epi(hipStream_t st, const GemmArgs &a, float *partials
     hipLaunchKernelGGL(skinny_epilogue_kernel<EPI>, dim3(eblocks), dim3(256), 0, st, a, partials, S, Nv);
 }
 
+// Whether the partial-sum pass of a plain projection (M <= 64 rows) can take the shared-activation streaming kernel.
+bool gemm_skinny_partials_shared(int N, int K) {
+    return K % 16 == 0 && skinny_kblocks(K) % (4 * RS_SHARED_CH) == 0 && N >= 4096;
+}
+
 void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *partials, int *S_out, int *Nv_out) {
+    if (gemm_skinny_partials_shared(a.N, a.K)) {
+        constexpr int CH = RS_SHARED_CH;
+        const int Nv = shared_virtual_n(a.N, EPI_STORE), S = shared_splits(a.N, a.K, EPI_STORE);
+        *S_out = S;
+        *Nv_out = Nv;
+        if (a.M <= 0 || a.N <= 0) return;
+        hipLaunchKernelGGL((gemm_skinny_shared_kernel<EPI_STORE, CH>), dim3(Nv / 256, S), dim3(256), 2 * CH * 2048, st, a, partials,
+                           skinny_kblocks(a.K) / S, skinny_kblocks(a.K), Nv);
+        return;
+    }
     constexpr int RT = RS_SKINNY_RT, PD = 10;
     const int Nv = skinny_virtual_n(a.N, EPI_STORE), S = skinny_splits(a.N, a.K, EPI_STORE);
     *S_out = S;
@@ -993,6 +1008,7 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_kernel<EPI_RESIDUAL, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_kernel<EPI_SWIGLU, RT, PD>, RT * 32768);
     set((const void *)gemm_skinny_shared_kernel<EPI_SWIGLU, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
+    set((const void *)gemm_skinny_shared_kernel<EPI_STORE, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_skinny_shared_kernel<EPI_RESIDUAL, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_direct_splitk_kernel, 5 * (128 + 256) * 32 * 2);
     set((const void *)gemm_grouped_kernel<EPI_STORE>, 131072);

@@ -89,6 +89,8 @@ void launch_gemm_skinny(hipStream_t st, const GemmArgs &a, float *partials);
 // Main pass only (a.epi must be EPI_STORE): leaves part[s][m][n], s < *S_out K-slices, row stride
 // *Nv_out floats; the product's element (m, n) is the sum of its slices in slice order.
 void launch_gemm_skinny_partials(hipStream_t st, const GemmArgs &a, float *partials, int *S_out, int *Nv_out);
+// True where that pass streams the weights with the shared-activation kernel (about HBM rate for M <= 64 rows).
+bool gemm_skinny_partials_shared(int N, int K);
 bool launch_gemm_direct_partials(hipStream_t st, const GemmArgs &a, float *part);
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);

@@ -588,7 +588,9 @@ int32_t head_greedy(rs_ctx *c, int side, const bf16_t *x, int n, float *logits, 
         GemmArgs g{w.h, (const bf16_t *)c->head.lm_head, nullptr, c->packed_lm, nullptr, nullptr, nullptr, mg, V, d, EPI_STORE,
                    0, c->side[side].cus};
         int S = 1, Nv = V;
-        if (!launch_gemm_direct_partials(st, g, c->head_part[side])) {
+        if (mg <= 64 && gemm_skinny_partials_shared(V, d)) {   // a function of the shapes alone
+            launch_gemm_skinny_partials(st, g, c->head_part[side], &S, &Nv);
+        } else if (!launch_gemm_direct_partials(st, g, c->head_part[side])) {
             if (mg > 64) return fail(RS_ERR_STATE, "head group of %d rows without the large-tile kernel", mg);
             launch_gemm_skinny_partials(st, g, c->head_part[side], &S, &Nv);
         }
