@@ -30,6 +30,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__
         const int c = t + i * TPR;
         xv[i] = c < nchunk ? ld_bf16x8(xr + c * 8) : zero_bf16x8();
     }
+    // the gains do not depend on the sum: fetched now, behind the row's own loads, not after the barrier
+    bf16x8 gv[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = t + i * TPR;
+        gv[i] = c < nchunk ? ld_bf16x8(g + c * 8) : zero_bf16x8();
+    }
 #pragma unroll
     for (int i = 0; i < NC; ++i)
 #pragma unroll
@@ -49,10 +56,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__
     for (int i = 0; i < NC; ++i) {
         const int c = t + i * TPR;
         if (c >= nchunk) break;
-        const bf16x8 gv = ld_bf16x8(g + c * 8);
         bf16x8 o;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)xv[i][e] * inv * (float)gv[e]);
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)xv[i][e] * inv * (float)gv[i][e]);
         st_bf16x8(out + packed_offset(row, c * 8, Mt), o);
     }
 }
