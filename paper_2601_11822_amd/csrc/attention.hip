@@ -493,7 +493,11 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                 for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) m_tile = fmaxf(m_tile, st[t2][i]);
-                m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
+                {   // the other half-wave holds the rest of this query column: one swap gives each lane both maxima
+                    const uint32_t mb = __builtin_bit_cast(uint32_t, m_tile);
+                    const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+                    m_tile = fmaxf(__builtin_bit_cast(float, (uint32_t)sw[0]), __builtin_bit_cast(float, (uint32_t)sw[1]));
+                }
                 const float m_new = fmaxf(m_run, m_tile);
                 const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
                 const float ms = m_safe * sc;
@@ -514,6 +518,10 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                     m_run = m_new;
                 }
                 l_run += psum;
+                // V fragments are read one block (DT fragments) ahead of their MFMAs
+                bf16x8 vfr[2][DT];
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) vfr[0][dt] = *(const bf16x8 *)&vs[vlds(0, h, 32 * dt + c32)];
 #pragma unroll
                 for (int blk4 = 0; blk4 < 4; ++blk4) {  // one 16-token block per MFMA step
                     // The score registers give lane half h the block's tokens 4h..4h+3 and 8+4h..8+4h+3.  The two
@@ -533,8 +541,9 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
                     pf = __builtin_bit_cast(bf16x8, pr4);
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        const bf16x8 vf = *(const bf16x8 *)&vs[vlds(blk4, h, 32 * dt + c32)];
-                        o[dt] = mfma32(vf, pf, o[dt]);
+                        if (blk4 + 1 < 4) vfr[(blk4 + 1) & 1][dt] = *(const bf16x8 *)&vs[vlds(blk4 + 1, h, 32 * dt + c32)];
+                        o[dt] = mfma32(vfr[blk4 & 1][dt], pf, o[dt]);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
