@@ -368,9 +368,26 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     }
 }
 
+// Order of the output tiles: super columns of four column tiles, inside one the row tiles four at a time, a
+// 4 x 4 block column by column.  Tiles that run at the same time on an XCD (16 on half the chip, 32 on the whole
+// chip) then share four weight slabs and four or eight activation slabs, whatever the number of row tiles: with
+// plain column-major order an XCD's set was all rows of one or two columns, and each round re-read the whole
+// activation matrix.
+__device__ __forceinline__ void tile_rc(int t, int m_tiles, int n_tiles, int &r, int &c) {
+    constexpr int CW = 4, RH = 4;
+    const int per_sc = CW * m_tiles;
+    const int sc = t / per_sc, c0 = sc * CW;
+    const int w = min(CW, n_tiles - c0);      // the last super column may be narrower
+    const int u = t - sc * per_sc;
+    const int rb = u / (RH * w), r0 = rb * RH;
+    const int hgt = min(RH, m_tiles - r0);    // the last row block may be lower
+    const int v = u - rb * (RH * w);
+    r = r0 + v % hgt;
+    c = c0 + v / hgt;
+}
+
 // The flat workgroup id is remapped so that the workgroups resident on one XCD (ids congruent
-// mod 8) own a contiguous run of column-major tiles: all row tiles of a few column tiles, served
-// by that XCD's L2.
+// mod 8) own a contiguous run of tiles in that order, served by that XCD's L2.
 template <int BM, int BN, int EPI, int NS, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(GemmArgs a, int m_tiles, int n_tiles) {
     extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
@@ -378,7 +395,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_direct_kernel(GemmArgs a, int m_
     const int per_xcd = (total + 7) >> 3;
     const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (t >= total) return;
-    gemm_direct_tile<BM, BN, EPI, NS, NW>(a, (t % m_tiles) * BM, t / m_tiles, smem);
+    int r, c;
+    tile_rc(t, m_tiles, n_tiles, r, c);
+    gemm_direct_tile<BM, BN, EPI, NS, NW>(a, r * BM, c, smem);
 }
 
 // Whole rounds of 256x256 tiles, then a last half round: when the 256x256 tiles do not divide by
@@ -390,17 +409,22 @@ template <int EPI>
 __global__ __launch_bounds__(256) void gemm_direct_mixed_kernel(GemmArgs a, int m_tiles, int n_full, int n_half) {
     extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
     const int id = blockIdx.x;
+    const int n_tiles = (n_full + (n_half >> 1)) / m_tiles;   // column tiles
     if (id < n_full) {
         const int t = (id & 7) * (n_full >> 3) + (id >> 3);          // n_full is a multiple of 8
-        gemm_direct_tile<256, 256, EPI, 4, 4>(a, (t % m_tiles) * 256, t / m_tiles, smem);
+        int r, c;
+        tile_rc(t, m_tiles, n_tiles, r, c);
+        gemm_direct_tile<256, 256, EPI, 4, 4>(a, r * 256, c, smem);
     } else {
         const int j = id - n_full;
         const int u = (j & 7) * ((n_half + 7) >> 3) + (j >> 3);
         if (u >= n_half) return;
         const int t = n_full + (u >> 1);
-        const int bm = (t % m_tiles) * 256 + (u & 1) * 128;
+        int r, c;
+        tile_rc(t, m_tiles, n_tiles, r, c);
+        const int bm = r * 256 + (u & 1) * 128;
         if (bm >= a.M) return;
-        gemm_direct_tile<128, 256, EPI, 5, 4>(a, bm, t / m_tiles, smem);
+        gemm_direct_tile<128, 256, EPI, 5, 4>(a, bm, c, smem);
     }
 }
 
