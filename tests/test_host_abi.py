@@ -223,3 +223,13 @@ def test_release_source_weights_only_where_the_packed_copies_suffice():
     with pytest.raises(rs.RapidServeError) as e:
         t.release_source_weights(0)
     assert e.value.code == rs.RS_ERR_STATE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py with --gpus above 1 exits with a message that says so, before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "ONE GPU" in (p.stderr + p.stdout)
