@@ -47,6 +47,7 @@ struct DecodeAttnArgs {
     float *part_ml;  // [B][Hq][n_chunks][2]
     int B, Hq, Hkv, hd, max_blk, n_blocks, max_ctx, n_chunks;
     float scale_log2;
+    int chunk_major;   // order of the workgroups only (results do not depend on it): chunks slowest, else requests slowest
 };
 #define RS_SKINNY_TARGET_WGS 384  // the skinny GEMM splits K until it has about this many workgroups
 #define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention

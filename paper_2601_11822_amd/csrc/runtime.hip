@@ -559,7 +559,7 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
                       B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
                       (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
-                      (float)(1.4426950408889634 / std::sqrt((double)hd))};
+                      (float)(1.4426950408889634 / std::sqrt((double)hd)), c->side[RS_SIDE_DECODE].cus < RS_TOTAL_CUS};
     launch_decode_attention(st, da);
     tick(c, RS_SIDE_DECODE, 4);
     ok = run_post_attention(c, RS_SIDE_DECODE, st, w, lw, c->packed[layer], c->moe[layer], (const bf16_t *)x_in, (bf16_t *)x_out, B, skinny) && ok;
