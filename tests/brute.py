@@ -43,9 +43,12 @@ def dense_causal_attention(q, k, v):
     return out
 
 
-def layer_dense(w, shape, x, cu_seqlens, prior_k=None, prior_v=None):
+def layer_dense(w, shape, x, cu_seqlens, prior_k=None, prior_v=None, stages=False):
     """Whole layer in float64 for a batch of independent requests, no paging at all.
-    w: dict of float arrays [out,in].  Returns y[T,d], and rotated k, v [T,Hkv,hd]."""
+    w: dict of float arrays [out,in].  Returns y[T,d], and rotated k, v [T,Hkv,hd]; with
+    stages=True also a dict of the intermediates: h (first RMSNorm), qkv (rotated q, rotated k,
+    v, concatenated as the projection lays them out), attn, x1 (after the attention residual),
+    act (silu(gate) * up)."""
     d, Hq, Hkv, hd = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     x = np.asarray(x, np.float64)
     T = x.shape[0]
@@ -70,4 +73,8 @@ def layer_dense(w, shape, x, cu_seqlens, prior_k=None, prior_v=None):
     up = h2 @ W["wu"].T
     act = gate / (1.0 + np.exp(-gate)) * up
     y = x1 + act @ W["wd"].T
+    if stages:
+        st = {"h": h, "qkv": np.concatenate([q.reshape(T, -1), k.reshape(T, -1), v.reshape(T, -1)], axis=1),
+              "attn": o.reshape(T, Hq * hd), "x1": x1, "act": act}
+        return y, k, v, st
     return y, k, v

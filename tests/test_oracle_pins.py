@@ -376,3 +376,69 @@ def test_oracle_reports_block_errors():
         L.prefill(x, [0, 20], np.array([[0, 2]], np.int32), Kc, Vc)      # id out of range
     with pytest.raises(ValueError):
         L.prefill(x, [0, 20], np.array([[0]], np.int32), Kc, Vc)         # table too short
+
+
+# ---------------------------------------------------------------- the taps the GPU stage checks rest on
+def _close(a, b, tol=1e-5):
+    return np.abs(np.asarray(a, np.float64) - b).max() <= tol * max(np.abs(b).max(), 1e-30)
+
+
+def test_prefill_taps_hold_the_intermediates_they_name():
+    """Every tap of the prefill layer against the float64 dense evaluation: h is the first
+    RMSNorm's output, qkv holds ROTATED q and k (v unrotated), attn the attention output, x1 the
+    hidden state after the attention residual, act silu(gate)*up.  Two ragged requests."""
+    shape = SMALL
+    wb, w32 = _w32(shape)
+    cu = [0, 21, 55]
+    xb = S.hidden_states(55, shape.d_model)
+    tabs = S.shuffled_block_tables([21, 34], 9)
+    _, _, _, (y, taps) = _prefill(shape, wb, xb, cu, tabs, 9, taps=True)
+    y64, _, _, st = brute.layer_dense(w32, shape, S.bf16_bits_to_f32(xb), cu, stages=True)
+    assert _close(y, y64)
+    for name in ("h", "qkv", "attn", "x1", "act"):
+        assert taps[name].shape == st[name].shape, name
+        assert _close(taps[name], st[name]), name
+    # the taps are different tensors: a tap wired to the wrong buffer cannot pass by accident
+    qd = shape.q_dim
+    assert not _close(taps["qkv"][:, :qd], st["attn"], 1e-2) and not _close(taps["x1"], st["h"], 1e-2)
+
+
+def test_prefill_taps_in_row_sampled_mode_are_scattered_to_their_rows():
+    """Row-sampled mode: x1 and act of evaluated row r sit at row r of the tap (not at its index in
+    the sample), rows not evaluated stay zero, and h / qkv still cover every row."""
+    shape = SMALL
+    wb, w32 = _w32(shape)
+    T = 50
+    xb = S.hidden_states(T, shape.d_model)
+    tabs = S.shuffled_block_tables([T], 5)
+    rows = [3, 0, 49, 16, 17]          # unsorted on purpose
+    _, _, _, (y, taps) = _prefill(shape, wb, xb, [0, T], tabs, 5, rows=rows, taps=True)
+    y64, _, _, st = brute.layer_dense(w32, shape, S.bf16_bits_to_f32(xb), [0, T], stages=True)
+    assert _close(y, y64[rows])
+    assert _close(taps["h"], st["h"]) and _close(taps["qkv"], st["qkv"])
+    others = np.setdiff1d(np.arange(T), rows)
+    for name in ("attn", "x1", "act"):
+        assert _close(taps[name][rows], st[name][rows]), name
+        assert np.all(taps[name][others] == 0.0), name
+
+
+def test_decode_taps_hold_the_intermediates_they_name():
+    """Decode taps: request i's new token is the last row of a dense float64 evaluation of its
+    whole sequence; every tap row equals that row's intermediate."""
+    shape = SMALL
+    wb, w32 = _w32(shape)
+    L = oracle.OracleLayer.from_shape(shape, wb)
+    ctx = np.array([15, 16, 33, 0], np.int32)
+    nb = 9
+    tabs = S.shuffled_block_tables([int(c) + 1 for c in ctx], nb, stream=2)
+    Kc, Vc = L.new_cache(nb)
+    seqs = [S.bf16_bits_to_f32(S.hidden_states(int(c) + 1, shape.d_model, stream=20 + i)) for i, c in enumerate(ctx)]
+    for i, c in enumerate(ctx):
+        if c:
+            L.prefill(seqs[i][:c], [0, int(c)], tabs[i:i + 1], Kc, Vc)
+    y, taps = L.decode(np.stack([s[-1] for s in seqs]), ctx, tabs, Kc, Vc, taps=True)
+    for i, c in enumerate(ctx):
+        y64, _, _, st = brute.layer_dense(w32, shape, seqs[i], [0, int(c) + 1], stages=True)
+        assert _close(y[i], y64[-1])
+        for name in ("h", "qkv", "attn", "x1", "act"):
+            assert _close(taps[name][i], st[name][-1]), (i, name)
