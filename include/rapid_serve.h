@@ -238,8 +238,11 @@ int32_t rs_choose_split(rs_ctx *ctx, int32_t decode_batch, int64_t sum_ctx, int3
 
 /* The hipStream_t a side currently enqueues on (valid until the next rs_set_cu_split). */
 int32_t rs_get_stream(rs_ctx *ctx, int32_t side, void **hip_stream_out);
-/* Blocks until the side's work is done; reports RS_ERR_BAD_BLOCK if a kernel met a bad id
- * since the last rs_sync (the flag is then cleared). */
+/* Blocks until the side's work is done (this side's stream only: it does not wait for the other side).
+ * Reports what the side's kernels met since its last rs_sync, then clears it: RS_ERR_BAD_BLOCK for a block
+ * id outside the pool, a position outside the rotary table or a context length outside [1, max_ctx];
+ * RS_ERR_BAD_ARG for a token outside the vocabulary.  rs_step_tokens and the engine report the same
+ * conditions themselves, one step late, when they read a step's tokens. */
 int32_t rs_sync(rs_ctx *ctx, int32_t side);
 /* Timing with HIP events on the side's own stream: rs_mark records event slot `slot`
  * (0..RS_MAX_MARKS-1) on the side's current stream; rs_elapsed_ms waits for both marks and gives
@@ -415,6 +418,11 @@ int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int3
 /* Host-clock times in seconds since the context was created: [0] submission, [1] the moment the
  * host saw the request's first token, [2] its latest token (0 while there is none). */
 int32_t rs_request_times(rs_ctx *ctx, int64_t req_id, double times_out[3]);
+/* Forgets a FINISHED request (rs_submit or rs_submit_tokens) whose output has been read: its record
+ * (tokens, times, state) is dropped and the id may be used again; a serving loop that runs for long calls
+ * this for every request it has collected, or the table grows with every request.  RS_ERR_STATE while
+ * the request is not finished (engine: until its end flag is set), RS_ERR_BAD_ARG if unknown. */
+int32_t rs_request_release(rs_ctx *ctx, int64_t req_id);
 int32_t rs_debug_push_sampled(rs_ctx *ctx, int64_t req_id, int32_t token);
 
 /* ---- engine: the two asynchronous sides of section 4.4 as two threads ---------------------------

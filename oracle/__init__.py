@@ -205,6 +205,22 @@ class OracleLayer:
         return cls(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                    shape.ffn_dim, shape.rms_eps, shape.rope_base, weights_bf16)
 
+    # ---- single steps of the layer on caller-supplied operands: the same C routines the layer
+    # calls (orc_linear_t, orc_rmsnorm), with this layer's weights, for stage-by-stage checks
+    def project(self, name: str, a) -> np.ndarray:
+        """a[M,K] @ W^T for W = one of "wqkv", "wo", "wg", "wu", "wd" ([N,K])."""
+        a = _f32c(a)
+        wt = self._keep[name + "_t"]
+        K, N = wt.shape
+        assert a.ndim == 2 and a.shape[1] == K
+        out = np.empty((a.shape[0], N), dtype=np.float32)
+        lib().orc_linear_t(_fp(a), _fp(wt), ctypes.c_int64(a.shape[0]), ctypes.c_int64(N), ctypes.c_int64(K), _fp(out))
+        return out
+
+    def norm(self, which: int, x) -> np.ndarray:
+        """RMSNorm with the layer's first (which = 1) or second (which = 2) gain vector."""
+        return rmsnorm(x, self._keep["g1" if which == 1 else "g2"], self.eps)
+
     def new_cache(self, n_blocks: int, fill: float = 0.0):
         shp = (n_blocks, self.block, self.hkv, self.hd)
         return np.full(shp, fill, dtype=np.float32), np.full(shp, fill, dtype=np.float32)

@@ -32,7 +32,7 @@ EXPORTS = [
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
-    "rs_debug_push_sampled", "rs_request_times", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
+    "rs_debug_push_sampled", "rs_request_times", "rs_request_release", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
 ]
 
 
@@ -385,6 +385,9 @@ class Context:
         t = (ctypes.c_double * 3)()
         _check(self._lib.rs_request_times(self._h, ctypes.c_int64(req_id), t))
         return t[0], t[1], t[2]
+
+    def request_release(self, req_id: int):
+        _check(self._lib.rs_request_release(self._h, ctypes.c_int64(req_id)))
 
     def engine_start(self):
         _check(self._lib.rs_engine_start(self._h))

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a) {
 
     int n_keys = a.ctx_lens[b] + 1;
     if (n_keys < 1 || n_keys > a.max_ctx) {
-        if (tid == 0 && chunk == 0 && hk == 0) atomicOr(a.err_flag, 4);
+        if (tid == 0 && chunk == 0 && hk == 0) atomicOr(a.err_flag, 8);
         if (n_keys < 1) return;
         n_keys = a.max_ctx;
     }

@@ -27,11 +27,7 @@ __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t *p) { return *(const bf
 // streaming read: data that is used once (decode weights, cached K/V) should not displace the other
 // side's working set from the shared caches
 __device__ __forceinline__ bf16x8 ld_bf16x8_stream(const bf16_t *p) {
-#ifdef RS_NO_STREAM_HINT
-    return *(const bf16x8 *)p;
-#else
     return __builtin_nontemporal_load((const bf16x8 *)p);
-#endif
 }
 __device__ __forceinline__ void st_bf16x8(bf16_t *p, bf16x8 v) { *(bf16x8 *)p = v; }
 __device__ __forceinline__ bf16x8 zero_bf16x8() {

@@ -159,7 +159,14 @@ struct rs_ctx {
                       size_t stride_gu = 0, stride_d = 0; };
     std::vector<MoeLayer> moe;
     CosSin *rope = nullptr;
+    // One error word per side (kernels OR bits into it: 1 position outside the rotary table, 2 block id outside
+    // the pool, 4 token outside the vocabulary, 8 context length outside [1, max_ctx]) and its pinned host
+    // mirrors: h_err[side] is what rs_sync reads, h_err[2 + i] travels with decode step buffer i, h_err[4]
+    // with a prefill pass of the serving loop.  Every copy and clear runs on the side's own stream: a
+    // blocking copy on the null stream would make one side wait for the other.
     int32_t *err_flag = nullptr;
+    int32_t *h_err = nullptr;
+    int32_t step_err = 0;            // bits met by serving steps and not yet reported
     Workspace ws[2];
     int last_rows[2] = {0, 0};   // rows of each side's last layer call: fixes the packed layout of h/attn/act
     // captured decode steps, keyed by everything a captured launch bakes in (rs_decode_layer_graph)
@@ -192,6 +199,7 @@ struct rs_ctx {
     std::deque<int64_t> arrival;  // FCFS order of all live requests
     std::unordered_map<int64_t, Request> reqs;
     std::vector<int64_t> running;  // decode batch, in promotion order
+    std::vector<int64_t> dead;     // engine: finished requests whose table entry goes once no staged step names them
     std::vector<int64_t> prefill_ids;   // the prompts of the prefill pass in flight (one pass at a time)
     bool prefill_host_done = false;     // host-only contexts: rs_debug_complete_prefill
     hipEvent_t prefill_ev = nullptr;    // end of that pass
@@ -508,11 +516,11 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     if (skinny) launch_gemm_skinny(st, gq, w.partials);
     else ok = launch_gemm_tiled(st, gq);
     tick(c, RS_SIDE_PREFILL, 2);
-    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag, T, m.n_q_heads, m.n_kv_heads, hd,
+    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, nullptr, c->err_flag + RS_SIDE_PREFILL, T, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, seq};
     launch_rope_kvwrite(st, ra);
     tick(c, RS_SIDE_PREFILL, 3);
-    PrefillAttnArgs pa{w.qkv, nqkv, w.attn, kp, vp, tables, c->err_flag, m.n_q_heads, m.n_kv_heads, hd,
+    PrefillAttnArgs pa{w.qkv, nqkv, w.attn, kp, vp, tables, c->err_flag + RS_SIDE_PREFILL, m.n_q_heads, m.n_kv_heads, hd,
                        max_blk, c->pool.n_blocks, (float)(1.4426950408889634 / std::sqrt((double)hd)), seq};
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
@@ -552,11 +560,11 @@ int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, co
     else ok = launch_gemm_tiled(st, g);
     tick(c, RS_SIDE_DECODE, 2);
     SeqInfo none{};
-    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, ctx_lens, c->err_flag, B, m.n_q_heads, m.n_kv_heads, hd,
+    RopeKvArgs ra{w.qkv, c->rope, kp, vp, tables, ctx_lens, c->err_flag + RS_SIDE_DECODE, B, m.n_q_heads, m.n_kv_heads, hd,
                   max_blk, c->pool.n_blocks, m.max_pos, none};
     launch_rope_kvwrite(st, ra);
     tick(c, RS_SIDE_DECODE, 3);
-    DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag, w.part_o, w.part_ml,
+    DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag + RS_SIDE_DECODE, w.part_o, w.part_ml,
                       B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
                       (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
                       (float)(1.4426950408889634 / std::sqrt((double)hd)), c->side[RS_SIDE_DECODE].cus < RS_TOTAL_CUS};
@@ -600,6 +608,25 @@ int32_t head_greedy(rs_ctx *c, int side, const bf16_t *x, int n, float *logits, 
     }
     HIP_TRY(hipGetLastError());
     return RS_OK;
+}
+
+// The status a set of error bits stands for (see rs_ctx::err_flag).
+int32_t report_flag(int32_t flag) {
+    if (flag & 4) return fail(RS_ERR_BAD_ARG, "a kernel met a token outside the vocabulary (flag %d)", flag);
+    return fail(RS_ERR_BAD_BLOCK, "a kernel skipped an illegal block id, rotary position or context length (flag %d)", flag);
+}
+
+// Captured decode steps bake in the addresses of the layer's packed matrices: whenever those may
+// change (rs_set_weights, rs_set_moe_weights) every cached graph of the layer is destroyed.
+void drop_layer_graphs(rs_ctx *c, int32_t layer) {
+    for (auto it = c->graphs.begin(); it != c->graphs.end();) {
+        if (it->first.layer == layer) {
+            (void)hipGraphExecDestroy(it->second);
+            it = c->graphs.erase(it);
+        } else {
+            ++it;
+        }
+    }
 }
 
 int32_t enter_mode(rs_ctx *c, int mode) {
@@ -701,8 +728,10 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
         }
         HIP_TRY(hipMalloc(&c->rope, tab.size() * sizeof(CosSin)));
         HIP_TRY(hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(CosSin), hipMemcpyHostToDevice));
-        HIP_TRY(hipMalloc(&c->err_flag, sizeof(int32_t)));
-        HIP_TRY(hipMemset(c->err_flag, 0, sizeof(int32_t)));
+        HIP_TRY(hipMalloc(&c->err_flag, 2 * sizeof(int32_t)));
+        HIP_TRY(hipMemset(c->err_flag, 0, 2 * sizeof(int32_t)));
+        HIP_TRY(hipHostMalloc((void **)&c->h_err, 8 * sizeof(int32_t)));
+        std::memset(c->h_err, 0, 8 * sizeof(int32_t));
         int32_t r = alloc_ws(c, c->ws[RS_SIDE_PREFILL], limits->max_prefill_tokens, false);
         if (r) return r;
         r = alloc_ws(c, c->ws[RS_SIDE_DECODE], limits->max_decode_batch, true);
@@ -759,6 +788,7 @@ int32_t rs_destroy(rs_ctx *c) {
                 if (q) (void)hipFree(q);
         if (c->rope) (void)hipFree(c->rope);
         if (c->err_flag) (void)hipFree(c->err_flag);
+        if (c->h_err) (void)hipHostFree(c->h_err);
         if (c->d_ctx) (void)hipFree(c->d_ctx);
         if (c->d_tab) (void)hipFree(c->d_tab);
         if (c->d_ptab) (void)hipFree(c->d_ptab);
@@ -798,6 +828,8 @@ int32_t rs_set_weights(rs_ctx *c, int32_t layer, const rs_layer_weights *w) {
     if (c->gpu) {
         // the GEMM kernels stream the matrices in MFMA fragment order: repack them once, here
         HIP_TRY(hipSetDevice(c->device));
+        HIP_TRY(hipDeviceSynchronize());   // a captured step of this layer may still be running
+        drop_layer_graphs(c, layer);
         const rs_model_desc &m = c->m;
         const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
         rs_ctx::PackedLayer &pl = c->packed[layer];
@@ -832,6 +864,7 @@ int32_t rs_set_moe_weights(rs_ctx *c, int32_t layer, const rs_moe_weights *w) {
         if (!w->router || !w->wg || !w->wu || !w->wd) return fail(RS_ERR_BAD_ARG, "null weight pointer");
         HIP_TRY(hipSetDevice(c->device));
         HIP_TRY(hipDeviceSynchronize());
+        drop_layer_graphs(c, layer);
         ml.stride_gu = packed_weight_elems(f, d);
         ml.stride_d = packed_weight_elems(d, f);
         if (ml.E != E) {
@@ -958,7 +991,7 @@ int32_t rs_embed(rs_ctx *c, int32_t side, const int32_t *tokens, int32_t n, void
     if (rc) return rc;
     if (!tokens || !x_out) return fail(RS_ERR_BAD_ARG, "null argument");
     HIP_TRY(hipSetDevice(c->device));
-    launch_embed(c->side[side].stream, EmbedArgs{tokens, nullptr, (const bf16_t *)c->head.embed, (bf16_t *)x_out, c->err_flag, n,
+    launch_embed(c->side[side].stream, EmbedArgs{tokens, nullptr, (const bf16_t *)c->head.embed, (bf16_t *)x_out, c->err_flag + side, n,
                                                  c->m.d_model, c->head.vocab});
     HIP_TRY(hipGetLastError());
     return RS_OK;
@@ -1117,15 +1150,18 @@ int32_t rs_get_stream(rs_ctx *c, int32_t side, void **out) {
 int32_t rs_sync(rs_ctx *c, int32_t side) {
     if (!c || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
     if (!c->gpu) return RS_OK;
-    if (c->side[side].stream) HIP_TRY(hipStreamSynchronize(c->side[side].stream));
-    int32_t flag = 0;
-    HIP_TRY(hipMemcpy(&flag, c->err_flag, sizeof flag, hipMemcpyDeviceToHost));
-    if (flag) {
-        HIP_TRY(hipMemset(c->err_flag, 0, sizeof flag));
-        if (flag & 4) return fail(RS_ERR_BAD_ARG, "a kernel met a token outside the vocabulary (flag %d)", flag);
-        return fail(RS_ERR_BAD_BLOCK, "a kernel skipped an illegal block id, position or context length (flag %d)", flag);
+    hipStream_t st = c->side[side].stream;
+    if (!st) return RS_OK;
+    // the side's own error word, copied and cleared on the side's own stream: nothing here waits for the other side
+    HIP_TRY(hipMemcpyAsync(&c->h_err[side], c->err_flag + side, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    int32_t flag = c->h_err[side] | (side == RS_SIDE_DECODE ? c->step_err : 0);
+    if (side == RS_SIDE_DECODE) c->step_err = 0;
+    if (c->h_err[side]) {
+        HIP_TRY(hipMemsetAsync(c->err_flag + side, 0, sizeof(int32_t), st));
+        HIP_TRY(hipStreamSynchronize(st));
     }
-    return RS_OK;
+    return flag ? report_flag(flag) : RS_OK;
 }
 
 int32_t rs_mark(rs_ctx *c, int32_t side, int32_t slot) {
@@ -1341,6 +1377,7 @@ void harvest(rs_ctx *c, int f) {
         Request &r = c->reqs[c->inflight[f][i]];
         accept_token(c, r, c->gpu ? c->h_sampled[f][i] : next_injected(r));
     }
+    if (c->gpu) c->step_err |= c->h_err[2 + f];   // reported by the serving step that harvested it
     c->pending[f] = false;
     c->inflight[f].clear();
 }
@@ -1363,7 +1400,14 @@ int32_t harvest_ready(rs_ctx *c, bool must) {
     return RS_OK;
 }
 
+bool in_flight(const rs_ctx *c, int64_t id) {
+    for (int f = 0; f < 2; ++f)
+        if (c->pending[f] && std::find(c->inflight[f].begin(), c->inflight[f].end(), id) != c->inflight[f].end()) return true;
+    return false;
+}
+
 void release_request(rs_ctx *c, Request &r) {
+    if (c->engine) c->dead.push_back(r.id);
     set_state(r, FINISHED);
     rs_kv_free(c, r.id);
     if (r.done) { (void)hipEventDestroy(r.done); r.done = nullptr; }
@@ -1418,7 +1462,7 @@ int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wa
     HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, (size_t)n * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipEventRecord(c->pstaged, st));
-    EmbedArgs ea{c->d_prompts, nullptr, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag, T, c->m.d_model, c->head.vocab};
+    EmbedArgs ea{c->d_prompts, nullptr, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + RS_SIDE_PREFILL, T, c->m.d_model, c->head.vocab};
     ea.slots = c->d_pslots;
     ea.slot_stride = c->lim.max_context;
     ea.seq = seq;
@@ -1432,6 +1476,7 @@ int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wa
     int32_t rc = head_greedy(c, RS_SIDE_PREFILL, w.x1, n, nullptr, c->d_pfirst, c->d_pslots, c->d_tok);
     if (rc) return rc;
     HIP_TRY(hipMemcpyAsync(c->h_pfirst, c->d_pfirst, n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&c->h_err[4], c->err_flag + RS_SIDE_PREFILL, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     return RS_OK;
 }
 
@@ -1442,10 +1487,15 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     const int maxB = c->lim.max_decode_batch;
     if (c->gpu) HIP_TRY(hipSetDevice(c->device));
 
-    // 0. tokens of earlier steps that have reached the host
+    // 0. tokens of earlier steps that have reached the host, and the error bits their kernels raised
     if (token_mode) {
         int32_t rc = harvest_ready(c, false);
         if (rc) return rc;
+    }
+    if (c->step_err) {
+        const int32_t flag = c->step_err;
+        c->step_err = 0;
+        return report_flag(flag);
     }
     // 1a. the prefill "notification": event completed -> PREFILL_DONE
     if (c->engine) {
@@ -1468,6 +1518,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
         }
         if (done) {
             c->prefill_host_done = false;
+            if (c->gpu && token_mode) c->step_err |= c->h_err[4];
             for (size_t i = 0; i < c->prefill_ids.size(); ++i) {
                 Request &r = c->reqs[c->prefill_ids[i]];
                 set_state(r, PREFILL_DONE);
@@ -1483,6 +1534,15 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     // 1b. retire requests that produced all their tokens
     out->n_finished += retire_finished(c);
     while (!c->arrival.empty() && c->reqs[c->arrival.front()].state == FINISHED) c->arrival.pop_front();
+    // engine: the application reads results from the Result records, so the decode thread's own table entry of a
+    // finished request goes as soon as no staged step still names it (the table would otherwise grow for ever)
+    for (size_t i = 0; i < c->dead.size();) {
+        const int64_t id = c->dead[i];
+        if (in_flight(c, id) || std::find(c->arrival.begin(), c->arrival.end(), id) != c->arrival.end()) { ++i; continue; }
+        c->reqs.erase(id);
+        c->dead[i] = c->dead.back();
+        c->dead.pop_back();
+    }
     // 1c. promote finished prefills into the decode batch, FCFS
     for (int64_t id : c->arrival) {
         Request &r = c->reqs[id];
@@ -1602,7 +1662,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             const void *x_first = in->decode_hidden;
             void *x_out = in->decode_out;
             if (token_mode) {
-                launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag, B,
+                launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + RS_SIDE_DECODE, B,
                                            c->m.d_model, c->head.vocab});
                 x_first = w.xbuf;
                 x_out = w.xbuf;
@@ -1616,6 +1676,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 int32_t rc = head_greedy(c, RS_SIDE_DECODE, w.xbuf, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
                 if (rc) return rc;
                 HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                HIP_TRY(hipMemcpyAsync(&c->h_err[2 + flip], c->err_flag + RS_SIDE_DECODE, sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipEventRecord(c->sampled_ev[flip], st));
             }
             c->step_end_idx ^= 1;
@@ -1735,6 +1796,7 @@ int32_t engine_run_prompts(rs_ctx *c, const std::vector<PrefillMsg> &ms) {
     rc = enqueue_prompts(c, items.data(), (int)items.size(), wait_idx >= 0 ? c->step_end[wait_idx] : nullptr);
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(c->side[RS_SIDE_PREFILL].stream));
+    if (c->h_err[4]) return report_flag(c->h_err[4]);
     return RS_OK;
 }
 
@@ -2004,6 +2066,26 @@ int32_t rs_request_output(rs_ctx *c, int64_t req_id, int32_t *tokens_out, int32_
     std::copy(r.toks.begin() + r.prompt_len, r.toks.end(), tokens_out);
     *n_out = n;
     if (finished_out) *finished_out = r.complete ? 1 : 0;
+    return RS_OK;
+}
+
+int32_t rs_request_release(rs_ctx *c, int64_t req_id) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->engine_ever) {
+        std::lock_guard<std::mutex> lr(c->res_mu);
+        auto ir = c->results.find(req_id);
+        if (ir == c->results.end()) return fail(RS_ERR_BAD_ARG, "unknown request");
+        if (!ir->second->finished.load(std::memory_order_acquire) || ir->second->state.load(std::memory_order_acquire) != FINISHED)
+            return fail(RS_ERR_STATE, "request %lld has not finished", (long long)req_id);
+        c->results.erase(ir);
+        return RS_OK;
+    }
+    auto it = c->reqs.find(req_id);
+    if (it == c->reqs.end()) return fail(RS_ERR_BAD_ARG, "unknown request");
+    if (it->second.state != FINISHED || in_flight(c, req_id))
+        return fail(RS_ERR_STATE, "request %lld has not finished", (long long)req_id);
+    c->arrival.erase(std::remove(c->arrival.begin(), c->arrival.end(), req_id), c->arrival.end());
+    c->reqs.erase(it);
     return RS_OK;
 }
 

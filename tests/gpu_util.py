@@ -36,7 +36,7 @@ def rel_err(got_f32: np.ndarray, ref_f32: np.ndarray) -> float:
 Q = 2.0 ** -8   # half an ulp of bf16 (8 significant bits) relative to the value, at most
 
 
-def tensor_fracs(got, ref, x=None, roundings=0):
+def tensor_fracs(got, ref, x=None, roundings=0, elem_mult=1.0, layers=1):
     """The parity bar for one activation tensor, as fractions of what is allowed (<= 1 passes).
 
     `got` was computed with bf16 operands and fp32 accumulation, `ref` by the fp32 oracle.  With
@@ -44,11 +44,19 @@ def tensor_fracs(got, ref, x=None, roundings=0):
     got - x against ref - x):
       max   : max|e| <= TOL * max|ref|            the stated bound: max relative error 2e-2
       rms   : rms(e) <= TOL/2 * rms(ref)          the bulk of the tensor, twice as tight
-      elem  : |e_i|  <= 3*TOL * max(|ref_i|, rms(ref row))   no element far off on its own row's
-              scale (3x: rounding q and k to bf16 perturbs sharply peaked softmax rows most)
+      elem  : |e_i|  <= elem_mult * TOL * max(|ref_i|, rms(ref row))   no element far off on its own
+              row's scale.  elem_mult is 1 (the stated 2e-2, element by element) wherever the
+              reference was computed from the SAME operands the kernel read (the own-operand stage
+              checks, and every tensor upstream of the softmax); it is 3 only where the fp32 oracle's
+              end-to-end value is compared downstream of the softmax, because the oracle keeps q and k
+              in fp32 while the kernels store them in bf16, which sharply peaked softmax rows amplify.
     For residual-stream tensors each bound is widened by `roundings` half-ulps of bf16 at the
     stored value (Q*|y|; Q*rms(y)/sqrt(3) in the rms bound): the hidden state is STORED in bf16,
-    so the delta cannot resolve finer than that whatever the branch computes."""
+    so the delta cannot resolve finer than that whatever the branch computes.
+    elem_mult=None leaves the per-element bound out (max and rms only).  layers=n is for the output
+    of a stack of n layers compared end to end: each layer's branch adds its own error and passes
+    the error of its input on with unit gain along the residual path, so to first order the errors
+    add and the three bounds are n times those of one layer."""
     ref = np.atleast_2d(np.asarray(ref, np.float64))
     got = np.atleast_2d(np.asarray(got, np.float64))
     if x is not None:
@@ -64,24 +72,31 @@ def tensor_fracs(got, ref, x=None, roundings=0):
         q_max = roundings * Q * float(np.max(np.abs(y_ref)))
         q_rms = math.sqrt(roundings) * Q / math.sqrt(3.0) * float(np.sqrt(np.mean(y_ref * y_ref)))
         q_el = roundings * Q * np.abs(y_ref)
-    return {
-        "max": float(e.max() / (TOL * float(np.max(np.abs(ref))) + q_max)),
-        "rms": float(np.sqrt(np.mean(e * e)) / (TOL / 2 * rms_all + q_rms)),
-        "elem": float(np.max(e / (3 * TOL * np.maximum(np.abs(ref), row_rms) + q_el))),
+    tol = TOL * layers
+    out = {
+        "max": float(e.max() / (tol * float(np.max(np.abs(ref))) + q_max)),
+        "rms": float(np.sqrt(np.mean(e * e)) / (tol / 2 * rms_all + q_rms)),
     }
+    if elem_mult is not None:
+        out["elem"] = float(np.max(e / (elem_mult * tol * np.maximum(np.abs(ref), row_rms) + q_el)))
+    return out
 
 
-def check_tensor(name, got, ref, x=None, roundings=0, limit=1.0):
-    f = tensor_fracs(got, ref, x, roundings)
+END_TO_END = 3.0   # elem_mult of the fp32-oracle comparisons downstream of the softmax (see tensor_fracs)
+
+
+def check_tensor(name, got, ref, x=None, roundings=0, elem_mult=1.0, layers=1):
+    f = tensor_fracs(got, ref, x, roundings, elem_mult, layers)
     print(f"  {name}: fractions of allowed error " + ", ".join(f"{k} {v:.3f}" for k, v in f.items()), flush=True)
     for k, v in f.items():
-        assert v <= limit, f"{name}: {k} error is {v:.3f} of the allowed"
+        assert v <= 1.0, f"{name}: {k} error is {v:.3f} of the allowed"
     return f
 
 
-def residual_err(y_got, y_ref, x, roundings: int = 2) -> float:
-    """Worst of the three fractions for a residual-stream output (see tensor_fracs)."""
-    return max(tensor_fracs(y_got, y_ref, x, roundings).values())
+def residual_err(y_got, y_ref, x, roundings: int = 2, elem_mult: float = END_TO_END, layers: int = 1) -> float:
+    """Worst of the three fractions for a residual-stream output against the fp32 oracle's
+    end-to-end value (see tensor_fracs)."""
+    return max(tensor_fracs(y_got, y_ref, x, roundings, elem_mult, layers).values())
 
 
 class Rig:
@@ -175,3 +190,50 @@ def check_cache_against_oracle(rig, Kc, Vc, oracle_sentinel, layer=0):
             got = S.bf16_bits_to_f32(bits)[dirty_ref]
             e = rel_err(got, ref[dirty_ref])
             assert e <= TOL, f"cache contents rel err {e}"
+
+
+def gather_prompt_kv(rig, cu, tables, layer=0):
+    """K and V of every prompt token as the GPU cache holds them (bf16 widened), [T, Hkv, hd] each,
+    gathered through the block tables: the operands the prefill attention kernel really read."""
+    kb, vb = rig.k_bits_logical(layer), rig.v_bits_logical(layer)
+    T = int(cu[-1])
+    k = np.zeros((T,) + kb.shape[2:], np.float32)
+    v = np.zeros_like(k)
+    for r in range(len(cu) - 1):
+        a, b = int(cu[r]), int(cu[r + 1])
+        pos = np.arange(b - a)
+        blk = np.asarray(tables)[r, pos // 16]
+        k[a:b] = S.bf16_bits_to_f32(kb[blk, pos % 16])
+        v[a:b] = S.bf16_bits_to_f32(vb[blk, pos % 16])
+    return k, v
+
+
+def check_stages_own_operands(rig, side, L, M, x, y_bits, *, cu=None, tables=None, ctx=None, rows=None, layer=0):
+    """Every stage downstream of the QKV projection against the oracle's routine for that stage fed
+    the operands the kernel itself read (its own bf16 intermediates, read back through
+    rs_debug_read_workspace, and the cache bits): element by element at the stated 2e-2, so that the
+    rounding of stored intermediates is outside the budget and a kernel error of a few per cent of
+    an element cannot hide.  Prefill: cu and tables given; decode: ctx and tables.  `rows` limits
+    the evaluation to those rows (large shapes)."""
+    f32 = S.bf16_bits_to_f32
+    sh = rig.shape
+    qd = sh.q_dim
+    rd = lambda which, width: f32(rig.ctx.debug_read_workspace(side, which, (M, width)))
+    q = rd(1, sh.qkv_dim)[:, :qd]
+    attn, x1, act, h2 = rd(2, qd), rd(3, sh.d_model), rd(4, sh.ffn_dim), rd(0, sh.d_model)
+    y = f32(y_bits)
+    sel = np.arange(M) if rows is None else np.asarray(rows)
+    if ctx is None:
+        k, v = gather_prompt_kv(rig, cu, tables, layer)
+        a_ref = oracle.attn_causal(q.reshape(M, sh.n_q_heads, sh.head_dim), k, v, cu, rows=rows).reshape(M, qd)
+    else:
+        a_ref = oracle.attn_paged(q.reshape(M, sh.n_q_heads, sh.head_dim), f32(rig.k_bits_logical(layer)),
+                                  f32(rig.v_bits_logical(layer)), tables, np.asarray(ctx, np.int32) + 1).reshape(M, qd)
+    out = {}
+    out["attn"] = check_tensor("own operands: attention(q, cached K/V as stored)", attn[sel], a_ref[sel])
+    out["x1"] = check_tensor("own operands: x + attn Wo", x1[sel], x[sel] + L.project("wo", attn[sel]), x[sel], 1)
+    out["h2"] = check_tensor("own operands: RMSNorm(x1)", h2[sel], L.norm(2, x1[sel]))
+    out["act"] = check_tensor("own operands: silu(h2 Wg) * (h2 Wu)", act[sel],
+                              oracle.silu_mul(L.project("wg", h2[sel]), L.project("wu", h2[sel])))
+    out["y"] = check_tensor("own operands: x1 + act Wd", y[sel], x1[sel] + L.project("wd", act[sel]), x1[sel], 1)
+    return out

@@ -7,7 +7,7 @@ import oracle
 from oracle import moe
 import paper_2601_11822_amd as rs
 import rs_synth as S
-from tests.gpu_util import TOL, Rig, check_cache_against_oracle, check_tensor, to_bits, to_dev
+from tests.gpu_util import END_TO_END, TOL, Rig, check_cache_against_oracle, check_tensor, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 f32 = S.bf16_bits_to_f32
@@ -62,11 +62,11 @@ def test_moe_prefill_matches_oracle(lens):
         Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
         x = f32(xb)
         _, x1_ref, _, _ = L.prefill(x, cu, tabs, Kc, Vc)
-        check_tensor("x1", f32(rig.ctx.debug_read_workspace(rs.RS_SIDE_PREFILL, 3, (T, shape.d_model))), x1_ref, x, 1)
+        check_tensor("x1", f32(rig.ctx.debug_read_workspace(rs.RS_SIDE_PREFILL, 3, (T, shape.d_model))), x1_ref, x, 1, elem_mult=END_TO_END)
         sel, wt = _check_routing(rs.RS_SIDE_PREFILL, rig, L, mw, x1_ref, T)
         Kc2, Vc2 = L.new_cache(n_blocks, fill=ORC_SENT)
         y_ref, _, _, _ = L.prefill(x, cu, tabs, Kc2, Vc2, sel=sel, wt=wt)     # the oracle under the library's routing
-        check_tensor("y (sparse block)", f32(y_bits), y_ref, x, 2)
+        check_tensor("y (sparse block)", f32(y_bits), y_ref, x, 2, elem_mult=END_TO_END)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
     finally:
         rig.close()
@@ -97,7 +97,7 @@ def test_moe_decode_matches_oracle(ctx):
         _, x1_ref, _, _ = L.decode(x, ctx, tabs, Kt, Vt)
         sel, wt = _check_routing(rs.RS_SIDE_DECODE, rig, L, mw, x1_ref, B)
         y_ref, _, _, _ = L.decode(x, ctx, tabs, Kc, Vc, sel=sel, wt=wt)
-        check_tensor("decode y (sparse block)", f32(yd), y_ref, x, 2)
+        check_tensor("decode y (sparse block)", f32(yd), y_ref, x, 2, elem_mult=END_TO_END)
     finally:
         rig.close()
 

@@ -7,7 +7,8 @@ import torch
 import oracle
 import paper_2601_11822_amd as rs
 import rs_synth as S
-from tests.gpu_util import TOL, Rig, check_cache_against_oracle, check_tensor, rel_err, residual_err, to_bits, to_dev
+from tests.gpu_util import (END_TO_END, TOL, Rig, check_cache_against_oracle, check_stages_own_operands, check_tensor,
+                            rel_err, residual_err, to_bits, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -15,22 +16,26 @@ ORC_SENT = np.float32(-777.0)
 f32 = S.bf16_bits_to_f32
 
 
-def _check_stages(rig, side, taps, M, x, attention_only=False, elem_limit=1.0):
-    """Intermediate tensors against the oracle's taps, each at the bar.  The first RMSNorm buffer
-    is reused by the second one and the k columns of the qkv buffer stay unrotated (the rotated
-    keys live in the cache, which is checked separately), so those two are not compared."""
+def _check_stages(rig, side, taps, M, x, attention_only=False, stage_elem=END_TO_END):
+    """Intermediate tensors against the fp32 oracle's taps.  Upstream of the softmax (rotated q, v)
+    the stated 2e-2 holds element by element; downstream of it the oracle's end-to-end value
+    differs by the bf16 rounding of the stored q and k, amplified by peaked softmax rows, so the
+    per-element bound there is END_TO_END times wider (max and rms bounds unchanged) -- the strict
+    per-element check of those stages is check_stages_own_operands.  The first RMSNorm buffer is
+    reused by the second one and the k columns of the qkv buffer stay unrotated (the rotated keys
+    live in the cache, which is checked separately), so those two are not compared.
+    stage_elem=None: max and rms bounds only for the attention output and the SwiGLU product."""
     sh = rig.shape
     qd, kvd = sh.q_dim, sh.kv_dim
     qkv = f32(rig.ctx.debug_read_workspace(side, 1, (M, sh.qkv_dim)))
     check_tensor("q (rotated)", qkv[:, :qd], taps["qkv"][:, :qd])
     check_tensor("v", qkv[:, qd + kvd:], taps["qkv"][:, qd + kvd:])
-    f = check_tensor("attention out", f32(rig.ctx.debug_read_workspace(side, 2, (M, qd))), taps["attn"], limit=max(1.0, elem_limit))
-    assert f["max"] <= 1.0 and f["rms"] <= 1.0 and f["elem"] <= elem_limit
-    check_tensor("x1 = x + attn Wo", f32(rig.ctx.debug_read_workspace(side, 3, (M, sh.d_model))), taps["x1"], x, 1)
+    check_tensor("attention out", f32(rig.ctx.debug_read_workspace(side, 2, (M, qd))), taps["attn"], elem_mult=stage_elem)
+    check_tensor("x1 = x + attn Wo", f32(rig.ctx.debug_read_workspace(side, 3, (M, sh.d_model))), taps["x1"], x, 1,
+                 elem_mult=END_TO_END)
     if not attention_only:
-        f = check_tensor("silu(gate)*up", f32(rig.ctx.debug_read_workspace(side, 4, (M, sh.ffn_dim))), taps["act"],
-                         limit=max(1.0, elem_limit))
-        assert f["max"] <= 1.0 and f["rms"] <= 1.0 and f["elem"] <= elem_limit
+        check_tensor("silu(gate)*up", f32(rig.ctx.debug_read_workspace(side, 4, (M, sh.ffn_dim))), taps["act"],
+                     elem_mult=stage_elem)
 
 
 def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
@@ -42,7 +47,7 @@ def _prefill_case(shape, lens, n_blocks_extra=3, stream=0):
     return cu, T, n_blocks, tabs, xb
 
 
-def _run_prefill_parity(shape, lens, wo_std=None, wd_std=None, elem_limit=1.0):
+def _run_prefill_parity(shape, lens, wo_std=None, wd_std=None, stage_elem=END_TO_END):
     cu, T, n_blocks, tabs, xb = _prefill_case(shape, lens)
     rig = Rig(shape, n_blocks, T, 1, max(lens) + 1, wo_std=wo_std, wd_std=wd_std)
     try:
@@ -54,10 +59,11 @@ def _run_prefill_parity(shape, lens, wo_std=None, wd_std=None, elem_limit=1.0):
         print("prefill", shape.name, lens)
         # a loud attention branch perturbs everything downstream of it by the branch's own
         # relative error: only the attention half of the layer is judged in that case
-        _check_stages(rig, rs.RS_SIDE_PREFILL, taps, T, x, attention_only=wo_std is not None, elem_limit=elem_limit)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        check_stages_own_operands(rig, rs.RS_SIDE_PREFILL, L, T, x, y_bits, cu=cu, tables=tabs)
+        _check_stages(rig, rs.RS_SIDE_PREFILL, taps, T, x, attention_only=wo_std is not None, stage_elem=stage_elem)
         if wo_std is None:
-            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2)
+            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2, elem_mult=END_TO_END)
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -149,10 +155,11 @@ def _run_decode_parity(shape, ctx, stream=0, wo_std=None, wd_std=None):
         x = f32(xb)
         y_ref, taps = L.decode(x, ctx, tabs, Kc, Vc, taps=True)
         print("decode", shape.name, ctx.tolist())
-        _check_stages(rig, rs.RS_SIDE_DECODE, taps, B, x, attention_only=wo_std is not None)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
+        check_stages_own_operands(rig, rs.RS_SIDE_DECODE, L, B, x, y_bits, ctx=ctx, tables=tabs)
+        _check_stages(rig, rs.RS_SIDE_DECODE, taps, B, x, attention_only=wo_std is not None)
         if wo_std is None:
-            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2)
+            check_tensor("y (layer output)", f32(y_bits), y_ref, x, 2, elem_mult=END_TO_END)
         assert np.isfinite(f32(y_bits)).all()
     finally:
         rig.close()
@@ -275,6 +282,7 @@ def test_bad_block_ids_are_reported_not_dereferenced():
         after_k = rig.k_bits_logical()
         # block 1 << 20 was skipped; blocks 0 and 2 were written
         assert (after_k[0] != before_k[0]).any() and (after_k[2, :8] != before_k[2, :8]).any()
+        rig.ctx.sync(1)          # each side has its own error word: the decode side met nothing
         rig.ctx.sync(0)          # flag cleared
         with pytest.raises(rs.RapidServeError) as e:   # table too short is caught on the host
             rig.ctx.prefill_layer(0, to_dev(xb), to_dev(xb), [0, 40], torch.zeros(2, dtype=torch.int32, device="cuda"), 2)
@@ -282,6 +290,12 @@ def test_bad_block_ids_are_reported_not_dereferenced():
         with pytest.raises(rs.RapidServeError) as e:
             rig.decode(S.hidden_states(2, shape.d_model), [20, 30], np.array([[0, -1, -1, -1], [1, -5, 2, 3]], np.int32))
         assert e.value.code == rs.RS_ERR_BAD_BLOCK
+        rig.ctx.sync(0)          # ... and the prefill side nothing
+        # a context length beyond the launch's max_ctx (a position outside the rotary table, too): never used as an extent
+        with pytest.raises(rs.RapidServeError) as e:
+            rig.decode(S.hidden_states(2, shape.d_model), [70, 30], np.array([[0, 1, 2, 3], [4, 5, 6, 7]], np.int32), max_ctx=64)
+        assert e.value.code == rs.RS_ERR_BAD_BLOCK
+        rig.ctx.sync(1)
     finally:
         rig.close()
 
@@ -317,9 +331,9 @@ def test_serving_step_small_stack_matches_oracle():
             xr = f32(dec_in[i])
             for l, L in enumerate(rig.olayers):
                 xr = L.decode(xr, [prompt + i], tabs, *caches[l])
-            e = residual_err(got, xr, f32(dec_in[i]), roundings=4)   # two layers: four bf16 stores
+            e = residual_err(got, xr, f32(dec_in[i]), roundings=4, layers=n_layers)   # two layers: four bf16 stores
             print("step", i, "fraction of allowed error", e)
-            assert e <= 1.5          # and layer 0's branch error feeds layer 1
+            assert e <= 1.0
         so = rig.ctx.step(to_dev(dec_in[0]), d_out)
         assert so.n_finished == 1 and rig.ctx.request_state(5) == 5 and rig.ctx.kv_num_free() == 16
     finally:
@@ -332,17 +346,15 @@ def test_8b_layer_short_prefill_passes(lens):
     weight-streaming GEMMs, above that the large-tile kernel with its K range cut into slices for the
     projections back to d_model (few output tiles, long K).  Every stage and every row against the oracle.
 
-    The stated bar (max error <= 2e-2 of the tensor's maximum) and the rms bar hold for every stage.  The
-    additional per-element bound (error <= 6e-2 of max(|element|, its row's rms)) is widened to 1.5x for
-    the attention output and the SwiGLU product at this shape.  With d_model = 4096 the vectors are long
-    (|q| ~ 15, |k| ~ 17), so rounding q and k to bf16 moves a score by ~1e-2 and a softmax weight by ~1 %;
-    where two keys with weights ~0.4 carry values of opposite sign, that is 6-7 % of the row's rms in one
-    element (measured: of a deviation of 0.046, 0.034 comes from q's rounding, 0.010 from K's, 0.003 from
-    V's; float64 attention over the kernel's own bf16 q and cache agrees with the kernel to 0.9 %).  In the
-    product, an element's up projection carries 1.28x the error of the normalised row and is multiplied by
-    silu(gate), up to 3.5 among 10^6 elements (float32 arithmetic on the kernel's own bf16 x1 reproduces its
-    output to the last bf16 bit)."""
-    _run_prefill_parity(S.LLAMA8B, lens, elem_limit=1.5)
+    Every stage downstream of the QKV projection holds the stated 2e-2 element by element against the oracle's
+    routine for that stage fed the kernel's own bf16 operands (check_stages_own_operands).  Against the fp32
+    oracle's END-TO-END taps the stated bound on the maximum and the rms bound hold for every stage too, but
+    no per-element bound is applied to the attention output and the SwiGLU product at this shape: with
+    d_model = 4096 the vectors are long (|q| ~ 15, |k| ~ 17), so rounding q and k to bf16 for storage moves a
+    score by ~1e-2 and a softmax weight by ~1 %; where two keys with weights ~0.4 carry values of opposite
+    sign that is 6-7 % of the row's rms in one element -- a property of the bf16 storage format both sides of
+    the comparison do not share, not of the kernel's arithmetic, which the own-operand check isolates."""
+    _run_prefill_parity(S.LLAMA8B, lens, stage_elem=None)
 
 
 def test_full_size_8b_layer_sampled_rows():
@@ -370,7 +382,7 @@ def test_full_size_8b_layer_sampled_rows():
         Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
         y_ref = L.prefill(x, [0, T], ptab, Kc, Vc, rows=rows)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        check_tensor("8B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2)
+        check_tensor("8B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2, elem_mult=END_TO_END)
         # ---- decode over a directly written cache (same bits on both sides)
         kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
         rig.load_pools_from_logical(kb, vb)
@@ -378,7 +390,7 @@ def test_full_size_8b_layer_sampled_rows():
         db = S.hidden_states(B, shape.d_model, stream=50)
         yd = rig.decode(db, ctx, dtab)
         yd_ref = L.decode(f32(db), ctx, dtab, Kc, Vc)
-        check_tensor("8B decode y, batch 64", f32(yd), yd_ref, f32(db), 2)
+        check_tensor("8B decode y, batch 64", f32(yd), yd_ref, f32(db), 2, elem_mult=END_TO_END)
         # appended K/V of the new tokens: exact slots, contents to tolerance
         kg, vg = f32(rig.k_bits_logical()), f32(rig.v_bits_logical())
         changed = (rig.k_bits_logical() != kb).any(axis=(2, 3))
@@ -388,6 +400,75 @@ def test_full_size_8b_layer_sampled_rows():
             assert rel_err(kg[dtab[i, c // 16], c % 16].reshape(1, -1), Kc[dtab[i, c // 16], c % 16].reshape(1, -1)) <= TOL
             assert rel_err(vg[dtab[i, c // 16], c % 16].reshape(1, -1), Vc[dtab[i, c // 16], c % 16].reshape(1, -1)) <= TOL
         assert np.array_equal(changed, want), "decode wrote K/V slots other than each request's next position"
+    finally:
+        rig.close()
+
+
+def test_8b_layer_bit_identical_across_splits_and_concurrency_with_oracle_rows():
+    """The benchmark's layer at the partitions bench.py times.  The prefill GEMMs pick their tile
+    schedule from the partition's CU count, so: the 2048-token prefill pass at 64, 128, 192 and 256
+    prefill CUs, alone and beside a running decode loop, must give the same bits -- layer output and
+    the K/V it writes -- and so must the batch-64 decode step at 64 ... 256 decode CUs, alone and
+    beside a prefill.  Sampled prefill rows and every decode row are then compared with the oracle
+    once, at the 128/128 split under co-run (stage by stage on the kernels' own operands at 2e-2
+    per element, and end to end)."""
+    shape = S.LLAMA8B
+    T, B = 2048, 64
+    ctx = S.uniform_context_lengths(B, 512, 4096)
+    counts = [int(c) + 1 for c in ctx] + [T]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 64
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)))
+    dtab, ptab = tabs[:B], tabs[B:B + 1]
+    rig = Rig(shape, n_blocks, T, B, int(ctx.max()) + 1, sentinel=0x7FC1)
+    try:
+        L = rig.olayers[0]
+        xb = S.hidden_states(T, shape.d_model, stream=0)
+        db = S.hidden_states(B, shape.d_model, stream=50)
+        kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
+        mine = torch.from_numpy(ptab[0, :S.blocks_for(T)].astype(np.int64)).cuda()
+        ref_bits = None
+        for (pc, dc), beside in [((256, 256), False), ((64, 192), False), ((128, 128), False), ((192, 64), False),
+                                 ((256, 0), False), ((0, 256), False), ((64, 192), True), ((128, 128), True)]:
+            rig.load_pools_from_logical(kb, vb)
+            rig.ctx.set_cu_split(pc, dc)
+            print("split", (pc, dc), "co-running" if beside else "alone", flush=True)
+            yp = yd = None
+            if beside:
+                # decode steps in front of, beside and behind the prefill pass
+                for _ in range(4):
+                    rig.decode(db, ctx, dtab, sync=False)
+                yp_t = rig.prefill(xb, [0, T], ptab, sync=False)
+                for _ in range(6):
+                    yd_t = rig.decode(db, ctx, dtab, sync=False)
+                rig.ctx.sync(rs.RS_SIDE_PREFILL); rig.ctx.sync(rs.RS_SIDE_DECODE)
+                yp, yd = to_bits(yp_t), to_bits(yd_t)
+            else:
+                if pc:
+                    yp = rig.prefill(xb, [0, T], ptab)
+                if dc:
+                    yd = rig.decode(db, ctx, dtab)
+            got = {"yp": yp, "yd": yd,
+                   "k": to_bits(rig.k_pool[0].index_select(0, mine)) if pc else None,
+                   "v": to_bits(rig.v_pool[0].index_select(0, mine)) if pc else None}
+            if ref_bits is None:
+                ref_bits = got
+            for name, val in got.items():
+                if val is not None:
+                    assert np.array_equal(val, ref_bits[name]), f"{name} differs at split {(pc, dc)}, beside={beside}"
+        # ---- the state left by the last configuration (128/128 under co-run) against the oracle
+        x, xd = f32(xb), f32(db)
+        rng = np.random.default_rng(11)
+        rows = np.unique(np.concatenate([[0, 1, 15, 16, 17, 127, 128, 255, 256, 1023, 1024, 2046, 2047],
+                                         rng.integers(0, T, 19)])).astype(np.int32)
+        check_stages_own_operands(rig, rs.RS_SIDE_PREFILL, L, T, x, ref_bits["yp"], cu=np.array([0, T], np.int32),
+                                  tables=ptab, rows=rows)
+        check_stages_own_operands(rig, rs.RS_SIDE_DECODE, L, B, xd, ref_bits["yd"], ctx=ctx, tables=dtab)
+        Kc, Vc = f32(kb), f32(vb)
+        y_ref = L.prefill(x, [0, T], ptab, Kc, Vc, rows=rows)
+        check_tensor("8B prefill y at 128/128 beside decode, sampled rows", f32(ref_bits["yp"])[rows], y_ref, x[rows], 2,
+                     elem_mult=END_TO_END)
+        yd_ref = L.decode(xd, ctx, dtab, Kc, Vc)
+        check_tensor("8B decode y at 128/128 beside prefill", f32(ref_bits["yd"]), yd_ref, xd, 2, elem_mult=END_TO_END)
     finally:
         rig.close()
 
@@ -416,13 +497,13 @@ def test_70b_shaped_layer_sampled_rows():
         Kc, Vc = L.new_cache(n_blocks, fill=ORC_SENT)
         y_ref = L.prefill(x, cu, ptab, Kc, Vc, rows=rows)
         check_cache_against_oracle(rig, Kc, Vc, ORC_SENT)
-        check_tensor("70B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2)
+        check_tensor("70B prefill y, sampled rows", f32(y_bits)[rows], y_ref, x[rows], 2, elem_mult=END_TO_END)
         kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
         rig.load_pools_from_logical(kb, vb)
         db = S.hidden_states(B, shape.d_model, stream=51)
         yd = rig.decode(db, ctx, dtab)
         yd_ref = L.decode(f32(db), ctx, dtab, f32(kb), f32(vb))
-        check_tensor("70B decode y, batch 16", f32(yd), yd_ref, f32(db), 2)
+        check_tensor("70B decode y, batch 16", f32(yd), yd_ref, f32(db), 2, elem_mult=END_TO_END)
     finally:
         rig.close()
 
@@ -472,8 +553,8 @@ def test_serving_steps_three_requests_async_matches_oracle():
                 xr = f32(x_bits)
                 for l, L in enumerate(rig.olayers):
                     xr = L.decode(xr, [ctx_len[i]], tabs, *caches[i][l])
-                e = residual_err(got[row:row + 1], xr, f32(x_bits), roundings=4)
-                assert e <= 1.5, (step, i, e)
+                e = residual_err(got[row:row + 1], xr, f32(x_bits), roundings=4, layers=n_layers)
+                assert e <= 1.0, (step, i, e)
                 ctx_len[i] += 1; checked += 1
             if all(rig.ctx.request_state(i) == 5 for i in reqs) and step > 3:
                 break
@@ -507,8 +588,8 @@ def test_long_context_decode_and_16k_prefill_mid_shape():
         yd = rig.decode(db, ctx, dtab)
         yd_ref, taps = L.decode(f32(db), ctx, dtab, Kc, Vc, taps=True)
         check_tensor("long-context decode attention out", f32(rig.ctx.debug_read_workspace(rs.RS_SIDE_DECODE, 2, (B, shape.q_dim))),
-                     taps["attn"])
-        check_tensor("long-context decode y", f32(yd), yd_ref, f32(db), 2)
+                     taps["attn"], elem_mult=END_TO_END)
+        check_tensor("long-context decode y", f32(yd), yd_ref, f32(db), 2, elem_mult=END_TO_END)
         # the 16384-token prompt overwrites its own blocks only (snapshot after the decode step's appends)
         kb, vb = rig.k_bits_logical(), rig.v_bits_logical()
         xb = S.hidden_states(T, shape.d_model, stream=62)
@@ -517,7 +598,7 @@ def test_long_context_decode_and_16k_prefill_mid_shape():
         rows = np.unique(np.concatenate([[0, 1, 127, 128, 8191, 8192, 16382, 16383], rng.integers(0, T, 24)])).astype(np.int32)
         Kp, Vp = L.new_cache(n_blocks, fill=ORC_SENT)
         y_ref = L.prefill(f32(xb), [0, T], ptab, Kp, Vp, rows=rows)
-        check_tensor("16K prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2)
+        check_tensor("16K prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2, elem_mult=END_TO_END)
         # K/V written by the prompt: exactly its blocks, contents to tolerance
         kg, vg = rig.k_bits_logical(), rig.v_bits_logical()
         mine = np.zeros(n_blocks, bool)
@@ -547,7 +628,7 @@ def test_prefill_prompt_longer_than_the_kernel_s_lds_block_table_mid_shape():
                                          rng.integers(0, T, 16)])).astype(np.int32)
         Kp, Vp = L.new_cache(n_blocks, fill=ORC_SENT)
         y_ref = L.prefill(f32(xb), [0, T], ptab, Kp, Vp, rows=rows)
-        check_tensor("33000-token prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2)
+        check_tensor("33000-token prefill y, sampled rows", f32(y_bits)[rows], y_ref, f32(xb)[rows], 2, elem_mult=END_TO_END)
         check_cache_against_oracle(rig, Kp, Vp, ORC_SENT)
     finally:
         rig.close()
@@ -569,16 +650,16 @@ def test_released_source_weights_are_not_read_again():
         Kc, Vc = L.new_cache(n_blocks + 4, fill=ORC_SENT)
         y = rig.prefill(xb, cu, tabs)
         y_ref = L.prefill(f32(xb), cu, tabs, Kc, Vc)
-        check_tensor("prefill y after release (190 rows)", f32(y), y_ref, f32(xb), 2)
+        check_tensor("prefill y after release (190 rows)", f32(y), y_ref, f32(xb), 2, elem_mult=END_TO_END)
         xs = S.hidden_states(40, shape.d_model, stream=12)
         one = tabs[1:2]
         ys = rig.prefill(xs, [0, 40], one)
         ys_ref = L.prefill(f32(xs), [0, 40], one, Kc, Vc)
-        check_tensor("prefill y after release (40 rows)", f32(ys), ys_ref, f32(xs), 2)
+        check_tensor("prefill y after release (40 rows)", f32(ys), ys_ref, f32(xs), 2, elem_mult=END_TO_END)
         db = S.hidden_states(2, shape.d_model, stream=13)
         ctx = np.array([150, 40], np.int32)
         yd = rig.decode(db, ctx, tabs)     # positions 150 and 40 fall inside the prompts' last blocks
         yd_ref = L.decode(f32(db), ctx, tabs, Kc, Vc)
-        check_tensor("decode y after release", f32(yd), yd_ref, f32(db), 2)
+        check_tensor("decode y after release", f32(yd), yd_ref, f32(db), 2, elem_mult=END_TO_END)
     finally:
         rig.close()

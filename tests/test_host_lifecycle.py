@@ -325,3 +325,43 @@ def test_engine_reports_a_pool_too_small():
     with pytest.raises(rs.RapidServeError) as e:
         c.engine_stop(drain=True)
     assert e.value.code == rs.RS_ERR_NO_BLOCKS
+
+
+def test_request_release_forgets_finished_requests_only():
+    """rs_request_release: refused while the request is live, drops the record once finished (the id can be
+    used again), in the single-loop driver and with the engine."""
+    c = _host_ctx(64, 4, -1)
+    c.submit_tokens(1, np.zeros(5, np.int32), 2)
+    with pytest.raises(rs.RapidServeError) as e:
+        c.request_release(1)
+    assert e.value.code == rs.RS_ERR_STATE
+    for _ in range(20):
+        so = c.step_tokens()
+        if so.prefill_started_req >= 0:
+            c.debug_complete_prefill(so.prefill_started_req)
+        if c.request_state(1) == 5:
+            break
+    toks, fin = c.request_output(1)
+    assert fin and len(toks) == 2
+    c.request_release(1)
+    with pytest.raises(rs.RapidServeError) as e:
+        c.request_output(1)
+    assert e.value.code == rs.RS_ERR_BAD_ARG
+    c.submit_tokens(1, np.zeros(3, np.int32), 1)      # the id is free again
+    c.destroy()
+
+    c = _host_ctx(64, 4, -1)
+    c.engine_start()
+    for rid in range(40):
+        c.submit_tokens(rid, np.zeros(4, np.int32), 3)
+    c.engine_stop(drain=True)
+    for rid in range(40):
+        toks, fin = c.request_output(rid)
+        assert fin and len(toks) == 3
+        c.request_release(rid)
+        with pytest.raises(rs.RapidServeError):
+            c.request_output(rid)
+    with pytest.raises(rs.RapidServeError) as e:
+        c.request_release(3)
+    assert e.value.code == rs.RS_ERR_BAD_ARG
+    c.destroy()

@@ -442,3 +442,21 @@ def test_decode_taps_hold_the_intermediates_they_name():
         assert _close(y[i], y64[-1])
         for name in ("h", "qkv", "attn", "x1", "act"):
             assert _close(taps[name][i], st[name][-1]), (i, name)
+
+
+def test_single_step_wrappers_use_the_layer_s_own_matrices():
+    """OracleLayer.project / norm (the stage-by-stage entry points of the GPU own-operand checks)
+    against float64 numpy with the matching matrix; a wrapper wired to the wrong matrix, or to an
+    untransposed one, fails on these non-square shapes."""
+    shape = SMALL
+    wb, w32 = _w32(shape)
+    L = oracle.OracleLayer.from_shape(shape, wb)
+    rng = np.random.default_rng(7)
+    for name, K in (("wqkv", shape.d_model), ("wo", shape.q_dim), ("wg", shape.d_model), ("wu", shape.d_model),
+                    ("wd", shape.ffn_dim)):
+        a = rng.standard_normal((3, K)).astype(np.float32)
+        assert _close(L.project(name, a), a.astype(np.float64) @ w32[name].astype(np.float64).T), name
+    x = rng.standard_normal((2, shape.d_model)).astype(np.float32)
+    assert _close(L.norm(1, x), brute.rmsnorm(x, w32["g1"], shape.rms_eps))
+    assert _close(L.norm(2, x), brute.rmsnorm(x, w32["g2"], shape.rms_eps))
+    assert not _close(L.norm(1, x), brute.rmsnorm(x, w32["g2"], shape.rms_eps), 1e-3)
