@@ -213,6 +213,24 @@ int32_t rs_decode_layer_graph(rs_ctx *ctx, int32_t layer, const void *x_in, void
                               const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
                               int32_t B, int32_t max_ctx_bucket);
 
+/* rs_decode_layer for callers that cannot allocate device memory or have it allocated on their behalf:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results, but every intermediate of the step (normalised rows, q|k|v,
+ * attention output and its per-chunk partial results, the GEMMs' K-slice partial sums, the SwiGLU product)
+ * lives in a static device array that is part of the library's code object, RS_STATIC_SCRATCH_BYTES =
+ * 32 MiB per GPU, held until the process ends; the call allocates nothing and calls nothing that
+ * allocates.  A step that needs more (it grows with B, d_model, ffn_dim and max_ctx: the
+ * Llama-3-8B-shaped layer at B = 64 and contexts up to 4096 needs 29 MB) is refused with RS_ERR_BAD_ARG and
+ * nothing is enqueued; a layer with a sparse feed-forward block is refused with RS_ERR_STATE.  Every
+ * context of the process on one GPU shares that GPU's array: calls that overlap on one GPU (two contexts,
+ * or a captured graph replayed while another call runs) race on it; calls on one context's decode stream
+ * are ordered and safe.  The array keeps the previous call's contents; the call clears what must start
+ * at zero with a kernel.  rs_debug_read_workspace does not see these buffers. */
+#define RS_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t rs_decode_layer_noalloc(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_out,
+                                const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
+                                int32_t B, int32_t max_ctx);
+
 /* ---- CU partitioning (sections 4.2, 4.5.3) -------------------------------------------------
  * Selects the masks for SUBSEQUENT enqueues.  Each count is 0 or a multiple of
  * RS_CU_GRANULE up to 256.  prefill+decode <= 256 gives disjoint masks (prefill takes mask

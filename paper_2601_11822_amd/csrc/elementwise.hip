@@ -1,4 +1,6 @@
 // RMSNorm and rotary-embedding + paged KV write kernels (bandwidth-trivial steps of the layer).
+#include <algorithm>
+
 #include "kernels.h"
 
 // ---------------------------------------------------------------------------------------------
@@ -265,4 +267,19 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t *__restr
 void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups) {
     hipLaunchKernelGGL(stream_read_kernel, dim3(n_workgroups), dim3(256), 0, st, (const u32x4_t *)src, (u32x4_t *)nullptr,
                        bytes / 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Zero fill by kernel: a memset node recorded into a captured graph is not something a caller's
+// graph should contain, a kernel node is fine.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4_t *dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = u32x4_t{0, 0, 0, 0};
+}
+
+void launch_fill_zero(hipStream_t st, void *dst, size_t bytes) {
+    const size_t n16 = bytes / 16;
+    if (!n16) return;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 1024);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, st, (u32x4_t *)dst, n16);
 }

@@ -156,6 +156,9 @@ void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);
 // Reads `bytes` (multiple of 16) once with coalesced 16-byte loads.
 void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups);
 
+// Zeroes `bytes` (a multiple of 16) of device memory with a kernel (usable under stream capture).
+void launch_fill_zero(hipStream_t st, void *dst, size_t bytes);
+
 // Called once per context creation (see gemm.hip).
 void gemm_kernels_init();
 void attention_kernels_init();

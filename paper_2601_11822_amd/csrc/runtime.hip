@@ -41,6 +41,14 @@ int32_t fail(int32_t code, const char *fmt, ...) {
         if (e_ != hipSuccess) return fail(RS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
+// Scratch of rs_decode_layer_noalloc: one array per GPU, part of the library's code object, so a
+// call needs no allocation at all.  Host code never uses this name as an address: g_static_scratch[]
+// holds each device's own address of it (hipGetSymbolAddress in rs_init, with that device current).
+#define RS_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[RS_STATIC_SCRATCH_BYTES];
+void *g_static_scratch[RS_MAX_DEVICES] = {};
+std::mutex g_static_scratch_mu;
+
 struct Workspace {
     bf16_t *h = nullptr, *qkv = nullptr, *attn = nullptr, *x1 = nullptr, *act = nullptr, *xbuf = nullptr;
     float *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
@@ -321,6 +329,43 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     return RS_OK;
 }
 
+// The decode side's buffers for a step of `rows` rows and contexts up to max_ctx, laid out one after the other
+// (256-byte aligned) from `base`; returns the bytes used.  base == nullptr only measures.  The three
+// fragment-packed GEMM inputs come first, contiguous: *packed_bytes is their extent (what must start at zero).
+size_t carve_decode_ws(const rs_ctx *c, Workspace &w, unsigned char *base, int rows, int max_ctx, size_t *packed_bytes) {
+    const rs_model_desc &m = c->m;
+    const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
+    const size_t nqkv = qd + 2 * (size_t)m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+    const size_t prow = (size_t)packed_mt(rows) * 32;
+    auto r16 = [](size_t v) { return (v + 15) / 16 * 16; };
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char *p = base ? base + off : nullptr;
+        off += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    w = Workspace{};
+    w.rows = rows;
+    w.h = (bf16_t *)take(prow * r16(d) * 2);
+    w.attn = (bf16_t *)take(prow * r16(qd) * 2);
+    w.act = (bf16_t *)take(prow * r16(f) * 2);
+    if (packed_bytes) *packed_bytes = off;
+    w.qkv = (bf16_t *)take(rows * nqkv * 2);
+    w.x1 = (bf16_t *)take(rows * d * 2);
+    const int Mmax = std::min(rows, 64);
+    size_t pe = rows > 64 ? RS_DIRECT_PARTIAL_ELEMS : 0;
+    pe = std::max(pe, skinny_partial_elems(Mmax, (int)nqkv, (int)d, EPI_STORE));
+    pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
+    pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
+    pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)f, EPI_RESIDUAL));
+    w.partials = (float *)take(pe * sizeof(float));
+    w.partial_cap = pe;
+    const size_t nch = (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
+    w.part_o = (float *)take((size_t)rows * m.n_q_heads * nch * m.head_dim * sizeof(float));
+    w.part_ml = (float *)take((size_t)rows * m.n_q_heads * nch * 2 * sizeof(float));
+    return off;
+}
+
 void free_ws(Workspace &w) {
     void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml,
                     w.m_sel, w.m_pos, w.m_src, w.m_tile, w.m_wt, w.m_a, w.m_act, w.m_out};
@@ -530,10 +575,9 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     return RS_OK;
 }
 
-int32_t decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
+int32_t decode_layer(rs_ctx *c, Workspace &w, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
                      const int32_t *tables, int32_t max_blk, int32_t B, int32_t max_ctx) {
     const rs_model_desc &m = c->m;
-    Workspace &w = c->ws[RS_SIDE_DECODE];
     if (!ctx_lens) return fail(RS_ERR_BAD_ARG, "null ctx_lens");
     if (B < 1 || B > w.rows) return fail(RS_ERR_BAD_ARG, "decode batch %d, workspace holds %d", B, w.rows);
     if (max_ctx < 1 || max_ctx > c->lim.max_context || max_ctx > m.max_pos)
@@ -714,6 +758,15 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
     int32_t rc;
     auto gpu_setup = [&]() -> int32_t {
         HIP_TRY(hipSetDevice(device));
+        if (device < 0 || device >= RS_MAX_DEVICES) return fail(RS_ERR_BAD_ARG, "device %d: at most %d devices", device, RS_MAX_DEVICES);
+        {   // this device's copy of the static scratch array (each GPU holds its own, at its own address)
+            std::lock_guard<std::mutex> lk(g_static_scratch_mu);
+            if (!g_static_scratch[device]) {
+                void *ptr = nullptr;
+                HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+                g_static_scratch[device] = ptr;
+            }
+        }
         gemm_kernels_init();
         attention_kernels_init();
         // rotary table, angles in float64
@@ -1047,7 +1100,27 @@ int32_t rs_decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out,
                         const int32_t *block_tables, int32_t max_blk, int32_t B, int32_t max_ctx) {
     int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
     if (rc) return rc;
-    return decode_layer(c, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
+    return decode_layer(c, c->ws[RS_SIDE_DECODE], layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
+}
+
+int32_t rs_decode_layer_noalloc(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
+                                const int32_t *block_tables, int32_t max_blk, int32_t B, int32_t max_ctx) {
+    int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
+    if (rc) return rc;
+    if (c->moe[layer].E > 0) return fail(RS_ERR_STATE, "layer %d has a sparse feed-forward block: not served from the static scratch", layer);
+    if (B < 1 || max_ctx < 1) return fail(RS_ERR_BAD_ARG, "decode batch %d, max_ctx %d", B, max_ctx);
+    unsigned char *base = (unsigned char *)g_static_scratch[c->device];
+    if (!base) return fail(RS_ERR_STATE, "the static scratch array of device %d was not resolved", c->device);
+    Workspace w;
+    size_t packed = 0;
+    const size_t need = carve_decode_ws(c, w, base, B, max_ctx, &packed);
+    if (need > RS_STATIC_SCRATCH_BYTES)
+        return fail(RS_ERR_BAD_ARG, "a step of %d rows over contexts up to %d needs %zu bytes of scratch; the static array holds %zu",
+                    B, max_ctx, need, (size_t)RS_STATIC_SCRATCH_BYTES);
+    // the array keeps the last call's contents, in that call's layout: the padding of the packed GEMM inputs
+    // must read as zero (a fill kernel, not a memset: the call may be recorded into a graph)
+    launch_fill_zero(c->side[RS_SIDE_DECODE].stream, base, packed);
+    return decode_layer(c, w, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
 }
 
 int32_t rs_decode_layer_graph(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,
@@ -1066,7 +1139,7 @@ int32_t rs_decode_layer_graph(rs_ctx *c, int32_t layer, const void *x_in, void *
         hipGraphExec_t exec = nullptr;
         HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
         c->capturing = true;
-        rc = decode_layer(c, layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx_bucket);
+        rc = decode_layer(c, c->ws[RS_SIDE_DECODE], layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx_bucket);
         c->capturing = false;
         const hipError_t e = hipStreamEndCapture(st, &graph);
         if (rc) {
@@ -1669,7 +1742,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             }
             for (int l = 0; l < c->m.n_layers; ++l) {
                 if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                int32_t rc = decode_layer(c, l, l == 0 ? x_first : (const void *)x_out, x_out, c->d_ctx, c->d_tab, mb, B, max_ctx);
+                int32_t rc = decode_layer(c, w, l, l == 0 ? x_first : (const void *)x_out, x_out, c->d_ctx, c->d_tab, mb, B, max_ctx);
                 if (rc) return rc;
             }
             if (token_mode) {
