@@ -294,6 +294,12 @@ int32_t rs_debug_cu_histogram(rs_ctx *ctx, int32_t side, int32_t n_workgroups, i
  * GPU time.  n_bytes / time is the read bandwidth that partition can pull (section 3.3's
  * question, asked of this GPU).  Blocks until done. */
 int32_t rs_debug_stream_read(rs_ctx *ctx, int32_t side, const void *buf, int64_t n_bytes, float *ms_out);
+/* Matrix-core probe: runs about 10 ms of back-to-back 32x32x16 bf16 MFMAs whose operands never leave
+ * registers (8 independent accumulator tiles per wave, 8 waves per compute unit) on the side's stream, i.e. on
+ * the side's CU partition, and gives the rate in TFLOP/s.  This is what the partition sustains at the clock
+ * it reaches under matrix load -- the ceiling a prefill GEMM can be measured against besides the published
+ * peak, which assumes the nominal clock.  Blocks until done. */
+int32_t rs_debug_mfma_probe(rs_ctx *ctx, int32_t side, float *tflops_out);
 /* rs_debug_cu_histogram with the probe kernel replayed from a captured graph on the side's stream:
  * shows whether a graph launch keeps the stream's CU mask. */
 int32_t rs_debug_cu_histogram_graph(rs_ctx *ctx, int32_t side, int32_t n_workgroups, int32_t *hist_out);

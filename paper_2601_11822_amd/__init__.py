@@ -30,7 +30,7 @@ EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
     "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_decode_layer_noalloc", "rs_set_cu_split", "rs_get_cu_split",
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
-    "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
+    "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_debug_mfma_probe", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
     "rs_debug_push_sampled", "rs_request_times", "rs_request_release", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
 ]
@@ -285,6 +285,12 @@ class Context:
         _check(self._lib.rs_debug_cu_histogram_graph(self._h, ctypes.c_int32(side), ctypes.c_int32(n_workgroups),
                                                      h.ctypes.data_as(_i32p)))
         return h
+
+    def debug_mfma_probe(self, side: int) -> float:
+        """TFLOP/s of register-only bf16 MFMAs on the side's partition."""
+        t = ctypes.c_float(0)
+        _check(self._lib.rs_debug_mfma_probe(self._h, ctypes.c_int32(side), ctypes.byref(t)))
+        return t.value
 
     def debug_stream_read(self, side: int, buf, n_bytes: int) -> float:
         """GPU milliseconds to read n_bytes of `buf` once on the side's CU partition."""

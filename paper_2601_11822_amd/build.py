@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librapid_serve.so")
-SOURCES = ["runtime.hip", "gemm.hip", "attention.hip", "elementwise.hip", "head.hip", "moe.hip"]
+SOURCES = ["runtime.hip", "gemm.hip", "decode_gemm.hip", "attention.hip", "elementwise.hip", "head.hip", "moe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

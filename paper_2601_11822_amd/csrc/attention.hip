@@ -46,6 +46,8 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a) {
     // index slowest the workgroups that have nothing to do (chunks past a request's context) gather at
     // the end of the grid instead of following each request: on a CU partition that measured 5 % faster
     // (128 CUs: 160 -> 152 us), on the whole chip 2 % slower, so the launcher chooses by partition size.
+    // (Consecutive ids go to the 8 XCDs in turn, so the kv heads of one block are read through 8 different L2s
+    // at about the same time; putting them on ONE XCD instead measured 7-10 % slower on every partition.)
     const int hk = blockIdx.x;
     const int b = a.chunk_major ? blockIdx.y : blockIdx.z, chunk = a.chunk_major ? blockIdx.z : blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a) {
     }
     __syncthreads();
     for (int idx = tid; idx < G * HD; idx += 256) {
-        const int gg = idx / HD, d = idx % HD;
+        const int gg = idx % G, d = idx / G;   // consecutive threads read consecutive words of s_o: no bank conflicts
         const float mx = fmaxf(fmaxf(s_m[gg], s_m[G + gg]), fmaxf(s_m[2 * G + gg], s_m[3 * G + gg]));
         const float ms = (mx == NEG_INF) ? 0.f : mx;
         float acc = 0.f, l = 0.f;

@@ -283,3 +283,39 @@ void launch_fill_zero(hipStream_t st, void *dst, size_t bytes) {
     const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 1024);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, st, (u32x4_t *)dst, n16);
 }
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core probe: what the chip sustains when nothing but MFMAs is issued.  Every wave keeps 8
+// independent 32x32x16 bf16 accumulator tiles in registers and issues MFMAs back to back, operands
+// never leave registers; 2 workgroups of 4 waves per compute unit.  2 * 32 * 32 * 16 flop per MFMA.
+// The published peak assumes the nominal clock; under this load the chip clocks lower, and no GEMM
+// can beat what this loop reaches on the same partition.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void mfma_probe_kernel(float *sink, int iters) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (bf16_t)(0.001f * (float)((threadIdx.x + i) & 7));
+        b[i] = (bf16_t)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[j][e];
+    if (t == -1.0f) sink[0] = t;   // never true (all products are non-negative): keeps the loop alive
+}
+
+double launch_mfma_probe(hipStream_t st, float *sink, int n_workgroups, int iters) {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_workgroups), dim3(256), 0, st, sink, iters);
+    return (double)n_workgroups * 4 * (double)iters * 8 * 32768.0;
+}

@@ -96,6 +96,51 @@ bool launch_gemm_direct_partials(hipStream_t st, const GemmArgs &a, float *part)
 size_t packed_weight_elems(int N, int K);
 void launch_pack_weights(hipStream_t st, const bf16_t *W, bf16_t *Wp, int N, int K);
 
+// ---- decode-side projections (decode_gemm.hip): at most 64 rows, weights streamed once, RMSNorm folded in ----
+struct DGemmArgs {
+    const bf16_t *A_packed;   // activations fragment-packed with two row tiles (packed_mt(M) == 2), or
+    const bf16_t *X_rows;     // row-major [M][K] hidden state: multiplied by gain[K] on the way in, and
+    const bf16_t *gain;       //   the sums of squares of each row over each K slice go to
+    float *ssq_part;          //   ssq_part[slice][64]  (the epilogue turns them into the RMSNorm scale)
+    const bf16_t *Wp, *Wp2;   // fragment-packed weights [N][K]; Wp2: the up matrix of a gate/up pair
+    float *part;              // out: float32 partial products [S][M][Nv]
+    int M, N, K;
+};
+struct DGemmPlan {
+    bool pair;
+    int cols, S, kb_per_wg, Nv;   // workgroups along N, K slices, k-blocks per slice, row stride of the partial products
+};
+// True if the streaming kernel takes this projection (K a multiple of 256, N a multiple of 4 and at least 128).
+bool dgemm_applies(int N, int K);
+DGemmPlan dgemm_plan(int N, int K, bool pair);
+size_t dgemm_partial_elems(int M, int N, int K, bool pair);
+void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &p);
+struct DEpiArgs {
+    const float *part;        // [S][M][Nv]
+    int S, Nv;
+    const float *ssq_part;    // [S_ssq][64] or nullptr: no row scale
+    int S_ssq, d;
+    float eps;
+    const bf16_t *resid;      // EPI_RESIDUAL: row-major [M][N]
+    bf16_t *out;              // EPI_RESIDUAL: row-major [M][N]; EPI_SWIGLU: fragment-packed [M][N]
+    int M, N;
+};
+void launch_dgemm_epilogue(hipStream_t st, const DEpiArgs &a, int epi);
+struct QkvEpiArgs {
+    const float *part;        // [S][M][Nv] partial q | k | v
+    const float *ssq_part;    // [S][64]
+    int S, Nv, d;
+    float eps;
+    bf16_t *qkv;              // out: [M][(Hq+2Hkv)*hd] with q and k rotated
+    const CosSin *table;
+    bf16_t *k_pool, *v_pool;  // this layer
+    const int32_t *tables, *ctx_lens;
+    int32_t *err_flag;
+    int M, Hq, Hkv, hd, max_blk, n_blocks, max_pos;
+};
+void launch_qkv_rope_epilogue(hipStream_t st, const QkvEpiArgs &a);
+void decode_gemm_kernels_init();
+
 // Grouped GEMM over 128-row tiles that each belong to one expert: STORE or SWIGLU epilogue, a.M = the padded
 // row capacity (a multiple of 128), a.expert_stride and a.tile_expert set, the latter followed by the work list
 // that moe_plan_kernel writes behind the a.M / 128 tile entries.  Needs K % 32 == 0 and N >= 1024.
@@ -155,6 +200,9 @@ void launch_cu_probe(hipStream_t st, int32_t *hist, int n_workgroups);
 
 // Reads `bytes` (multiple of 16) once with coalesced 16-byte loads.
 void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_workgroups);
+
+// Back-to-back register-only 32x32x16 bf16 MFMAs; returns the flops the launch performs.
+double launch_mfma_probe(hipStream_t st, float *sink, int n_workgroups, int iters);
 
 // Zeroes `bytes` (a multiple of 16) of device memory with a kernel (usable under stream capture).
 void launch_fill_zero(hipStream_t st, void *dst, size_t bytes);

@@ -52,6 +52,7 @@ std::mutex g_static_scratch_mu;
 struct Workspace {
     bf16_t *h = nullptr, *qkv = nullptr, *attn = nullptr, *x1 = nullptr, *act = nullptr, *xbuf = nullptr;
     float *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
+    float *ssq = nullptr;   // decode side: per-slice sums of squares of the two normalised inputs, 2 x [64 slices][64 rows]
     size_t partial_cap = 0;
     int rows = 0;
     // sparse feed-forward block (allocated by the first rs_set_moe_weights)
@@ -177,6 +178,7 @@ struct rs_ctx {
     int32_t step_err = 0;            // bits met by serving steps and not yet reported
     Workspace ws[2];
     int last_rows[2] = {0, 0};   // rows of each side's last layer call: fixes the packed layout of h/attn/act
+    bool decode_fused = false;   // the decode side's last layer call folded its RMSNorms into the projections (no h buffer)
     // captured decode steps, keyed by everything a captured launch bakes in (rs_decode_layer_graph)
     struct GraphKey {
         int32_t layer, max_blk, B, max_ctx;
@@ -292,6 +294,23 @@ int32_t get_stream(rs_ctx *c, int side, int cus, hipStream_t *out) {
     return RS_OK;
 }
 
+// Whether a decode step of at most 64 rows takes the weight-streaming projections with the RMSNorm folded in
+// (a function of the model's shape), and the partial-product elements they need.
+bool fused_decode_applies(const rs_ctx *c) {
+    const rs_model_desc &m = c->m;
+    const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+    return dgemm_applies(nqkv, d) && dgemm_applies(d, qd) && dgemm_applies(f, d);
+}
+size_t fused_partial_elems(const rs_ctx *c, int M) {
+    if (!fused_decode_applies(c)) return 0;
+    const rs_model_desc &m = c->m;
+    const int d = m.d_model, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim, f = m.ffn_dim;
+    size_t pe = std::max(dgemm_partial_elems(M, nqkv, d, false), dgemm_partial_elems(M, d, qd, false));
+    pe = std::max(pe, dgemm_partial_elems(M, f, d, true));
+    if (dgemm_applies(d, f)) pe = std::max(pe, dgemm_partial_elems(M, d, f, false));
+    return pe;
+}
+
 int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
     const rs_model_desc &m = c->m;
     const size_t d = m.d_model, qd = (size_t)m.n_q_heads * m.head_dim;
@@ -318,10 +337,12 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
         pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)f, EPI_RESIDUAL));
+        if (decode) pe = std::max(pe, fused_partial_elems(c, Mmax));
         HIP_TRY(hipMalloc(&w.partials, pe * sizeof(float)));
         w.partial_cap = pe;
     }
     if (decode) {
+        HIP_TRY(hipMalloc(&w.ssq, 2 * 64 * 64 * sizeof(float)));
         const size_t nch = (c->lim.max_context + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
         HIP_TRY(hipMalloc(&w.part_o, (size_t)rows * m.n_q_heads * nch * m.head_dim * sizeof(float)));
         HIP_TRY(hipMalloc(&w.part_ml, (size_t)rows * m.n_q_heads * nch * 2 * sizeof(float)));
@@ -358,6 +379,8 @@ size_t carve_decode_ws(const rs_ctx *c, Workspace &w, unsigned char *base, int r
     pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)qd, EPI_RESIDUAL));
     pe = std::max(pe, skinny_partial_elems(Mmax, (int)f, (int)d, EPI_SWIGLU));
     pe = std::max(pe, skinny_partial_elems(Mmax, (int)d, (int)f, EPI_RESIDUAL));
+    pe = std::max(pe, fused_partial_elems(c, Mmax));
+    w.ssq = (float *)take(2 * 64 * 64 * sizeof(float));
     w.partials = (float *)take(pe * sizeof(float));
     w.partial_cap = pe;
     const size_t nch = (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
@@ -367,7 +390,7 @@ size_t carve_decode_ws(const rs_ctx *c, Workspace &w, unsigned char *base, int r
 }
 
 void free_ws(Workspace &w) {
-    void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml,
+    void *ptrs[] = {w.h, w.qkv, w.attn, w.x1, w.act, w.xbuf, w.partials, w.part_o, w.part_ml, w.ssq,
                     w.m_sel, w.m_pos, w.m_src, w.m_tile, w.m_wt, w.m_a, w.m_act, w.m_out};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -593,6 +616,51 @@ int32_t decode_layer(rs_ctx *c, Workspace &w, int32_t layer, const void *x_in, v
     bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
     const bool skinny = B <= 64;
     c->last_rows[RS_SIDE_DECODE] = B;
+    c->decode_fused = skinny && c->moe[layer].E == 0 && fused_decode_applies(c);
+    if (c->decode_fused) {
+        // At most 64 rows: every projection is a stream of its weights with the RMSNorm of its input folded in
+        // (decode_gemm.hip).  10 launches: QKV stream, its epilogue (row scale, rotary, cache append), attention,
+        // chunk merge, O stream + residual, gate/up stream + SwiGLU, down stream + residual.
+        const rs_ctx::PackedLayer &pl = c->packed[layer];
+        const int f = m.ffn_dim;
+        float *ssq1 = w.ssq, *ssq2 = w.ssq + 64 * 64;
+        tick(c, RS_SIDE_DECODE, 0);
+        tick(c, RS_SIDE_DECODE, 1);
+        const DGemmPlan pq = dgemm_plan(nqkv, d, false);
+        launch_dgemm_partials(st, DGemmArgs{nullptr, (const bf16_t *)x_in, (const bf16_t *)lw.g1, ssq1, pl.wqkv, nullptr, w.partials, B, nqkv, d}, pq);
+        launch_qkv_rope_epilogue(st, QkvEpiArgs{w.partials, ssq1, pq.S, pq.Nv, d, m.rms_eps, w.qkv, c->rope, kp, vp, tables, ctx_lens,
+                                                c->err_flag + RS_SIDE_DECODE, B, m.n_q_heads, m.n_kv_heads, hd, max_blk,
+                                                c->pool.n_blocks, m.max_pos});
+        tick(c, RS_SIDE_DECODE, 2);
+        tick(c, RS_SIDE_DECODE, 3);
+        DecodeAttnArgs da{w.qkv, nqkv, w.attn, kp, vp, tables, ctx_lens, c->err_flag + RS_SIDE_DECODE, w.part_o, w.part_ml,
+                          B, m.n_q_heads, m.n_kv_heads, hd, max_blk, c->pool.n_blocks, max_ctx,
+                          (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK,
+                          (float)(1.4426950408889634 / std::sqrt((double)hd)), c->side[RS_SIDE_DECODE].cus < RS_TOTAL_CUS};
+        launch_decode_attention(st, da);
+        tick(c, RS_SIDE_DECODE, 4);
+        const DGemmPlan po = dgemm_plan(d, qd, false);
+        launch_dgemm_partials(st, DGemmArgs{w.attn, nullptr, nullptr, nullptr, pl.wo, nullptr, w.partials, B, d, qd}, po);
+        launch_dgemm_epilogue(st, DEpiArgs{w.partials, po.S, po.Nv, nullptr, 0, d, m.rms_eps, (const bf16_t *)x_in, w.x1, B, d}, EPI_RESIDUAL);
+        tick(c, RS_SIDE_DECODE, 5);
+        tick(c, RS_SIDE_DECODE, 6);
+        const DGemmPlan pg = dgemm_plan(f, d, true);
+        launch_dgemm_partials(st, DGemmArgs{nullptr, w.x1, (const bf16_t *)lw.g2, ssq2, pl.wg, pl.wu, w.partials, B, f, d}, pg);
+        launch_dgemm_epilogue(st, DEpiArgs{w.partials, pg.S, pg.Nv, ssq2, pg.S, d, m.rms_eps, nullptr, w.act, B, f}, EPI_SWIGLU);
+        tick(c, RS_SIDE_DECODE, 7);
+        if (dgemm_applies(d, f)) {
+            const DGemmPlan pd = dgemm_plan(d, f, false);
+            launch_dgemm_partials(st, DGemmArgs{w.act, nullptr, nullptr, nullptr, pl.wd, nullptr, w.partials, B, d, f}, pd);
+            launch_dgemm_epilogue(st, DEpiArgs{w.partials, pd.S, pd.Nv, nullptr, 0, d, m.rms_eps, w.x1, (bf16_t *)x_out, B, d}, EPI_RESIDUAL);
+        } else {
+            GemmArgs gd{w.act, (const bf16_t *)lw.wd, nullptr, pl.wd, nullptr, w.x1, (bf16_t *)x_out, B, d, f, EPI_RESIDUAL,
+                        0, c->side[RS_SIDE_DECODE].cus, w.partials, w.partial_cap};
+            launch_gemm_skinny(st, gd, w.partials);
+        }
+        tick(c, RS_SIDE_DECODE, 8);
+        HIP_TRY(hipGetLastError());
+        return RS_OK;
+    }
 
     tick(c, RS_SIDE_DECODE, 0);
     launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, B, d, m.rms_eps);
@@ -768,6 +836,7 @@ int32_t rs_init(const rs_model_desc *model, const rs_pool_desc *pool, const rs_l
             }
         }
         gemm_kernels_init();
+        decode_gemm_kernels_init();
         attention_kernels_init();
         // rotary table, angles in float64
         const int half = m.head_dim / 2;
@@ -1297,7 +1366,10 @@ int32_t rs_debug_read_workspace(rs_ctx *c, int32_t side, int32_t which, void *ho
     const void *src = nullptr;
     size_t cap = 0;
     switch (which) {
-        case 0: src = w.h; cap = (size_t)w.rows * m.d_model * 2; break;  // (decode buffers are at least 64 rows)
+        case 0:
+            if (side == RS_SIDE_DECODE && c->decode_fused)
+                return fail(RS_ERR_STATE, "this decode step folded its RMSNorms into the projections: no normalised rows were written");
+            src = w.h; cap = (size_t)w.rows * m.d_model * 2; break;  // (decode buffers are at least 64 rows)
         case 1: src = w.qkv; cap = (size_t)w.rows * nqkv * 2; break;
         case 2: src = w.attn; cap = (size_t)w.rows * qd * 2; break;
         case 3: src = w.x1; cap = (size_t)w.rows * m.d_model * 2; break;
@@ -1335,6 +1407,27 @@ int32_t rs_debug_stream_read(rs_ctx *c, int32_t side, const void *buf, int64_t n
     rc = rs_mark(c, side, RS_MAX_MARKS - 3);
     if (rc) return rc;
     return rs_elapsed_ms(c, side, RS_MAX_MARKS - 4, side, RS_MAX_MARKS - 3, ms_out);
+}
+
+int32_t rs_debug_mfma_probe(rs_ctx *c, int32_t side, float *tflops_out) {
+    if (!c || !tflops_out || side < 0 || side > 1) return fail(RS_ERR_BAD_ARG, "bad argument");
+    if (!c->gpu) return fail(RS_ERR_STATE, "host-only context");
+    if (c->side[side].cus <= 0) return fail(RS_ERR_STATE, "side has no compute units");
+    hipStream_t st = c->side[side].stream;
+    float *sink = (float *)c->ws[side].partials;   // never written (the kernel's store is dead by construction)
+    if (!sink) sink = (float *)c->err_flag;
+    const int wgs = c->side[side].cus * 2;
+    (void)launch_mfma_probe(st, sink, wgs, 2000);                     // warm-up: clocks settle under the load
+    int32_t rc = rs_mark(c, side, RS_MAX_MARKS - 4);
+    if (rc) return rc;
+    const double flops = launch_mfma_probe(st, sink, wgs, 40000);   // about 10 ms
+    rc = rs_mark(c, side, RS_MAX_MARKS - 3);
+    if (rc) return rc;
+    float ms = 0.f;
+    rc = rs_elapsed_ms(c, side, RS_MAX_MARKS - 4, side, RS_MAX_MARKS - 3, &ms);
+    if (rc) return rc;
+    *tflops_out = (float)(flops / (ms * 1e-3) / 1e12);
+    return RS_OK;
 }
 
 int32_t rs_debug_cu_histogram(rs_ctx *c, int32_t side, int32_t n_workgroups, int32_t *hist_out) {
