@@ -9,9 +9,12 @@ A "step" is one pass of the whole hot path: one prefill-layer pass (all 8 kernel
 prefill partition while decode-layer passes run back to back on the decode partition.
 --steps K times K prefill passes under co-run (host-clock bracket, see run_corun); the decode
 side runs as many decode steps as fit that window.  Reported: prefill tokens/s under co-run
-(`value`), decode inter-token latency (p50 of the per-step GPU time of one layer), both also
-alone at the same mask and alone on all 256 CUs, the normalised combined throughput, and the
-rooflines of the two dominant kernels.
+(`value`, at the headline split 128/128), decode inter-token latency (p50 of the per-step GPU
+time of one layer), both also alone at the same mask and alone on all 256 CUs, the normalised
+combined throughput, the same for the configuration's other splits ({64, 192} prefill CUs), the
+rooflines of the two dominant kernels against the published peaks and against what the chip
+sustains in this very run (register-only MFMA probe, plain streaming read), and the oracle timed
+whole on the host.
 
 One GPU only: --gpus above 1 is refused.
 """
@@ -66,11 +69,21 @@ def build_rig(args):
     log(f"[bench] weights drawn in {time.time() - t0:.1f}s")
     to_dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
     w = {k: to_dev(v) for k, v in wb.items()}
-    g = torch.Generator(device=dev)
-    g.manual_seed(S.SEED_CACHE)
     Hkv, hd = shape.n_kv_heads, shape.head_dim
-    k_pool = torch.randn((n_blocks, Hkv, 16, hd), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    v_pool = torch.randn((n_blocks, Hkv, hd, 16), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    # cache contents from the seeded generator (stream 5), drawn in the logical order [block, slot, head, dim]
+    # and laid out as the library's pools: K [block][head][hd/32][4][permuted slot][8], V [block][head][dim][slot]
+    t0 = time.time()
+    n_draw = min(n_blocks, 1024)   # 1024 blocks drawn, repeated through the pool: timing does not depend on the values
+    kb, vb = S.kv_cache_bits(n_draw, Hkv, hd)
+    reps = -(-n_blocks // n_draw)
+    kb, vb = np.tile(kb, (reps, 1, 1, 1))[:n_blocks], np.tile(vb, (reps, 1, 1, 1))[:n_blocks]
+    prow = [(t & 3) | ((t & 8) >> 1) | ((t & 4) << 1) for t in range(16)]
+    inv = [prow.index(r_) for r_ in range(16)]
+    k_log = to_dev(kb).reshape(n_blocks, 16, Hkv, hd // 32, 4, 8).permute(0, 2, 3, 4, 1, 5)
+    k_pool = k_log[:, :, :, :, inv, :].reshape(n_blocks, Hkv, 16, hd).contiguous()
+    v_pool = to_dev(vb).permute(0, 2, 3, 1).contiguous()
+    del kb, vb, k_log
+    log(f"[bench] cache contents drawn in {time.time() - t0:.1f}s")
     max_ctx = int(ctx.max()) + 1
     c = rs.Context.from_shape(shape, max_pos=max(max_ctx, T), n_blocks=n_blocks, k_pool=k_pool, v_pool=v_pool,
                               max_prefill_tokens=T, max_decode_batch=B, max_context=max_ctx, device=0)
@@ -132,50 +145,39 @@ def pct(a, q):
     return float(np.percentile(a, q)) if len(a) else float("nan")
 
 
-def cpu_baseline(r, budget_rows=(512, 1536)):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the same
-    workload: K/V of all T prompt rows plus the rest of the layer for a few sampled rows (two
-    sample sizes give the per-row cost), and one decode step for a slice of the batch."""
+def cpu_baseline(r):
+    """The oracle as it stands, timed whole on the host cores on the benchmark's own inputs: the
+    prefill layer over all T prompt rows (every row's attention and feed-forward block, no
+    sampling) and one decode step over the whole batch with its real context lengths."""
     import oracle
     import rs_synth as S
-    shape, T = r["shape"], r["T"]
+    shape, T, B = r["shape"], r["T"], r["B"]
     t0 = time.time()
     L = oracle.OracleLayer.from_shape(shape, r["wbits"])
     log(f"[bench] oracle weights widened in {time.time() - t0:.1f}s")
     x = S.bf16_bits_to_f32(S.hidden_states(T, shape.d_model, stream=0))
-    nb = S.blocks_for(T)
     tabs = S.identity_block_tables([T])
-    times = []
-    for n in budget_rows:
-        rows = np.linspace(0, T - 1, n).astype(np.int32)
-        Kc, Vc = L.new_cache(nb)
-        t0 = time.time()
-        L.prefill(x, [0, T], tabs, Kc, Vc, rows=rows)
-        times.append(time.time() - t0)
-        log(f"[bench] oracle prefill, {n} sampled rows of {T}: {times[-1]:.2f}s")
-    per_row = (times[1] - times[0]) / (budget_rows[1] - budget_rows[0])
-    fixed = max(times[0] - budget_rows[0] * per_row, 0.0)
-    full = fixed + T * per_row
-    # decode: 32 of the 64 requests
-    nd = 32
-    ctx = r["ctx"][:nd]
+    Kc, Vc = L.new_cache(S.blocks_for(T))
+    t0 = time.time()
+    L.prefill(x, [0, T], tabs, Kc, Vc)
+    t_pre = time.time() - t0
+    log(f"[bench] oracle prefill layer, all {T} rows: {t_pre:.2f}s")
+    ctx = r["ctx"]
     counts = [int(c_) + 1 for c_ in ctx]
     dt = S.identity_block_tables(counts)
     nbd = int(dt.max()) + 1
     Kd = np.random.default_rng(0).standard_normal((nbd, 16, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
     Vd = Kd.copy()
-    xd = S.bf16_bits_to_f32(S.hidden_states(nd, shape.d_model, stream=50))
+    xd = S.bf16_bits_to_f32(S.hidden_states(B, shape.d_model, stream=50))
     t0 = time.time()
     L.decode(xd, ctx, dt, Kd, Vd)
     t_dec = time.time() - t0
-    log(f"[bench] oracle decode step, {nd} requests: {t_dec:.2f}s")
+    log(f"[bench] oracle decode step, all {B} requests: {t_dec:.2f}s")
     return {
-        "value": T / full, "unit": "tok/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": (f"prefill layer T={T}: K/V of all rows + {budget_rows[0]} and {budget_rows[1]} sampled rows "
-                   f"({times[0]:.1f}s, {times[1]:.1f}s) extrapolated linearly to all rows ({full:.0f}s); "
-                   f"decode step on {nd} of {r['B']} requests"),
-        "prefill_layer_s_extrapolated": full,
-        "decode_step_ms_extrapolated": 1e3 * t_dec * r["B"] / nd,
+        "value": T / t_pre, "unit": "tok/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"the whole workload, once: prefill layer over all {T} rows ({t_pre:.1f}s) and one decode step over all "
+                   f"{B} requests ({t_dec:.2f}s); the oracle never co-runs with itself, so this is each phase alone"),
+        "prefill_layer_s": t_pre, "decode_step_ms": 1e3 * t_dec,
     }
 
 
@@ -191,7 +193,8 @@ def main():
     ap.add_argument("--ctx-lo", type=int, default=512)
     ap.add_argument("--ctx-hi", type=int, default=4096)
     ap.add_argument("--split", type=str, default="128,128", help="headline prefill,decode CUs")
-    ap.add_argument("--sweep", action="store_true", help="also co-run at other splits, from 64/192 to 224/32, and unpartitioned")
+    ap.add_argument("--sweep", action="store_true",
+                    help="besides the configuration's own {64,128,192} prefill CUs, also 96, 160, 224 and unpartitioned")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--alone-only", action="store_true", help="only the alone-at-256-CUs phases (for profiling)")
     args = ap.parse_args()
@@ -213,6 +216,7 @@ def main():
     default_workload = (args.shape, T, B, args.ctx_lo, args.ctx_hi) == ("llama3-8b-layer", 2048, 64, 512, 4096)
     probe = torch.empty(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB, read by the bandwidth probe
     probe.fill_(1.0)
+    med = lambda v: float(np.median(v))
 
     # ---- alone on all 256 CUs, with per-kernel times (the roofline figures)
     c.set_cu_split(256, 256)
@@ -221,64 +225,71 @@ def main():
     p256_bb, _ = run_alone(r, 0, K, W)
     d256_bb, _ = run_alone(r, 1, max(4 * K, 100), W)
     names = rs.KERNEL_SLOT_NAMES
-    log("[bench] prefill alone @256: %.3f ms/pass  " % np.median(p256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_p)))
-    log("[bench] decode  alone @256: %.3f ms/step  " % np.median(d256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_d)))
+    log("[bench] prefill alone @256: %.3f ms/pass  " % med(p256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_p)))
+    log("[bench] decode  alone @256: %.3f ms/step  " % med(d256_bb) + ", ".join(f"{n} {t:.3f}" for n, t in zip(names, kt_d)))
+    # what the chip sustains: register-only bf16 MFMAs (TFLOP/s) and a plain streaming read (GB/s), all 256 CUs
+    mfma_256 = max(c.debug_mfma_probe(0) for _ in range(2))
+    c.debug_stream_read(1, probe, probe.numel() * 4)
+    stream_256 = probe.numel() * 4 / (min(c.debug_stream_read(1, probe, probe.numel() * 4) for _ in range(3)) * 1e-3) / 1e9
+    log(f"[bench] sustained on 256 CUs: MFMA probe {mfma_256:.0f} TFLOP/s, streaming read {stream_256:.0f} GB/s")
     gu_flops = 2.0 * T * shape.d_model * 2 * shape.ffn_dim
+    traffic_note = ("stored constant: FETCH_SIZE / WRITE_SIZE counter passes over `bench.py --alone-only`, scaled by a 1 GiB copy; "
+                    "see profiles/hbm_traffic_alone_256cu_llama8b_layer.md for the commit they were taken at")
     roof = {"kernel": "gateup_swiglu_gemm (prefill, alone on 256 CUs)", "bound": "mfma",
             "achieved": gu_flops / (kt_p[6] * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "traffic": TRAFFIC_BYTES["gateup"] if default_workload else None}
+            "traffic": TRAFFIC_BYTES["gateup"] if default_workload else None, "traffic_source": traffic_note}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["sustained_peak"] = mfma_256                       # measured in this run (rs_debug_mfma_probe)
+    roof["frac_of_sustained"] = roof["achieved"] / mfma_256
     roof_d = {"kernel": "paged decode attention + chunk merge (alone on 256 CUs)", "bound": "hbm",
               "achieved": attn_bytes / (kt_d[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-              "traffic": TRAFFIC_BYTES["decode_attn"] if default_workload else None}
+              "traffic": TRAFFIC_BYTES["decode_attn"] if default_workload else None, "traffic_source": traffic_note}
     roof_d["frac"] = roof_d["achieved"] / roof_d["peak"]
-    layer_p = {"tflops": flops_layer / (np.median(p256_bb) * 1e-3) / 1e12}
+    roof_d["sustained_peak"] = stream_256                   # measured in this run (rs_debug_stream_read)
+    roof_d["frac_of_sustained"] = roof_d["achieved"] / stream_256
+    layer_p = {"tflops": flops_layer / (med(p256_bb) * 1e-3) / 1e12}
     layer_p["frac_mfma"] = layer_p["tflops"] / MFMA_PEAK_TFLOPS
-    layer_d = {"gbs": bytes_layer / (np.median(d256_bb) * 1e-3) / 1e9}
+    layer_p["frac_of_sustained"] = layer_p["tflops"] / mfma_256
+    layer_d = {"gbs": bytes_layer / (med(d256_bb) * 1e-3) / 1e9}
     layer_d["frac_hbm"] = layer_d["gbs"] / HBM_PEAK_GBS
-    # ---- the captured decode step (one graph launch instead of 14 kernel launches)
+    layer_d["frac_of_sustained"] = layer_d["gbs"] / stream_256
+    # ---- the captured decode step (one graph launch instead of the layer's kernel launches)
     enqueue_decode_graph(r)
     c.sync(1)
-    dg, _ = timing.run_alone(c, 1, lambda: enqueue_decode_graph(r), max(4 * K, 100), W)
-    graph = {"decode_ms_alone_256_graph": float(np.median(dg)), "decode_ms_alone_256_eager": float(np.median(d256_bb)),
-             "host_us_per_step_eager": host_cost_us(enqueue_decode, r), "host_us_per_step_graph": host_cost_us(enqueue_decode_graph, r)}
+    dg, _ = timing.run_alone(c, 1, lambda: enqueue_decode_graph(r), max(2 * K, 60), W)
+    graph = {"decode_ms_alone_256_graph": med(dg), "decode_ms_alone_256_eager": med(d256_bb),
+             "host_us_per_step_eager": host_cost_us(enqueue_decode, r, 100), "host_us_per_step_graph": host_cost_us(enqueue_decode_graph, r, 100)}
     log("[bench] decode step as a graph: %s" % json.dumps(graph))
     if args.alone_only:
         # a plain copy of known size, so that HBM byte counters can be scaled against it
         for _ in range(3):
             dst = probe.clone()
         torch.cuda.synchronize()
-        print(json.dumps({"prefill_ms": float(np.median(p256_bb)), "decode_ms": float(np.median(d256_bb)),
+        print(json.dumps({"prefill_ms": med(p256_bb), "decode_ms": med(d256_bb),
                           "prefill_kernels_ms": dict(zip(names, map(float, kt_p))),
                           "decode_kernels_ms": dict(zip(names, map(float, kt_d))), "roofline": roof,
                           "roofline_decode": roof_d}))
         return
 
-    # ---- co-run at the requested split(s)
+    # ---- co-run: the headline split first, then the rest of the configuration's sweep
     splits = [tuple(int(v) for v in args.split.split(","))]
+    extra = [(64, 192), (128, 128), (192, 64)]
     if args.sweep:
-        for s in [(64, 192), (96, 160), (128, 128), (160, 96), (192, 64), (224, 32), (256, 256)]:
-            if s not in splits:
-                splits.append(s)
+        extra += [(96, 160), (160, 96), (224, 32), (256, 256)]
+    for s_ in extra:
+        if s_ not in splits:
+            splits.append(s_)
     sweep = []
     for (pc, dc) in splits:
         c.set_cu_split(pc, dc)
         pa, _ = run_alone(r, 0, max(K // 2, 5), W)
         da, _ = run_alone(r, 1, max(K, 30), W)
-        # Settling: once per process the HIP runtime blocks a kernel-launch call for 30-40 ms some
-        # tens of passes into the first co-run (nothing of this library runs in that call but
-        # launches; the GPU work queued at that moment is under 4 ms).  An untimed co-run of the same
-        # shape comes first so that this one-off lands outside the K timed steps; should a launch
-        # still block inside them, it is timed as it is and listed under "host_stalls".
-        for _ in range(3):
-            if not run_corun(r, max(K, 30), W)[4]:
-                break
         wall_ms, p_co, d_co, n_dec_wall, stalls = run_corun(r, K, W)
         _, kt_pa = run_alone(r, 0, 5, 2, kernel_times=True)
         _, kt_da = run_alone(r, 1, 10, 2, kernel_times=True)
         rec = {
             "prefill_cus": pc, "decode_cus": dc,
-            "prefill_alone_ms": float(np.median(pa)), "decode_alone_ms": float(np.median(da)),
+            "prefill_alone_ms": med(pa), "decode_alone_ms": med(da),
             # host-bracketed: wall time of the K co-run passes / K
             "prefill_corun_ms": wall_ms / K,
             # the same passes by HIP events, for the spread (a late event timestamp shows up as one large max)
@@ -291,30 +302,38 @@ def main():
             "host_stalls": stalls,
             "prefill_tok_s_corun": T / (wall_ms / K * 1e-3),
             "decode_tok_s_corun": B / (pct(d_co, 50) * 1e-3) if len(d_co) else float("nan"),
-            "itl_vs_alone_256": pct(d_co, 50) / float(np.median(d256_bb)),
-            "itl_vs_alone_same_mask": pct(d_co, 50) / float(np.median(da)),
-            "prefill_vs_alone_same_mask": wall_ms / K / float(np.median(pa)),
+            "itl_vs_alone_256": pct(d_co, 50) / med(d256_bb),
+            "itl_vs_alone_same_mask": pct(d_co, 50) / med(da),
+            "prefill_vs_alone_same_mask": wall_ms / K / med(pa),
             "prefill_kernels_ms_alone": dict(zip(names, (round(float(v), 4) for v in kt_pa))),
             "decode_kernels_ms_alone": dict(zip(names, (round(float(v), 4) for v in kt_da))),
         }
-        rec["combined_norm_throughput"] = (float(np.median(p256_bb)) / rec["prefill_corun_ms"]
-                                           + float(np.median(d256_bb)) / rec["decode_corun_p50_ms"])
-        # what a plain streaming read achieves on the decode partition alone: the ceiling of that share
-        c.debug_stream_read(1, probe, probe.numel() * 4)
-        bw_ms = min(c.debug_stream_read(1, probe, probe.numel() * 4) for _ in range(3))
-        rec["decode_partition_stream_read_gbs"] = probe.numel() * 4 / (bw_ms * 1e-3) / 1e9
+        rec["combined_norm_throughput"] = med(p256_bb) / rec["prefill_corun_ms"] + med(d256_bb) / rec["decode_corun_p50_ms"]
+        # what the partitions sustain alone: a plain streaming read on the decode partition, register-only MFMAs on
+        # the prefill partition -- the ceilings of the two shares
+        if dc < 256 or pc < 256:
+            c.debug_stream_read(1, probe, probe.numel() * 4)
+            bw_ms = min(c.debug_stream_read(1, probe, probe.numel() * 4) for _ in range(3))
+            rec["decode_partition_stream_read_gbs"] = probe.numel() * 4 / (bw_ms * 1e-3) / 1e9
+            rec["prefill_partition_mfma_probe_tflops"] = c.debug_mfma_probe(0)
+        else:
+            rec["decode_partition_stream_read_gbs"], rec["prefill_partition_mfma_probe_tflops"] = stream_256, mfma_256
         rec["decode_alone_frac_of_partition_stream"] = (bytes_layer / (rec["decode_alone_ms"] * 1e-3) / 1e9
                                                         / rec["decode_partition_stream_read_gbs"])
         share_p = pc / 256.0
-        rec["prefill_frac_mfma_of_share"] = flops_layer / (rec["prefill_corun_ms"] * 1e-3) / 1e12 / (MFMA_PEAK_TFLOPS * share_p)
-        rec["decode_frac_hbm"] = bytes_layer / (rec["decode_corun_p50_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        p_tflops = flops_layer / (rec["prefill_corun_ms"] * 1e-3) / 1e12
+        d_gbs = bytes_layer / (rec["decode_corun_p50_ms"] * 1e-3) / 1e9
+        rec["prefill_frac_mfma_of_share"] = p_tflops / (MFMA_PEAK_TFLOPS * share_p)
+        rec["prefill_frac_of_partition_mfma_probe"] = p_tflops / rec["prefill_partition_mfma_probe_tflops"]
+        rec["decode_frac_hbm"] = d_gbs / HBM_PEAK_GBS
+        rec["decode_frac_of_partition_stream"] = d_gbs / rec["decode_partition_stream_read_gbs"]
         log("[bench] split %s: %s" % ((pc, dc), json.dumps(rec)))
         sweep.append(rec)
     head = sweep[0]
 
     # ---- measured sequential baseline: same kernels, all CUs, the two phases alternating
     c.set_cu_split(256, 256)
-    k_dec = max(1, int(round(float(np.median(p256_bb)) / float(np.median(d256_bb)))))
+    k_dec = max(1, int(round(med(p256_bb) / med(d256_bb))))
     c.sync(0); c.sync(1)
     t0 = time.perf_counter()
     for _ in range(K):
@@ -324,7 +343,7 @@ def main():
             enqueue_decode(r)
         c.sync(1)
     seq_s = time.perf_counter() - t0
-    seq_norm = (K * float(np.median(p256_bb)) + K * k_dec * float(np.median(d256_bb))) / (seq_s * 1e3)
+    seq_norm = (K * med(p256_bb) + K * k_dec * med(d256_bb)) / (seq_s * 1e3)
 
     out = {
         "metric": "prefill tok/s under co-run with decode (decode p50 ITL alongside)",
@@ -336,16 +355,26 @@ def main():
                                f"split {head['prefill_cus']}/{head['decode_cus']} CUs",
                    "prefill_tokens": T, "decode_batch": B, "sum_ctx": int(r["ctx"].sum()),
                    "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"]},
+        # the four targets at the headline split, each with what it is measured against
+        "targets": {
+            "itl_corun_vs_alone_256": {"value": head["itl_vs_alone_256"], "target": "<= 1.2"},
+            "combined_vs_sequential": {"value": head["combined_norm_throughput"] / seq_norm, "target": ">= 1.5"},
+            "prefill_frac_mfma_peak_of_share_corun": {"value": head["prefill_frac_mfma_of_share"], "target": ">= 0.60",
+                                                      "of_measured_mfma_probe_on_partition": head["prefill_frac_of_partition_mfma_probe"]},
+            "decode_frac_hbm_peak_corun": {"value": head["decode_frac_hbm"], "target": ">= 0.70",
+                                           "of_measured_stream_read_on_partition": head["decode_frac_of_partition_stream"]},
+        },
         "decode_itl_p50_ms_corun": head["decode_corun_p50_ms"],
         "decode_itl_p95_ms_corun": head["decode_corun_p95_ms"],
-        "decode_itl_ms_alone_256": float(np.median(d256_bb)),
-        "prefill_ms_alone_256": float(np.median(p256_bb)),
+        "decode_itl_ms_alone_256": med(d256_bb),
+        "prefill_ms_alone_256": med(p256_bb),
         "itl_corun_vs_alone_256": head["itl_vs_alone_256"],
         "combined_norm_throughput": head["combined_norm_throughput"],
         "sequential_baseline_norm_throughput_measured": seq_norm,
         "prefill_layer_alone_256": layer_p, "decode_layer_alone_256": layer_d,
         "prefill_kernels_ms_alone_256": dict(zip(names, map(float, kt_p))),
         "decode_kernels_ms_alone_256": dict(zip(names, map(float, kt_d))),
+        "sustained_256": {"mfma_probe_tflops": mfma_256, "stream_read_gbs": stream_256},
         "roofline": roof, "roofline_decode": roof_d, "decode_graph": graph, "sweep": sweep,
     }
     if not args.no_cpu_baseline:

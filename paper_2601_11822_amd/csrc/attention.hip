@@ -29,6 +29,18 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // from the pools into MFMA fragments with 16-byte loads (no LDS staging).
 // The chunking depends on the context length only, never on the launch's CU share.
 //
+// Measured alternatives that were no better (Llama-3-8B shape, batch 64, contexts U[512,4096]; whole chip /
+// 128-CU partition / partition beside a prefill pass; this kernel: 110 / 144 / 172 us):
+//   * a persistent launch whose waves are independent workers on 128-token items, the next item's block ids
+//     and first K/V loads in flight while an item is computed, items dealt round-robin: 126 / 156 / 171 us
+//     (no round trip is exposed any more, yet nothing is gained: the kernel is not bound by the start-up of
+//     its workgroups); the same with a device-side item counter: 200 us on any partition (12 500
+//     single-address atomics serialise at about 16 ns each);
+//   * the kv heads of one (request, chunk) on ONE XCD instead of eight: 7-10 % slower everywhere.
+// What the measurements fit: a compute unit sustains a bounded number of outstanding lines, so its rate is
+// that bound over the memory latency of the access pattern -- 47 GB/s for a linear stream, 34 GB/s for
+// these 4 KB pieces of shuffled 32 KB blocks (38 GB/s with consecutive block ids), on a 128-CU partition.
+//
 // Row permutation: the two 16x16 score tiles of an iteration do not hold "block 0" and "block 1"
 // but, with h = lane>>4, tile A row 4h+i <- token 8(h&1)+i of block h>>1 and tile B row 4h+i <-
 // token 8(h&1)+4+i of block h>>1.  A lane's 4+4 score registers are then 8 consecutive tokens of

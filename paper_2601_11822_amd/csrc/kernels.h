@@ -204,6 +204,8 @@ void launch_stream_read(hipStream_t st, const void *src, size_t bytes, int n_wor
 // Back-to-back register-only 32x32x16 bf16 MFMAs; returns the flops the launch performs.
 double launch_mfma_probe(hipStream_t st, float *sink, int n_workgroups, int iters);
 
+void launch_noop(hipStream_t st);
+
 // Zeroes `bytes` (a multiple of 16) of device memory with a kernel (usable under stream capture).
 void launch_fill_zero(hipStream_t st, void *dst, size_t bytes);
 

@@ -194,6 +194,7 @@ struct rs_ctx {
     std::vector<int64_t> last_batch;   // request ids of the rows of the most recent rs_step's decode batch
     Side side[2];
     bool over_alloc = true;
+    bool new_stream = false;     // a masked stream was created since the pair was last warmed (set_split)
     bool kernel_timing = false;
 
     // allocator
@@ -290,6 +291,7 @@ int32_t get_stream(rs_ctx *c, int side, int cus, hipStream_t *out) {
     hipStream_t st;
     HIP_TRY(hipExtStreamCreateWithCUMask(&st, 8, mask));
     s.pool[cus] = st;
+    c->new_stream = true;
     *out = st;
     return RS_OK;
 }
@@ -478,6 +480,19 @@ int32_t set_split(rs_ctx *c, int32_t p, int32_t d) {
         if (rc) return rc;
     }
     c->over_alloc = over;
+    if (c->gpu && c->new_stream && p > 0 && d > 0) {
+        // The first time two queues have work at the same moment the runtime blocks a launch call for tens of
+        // milliseconds (observed once per process: the first layer call that overlapped the other side stalled
+        // 30-60 ms, with both streams long created and used one at a time).  A new stream has just joined the
+        // pool: overlap a few empty kernels on the pair now, in this set-up call, and wait for them.
+        c->new_stream = false;
+        for (int i = 0; i < 8; ++i) {
+            launch_noop(c->side[0].stream);
+            launch_noop(c->side[1].stream);
+        }
+        HIP_TRY(hipStreamSynchronize(c->side[0].stream));
+        HIP_TRY(hipStreamSynchronize(c->side[1].stream));
+    }
     return RS_OK;
 }
 
