@@ -439,6 +439,17 @@ int32_t rs_submit_tokens(rs_ctx *ctx, int64_t req_id, const int32_t *prompt_toke
 int32_t rs_step_tokens(rs_ctx *ctx, int32_t wait_decode, rs_step_out *out);
 int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out,
                           int32_t *finished_out);
+/* rs_step_tokens and the engine's decode thread launch every decode step as ONE captured HIP graph (section
+ * 4.5.2: decode steps are captured as graphs and replayed; section 4.5.3: a graph keeps the CU mask it was
+ * captured under): embedding, every layer and the head are recorded once per (decode batch size, context bound
+ * rounded up to 512 tokens, masked decode stream) and replayed with one runtime call; tokens, context lengths
+ * and block tables are read from library buffers that are refreshed before every launch.  The first step of a
+ * new key records and instantiates (set-up work: allocates inside the runtime); at most 512 graphs are kept.
+ * Results are bit-identical to the uncaptured step.  rs_set_step_graphs(ctx, 0) turns this off (the step's
+ * kernels are then launched one by one); not while the engine runs (RS_ERR_STATE).
+ * rs_step_graph_stats: stats_out[0] graphs captured so far, [1] steps launched as a graph. */
+int32_t rs_set_step_graphs(rs_ctx *ctx, int32_t on);
+int32_t rs_step_graph_stats(rs_ctx *ctx, int64_t stats_out[2]);
 /* Host-clock times in seconds since the context was created: [0] submission, [1] the moment the
  * host saw the request's first token, [2] its latest token (0 while there is none). */
 int32_t rs_request_times(rs_ctx *ctx, int64_t req_id, double times_out[3]);

@@ -32,7 +32,7 @@ EXPORTS = [
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_debug_mfma_probe", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
-    "rs_debug_push_sampled", "rs_request_times", "rs_request_release", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
+    "rs_debug_push_sampled", "rs_request_times", "rs_request_release", "rs_set_step_graphs", "rs_step_graph_stats", "rs_engine_start", "rs_engine_stop", "rs_engine_stats", "rs_release_source_weights", "rs_set_moe_weights", "rs_debug_read_moe_routing",
 ]
 
 
@@ -399,6 +399,15 @@ class Context:
 
     def request_release(self, req_id: int):
         _check(self._lib.rs_request_release(self._h, ctypes.c_int64(req_id)))
+
+    def set_step_graphs(self, on: bool):
+        _check(self._lib.rs_set_step_graphs(self._h, ctypes.c_int32(1 if on else 0)))
+
+    def step_graph_stats(self):
+        """(graphs captured, decode steps launched as a graph)."""
+        st = (ctypes.c_int64 * 2)()
+        _check(self._lib.rs_step_graph_stats(self._h, st))
+        return st[0], st[1]
 
     def engine_start(self):
         _check(self._lib.rs_engine_start(self._h))

@@ -190,6 +190,11 @@ struct rs_ctx {
         }
     };
     std::map<GraphKey, hipGraphExec_t> graphs;
+    // whole decode steps of the closed-loop server (embedding, every layer, head), captured per (batch, context
+    // bucket, masked decode stream); every pointer in them is a library buffer
+    std::map<std::tuple<int32_t, int32_t, hipStream_t>, hipGraphExec_t> step_graphs;
+    bool step_graphs_on = true;
+    int64_t step_graph_captures = 0, step_graph_launches = 0;
     bool capturing = false;      // a decode step is being recorded: no event records on the stream
     std::vector<int64_t> last_batch;   // request ids of the rows of the most recent rs_step's decode batch
     Side side[2];
@@ -745,7 +750,13 @@ int32_t report_flag(int32_t flag) {
 
 // Captured decode steps bake in the addresses of the layer's packed matrices: whenever those may
 // change (rs_set_weights, rs_set_moe_weights) every cached graph of the layer is destroyed.
+void drop_step_graphs(rs_ctx *c) {
+    for (auto &kv : c->step_graphs) (void)hipGraphExecDestroy(kv.second);
+    c->step_graphs.clear();
+}
+
 void drop_layer_graphs(rs_ctx *c, int32_t layer) {
+    drop_step_graphs(c);
     for (auto it = c->graphs.begin(); it != c->graphs.end();) {
         if (it->first.layer == layer) {
             (void)hipGraphExecDestroy(it->second);
@@ -917,6 +928,7 @@ int32_t rs_destroy(rs_ctx *c) {
             free_ws(c->ws[s]);
         }
         for (auto &kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+        drop_step_graphs(c);
         for (auto &pl : c->packed)
             for (bf16_t *q : {pl.wqkv, pl.wo, pl.wg, pl.wu, pl.wd})
                 if (q) (void)hipFree(q);
@@ -1082,6 +1094,7 @@ int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
         if (!w->embed || !w->final_norm || !w->lm_head) return fail(RS_ERR_BAD_ARG, "null head pointer");
         HIP_TRY(hipSetDevice(c->device));
         HIP_TRY(hipDeviceSynchronize());   // the packed copy and the partial-sum buffers may be in use
+        drop_step_graphs(c);
         const int d = c->m.d_model;
         if (c->packed_lm) { (void)hipFree(c->packed_lm); c->packed_lm = nullptr; }
         HIP_TRY(hipMalloc((void **)&c->packed_lm, packed_weight_elems(w->vocab, d) * sizeof(bf16_t)));
@@ -1238,6 +1251,20 @@ int32_t rs_decode_layer_graph(rs_ctx *c, int32_t layer, const void *x_in, void *
     }
     c->last_rows[RS_SIDE_DECODE] = B;
     HIP_TRY(hipGraphLaunch(it->second, st));
+    return RS_OK;
+}
+
+int32_t rs_set_step_graphs(rs_ctx *c, int32_t on) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->engine) return fail(RS_ERR_STATE, "the engine's threads drive this context");
+    c->step_graphs_on = on != 0;
+    return RS_OK;
+}
+
+int32_t rs_step_graph_stats(rs_ctx *c, int64_t stats_out[2]) {
+    if (!c || !stats_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    stats_out[0] = c->step_graph_captures;
+    stats_out[1] = c->step_graph_launches;
     return RS_OK;
 }
 
@@ -1840,22 +1867,60 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             HIP_TRY(hipEventRecord(c->staged[flip], st));
             if (in->wait_decode) { int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2); if (rc) return rc; }
             Workspace &w = c->ws[RS_SIDE_DECODE];
-            const void *x_first = in->decode_hidden;
-            void *x_out = in->decode_out;
-            if (token_mode) {
-                launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + RS_SIDE_DECODE, B,
-                                           c->m.d_model, c->head.vocab});
-                x_first = w.xbuf;
-                x_out = w.xbuf;
-            }
-            for (int l = 0; l < c->m.n_layers; ++l) {
-                if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                int32_t rc = decode_layer(c, w, l, l == 0 ? x_first : (const void *)x_out, x_out, c->d_ctx, c->d_tab, mb, B, max_ctx);
+            // the step's kernels: embedding (token mode), every layer, head (token mode)
+            auto enqueue_kernels = [&](int ctx_bound) -> int32_t {
+                const void *x_first = in->decode_hidden;
+                void *x_out = in->decode_out;
+                if (token_mode) {
+                    launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + RS_SIDE_DECODE, B,
+                                               c->m.d_model, c->head.vocab});
+                    x_first = w.xbuf;
+                    x_out = w.xbuf;
+                }
+                for (int l = 0; l < c->m.n_layers; ++l) {
+                    if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+                    int32_t rc = decode_layer(c, w, l, l == 0 ? x_first : (const void *)x_out, x_out, c->d_ctx, c->d_tab, mb, B, ctx_bound);
+                    if (rc) return rc;
+                }
+                if (token_mode) return head_greedy(c, RS_SIDE_DECODE, w.xbuf, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
+                return RS_OK;
+            };
+            if (token_mode && c->step_graphs_on) {
+                // Section 4.5.2: decode steps are captured as graphs per batch size and replayed.  The key is
+                // (batch, context bucket, masked stream): the captured launches bake in the batch, a bound on the
+                // contexts (a multiple of 512 tokens) and the stream's CU mask; everything else they read --
+                // tokens, context lengths, block tables -- sits in library buffers refreshed before every launch.
+                const int cap = std::min(c->lim.max_context, c->m.max_pos);
+                const int bucket = std::min(((max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK) * RS_DECODE_CHUNK, cap);
+                const auto key = std::make_tuple((int32_t)B, (int32_t)bucket, st);
+                auto it = c->step_graphs.find(key);
+                if (it == c->step_graphs.end()) {
+                    if (c->step_graphs.size() >= 512) drop_step_graphs(c);   // set-up work either way; start over
+                    hipGraph_t graph = nullptr;
+                    hipGraphExec_t exec = nullptr;
+                    HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+                    c->capturing = true;
+                    const int32_t rc = enqueue_kernels(bucket);
+                    c->capturing = false;
+                    const hipError_t e = hipStreamEndCapture(st, &graph);
+                    if (rc) {
+                        if (graph) (void)hipGraphDestroy(graph);
+                        return rc;
+                    }
+                    HIP_TRY(e);
+                    const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+                    (void)hipGraphDestroy(graph);
+                    HIP_TRY(ei);
+                    it = c->step_graphs.emplace(key, exec).first;
+                    c->step_graph_captures++;
+                }
+                HIP_TRY(hipGraphLaunch(it->second, st));
+                c->step_graph_launches++;
+            } else {
+                const int32_t rc = enqueue_kernels(max_ctx);
                 if (rc) return rc;
             }
             if (token_mode) {
-                int32_t rc = head_greedy(c, RS_SIDE_DECODE, w.xbuf, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
-                if (rc) return rc;
                 HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipMemcpyAsync(&c->h_err[2 + flip], c->err_flag + RS_SIDE_DECODE, sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipEventRecord(c->sampled_ev[flip], st));

@@ -223,6 +223,40 @@ def test_closed_loop_generation_matches_oracle(wait):
         rig.close()
 
 
+def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
+    """Section 4.5.2: the serving loop launches each decode step (embedding, both layers, head) as one captured
+    graph per (batch size, context bucket, stream).  The generated tokens are checked against the oracle like any
+    closed-loop run, the counters show that every decode step went out as a graph and that graphs were reused,
+    and the same requests served with graphs off give the same tokens."""
+    shape, n_layers, vocab = S.TINY, 2, 1000
+    prompts = [(1, 37, 30, 0), (2, 5, 40, 0), (3, 64, 25, 2), (4, 16, 3, 3), (5, 23, 33, 6)]
+    requests = [(rid, S.prompt_tokens(pl, vocab, rid), mn, arr) for rid, pl, mn, arr in prompts]
+    hb = S.head_weights(shape.d_model, vocab)
+    wbits = [S.layer_weights(shape, l) for l in range(n_layers)]
+    results = {}
+    for graphs in (True, False):
+        rig = Rig(shape, n_blocks=64, max_prefill_tokens=128, max_decode_batch=4, max_context=128, n_layers=n_layers,
+                  with_oracle=False)
+        try:
+            hd = {k: to_dev(v) for k, v in hb.items()}
+            rig.ctx.set_head(hd["embed"], hd["final_norm"], hd["lm_head"], vocab, -1)
+            rig.ctx.set_step_graphs(graphs)
+            rig.ctx.set_cu_split(128, 128)   # the manager (no profile) moves to (0,256) / (256,256): several streams, several graphs
+            outs, _ = _serve(rig, hb, vocab, -1, requests, wait=False)
+            captured, launched = rig.ctx.step_graph_stats()
+            print(f"  graphs={graphs}: {captured} graphs captured, {launched} steps launched as graphs", flush=True)
+            if graphs:
+                assert captured >= 2 and launched >= 30 and launched > 3 * captured
+                frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, -1, requests, outs)
+                assert frac >= 0.9
+            else:
+                assert captured == 0 and launched == 0
+            results[graphs] = outs
+        finally:
+            rig.close()
+    assert results[True] == results[False]
+
+
 def test_closed_loop_with_preemption_matches_oracle():
     # pool of 6 blocks: two 20-token prompts growing to 60 tokens each need 8: one is recomputed
     shape, n_layers, vocab = S.TINY, 2, 1000
