@@ -447,9 +447,11 @@ int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int3
  * new key records and instantiates (set-up work: allocates inside the runtime); at most 512 graphs are kept.
  * Results are bit-identical to the uncaptured step.  rs_set_step_graphs(ctx, 0) turns this off (the step's
  * kernels are then launched one by one); not while the engine runs (RS_ERR_STATE).
- * rs_step_graph_stats: stats_out[0] graphs captured so far, [1] steps launched as a graph. */
+ * rs_step_graph_stats: stats_out[0] graphs captured so far, [1] steps launched as a graph, [2] decode steps
+ * enqueued by the serving loop outside of a capture, [3] host nanoseconds those steps' launches took in total
+ * (one graph launch, or the step's kernel launches one by one). */
 int32_t rs_set_step_graphs(rs_ctx *ctx, int32_t on);
-int32_t rs_step_graph_stats(rs_ctx *ctx, int64_t stats_out[2]);
+int32_t rs_step_graph_stats(rs_ctx *ctx, int64_t stats_out[4]);
 /* Host-clock times in seconds since the context was created: [0] submission, [1] the moment the
  * host saw the request's first token, [2] its latest token (0 while there is none). */
 int32_t rs_request_times(rs_ctx *ctx, int64_t req_id, double times_out[3]);

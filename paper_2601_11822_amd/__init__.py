@@ -404,10 +404,10 @@ class Context:
         _check(self._lib.rs_set_step_graphs(self._h, ctypes.c_int32(1 if on else 0)))
 
     def step_graph_stats(self):
-        """(graphs captured, decode steps launched as a graph)."""
-        st = (ctypes.c_int64 * 2)()
+        """(graphs captured, decode steps launched as a graph, decode steps enqueued outside a capture, host ns of their launches)."""
+        st = (ctypes.c_int64 * 4)()
         _check(self._lib.rs_step_graph_stats(self._h, st))
-        return st[0], st[1]
+        return st[0], st[1], st[2], st[3]
 
     def engine_start(self):
         _check(self._lib.rs_engine_start(self._h))

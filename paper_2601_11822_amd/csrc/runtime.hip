@@ -195,6 +195,7 @@ struct rs_ctx {
     std::map<std::tuple<int32_t, int32_t, hipStream_t>, hipGraphExec_t> step_graphs;
     bool step_graphs_on = true;
     int64_t step_graph_captures = 0, step_graph_launches = 0;
+    int64_t steps_enqueued = 0, step_enqueue_ns = 0;   // decode steps of the serving loop and the host time their launches took
     bool capturing = false;      // a decode step is being recorded: no event records on the stream
     std::vector<int64_t> last_batch;   // request ids of the rows of the most recent rs_step's decode batch
     Side side[2];
@@ -1261,10 +1262,12 @@ int32_t rs_set_step_graphs(rs_ctx *c, int32_t on) {
     return RS_OK;
 }
 
-int32_t rs_step_graph_stats(rs_ctx *c, int64_t stats_out[2]) {
+int32_t rs_step_graph_stats(rs_ctx *c, int64_t stats_out[4]) {
     if (!c || !stats_out) return fail(RS_ERR_BAD_ARG, "null argument");
     stats_out[0] = c->step_graph_captures;
     stats_out[1] = c->step_graph_launches;
+    stats_out[2] = c->steps_enqueued;
+    stats_out[3] = c->step_enqueue_ns;
     return RS_OK;
 }
 
@@ -1885,6 +1888,8 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 if (token_mode) return head_greedy(c, RS_SIDE_DECODE, w.xbuf, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
                 return RS_OK;
             };
+            const auto t_enq = std::chrono::steady_clock::now();
+            bool captured_now = false;
             if (token_mode && c->step_graphs_on) {
                 // Section 4.5.2: decode steps are captured as graphs per batch size and replayed.  The key is
                 // (batch, context bucket, masked stream): the captured launches bake in the batch, a bound on the
@@ -1913,12 +1918,17 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                     HIP_TRY(ei);
                     it = c->step_graphs.emplace(key, exec).first;
                     c->step_graph_captures++;
+                    captured_now = true;
                 }
                 HIP_TRY(hipGraphLaunch(it->second, st));
                 c->step_graph_launches++;
             } else {
                 const int32_t rc = enqueue_kernels(max_ctx);
                 if (rc) return rc;
+            }
+            if (!captured_now) {   // steady state only: a step that recorded its graph is set-up work
+                c->steps_enqueued++;
+                c->step_enqueue_ns += std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t_enq).count();
             }
             if (token_mode) {
                 HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));

@@ -108,12 +108,15 @@ def serve(c: Context, work, wait_decode: bool, time_limit: float):
             time.sleep(min(0.002, max(0.0, todo[0][1] - now)))
             last_t = None
             continue
+        t_call = time.perf_counter()
         so = c.step_tokens(wait_decode=wait_decode)
         t = time.perf_counter() - t0
+        t_call = time.perf_counter() - t_call
         if so.decode_batch == 0 and so.prefill_started_req < 0:
             time.sleep(0.0005)   # only a prefill in flight: nothing to enqueue until it is done
         steps.append((t, so.decode_batch, so.decode_sum_ctx, so.prefill_cus, so.decode_cus, so.prefill_started_tokens,
-                      so.n_preempted, so.decode_ms, (t - last_t) if (last_t is not None and so.decode_batch) else -1.0))
+                      so.n_preempted, so.decode_ms, (t - last_t) if (last_t is not None and so.decode_batch) else -1.0,
+                      t_call if (so.decode_batch and so.prefill_started_req < 0 and not wait_decode) else -1.0))
         last_t = t if so.decode_batch else None
         n_done += so.n_finished
         live -= so.n_finished
@@ -205,6 +208,11 @@ def summarise(c: Context, work, steps, wall: float):
         "decode_steps": int(sum(1 for s in steps if s[1] > 0)), "mean_batch": float(wts.mean()) if len(wts) else 0.0,
         "max_batch": int(max((s[1] for s in steps), default=0)), "preemptions": int(sum(s[6] for s in steps)),
         "splits_used": splits,
+        # host time inside rs_step_tokens for a step that enqueued a decode step and no prefill (scheduling + launches)
+        "host_us_per_decode_step_p50": (lambda v: float(np.percentile(v, 50) * 1e6) if len(v) else None)(
+            [s[9] for s in steps if len(s) > 9 and s[9] > 0]),
+        "step_graphs": dict(zip(("captured", "launched", "steps_enqueued", "enqueue_ns_total"), c.step_graph_stats())),
+        "host_launch_us_per_decode_step": (lambda g: g[3] / max(g[2], 1) / 1e3)(c.step_graph_stats()),
         "step_ms_p50_by_split": {k: float(np.percentile(v, 50)) for k, v in sorted(by_split.items())},
     }
 
@@ -237,6 +245,7 @@ def main(argv=None):
     ap.add_argument("--wait-decode", action="store_true", help="wait for each decode step (exact per-step GPU times)")
     ap.add_argument("--experts", type=int, default=0, help="sparse feed-forward block with this many experts (two per token)")
     ap.add_argument("--release-weights", action="store_true", help="free each layer's row-major matrices after packing")
+    ap.add_argument("--no-step-graphs", action="store_true", help="launch each decode step's kernels one by one (rs_set_step_graphs(0))")
     ap.add_argument("--engine", action="store_true", help="let the library's two threads drive (rs_engine_start)")
     ap.add_argument("--time-limit", type=float, default=120.0)
     ap.add_argument("--seed", type=int, default=4)
@@ -266,6 +275,8 @@ def main(argv=None):
                           release=a.release_weights, experts=a.experts)
     _log(f"[serve] model of {a.layers} layers built in {time.time() - t0:.1f}s; {a.requests} requests over "
          f"{work[-1][1]:.1f}s, {sum(len(w[2]) for w in work)} prompt tokens, {sum(w[3] for w in work)} to generate")
+    if a.no_step_graphs:
+        c.set_step_graphs(False)
     # one throw-away request settles lazy runtime work (first launches, masked streams)
     settle_id = 1 << 40
     c.submit_tokens(settle_id, work[0][2][:64], 4)
@@ -280,7 +291,8 @@ def main(argv=None):
         steps, wall = serve(c, work, a.wait_decode, a.time_limit)
         rec = summarise(c, work, steps, wall)
     rec.update({"policy": a.policy, "shape": shape.name, "layers": a.layers, "rate_per_s": a.rate, "slo_ms": a.slo_ms,
-                "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "experts": a.experts, "data": "synthetic"})
+                "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "experts": a.experts, "data": "synthetic",
+                "step_graphs": rec.get("step_graphs") if not a.no_step_graphs else "off"})
     line = json.dumps(rec)
     print(line, flush=True)
     if a.out:

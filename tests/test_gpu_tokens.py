@@ -243,7 +243,7 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
             rig.ctx.set_step_graphs(graphs)
             rig.ctx.set_cu_split(128, 128)   # the manager (no profile) moves to (0,256) / (256,256): several streams, several graphs
             outs, _ = _serve(rig, hb, vocab, -1, requests, wait=False)
-            captured, launched = rig.ctx.step_graph_stats()
+            captured, launched, _, _ = rig.ctx.step_graph_stats()
             print(f"  graphs={graphs}: {captured} graphs captured, {launched} steps launched as graphs", flush=True)
             if graphs:
                 assert captured >= 2 and launched >= 30 and launched > 3 * captured
