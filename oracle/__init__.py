@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(build())
         _lib.orc_prefill_layer.restype = ctypes.c_int
         _lib.orc_decode_layer.restype = ctypes.c_int
+        _lib.orc_prefill_chunk_layer.restype = ctypes.c_int
         _lib.orc_attn_causal.restype = ctypes.c_int
         _lib.orc_attn_paged.restype = ctypes.c_int
         _lib.orc_kv_write.restype = ctypes.c_int
@@ -252,6 +253,27 @@ class OracleLayer:
                                      ctypes.byref(t) if t is not None else None)
         if rc:
             raise ValueError(f"orc_prefill_layer failed: {rc}")
+        return (y, arrs) if taps else y
+
+    def prefill_chunk(self, x, cu_seqlens: Sequence[int], start_pos: Sequence[int], tables, Kc, Vc, rows=None,
+                      taps: bool = False):
+        """One chunk of each prompt: request r's rows sit at positions start_pos[r].. and attend to everything
+        cached before them plus themselves.  Returns y [n_eval,d] (and taps dict)."""
+        x = _f32c(x); cu = _i32c(cu_seqlens); tables = _i32c(tables); sp = _i32c(start_pos)
+        T = int(cu[-1])
+        assert x.shape == (T, self.d) and len(sp) == len(cu) - 1
+        assert Kc.dtype == np.float32 and Kc.flags.c_contiguous and Vc.flags.c_contiguous
+        r = None if rows is None else _i32c(rows)
+        n_eval = T if r is None else len(r)
+        y = np.empty((n_eval, self.d), dtype=np.float32)
+        t, arrs = self._taps(T, taps)
+        rc = lib().orc_prefill_chunk_layer(ctypes.byref(self._c), _fp(x), _ip(cu), ctypes.c_int32(len(cu) - 1), _ip(sp),
+                                           _ip(tables), ctypes.c_int64(tables.shape[1]), _fp(Kc), _fp(Vc),
+                                           ctypes.c_int64(Kc.shape[0]), _ip(r),
+                                           ctypes.c_int64(0 if r is None else len(r)), _fp(y),
+                                           ctypes.byref(t) if t is not None else None)
+        if rc:
+            raise ValueError(f"orc_prefill_chunk_layer failed: {rc}")
         return (y, arrs) if taps else y
 
     def decode(self, x, ctx_lens, tables, Kc, Vc, taps: bool = False):

@@ -24,6 +24,11 @@
  *   h2 = RMSNorm(x1; g2)
  *   y  = x1 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T        silu(z) = z / (1 + exp(-z))
  *
+ * A prompt may also be evaluated in chunks (section 3.1: chunked prefill, the hybrid-batching baseline the
+ * paper compares with): a chunk's tokens sit at positions start..start+len-1 and attend to every cached
+ * position before them plus themselves; orc_prefill_chunk_layer reads all keys back through the block table.
+ * Pinned by: chunked == whole prefill rows == float64 dense rows (tests/test_oracle_pins.py).
+ *
  * Arithmetic is float32 (the precision the task fixes for the oracle); the
  * rotary angles are formed in float64 and their cos/sin rounded to float32.
  * Matrix products accumulate k = 0..K-1 in order for every output element.
@@ -253,6 +258,48 @@ int orc_attn_paged(const float *q, const float *Kc, const float *Vc, int64_t n_b
     return err == 2 ? ORC_ERR_BLOCK : (err ? ORC_ERR_ARG : ORC_OK);
 }
 
+/* Attention of query rows over the paged cache: row r belongs to request req_of_row[r] and sits at position
+ * pos_of_row[r]; it attends to the cached positions 0..pos_of_row[r] of that request (its own key included:
+ * the caller has written it).  This is the chunked-prefill case (section 3.1: a prompt processed in chunks;
+ * a later chunk's queries see the keys of the earlier chunks in the cache).  q: [T][Hq][hd], row stride
+ * q_stride; rows/n_rows as in orc_attn_causal; o: [T][Hq*hd]. */
+int orc_attn_cached_rows(const float *q, int64_t q_stride, const int32_t *req_of_row, const int32_t *pos_of_row,
+                         int64_t T, const float *Kc, const float *Vc, int64_t n_blocks, int64_t block, int64_t Hq,
+                         int64_t Hkv, int64_t hd, const int32_t *tables, int64_t max_blk, const int32_t *rows,
+                         int64_t n_rows, float *o) {
+    if (Hq % Hkv) return ORC_ERR_ARG;
+    int64_t G = Hq / Hkv;
+    int64_t n_eval = rows ? n_rows : T;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t e = 0; e < n_eval; ++e) {
+        int64_t r = rows ? rows[e] : e;
+        if (r < 0 || r >= T) { err = 1; continue; }
+        int64_t n = (int64_t)pos_of_row[r] + 1;
+        const int32_t *tab = tables + (int64_t)req_of_row[r] * max_blk;
+        if (n <= 0 || (n + block - 1) / block > max_blk) { err = 1; continue; }
+        const float **kp = (const float **)malloc(sizeof(float *) * n * 2);
+        const float **vp = kp + n;
+        float *scratch = (float *)malloc(sizeof(float) * n);
+        for (int64_t hq = 0; hq < Hq; ++hq) {
+            int64_t hk = hq / G;
+            int bad = 0;
+            for (int64_t j = 0; j < n; ++j) {
+                int64_t blk = tab[j / block];
+                if (blk < 0 || blk >= n_blocks) { bad = 1; break; }
+                int64_t off = ((blk * block + j % block) * Hkv + hk) * hd;
+                kp[j] = Kc + off;
+                vp[j] = Vc + off;
+            }
+            if (bad) { err = 2; break; }
+            attend_one(q + r * q_stride + hq * hd, kp, vp, n, hd, o + r * Hq * hd + hq * hd, scratch);
+        }
+        free(scratch);
+        free((void *)kp);
+    }
+    return err == 2 ? ORC_ERR_BLOCK : (err ? ORC_ERR_ARG : ORC_OK);
+}
+
 /* Weights of one layer, float32, [out][in]; *_t are their [in][out] copies. */
 typedef struct {
     int32_t d, hq, hkv, hd, f, block;
@@ -299,10 +346,31 @@ static void ffn_rows(const orc_layer *L, const float *x_rows, const float *attn_
  * 4.5.2).  x: [T][d].  K and V of EVERY token are computed and written to the
  * pools; attention and the rest of the layer are evaluated for the rows listed
  * in rows (NULL = all).  y: [n_eval][d] in the order of rows. */
+static int prefill_layer_from(const orc_layer *L, const float *x, const int32_t *cu_seqlens, int32_t n_req,
+                              const int32_t *start_pos, const int32_t *tables, int64_t max_blk, float *Kc, float *Vc,
+                              int64_t n_blocks, const int32_t *rows, int64_t n_rows, float *y, const orc_taps *taps);
+
 int orc_prefill_layer(const orc_layer *L, const float *x, const int32_t *cu_seqlens, int32_t n_req,
                       const int32_t *tables, int64_t max_blk, float *Kc, float *Vc,
                       int64_t n_blocks, const int32_t *rows, int64_t n_rows, float *y,
                       const orc_taps *taps) {
+    return prefill_layer_from(L, x, cu_seqlens, n_req, NULL, tables, max_blk, Kc, Vc, n_blocks, rows, n_rows, y, taps);
+}
+
+/* One CHUNK of each of n_req prompts (section 3.1, chunked prefill): request r's rows are its tokens at
+ * positions start_pos[r] .. start_pos[r] + len_r - 1; the tokens before start_pos[r] are already in the
+ * cache (written by earlier chunks).  K/V of the chunk's tokens are appended at their positions, and every
+ * evaluated row attends to cached positions 0..its own, read back through the block table. */
+int orc_prefill_chunk_layer(const orc_layer *L, const float *x, const int32_t *cu_seqlens, int32_t n_req,
+                            const int32_t *start_pos, const int32_t *tables, int64_t max_blk, float *Kc, float *Vc,
+                            int64_t n_blocks, const int32_t *rows, int64_t n_rows, float *y, const orc_taps *taps) {
+    if (!start_pos) return ORC_ERR_ARG;
+    return prefill_layer_from(L, x, cu_seqlens, n_req, start_pos, tables, max_blk, Kc, Vc, n_blocks, rows, n_rows, y, taps);
+}
+
+static int prefill_layer_from(const orc_layer *L, const float *x, const int32_t *cu_seqlens, int32_t n_req,
+                              const int32_t *start_pos, const int32_t *tables, int64_t max_blk, float *Kc, float *Vc,
+                              int64_t n_blocks, const int32_t *rows, int64_t n_rows, float *y, const orc_taps *taps) {
     int64_t d = L->d, hd = L->hd, Hq = L->hq, Hkv = L->hkv;
     int64_t qd = Hq * hd, kvd = Hkv * hd, nqkv = qd + 2 * kvd;
     int64_t T = cu_seqlens[n_req];
@@ -314,7 +382,7 @@ int orc_prefill_layer(const orc_layer *L, const float *x, const int32_t *cu_seql
     int32_t *req = (int32_t *)malloc(sizeof(int32_t) * T);
     for (int32_t r = 0; r < n_req; ++r)
         for (int64_t t = cu_seqlens[r]; t < cu_seqlens[r + 1]; ++t) {
-            pos[t] = (int32_t)(t - cu_seqlens[r]);
+            pos[t] = (int32_t)(t - cu_seqlens[r]) + (start_pos ? start_pos[r] : 0);
             req[t] = r;
         }
     orc_rmsnorm(x, L->g1, T, d, L->eps, h);
@@ -326,8 +394,12 @@ int orc_prefill_layer(const orc_layer *L, const float *x, const int32_t *cu_seql
     float *attn = NULL, *xe = NULL, *ae = NULL;
     if (rc == ORC_OK) {
         attn = (float *)calloc((size_t)T * qd, sizeof(float));
-        rc = orc_attn_causal(qkv, nqkv, qkv + qd, qkv + qd + kvd, nqkv, cu_seqlens, n_req, Hq, Hkv,
-                             hd, rows, n_rows, attn);
+        if (start_pos)   /* keys of earlier chunks live in the cache only: every key is read back from it */
+            rc = orc_attn_cached_rows(qkv, nqkv, req, pos, T, Kc, Vc, n_blocks, L->block, Hq, Hkv, hd, tables, max_blk,
+                                      rows, n_rows, attn);
+        else
+            rc = orc_attn_causal(qkv, nqkv, qkv + qd, qkv + qd + kvd, nqkv, cu_seqlens, n_req, Hq, Hkv,
+                                 hd, rows, n_rows, attn);
     }
     if (rc == ORC_OK) {
         xe = (float *)malloc(sizeof(float) * n_eval * d);

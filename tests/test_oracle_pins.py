@@ -460,3 +460,58 @@ def test_single_step_wrappers_use_the_layer_s_own_matrices():
     assert _close(L.norm(1, x), brute.rmsnorm(x, w32["g1"], shape.rms_eps))
     assert _close(L.norm(2, x), brute.rmsnorm(x, w32["g2"], shape.rms_eps))
     assert not _close(L.norm(1, x), brute.rmsnorm(x, w32["g2"], shape.rms_eps), 1e-3)
+
+
+# ---------------------------------------------------------------- chunked prefill (section 3.1)
+@pytest.mark.parametrize("chunks", [[32, 18], [16, 16, 16, 2], [48, 2]])
+def test_chunked_prefill_equals_the_rows_of_the_whole_prefill(chunks):
+    """A prompt evaluated chunk by chunk (each chunk's queries reading the earlier chunks' keys back from the
+    paged cache) gives the rows of the un-chunked prefill, the same cache contents, and the rows of the
+    float64 dense evaluation; a second request of another length rides along in the same calls."""
+    shape = SMALL
+    wb, w32 = _w32(shape)
+    T = sum(chunks)
+    lens = [T, 24]
+    xb = [S.hidden_states(n, shape.d_model, stream=40 + i) for i, n in enumerate(lens)]
+    x = [S.bf16_bits_to_f32(b) for b in xb]
+    nb = 9
+    tabs = S.shuffled_block_tables(lens, nb, stream=5)
+    L = oracle.OracleLayer.from_shape(shape, wb)
+    Kw, Vw = L.new_cache(nb, fill=np.float32(-777.0))
+    y_whole = L.prefill(np.concatenate(x), [0, T, T + 24], tabs, Kw, Vw)
+    Kc, Vc = L.new_cache(nb, fill=np.float32(-777.0))
+    got0, got1, at = [], None, 0
+    for i, n in enumerate(chunks):
+        if i == 0:      # the second request's only chunk rides with the first chunk of the first
+            y = L.prefill_chunk(np.concatenate([x[0][at:at + n], x[1]]), [0, n, n + 24], [at, 0], tabs, Kc, Vc)
+            got0.append(y[:n]); got1 = y[n:]
+        else:
+            got0.append(L.prefill_chunk(x[0][at:at + n], [0, n], [at], tabs[:1], Kc, Vc))
+        at += n
+    y_chunked = np.concatenate(got0 + [got1])
+    assert np.abs(y_chunked - y_whole).max() <= 1e-5 * np.abs(y_whole).max()
+    assert np.array_equal(Kc, Kw) and np.array_equal(Vc, Vw)
+    y64, _, _ = brute.layer_dense(w32, shape, np.concatenate(x), [0, T, T + 24])
+    assert np.abs(y_chunked - y64).max() <= 1e-5 * np.abs(y64).max()
+
+
+def test_chunk_rows_see_the_cache_not_the_call():
+    """The prior context comes from the cache: with another prefix cached under the same block table the chunk's
+    rows change, and equal the whole prefill of (other prefix + chunk)."""
+    shape = SMALL
+    wb, _ = _w32(shape)
+    L = oracle.OracleLayer.from_shape(shape, wb)
+    pre_a = S.bf16_bits_to_f32(S.hidden_states(32, shape.d_model, stream=50))
+    pre_b = S.bf16_bits_to_f32(S.hidden_states(32, shape.d_model, stream=51))
+    chunk = S.bf16_bits_to_f32(S.hidden_states(10, shape.d_model, stream=52))
+    tabs = S.shuffled_block_tables([42], 4, stream=6)
+    outs = []
+    for pre in (pre_a, pre_b):
+        Kc, Vc = L.new_cache(4)
+        L.prefill(pre, [0, 32], tabs, Kc, Vc)
+        y = L.prefill_chunk(chunk, [0, 10], [32], tabs, Kc, Vc)
+        Kw, Vw = L.new_cache(4)
+        y_whole = L.prefill(np.concatenate([pre, chunk]), [0, 42], tabs, Kw, Vw)
+        assert np.abs(y - y_whole[32:]).max() <= 1e-5 * np.abs(y_whole).max()
+        outs.append(y)
+    assert np.abs(outs[0] - outs[1]).max() > 1e-3
