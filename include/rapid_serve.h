@@ -213,6 +213,23 @@ int32_t rs_decode_layer_graph(rs_ctx *ctx, int32_t layer, const void *x_in, void
                               const int32_t *ctx_lens, const int32_t *block_tables, int32_t max_blk,
                               int32_t B, int32_t max_ctx_bucket);
 
+/* One layer over a HYBRID BATCH: chunked prefill co-batched with decode, the scheme the paper argues against
+ * and measures itself against (section 3.1: a prompt is cut into chunks of 512 or 1024 tokens and each chunk
+ * shares a batch, and so a latency, with the running decode tokens; section 5.1: the comparison system).  Built
+ * from the same kernels as the two separate passes so that the comparison can be run on this GPU:
+ *   rows [0, T) of x_in / x_out (T = cu_seqlens[n_req]) are one chunk of each of n_req prompts: prompt r's rows
+ *                sit at positions start_pos[r] .. start_pos[r] + len_r - 1, the positions before start_pos[r] are
+ *                already cached (earlier chunks), and each row attends to all cached positions before it and to
+ *                the chunk's rows up to itself; start_pos[r] is a multiple of 16 (host array, like cu_seqlens);
+ *   rows [T, T+B) are decode rows exactly as in rs_decode_layer (ctx_lens, decode_tables device arrays).
+ * All rows go through every projection together (the weights are read once for the whole batch); each kind
+ * takes its own attention kernel.  Enqueued on the PREFILL side's stream with that side's workspace: T + B <=
+ * max_prefill_tokens, B <= max_decode_batch (B may be 0: a chunk alone).  Errors as for the two passes. */
+int32_t rs_hybrid_layer(rs_ctx *ctx, int32_t layer, const void *x_in, void *x_out, const int32_t *cu_seqlens,
+                        const int32_t *start_pos, int32_t n_req, const int32_t *prefill_tables,
+                        int32_t max_blk_prefill, const int32_t *ctx_lens, const int32_t *decode_tables,
+                        int32_t max_blk_decode, int32_t B, int32_t max_ctx);
+
 /* rs_decode_layer for callers that cannot allocate device memory or have it allocated on their behalf:
  * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same kernels and bit-identical results, but every intermediate of the step (normalised rows, q|k|v,

@@ -28,7 +28,7 @@ RS_CU_HIST_BINS = 4096
 
 EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
-    "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_decode_layer_noalloc", "rs_set_cu_split", "rs_get_cu_split",
+    "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_decode_layer_noalloc", "rs_hybrid_layer", "rs_set_cu_split", "rs_get_cu_split",
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_debug_mfma_probe", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
@@ -243,6 +243,16 @@ class Context:
         _check(self._lib.rs_decode_layer(self._h, ctypes.c_int32(layer), _ptr(x_in), _ptr(x_out), _ptr(ctx_lens),
                                          _ptr(block_tables), ctypes.c_int32(max_blk), ctypes.c_int32(B),
                                          ctypes.c_int32(max_ctx)))
+
+    def hybrid_layer(self, layer: int, x_in, x_out, cu_seqlens: Sequence[int], start_pos: Sequence[int], prefill_tables,
+                     max_blk_prefill: int, ctx_lens=None, decode_tables=None, max_blk_decode: int = 0, B: int = 0, max_ctx: int = 1):
+        cu = (ctypes.c_int32 * len(cu_seqlens))(*[int(v) for v in cu_seqlens])
+        sp = (ctypes.c_int32 * max(len(start_pos), 1))(*[int(v) for v in start_pos])
+        _check(self._lib.rs_hybrid_layer(self._h, ctypes.c_int32(layer), _ptr(x_in), _ptr(x_out), cu, sp,
+                                         ctypes.c_int32(len(cu_seqlens) - 1), _ptr(prefill_tables), ctypes.c_int32(max_blk_prefill),
+                                         _ptr(ctx_lens) if ctx_lens is not None else None,
+                                         _ptr(decode_tables) if decode_tables is not None else None,
+                                         ctypes.c_int32(max_blk_decode), ctypes.c_int32(B), ctypes.c_int32(max_ctx)))
 
     def decode_layer_noalloc(self, layer: int, x_in, x_out, ctx_lens, block_tables, max_blk: int, B: int, max_ctx: int):
         _check(self._lib.rs_decode_layer_noalloc(self._h, ctypes.c_int32(layer), _ptr(x_in), _ptr(x_out), _ptr(ctx_lens),

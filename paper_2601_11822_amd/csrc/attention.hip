@@ -257,7 +257,7 @@ __global__ __launch_bounds__(HD) void decode_combine_kernel(DecodeAttnArgs a) {
     const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     int n_keys = a.ctx_lens[b] + 1;
     const int col = hq * HD + d;
-    bf16_t *op = a.out + packed_offset(b, col, packed_mt(a.B)) + (col & 7);   // feeds the output projection
+    bf16_t *op = a.out + packed_offset(a.out_row0 + b, col, a.out_Mt ? a.out_Mt : packed_mt(a.B)) + (col & 7);   // feeds the output projection
     if (n_keys < 1) {
         *op = (bf16_t)0.f;
         return;
@@ -330,12 +330,16 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
     if (pr >= ((nt + 1) >> 1)) return;
     const int row0 = a.seq.cu[req];
     const int len = a.seq.cu[req + 1] - row0;
+    // a later chunk of a prompt: its first row sits at position `prior`, and the positions before it are keys too
+    // (read from the cache like the chunk's own); key positions below are absolute, query rows relative to the chunk
+    const int prior = a.seq.start[req];
+    const int tot = prior + len;
     const int hq = blockIdx.y;
     const int G = a.Hq / a.Hkv;
     const int hk = hq / G;
     const int32_t *tab = a.tables + (size_t)req * a.max_blk;
     const float sc = a.scale_log2;
-    const int n_blk = (len + 15) >> 4;
+    const int n_blk = (tot + 15) >> 4;
     for (int i = tid; i < min(n_blk, PREFILL_TAB_LDS); i += 256) s_tab[i] = tab[i];
     // (two separate loads: a pointer chosen between the LDS copy and the table would become a generic-address
     // load, which waits for every outstanding LDS and global access)
@@ -361,7 +365,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
     auto load_tile = [&](int kv0, int buf) {
         bf16_t *ks = Ks + buf * 64 * HD;
         bf16_t *vs = Vs + buf * HD * 64;
-        if (HD == 128 && kv0 + 64 <= len && (kv0 >> 4) + 4 <= PREFILL_TAB_LDS) {
+        if (HD == 128 && kv0 + 64 <= tot && (kv0 >> 4) + 4 <= PREFILL_TAB_LDS) {
             const int b0 = kv0 >> 4;
             int blk[4];
             bool ok = true;
@@ -400,7 +404,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
             const int r = c / CPR, cc = c % CPR;
             const int tok = kv0 + r;
             bf16x8 v = zero_bf16x8();
-            if ((tok & ~15) < len) {
+            if ((tok & ~15) < tot) {
                 const int blk = block_of(tok >> 4);
                 if ((unsigned)blk < (unsigned)a.n_blocks)
                     v = ld_bf16x8(a.k_pool + ((size_t)blk * a.Hkv + hk) * 16 * HD + kpool_chunk_offset(tok & 15, cc * 8));
@@ -415,14 +419,14 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
             const int d = c >> 3, cc = c & 7;
             const int tok0 = kv0 + (cc >> 1) * 16 + (cc & 1) * 8;
             bf16x8 v = zero_bf16x8();
-            if (tok0 < len) {
+            if (tok0 < tot) {
                 const int blk = block_of(tok0 >> 4);
                 if ((unsigned)blk < (unsigned)a.n_blocks) {
                     v = ld_bf16x8(a.v_pool + (((size_t)blk * a.Hkv + hk) * HD + d) * 16 + (cc & 1) * 8);
-                    if (tok0 + 8 > len) {  // zero V past the prompt: 0 * garbage must not be NaN
+                    if (tok0 + 8 > tot) {  // zero V past the prompt: 0 * garbage must not be NaN
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
-                            if (tok0 + i >= len) v[i] = (bf16_t)0.f;
+                            if (tok0 + i >= tot) v[i] = (bf16_t)0.f;
                     }
                 }
             }
@@ -446,16 +450,17 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
         const int q0 = tile * 128;
         const int q_local = q0 + wave * 32 + c32;
         const bool q_valid = q_local < len;
-        const int q_pos = q_valid ? q_local : len - 1;
+        const int q_row = q_valid ? q_local : len - 1;
+        const int q_pos = prior + q_row;   // absolute position: the causal bound
         bf16x8 qf[KS];
         {
-            const bf16_t *qp = a.q + (size_t)(row0 + q_pos) * a.q_stride + (size_t)hq * HD + 8 * h;
+            const bf16_t *qp = a.q + (size_t)(row0 + q_row) * a.q_stride + (size_t)hq * HD + 8 * h;
 #pragma unroll
             for (int s = 0; s < KS; ++s) qf[s] = ld_bf16x8(qp + 16 * s);
         }
-        const int wave_q_min = q0 + wave * 32;
-        const int wave_q_max = min(wave_q_min + 31, len - 1);
-        const int kv_end = min(q0 + 128, len);
+        const int wave_q_min = prior + q0 + wave * 32;
+        const int wave_q_max = min(wave_q_min + 31, tot - 1);
+        const int kv_end = prior + min(q0 + 128, len);
         const int n_kv_tiles = (kv_end + 63) >> 6;
 
         float m_run = NEG_INF, l_run = 0.f;   // running max of raw scores, running sum
@@ -572,7 +577,7 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a)
         if (q_valid) {
             const float inv = 1.0f / l_run;
             // the output feeds the output projection: fragment-packed operand layout
-            const int Mt = packed_mt(a.seq.cu[a.seq.n_req]);
+            const int Mt = a.Mt_out ? a.Mt_out : packed_mt(a.seq.cu[a.seq.n_req]);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll

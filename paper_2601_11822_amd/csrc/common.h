@@ -15,7 +15,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // Prompt boundaries passed by value to kernels (no host->device copy on the launch path).
 struct SeqInfo {
     int32_t n_req;
-    int32_t cu[65];  // cu[0..n_req]
+    int32_t cu[65];     // cu[0..n_req]
+    int32_t start[64];  // position of each prompt's first row (0: a whole prompt; a multiple of 16: a later chunk of it)
 };
 
 // Rotary table entry: cos and sin of pos * base^(-2i/hd), formed in float64 on the host.

@@ -107,10 +107,11 @@ static __device__ void v_block_write(const RopeKvArgs &a, int vb) {
         first += nb;
     }
     const int bi = vb - first;
-    const int len = min(a.seq.cu[req + 1] - a.seq.cu[req], a.max_pos);   // rows past the table are flagged by their own workgroup
+    const int b0 = a.seq.start[req] / RS_BLOCK_TOKENS;                   // a chunk starts on a block boundary
+    const int len = min(a.seq.cu[req + 1] - a.seq.cu[req], a.max_pos - a.seq.start[req]);   // rows past the table are flagged by their own workgroup
     const int nvalid = min(len - bi * RS_BLOCK_TOKENS, RS_BLOCK_TOKENS);
-    if (nvalid <= 0 || bi >= a.max_blk) return;
-    const int blk = a.tables[(size_t)req * a.max_blk + bi];
+    if (nvalid <= 0 || b0 + bi >= a.max_blk) return;
+    const int blk = a.tables[(size_t)req * a.max_blk + b0 + bi];
     if ((unsigned)blk >= (unsigned)a.n_blocks) return;                   // flagged by the token rows
     const int hd = a.hd, nqkv = (a.Hq + 2 * a.Hkv) * hd;
     const bf16_t *row0 = a.qkv + (size_t)(a.seq.cu[req] + bi * RS_BLOCK_TOKENS) * nqkv + (a.Hq + a.Hkv) * hd;
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(RopeKvArgs a) {
     } else {
         req = 0;
         while (req + 1 < a.seq.n_req && row >= a.seq.cu[req + 1]) ++req;
-        pos = row - a.seq.cu[req];
+        pos = a.seq.start[req] + row - a.seq.cu[req];
     }
     if (pos < 0 || pos >= a.max_pos) {
         if (tid == 0) atomicOr(a.err_flag, 1);

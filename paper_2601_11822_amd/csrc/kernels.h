@@ -31,7 +31,8 @@ struct PrefillAttnArgs {
     int32_t *err_flag;
     int Hq, Hkv, hd, max_blk, n_blocks;
     float scale_log2;  // log2(e)/sqrt(hd)
-    SeqInfo seq;
+    SeqInfo seq;       // seq.start[r] > 0: the rows are a later chunk of prompt r and also attend to its cached positions before them
+    int Mt_out = 0;    // row tiles of the packed output matrix when it holds more rows than this call's (0: packed_mt of this call's rows)
 };
 void launch_prefill_attention(hipStream_t st, const PrefillAttnArgs &a);
 
@@ -48,6 +49,7 @@ struct DecodeAttnArgs {
     int B, Hq, Hkv, hd, max_blk, n_blocks, max_ctx, n_chunks;
     float scale_log2;
     int chunk_major;   // order of the workgroups only (results do not depend on it): chunks slowest, else requests slowest
+    int out_row0 = 0, out_Mt = 0;   // the packed output matrix holds other rows first / more row tiles (0: packed_mt(B))
 };
 #define RS_SKINNY_TARGET_WGS 384  // the skinny GEMM splits K until it has about this many workgroups
 #define RS_DECODE_CHUNK 512  // tokens per workgroup of the decode attention

@@ -349,6 +349,13 @@ int32_t alloc_ws(rs_ctx *c, Workspace &w, int rows, bool decode) {
         HIP_TRY(hipMalloc(&w.partials, pe * sizeof(float)));
         w.partial_cap = pe;
     }
+    if (!decode && c->lim.max_decode_batch > 0) {
+        // a hybrid batch (rs_hybrid_layer) runs decode rows through the prefill side's workspace
+        const size_t nch = (c->lim.max_context + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
+        const size_t br = std::min(rows, c->lim.max_decode_batch);
+        HIP_TRY(hipMalloc(&w.part_o, br * m.n_q_heads * nch * m.head_dim * sizeof(float)));
+        HIP_TRY(hipMalloc(&w.part_ml, br * m.n_q_heads * nch * 2 * sizeof(float)));
+    }
     if (decode) {
         HIP_TRY(hipMalloc(&w.ssq, 2 * 64 * 64 * sizeof(float)));
         const size_t nch = (c->lim.max_context + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK;
@@ -614,6 +621,88 @@ int32_t prefill_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, c
     launch_prefill_attention(st, pa);
     tick(c, RS_SIDE_PREFILL, 4);
     ok = run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], c->moe[layer], (const bf16_t *)x_in, (bf16_t *)x_out, T, skinny) && ok;
+    HIP_TRY(hipGetLastError());
+    if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this pass needs the row-major matrices that were released", layer);
+    return RS_OK;
+}
+
+// One layer over a hybrid batch (section 3.1: chunked prefill co-batched with decode, the baseline the paper
+// compares with): rows [0, T) are one chunk of each of n_req prompts (prompt r's chunk starts at position
+// start[r]), rows [T, T+B) are decode rows.  Both kinds share every projection (one pass over the weights for
+// all rows) and take their own attention kernel.  Runs on the prefill side's stream and workspace.
+int32_t hybrid_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu, const int32_t *start,
+                     int32_t n_req, const int32_t *ptables, int32_t max_blk_p, const int32_t *ctx_lens,
+                     const int32_t *dtables, int32_t max_blk_d, int32_t B, int32_t max_ctx) {
+    const rs_model_desc &m = c->m;
+    if (!cu || !start || n_req < 1 || n_req > RS_MAX_PREFILL_REQS) return fail(RS_ERR_BAD_ARG, "n_req %d out of range", n_req);
+    if (cu[0] != 0) return fail(RS_ERR_BAD_ARG, "cu_seqlens must start at 0");
+    SeqInfo seq{};
+    seq.n_req = n_req;
+    for (int r = 0; r <= n_req; ++r) {
+        if (r && cu[r] < cu[r - 1]) return fail(RS_ERR_BAD_ARG, "cu_seqlens must ascend");
+        seq.cu[r] = cu[r];
+    }
+    for (int r = 0; r < n_req; ++r) {
+        const int len = cu[r + 1] - cu[r];
+        if (start[r] < 0 || start[r] % RS_KV_BLOCK) return fail(RS_ERR_BAD_ARG, "chunk start %d: a non-negative multiple of %d", start[r], RS_KV_BLOCK);
+        if (start[r] + len > m.max_pos) return fail(RS_ERR_BAD_ARG, "chunk ends at position %d, max_pos is %d", start[r] + len, m.max_pos);
+        if ((start[r] + len + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk_p)
+            return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for %d tokens", max_blk_p, start[r] + len);
+        seq.start[r] = start[r];
+    }
+    const int T = cu[n_req], M = T + B;
+    Workspace &w = c->ws[RS_SIDE_PREFILL];
+    if (T < 1 || B < 0 || M > w.rows) return fail(RS_ERR_BAD_ARG, "%d chunk rows + %d decode rows, workspace holds %d", T, B, w.rows);
+    if (B > 0) {
+        if (!ctx_lens || !dtables) return fail(RS_ERR_BAD_ARG, "null decode arguments");
+        if (B > c->lim.max_decode_batch) return fail(RS_ERR_BAD_ARG, "decode batch %d exceeds max_decode_batch %d", B, c->lim.max_decode_batch);
+        if (max_ctx < 1 || max_ctx > c->lim.max_context || max_ctx > m.max_pos)
+            return fail(RS_ERR_BAD_ARG, "max_ctx %d outside [1, min(%d,%d)]", max_ctx, c->lim.max_context, m.max_pos);
+        if ((max_ctx + RS_KV_BLOCK - 1) / RS_KV_BLOCK > max_blk_d)
+            return fail(RS_ERR_BAD_BLOCK, "block table of %d entries too short for context %d", max_blk_d, max_ctx);
+    }
+    if (!c->packed[layer].wg && c->moe[layer].E == 0) return fail(RS_ERR_STATE, "layer %d has no feed-forward weights", layer);
+    const rs_layer_weights &lw = c->weights[layer];
+    hipStream_t st = c->side[RS_SIDE_PREFILL].stream;
+    const int d = m.d_model, hd = m.head_dim, qd = m.n_q_heads * hd, nqkv = qd + 2 * m.n_kv_heads * hd;
+    bf16_t *kp = (bf16_t *)c->pool.k_pool + (size_t)layer * c->pool.layer_stride;
+    bf16_t *vp = (bf16_t *)c->pool.v_pool + (size_t)layer * c->pool.layer_stride;
+    int32_t *err = c->err_flag + RS_SIDE_PREFILL;
+    const float sl2 = (float)(1.4426950408889634 / std::sqrt((double)hd));
+
+    tick(c, RS_SIDE_PREFILL, 0);
+    c->last_rows[RS_SIDE_PREFILL] = M;
+    launch_rmsnorm(st, (const bf16_t *)x_in, (const bf16_t *)lw.g1, w.h, M, d, m.rms_eps);
+    tick(c, RS_SIDE_PREFILL, 1);
+    const bool skinny = M <= 64;
+    GemmArgs gq{w.h, (const bf16_t *)lw.wqkv, nullptr, c->packed[layer].wqkv, nullptr, nullptr, w.qkv,
+                M, nqkv, d, EPI_STORE, 0, c->side[RS_SIDE_PREFILL].cus, w.partials, w.partial_cap};
+    bool ok = true;
+    if (skinny) launch_gemm_skinny(st, gq, w.partials);
+    else ok = launch_gemm_tiled(st, gq);
+    tick(c, RS_SIDE_PREFILL, 2);
+    launch_rope_kvwrite(st, RopeKvArgs{w.qkv, c->rope, kp, vp, ptables, nullptr, err, T, m.n_q_heads, m.n_kv_heads, hd,
+                                       max_blk_p, c->pool.n_blocks, m.max_pos, seq});
+    if (B > 0) {
+        SeqInfo none{};
+        launch_rope_kvwrite(st, RopeKvArgs{w.qkv + (size_t)T * nqkv, c->rope, kp, vp, dtables, ctx_lens, err, B, m.n_q_heads,
+                                           m.n_kv_heads, hd, max_blk_d, c->pool.n_blocks, m.max_pos, none});
+    }
+    tick(c, RS_SIDE_PREFILL, 3);
+    PrefillAttnArgs pa{w.qkv, nqkv, w.attn, kp, vp, ptables, err, m.n_q_heads, m.n_kv_heads, hd,
+                       max_blk_p, c->pool.n_blocks, sl2, seq};
+    pa.Mt_out = packed_mt(M);
+    launch_prefill_attention(st, pa);
+    if (B > 0) {
+        DecodeAttnArgs da{w.qkv + (size_t)T * nqkv, nqkv, w.attn, kp, vp, dtables, ctx_lens, err, w.part_o, w.part_ml,
+                          B, m.n_q_heads, m.n_kv_heads, hd, max_blk_d, c->pool.n_blocks, max_ctx,
+                          (max_ctx + RS_DECODE_CHUNK - 1) / RS_DECODE_CHUNK, sl2, c->side[RS_SIDE_PREFILL].cus < RS_TOTAL_CUS};
+        da.out_row0 = T;
+        da.out_Mt = packed_mt(M);
+        launch_decode_attention(st, da);
+    }
+    tick(c, RS_SIDE_PREFILL, 4);
+    ok = run_post_attention(c, RS_SIDE_PREFILL, st, w, lw, c->packed[layer], c->moe[layer], (const bf16_t *)x_in, (bf16_t *)x_out, M, skinny) && ok;
     HIP_TRY(hipGetLastError());
     if (!ok) return fail(RS_ERR_STATE, "layer %d: a GEMM of this pass needs the row-major matrices that were released", layer);
     return RS_OK;
@@ -1199,6 +1288,16 @@ int32_t rs_decode_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out,
     int32_t rc = check_layer_call(c, RS_SIDE_DECODE, layer, x_in, x_out, block_tables);
     if (rc) return rc;
     return decode_layer(c, c->ws[RS_SIDE_DECODE], layer, x_in, x_out, ctx_lens, block_tables, max_blk, B, max_ctx);
+}
+
+int32_t rs_hybrid_layer(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *cu_seqlens,
+                        const int32_t *start_pos, int32_t n_req, const int32_t *prefill_tables, int32_t max_blk_prefill,
+                        const int32_t *ctx_lens, const int32_t *decode_tables, int32_t max_blk_decode, int32_t B,
+                        int32_t max_ctx) {
+    int32_t rc = check_layer_call(c, RS_SIDE_PREFILL, layer, x_in, x_out, prefill_tables);
+    if (rc) return rc;
+    return hybrid_layer(c, layer, x_in, x_out, cu_seqlens, start_pos, n_req, prefill_tables, max_blk_prefill, ctx_lens,
+                        decode_tables, max_blk_decode, B, max_ctx);
 }
 
 int32_t rs_decode_layer_noalloc(rs_ctx *c, int32_t layer, const void *x_in, void *x_out, const int32_t *ctx_lens,

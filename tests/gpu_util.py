@@ -157,6 +157,25 @@ class Rig:
             return to_bits(y)
         return y
 
+    def hybrid(self, x_bits, cu, start_pos, ptables, ctx_lens=None, dtables=None, layer=0, max_ctx=None):
+        """One hybrid batch: chunk rows of the prompts first, then the decode rows."""
+        x = to_dev(x_bits)
+        y = torch.empty_like(x)
+        ptab = torch.from_numpy(np.ascontiguousarray(ptables, dtype=np.int32)).cuda()
+        B = 0 if ctx_lens is None else len(ctx_lens)
+        cl = dtab = None
+        if B:
+            cl = torch.from_numpy(np.ascontiguousarray(ctx_lens, dtype=np.int32)).cuda()
+            dtab = torch.from_numpy(np.ascontiguousarray(dtables, dtype=np.int32)).cuda()
+            if max_ctx is None:
+                max_ctx = int(np.max(ctx_lens)) + 1
+        torch.cuda.synchronize()
+        self.ctx.hybrid_layer(layer, x, y, cu, start_pos, ptab, ptab.shape[1], cl, dtab, dtab.shape[1] if B else 0, B,
+                              max_ctx or 1)
+        self._keep.append((x, y, ptab, cl, dtab))
+        self.ctx.sync(rs.RS_SIDE_PREFILL)
+        return to_bits(y)
+
     # ---- pools in the oracle's logical order [n_blocks, 16, Hkv, hd]
     # K pool: [n_blocks][Hkv][hd/32][4][16 permuted slots][8]; slot t sits in row t with bits 2, 3 swapped
     _PROW = [(t & 3) | ((t & 8) >> 1) | ((t & 4) << 1) for t in range(16)]
