@@ -141,6 +141,27 @@ def run_corun(r, steps, warmup):
                             dump=bool(os.environ.get("RS_BENCH_DUMP")))
 
 
+def run_hybrid(r, chunk, cycles, warmup):
+    """The comparison scheme (section 3.1): the prompt goes through in chunks of `chunk` tokens, each chunk in
+    one batch with all the decode rows, on all CUs.  Returns the per-step GPU ms of cycles * T/chunk steps."""
+    import torch
+    c, T, B = r["ctx_obj"], r["T"], r["B"]
+    starts = list(range(0, T, chunk))
+    xh = [torch.cat([r["xp"][s:s + chunk], r["xd"]]).contiguous() for s in starts]
+    yh = torch.empty_like(xh[0])
+    torch.cuda.synchronize()
+    state = {"i": 0}
+
+    def step():
+        i = state["i"] % len(starts)
+        state["i"] += 1
+        n = min(chunk, T - starts[i])
+        c.hybrid_layer(0, xh[i], yh, [0, n], [starts[i]], r["ptab"], r["max_blk"], r["cl"], r["dtab"], r["max_blk"], B, r["max_ctx"])
+
+    per, _ = timing.run_alone(c, 0, step, cycles * len(starts), warmup * len(starts))
+    return per, len(starts)
+
+
 def pct(a, q):
     return float(np.percentile(a, q)) if len(a) else float("nan")
 
@@ -345,6 +366,22 @@ def main():
     seq_s = time.perf_counter() - t0
     seq_norm = (K * med(p256_bb) + K * k_dec * med(d256_bb)) / (seq_s * 1e3)
 
+    # ---- measured hybrid-batching baseline (chunked prefill in one batch with the decode rows, all 256 CUs)
+    hybrid = []
+    for chunk in (512, 1024):
+        if chunk + B > T or T % chunk:
+            continue
+        per, n_steps = run_hybrid(r, chunk, max(K // 2, 5), 2)
+        prompt_ms = float(per.reshape(-1, n_steps).sum(axis=1).mean())
+        rec = {"chunk": chunk, "steps_per_prompt": n_steps, "step_ms_p50": pct(per, 50), "step_ms_p95": pct(per, 95),
+               "step_ms_mean": float(per.mean()), "prefill_tok_s": T / (prompt_ms * 1e-3),
+               "decode_tok_s": B / (float(per.mean()) * 1e-3),
+               "corun_itl_p50_over_hybrid_step_p50": head["decode_corun_p50_ms"] / pct(per, 50),
+               "corun_prefill_tok_s_over_hybrid": head["prefill_tok_s_corun"] / (T / (prompt_ms * 1e-3)),
+               "corun_decode_tok_s_over_hybrid": (B / (head["decode_corun_p50_ms"] * 1e-3)) / (B / (float(per.mean()) * 1e-3))}
+        log("[bench] hybrid baseline: %s" % json.dumps(rec))
+        hybrid.append(rec)
+
     out = {
         "metric": "prefill tok/s under co-run with decode (decode p50 ITL alongside)",
         "value": head["prefill_tok_s_corun"], "unit": "tok/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -371,6 +408,8 @@ def main():
         "itl_corun_vs_alone_256": head["itl_vs_alone_256"],
         "combined_norm_throughput": head["combined_norm_throughput"],
         "sequential_baseline_norm_throughput_measured": seq_norm,
+        # a decode token's latency under hybrid batching is the whole hybrid step (its ITL), per layer like the rest
+        "hybrid_batching_baseline": hybrid,
         "prefill_layer_alone_256": layer_p, "decode_layer_alone_256": layer_d,
         "prefill_kernels_ms_alone_256": dict(zip(names, map(float, kt_p))),
         "decode_kernels_ms_alone_256": dict(zip(names, map(float, kt_d))),
