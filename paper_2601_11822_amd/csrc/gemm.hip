@@ -181,8 +181,15 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 // Per K tile (two MFMA steps, one barrier): the loads of tile kt+NS-1 trickle out between the
 // MFMAs; step 0 reads the step-1 fragments; step 1 waits until tile kt+1 has landed (vmcnt counts
 // the younger loads that may still fly), meets the other waves at the barrier and reads tile
-// kt+1's step-0 fragments.  In both steps the first MFMAs are issued before the reads, so a wait
+// kt+1's step-0 fragments.  In both steps the first MFMA is issued before the reads, so a wait
 // in front of a step is already satisfied and the barrier never sits between idle matrix cores.
+//
+// One wave runs per SIMD, so every instruction issued between two MFMAs that takes longer than the
+// MFMA itself (32 cycles) leaves the matrix core idle.  The loop therefore issues at most one fragment
+// read and one load between two MFMAs, and a load costs three instructions: the slab bases of the K
+// tile being fetched are uniform (scalar registers, advanced by a constant per K tile with scalar
+// adds), each load's lane offset inside the slab is loop invariant, and the wave index is a compile-time
+// constant of the loop copy a wave runs, so the LDS address of a load is scalar too (no lane read-back).
 // ---------------------------------------------------------------------------------------------
 // One output tile: rows [bm, bm + BM), column tile nb (of width BN; BN/2 output columns for SwiGLU).
 // PARTIAL: the tile covers K tiles [kt0, kt0 + nk_part) only and stores its raw float32 sums to
@@ -198,6 +205,7 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
     constexpr int LA = 2 * TA / NW, LB = 2 * TB / NW;   // wave-wide loads per wave per stage
     constexpr int STAGE = (BM + BN) * BK;            // elements per stage: [2][TA] A blocks, then [2][TB] B blocks
     constexpr int D = NS - 1;                        // prefetch distance in K tiles
+    static_assert(TN + TM + 1 <= TN * TM, "a step must have a slot per fragment read");
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -212,42 +220,8 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
         wp += (size_t)e * a.expert_stride;
         if (EPI == EPI_SWIGLU) wp2 += (size_t)e * a.expert_stride;
     }
-    const bf16_t *pa[LA];
-    const bf16_t *pb[LB];
-#pragma unroll
-    for (int j = 0; j < LA; ++j) {
-        const int q = wave * LA + j, s = q / TA, t = q % TA;
-        pa[j] = a.A + ((size_t)s * Mt + min((bm >> 5) + t, Mt - 1)) * 512 + lane * 8;
-    }
-#pragma unroll
-    for (int j = 0; j < LB; ++j) {
-        const int q = wave * LB + j, s = q / TB, t = q % TB;
-        if (EPI == EPI_SWIGLU)   // blocks alternate: 32 gate rows, the 32 matching up rows
-            pb[j] = ((t & 1) ? wp2 : wp) + ((size_t)s * Nt + min(nb * (TB / 2) + (t >> 1), Nt - 1)) * 512 + lane * 8;
-        else
-            pb[j] = wp + ((size_t)s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8;
-    }
     const size_t ksa = (size_t)Mt * 1024, ksb = (size_t)Nt * 1024;   // elements per K tile (2 k blocks)
     const int nk = PARTIAL ? nk_part : K / BK;
-    // loads [j0, j1) of the LA + LB wave-wide loads that bring K tile kt into its stage
-    auto issue = [&](int kt, int j0, int j1) {
-        const int stage = kt % NS;
-        const size_t kc = (size_t)(kt0 + min(kt, nk - 1));
-        bf16_t *sa = smem + stage * STAGE;
-        bf16_t *sb = sa + BM * BK;
-#pragma unroll
-        for (int j = 0; j < LA + LB; ++j) {
-            if (j < j0 || j >= j1) continue;
-            if (j < LA)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[j] + kc * ksa),
-                                                 (__attribute__((address_space(3))) void *)(sa + (wave * LA + j) * 512),
-                                                 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[j - LA] + kc * ksb),
-                                                 (__attribute__((address_space(3))) void *)(sb + (wave * LB + j - LA) * 512),
-                                                 16, 0, 0);
-        }
-    };
 
     f32x16 acc[TN][TM];
 #pragma unroll
@@ -257,32 +231,93 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    bf16x8 wf[2][TN], xf[2][TM];
-    auto read_frags = [&](int set, int kt, int step) {
-        const bf16_t *sa = smem + (kt % NS) * STAGE + lane * 8;
-        const bf16_t *sb = sa + BM * BK;
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) wf[set][tn] = *(const bf16x8 *)&sb[(step * TB + wn * TN + tn) * 512];
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) xf[set][tm] = *(const bf16x8 *)&sa[(step * TA + wm * TM + tm) * 512];
-    };
-#pragma unroll
-    for (int i = 0; i < D; ++i) issue(i, 0, LA + LB);
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((D - 1) * (LA + LB)) : "memory");
-    read_frags(0, 0, 0);
-
-    // One K tile = SL MFMA slots (two steps of TN x TM).  A load instruction holds up the
-    // issuing wave while the CU's one memory pipeline takes it, and a wave that cannot issue
-    // cannot feed its matrix core either; so the LT loads of the next tile are placed one at a
-    // time, evenly between the MFMAs, and wave w places its loads w quarter-spacings later than
-    // wave 0: the four lock-stepped waves never queue behind one another.
     constexpr int SL = 2 * TN * TM, LT = LA + LB, SP = SL / LT;
     auto k_loop = [&](auto wtag) {
         constexpr int W = decltype(wtag)::value;
+        constexpr int CWM = W / WGN, CWN = W % WGN;
+        // The LT loads of a K tile are spread evenly over its SL MFMA slots, and wave w places its own w
+        // quarter-spacings later than wave 0: the lock-stepped waves never queue behind one another at the
+        // CU's one memory pipeline.
         constexpr int SHIFT = (W * SP) / NW;
         // loads of the current iteration already issued when the barrier of slot SL/2 is reached
         constexpr int EARLY = ((SL / 2 - 1 - SHIFT) / SP) + 1;
+        // byte offsets of this wave's loads inside a K tile's slab: the slab bases are uniform and advance by a
+        // constant per K tile, so a load costs its own instruction and the LDS address register, nothing else
+        uint32_t oa[LA], ob[LB];
+#pragma unroll
+        for (int j = 0; j < LA; ++j) {
+            const int q = W * LA + j, s = q / TA, t = q % TA;
+            oa[j] = (uint32_t)(((s * Mt + min((bm >> 5) + t, Mt - 1)) * 512 + lane * 8) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            const int q = W * LB + j, s = q / TB, t = q % TB;
+            if (EPI == EPI_SWIGLU)   // blocks alternate: 32 gate rows, the 32 matching up rows
+                ob[j] = (uint32_t)(((s * Nt + min(nb * (TB / 2) + (t >> 1), Nt - 1)) * 512 + lane * 8) * 2);
+            else
+                ob[j] = (uint32_t)(((s * Nt + min(nb * TB + t, Nt - 1)) * 512 + lane * 8) * 2);
+        }
+        const char *ga = (const char *)(a.A + (size_t)kt0 * ksa);
+        const char *gb = (const char *)(wp + (size_t)kt0 * ksb);
+        const char *gb2 = EPI == EPI_SWIGLU ? (const char *)(wp2 + (size_t)kt0 * ksb) : nullptr;
+        int fetch_kt = 0;   // the K tile the slab bases point at
+        auto advance = [&]() {   // to the next K tile, staying on the last one (its re-fetches land in a stage nobody reads)
+            const size_t in = fetch_kt + 1 < nk ? 1 : 0;
+            ga += in * ksa * 2;
+            gb += in * ksb * 2;
+            if (EPI == EPI_SWIGLU) gb2 += in * ksb * 2;
+            ++fetch_kt;
+        };
+        // loads [j0, j1) of the LA + LB wave-wide loads that bring the K tile at the slab bases into the stage at
+        // element offset so
+        auto issue = [&](int so, int j0, int j1) {
+            bf16_t *sa = smem + so;
+            bf16_t *sb = sa + BM * BK;
+#pragma unroll
+            for (int j = 0; j < LA + LB; ++j) {
+                if (j < j0 || j >= j1) continue;
+                if (j < LA) {
+                    const char *g = ga;
+                    asm volatile("" : "+s"(g));   // the address is formed here, next to its load, not at the top of the K tile
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(g + oa[j]),
+                                                     (__attribute__((address_space(3))) void *)(sa + (W * LA + j) * 512), 16, 0, 0);
+                } else {
+                    const bool up = EPI == EPI_SWIGLU && (((W * LB + j - LA) % TB) & 1);
+                    const char *g = up ? gb2 : gb;
+                    asm volatile("" : "+s"(g));
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(g + ob[j - LA]),
+                                                     (__attribute__((address_space(3))) void *)(sb + (W * LB + j - LA) * 512), 16, 0, 0);
+                }
+            }
+        };
+        bf16x8 wf[2][TN], xf[2][TM];
+        // fragment f (weights first, then activations) of step `step` of the K tile in the stage at element offset so
+        auto read_frag = [&](int set, int so, int step, int f) {
+            const bf16_t *sa = smem + so + lane * 8;
+            const bf16_t *sb = sa + BM * BK;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                if (f == tn) wf[set][tn] = *(const bf16x8 *)&sb[(step * TB + CWN * TN + tn) * 512];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                if (f == TN + tm) xf[set][tm] = *(const bf16x8 *)&sa[(step * TA + CWM * TM + tm) * 512];
+        };
+        // prologue: K tiles 0 .. D-1 into stages 0 .. D-1
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            issue(i * STAGE, 0, LA + LB);
+            advance();
+        }
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((D - 1) * (LA + LB)) : "memory");
+#pragma unroll
+        for (int f = 0; f < TN + TM; ++f) read_frag(0, 0, 0, f);
+
+        // One K tile = SL MFMA slots (two steps of TN x TM); its loads fill the stage before its own (tile kt + D).
+        // The fragment reads and the loads are placed one per slot between the MFMAs.
+        int so_cur = 0;   // element offset of the stage that holds K tile kt (uniform)
         for (int kt = 0; kt < nk; ++kt) {
+            const int so_ld = so_cur == 0 ? (NS - 1) * STAGE : so_cur - STAGE;
+            const int so_nxt = so_cur == (NS - 1) * STAGE ? 0 : so_cur + STAGE;
 #pragma unroll
             for (int sl = 0; sl < SL; ++sl) {
                 const int step = sl / (TN * TM), tn = (sl % (TN * TM)) / TM, tm = sl % TM;
@@ -292,12 +327,14 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
                     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((D - 2) * LT + EARLY) : "memory");
                 acc[tn][tm] = mfma32(wf[step][tn], xf[step][tm], acc[tn][tm]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (sl == TM - 1) read_frags(1, kt, 1);
-                if (sl == SL / 2 + TM - 1) read_frags(0, kt + 1, 0);
+                if (sl >= 1 && sl < 1 + TN + TM) read_frag(1, so_cur, 1, sl - 1);
+                if (sl >= SL / 2 + 1 && sl < SL / 2 + 1 + TN + TM) read_frag(0, so_nxt, 0, sl - SL / 2 - 1);
                 if (sl >= SHIFT && (sl - SHIFT) % SP == 0 && (sl - SHIFT) / SP < LT)
-                    issue(kt + D, (sl - SHIFT) / SP, (sl - SHIFT) / SP + 1);
+                    issue(so_ld, (sl - SHIFT) / SP, (sl - SHIFT) / SP + 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            advance();
+            so_cur = so_nxt;
         }
     };
     switch (__builtin_amdgcn_readfirstlane(wave)) {
