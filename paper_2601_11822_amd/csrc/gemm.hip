@@ -194,6 +194,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
 // One output tile: rows [bm, bm + BM), column tile nb (of width BN; BN/2 output columns for SwiGLU).
 // PARTIAL: the tile covers K tiles [kt0, kt0 + nk_part) only and stores its raw float32 sums to
 // part[z][m][n] (row stride N), for an epilogue pass that adds the slices in order.
+// LDS stages of the 256x256 tile's ring (32 KB each): a K tile is requested three tiles ahead.  A fifth stage (the
+// whole 160 KB of a compute unit) measured the same, alone and beside a bandwidth-bound kernel on the other
+// partition: what that neighbour costs is not memory latency the ring could cover.
+#define RS_NS_FULL 4
 template <int BM, int BN, int EPI, int NS, int NW, bool PARTIAL = false>
 __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm, const int nb, bf16_t *smem,
                                                  const int kt0 = 0, const int nk_part = 0, float *part = nullptr, const int z = 0) {
@@ -451,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_direct_mixed_kernel(GemmArgs a, int 
         const int t = (id & 7) * (n_full >> 3) + (id >> 3);          // n_full is a multiple of 8
         int r, c;
         tile_rc(t, m_tiles, n_tiles, r, c);
-        gemm_direct_tile<256, 256, EPI, 4, 4>(a, r * 256, c, smem);
+        gemm_direct_tile<256, 256, EPI, RS_NS_FULL, 4>(a, r * 256, c, smem);
     } else {
         const int j = id - n_full;
         const int u = (j & 7) * ((n_half + 7) >> 3) + (j >> 3);
@@ -514,7 +518,7 @@ bool launch_gemm_direct_partials(hipStream_t st, const GemmArgs &a, float *part)
 
 template <int EPI>
 static void launch_direct_mixed_epi(hipStream_t st, const GemmArgs &a, int m_tiles, int n_full, int n_half) {
-    constexpr int lds = 4 * 512 * 32 * 2;   // the larger of the two rings
+    constexpr int lds = RS_NS_FULL * 512 * 32 * 2;   // the larger of the two rings
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)gemm_direct_mixed_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -566,7 +570,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(GemmArgs a, int n_til
     const int32_t *units = a.tile_expert + n128;
     if (u >= __builtin_amdgcn_readfirstlane(units[0])) return;
     const int code = __builtin_amdgcn_readfirstlane(units[1 + u]);
-    if (code & 1) gemm_direct_tile<256, 256, EPI, 4, 4>(a, (code >> 1) * 128, nb, smem);
+    if (code & 1) gemm_direct_tile<256, 256, EPI, RS_NS_FULL, 4>(a, (code >> 1) * 128, nb, smem);
     else gemm_direct_tile<128, 256, EPI, 5, 4>(a, (code >> 1) * 128, nb, smem);
 }
 
@@ -574,7 +578,7 @@ template <int EPI>
 static void launch_grouped_epi(hipStream_t st, const GemmArgs &a) {
     const int n_tiles = (EPI == EPI_SWIGLU) ? (a.N + 127) / 128 : (a.N + 255) / 256;
     const int grid = (((a.M >> 7) * n_tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_grouped_kernel<EPI>), dim3(grid), dim3(256), 131072, st, a, n_tiles);
+    hipLaunchKernelGGL((gemm_grouped_kernel<EPI>), dim3(grid), dim3(256), RS_NS_FULL * 32768, st, a, n_tiles);
 }
 
 bool launch_gemm_grouped(hipStream_t st, const GemmArgs &a) {
@@ -632,7 +636,7 @@ bool launch_gemm_tiled(hipStream_t st, const GemmArgs &a) {
         const double cost_mixed = mixed_ok ? n_full / cus + C_HALF : 1e30;
         const double best = std::min(std::min(cost_full, cost_mixed), std::min(cost_half, cost_192));
         if (best == cost_full) {
-            launch_direct<256, 256, 4, 4>(st, a);   // 4 x 32 KB of LDS
+            launch_direct<256, 256, RS_NS_FULL, 4>(st, a);   // RS_NS_FULL x 32 KB of LDS
         } else if (best == cost_mixed) {
             switch (a.epi) {
                 case EPI_STORE: launch_direct_mixed_epi<EPI_STORE>(st, a, mt256, n_full, 2 * rest); break;
@@ -1072,14 +1076,14 @@ void gemm_kernels_init() {
     set((const void *)gemm_skinny_shared_kernel<EPI_STORE, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_skinny_shared_kernel<EPI_RESIDUAL, RS_SHARED_CH>, 2 * RS_SHARED_CH * 2048);
     set((const void *)gemm_direct_splitk_kernel, 5 * (128 + 256) * 32 * 2);
-    set((const void *)gemm_grouped_kernel<EPI_STORE>, 131072);
-    set((const void *)gemm_grouped_kernel<EPI_SWIGLU>, 131072);
-    set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, 131072);
-    set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, 131072);
-    set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, 131072);
-    set((const void *)gemm_direct_kernel<256, 256, EPI_STORE, 4, 4>, 131072);
-    set((const void *)gemm_direct_kernel<256, 256, EPI_RESIDUAL, 4, 4>, 131072);
-    set((const void *)gemm_direct_kernel<256, 256, EPI_SWIGLU, 4, 4>, 131072);
+    set((const void *)gemm_grouped_kernel<EPI_STORE>, RS_NS_FULL * 32768);
+    set((const void *)gemm_grouped_kernel<EPI_SWIGLU>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_mixed_kernel<EPI_STORE>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_mixed_kernel<EPI_RESIDUAL>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_mixed_kernel<EPI_SWIGLU>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_STORE, RS_NS_FULL, 4>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_RESIDUAL, RS_NS_FULL, 4>, RS_NS_FULL * 32768);
+    set((const void *)gemm_direct_kernel<256, 256, EPI_SWIGLU, RS_NS_FULL, 4>, RS_NS_FULL * 32768);
     set((const void *)gemm_direct_kernel<128, 256, EPI_STORE, 5, 4>, 122880);
     set((const void *)gemm_direct_kernel<128, 256, EPI_RESIDUAL, 5, 4>, 122880);
     set((const void *)gemm_direct_kernel<128, 256, EPI_SWIGLU, 5, 4>, 122880);
