@@ -19,6 +19,16 @@ Readings where the paper is silent:
     starved request is the only block holder the pool is simply too small;
   * here every sampled token is visible to the scheduler at the next step (no lag).
 
+Hybrid batching (`hybrid_chunk` > 0; section 3.1 describes the scheme the paper compares with: a
+prompt is cut into chunks of 512 or 1024 tokens and every chunk shares a batch with the running
+decode tokens).  Readings: one prompt is chunked at a time, first come first served; a step takes the
+next `hybrid_chunk` tokens of it (the rest, if fewer remain) into the same batch as the decode step of
+all running requests; the step that takes a prompt's last chunk also yields its first output token,
+which the scheduler sees at the next step; the prompt taken up in a step has its first chunk in that
+same step; a request being chunked is "being prefilled" for the preemption rule.  Everything else --
+block accounting, promotion, retirement, preemption -- is unchanged, so the tokens a request
+receives are the same under either policy.
+
 The tokens themselves come from outside: `script[req]` is the sequence of tokens the request's
 successive sampling events yield (a missing entry yields 0).  Everything is integer and exact.
 """
@@ -46,8 +56,10 @@ class _Req:
 class Lifecycle:
     def __init__(self, n_blocks: int, max_batch: int, eos: int = -1,
                  split: Optional[Callable[[int, int, bool], Tuple[int, int]]] = None,
-                 max_prefill_tokens: int = 1 << 30, max_prefill_reqs: int = 64):
+                 max_prefill_tokens: int = 1 << 30, max_prefill_reqs: int = 64, hybrid_chunk: int = 0):
         self.max_prefill_tokens, self.max_prefill_reqs = max_prefill_tokens, max_prefill_reqs
+        self.hybrid_chunk = hybrid_chunk
+        self.chunk_done = 0                  # tokens of the prompt being chunked that earlier steps took
         self.alloc = KVAllocator(n_blocks)
         self.max_batch, self.eos = max_batch, eos
         self.split = split
@@ -138,6 +150,8 @@ class Lifecycle:
             v.state, v.n_prefill, v.ctx = WAITING, v.prompt_len + len(v.out), 0
             o["n_preempted"] += 1
         o["n_waiting"] = sum(1 for rid in self.arrival if self.reqs[rid].state == WAITING)
+        if self.hybrid_chunk:
+            return self._hybrid_tail(o)
         nxt: List[int] = []
         if not self.prefilling:
             total = 0
@@ -169,4 +183,33 @@ class Lifecycle:
             o["prefill_started_tokens"] = sum(self.reqs[rid].n_prefill for rid in nxt)
             o["prefill_started_count"] = len(nxt)
             o["prefill_started_ids"] = list(nxt)
+        return o
+
+    def _hybrid_tail(self, o: dict) -> dict:
+        """The rest of a step under hybrid batching: the next chunk and the decode step, one batch."""
+        o["prefill_started_count"] = 0
+        if not self.prefilling:
+            rid = next((rid for rid in self.arrival if self.reqs[rid].state == PREFILL_READY), None)
+            if rid is not None:
+                self.reqs[rid].state = PREFILLING
+                self.prefilling = [rid]
+                self.chunk_done = 0
+                o["prefill_started_req"] = rid
+                o["prefill_started_tokens"] = self.reqs[rid].n_prefill
+                o["prefill_started_count"] = 1
+                o["prefill_started_ids"] = [rid]
+        o["decode_batch"] = len(self.running)
+        o["decode_sum_ctx"] = sum(self.reqs[rid].ctx for rid in self.running)
+        o["batch_ids"] = list(self.running)
+        o["chunk"] = None
+        if self.prefilling and not self.pass_done:
+            r = self.reqs[self.prefilling[0]]
+            n = min(self.hybrid_chunk, r.n_prefill - self.chunk_done)
+            o["chunk"] = (r.id, self.chunk_done, n)
+            self.chunk_done += n
+            if self.chunk_done == r.n_prefill:
+                self.pass_done = True           # its first token is seen at the next step
+        for rid in self.running:                           # the decode rows of the same batch
+            self.reqs[rid].ctx += 1
+        self.last_tokens = list(self.running)
         return o

@@ -128,6 +128,68 @@ def test_oracle_pool_too_small_for_one_request():
 
 
 # ------------------------------------------------------------------ the library against the oracle
+# ------------------------------------------------------------ pins of the oracle, hybrid batching
+def test_oracle_hybrid_worked_example():
+    # Chunk 16.  A (prompt 40, 3 tokens) and B (prompt 10, 2 tokens) arrive together.  A is cut into 16 + 16 + 8;
+    # the step that takes its last chunk yields its first token, seen one step later (step 3), when A joins the
+    # decode batch and B's only chunk rides in the same batch as A's first decode row.  Step 4: A's second token
+    # and B's first are read, B joins; both decode.  Step 5: A's third and B's second token end both.
+    lc = Lifecycle(100, max_batch=4, eos=-1, hybrid_chunk=16)
+    lc.submit(1, 40, 3, [5, 6, 7, 8])
+    lc.submit(2, 10, 2, [9, 10, 11])
+    log = [lc.step() for _ in range(6)]
+    assert [o["chunk"] for o in log] == [(1, 0, 16), (1, 16, 16), (1, 32, 8), (2, 0, 10), None, None]
+    assert [o["decode_batch"] for o in log] == [0, 0, 0, 1, 2, 0]
+    assert [o["n_promoted"] for o in log] == [0, 0, 0, 1, 1, 0]
+    assert [o["n_finished"] for o in log] == [0, 0, 0, 0, 0, 2]
+    assert [o["prefill_started_req"] for o in log] == [1, -1, -1, 2, -1, -1]
+    assert [o["prefill_started_tokens"] for o in log] == [40, 0, 0, 10, 0, 0]
+    assert log[3]["decode_sum_ctx"] == 40 and log[4]["decode_sum_ctx"] == 41 + 10
+    assert lc.reqs[1].out == [5, 6, 7] and lc.reqs[2].out == [9, 10]
+    assert lc.alloc.n_free() == 100
+
+
+@pytest.mark.parametrize("n_blocks,seed,chunk", [(1000, 1, 16), (1000, 2, 32), (12, 2, 16), (8, 3, 48), (7, 4, 16)])
+def test_oracle_hybrid_tokens_equal_the_other_policy_and_chunks_tile_every_prefill(n_blocks, seed, chunk):
+    reqs, delays = _trace(seed)
+    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS, hybrid_chunk=chunk)
+
+    def step():
+        o = lc.step()
+        for rid in lc.running:
+            assert len(lc.alloc.owned[rid]) == -(-lc.reqs[rid].ctx // 16)
+        ids = [b for v in lc.alloc.owned.values() for b in v]
+        assert len(ids) == len(set(ids)) and len(ids) + lc.alloc.n_free() == n_blocks
+        return o
+
+    log = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), step, lambda rid: None, reqs, delays)
+    # the tokens do not depend on the batching policy: the same script prefixes as under whole-prompt prefill
+    for rid, pl, mn, script, _ in reqs:
+        assert lc.reqs[rid].state == FINISHED and lc.reqs[rid].out == _expected_output(script, mn, EOS)
+    assert lc.alloc.n_free() == n_blocks
+    # every prefill (a preempted request has several) is covered by its chunks exactly once, in order, each of the
+    # chunk size but the last; the first chunk rides in the step that takes the prompt up
+    cur = None
+    for o in log:
+        if o["prefill_started_req"] >= 0:
+            assert cur is None and o["prefill_started_count"] == 1
+            cur = [o["prefill_started_req"], o["prefill_started_tokens"], 0]
+            assert o["chunk"] is not None
+        if o["chunk"] is not None:
+            rid, start, n = o["chunk"]
+            assert cur is not None and rid == cur[0] and start == cur[2] and 1 <= n <= chunk
+            cur[2] += n
+            assert n == chunk or cur[2] == cur[1]
+            if cur[2] == cur[1]:
+                cur = None
+    assert cur is None
+    if n_blocks == 1000:
+        assert sum(o["n_preempted"] for o in log) == 0
+        assert [o["prefill_started_req"] for o in log if o["prefill_started_req"] >= 0] == [r[0] for r in sorted(reqs, key=lambda r: r[4])]
+    else:
+        assert sum(o["n_preempted"] for o in log) > 0
+
+
 def _host_ctx(n_blocks, max_batch, eos, max_prefill=4096):
     c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=max_prefill,
                               max_decode_batch=max_batch, max_context=4096, device=rs.RS_HOST_ONLY)
