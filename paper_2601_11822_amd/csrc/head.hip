@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a) {
     if (a.slots) {
         int q = 0;
         while (q + 1 < a.seq.n_req && row >= a.seq.cu[q + 1]) ++q;
-        tok = a.tokens[(size_t)a.slots[q] * a.slot_stride + (row - a.seq.cu[q])];
+        tok = a.tokens[(size_t)a.slots[q] * a.slot_stride + a.seq.start[q] + (row - a.seq.cu[q])];
     } else {
         tok = a.tokens[a.row_slot ? a.row_slot[row] : row];
     }

@@ -177,8 +177,8 @@ struct EmbedArgs {
     bf16_t *x;                 // [n][d] row-major
     int32_t *err_flag;
     int n, d, vocab;
-    // several whole prompts in one call: row r of prompt q (seq.cu delimits them) is token
-    // tokens[slots[q] * slot_stride + (r - seq.cu[q])]
+    // several prompts (or a chunk of each, from position seq.start[q]) in one call: row r of prompt q (seq.cu
+    // delimits them) is token tokens[slots[q] * slot_stride + seq.start[q] + (r - seq.cu[q])]
     const int32_t *slots = nullptr;
     int slot_stride = 0;
     SeqInfo seq{};

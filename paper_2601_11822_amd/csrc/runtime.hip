@@ -135,6 +135,7 @@ struct Request {
     int32_t n_prefill = 0;         // tokens the next prefill covers (prompt, plus generated ones after a preemption)
     int32_t n_sampled = 0;         // sampling events enqueued so far (known without looking at any token)
     bool complete = false;         // last token seen (end-of-sequence or the token limit)
+    int32_t chunk_done = 0;        // hybrid batching: tokens of the prefill in progress that earlier steps took
     std::deque<int32_t> injected;  // host-only contexts: tokens the next sampling events will yield
     double t_submit = 0, t_first = 0, t_last = 0;   // host clock: submission, first and latest token seen
     Result *res = nullptr;         // engine requests: where the application looks
@@ -219,6 +220,11 @@ struct rs_ctx {
     std::vector<int64_t> dead;     // engine: finished requests whose table entry goes once no staged step names them
     std::vector<int64_t> prefill_ids;   // the prompts of the prefill pass in flight (one pass at a time)
     bool prefill_host_done = false;     // host-only contexts: rs_debug_complete_prefill
+    // hybrid batching (the comparison scheme of section 3.1): chunk size in tokens, 0 = off; whether the last chunk
+    // of the prompt in prefill_ids has been enqueued; the stream the previous step ran on
+    int32_t hybrid_chunk = 0;
+    bool hyb_last = false;
+    hipStream_t hyb_prev_stream = nullptr;
     hipEvent_t prefill_ev = nullptr;    // end of that pass
     int32_t max_blk_per_req = 0;
     int32_t *d_ctx = nullptr, *d_tab = nullptr, *d_ptab = nullptr;   // device staging
@@ -1793,7 +1799,9 @@ int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wa
 int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token_mode) {
     *out = rs_step_out{};
     out->prefill_started_req = -1;
+    out->chunk_req = -1;
     out->decode_ms = -1.f;
+    if (c->hybrid_chunk && !token_mode) return fail(RS_ERR_STATE, "hybrid batching serves token requests only (rs_step_tokens)");
     const int maxB = c->lim.max_decode_batch;
     if (c->gpu) HIP_TRY(hipSetDevice(c->device));
 
@@ -1819,7 +1827,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             accept_token(c, r, c->gpu ? dm.token : next_injected(r));
             if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
         }
-    } else if (!c->prefill_ids.empty()) {
+    } else if (!c->prefill_ids.empty() && (!c->hybrid_chunk || c->hyb_last)) {
         bool done = c->prefill_host_done;
         if (c->gpu) {
             hipError_t q = hipEventQuery(c->prefill_ev);
@@ -1839,6 +1847,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 }
             }
             c->prefill_ids.clear();
+            c->hyb_last = false;
         }
     }
     // 1b. retire requests that produced all their tokens
@@ -1927,6 +1936,8 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     for (int64_t id : c->running) sum_ctx += c->reqs[id].ctx_len;
     int32_t p, d;
     choose_split(c, B, sum_ctx, prefill_pending, &p, &d);
+    const bool hyb = c->hybrid_chunk > 0;
+    if (hyb) p = d = RS_TOTAL_CUS;   // one batch, the whole chip
     if (B == 0 && !prefill_pending) { p = c->engine ? c->prefill_cus_pub.load() : c->side[0].cus; d = c->side[1].cus; }
     else {
         int32_t rc = set_split(c, p, d);
@@ -1941,18 +1952,45 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     // the previous call may still write: it is ordered behind that step
     const int prev_end = c->step_end_idx;
 
-    // 5. one decode step over the running batch
+    // 5h. hybrid batching: the prompt being chunked (taken up here if none is) gives this step its next chunk,
+    //     which shares the step's batch with the decode rows
+    int n_chunk = 0, chunk_start = 0;
+    Request *chunk_req = nullptr;
+    if (hyb) {
+        if (c->prefill_ids.empty() && next_prefill >= 0) {
+            Request &r = c->reqs[next_prefill];
+            r.n_sampled++;
+            r.chunk_done = 0;
+            set_state(r, PREFILLING);
+            c->prefill_ids.assign(1, next_prefill);
+            c->hyb_last = false;
+            out->prefill_started_req = next_prefill;
+            out->prefill_started_tokens = r.n_prefill;
+            out->prefill_started_count = 1;
+        }
+        if (!c->prefill_ids.empty() && !c->hyb_last) {
+            chunk_req = &c->reqs[c->prefill_ids[0]];
+            chunk_start = chunk_req->chunk_done;
+            n_chunk = std::min(c->hybrid_chunk, chunk_req->n_prefill - chunk_start);
+            out->chunk_req = chunk_req->id;
+            out->chunk_start = chunk_start;
+            out->chunk_tokens = n_chunk;
+        }
+    }
+    const bool last_chunk = n_chunk > 0 && chunk_start + n_chunk == chunk_req->n_prefill;
+
+    // 5. one decode step over the running batch (hybrid batching: and the chunk, in one batch)
     c->last_batch.assign(c->running.begin(), c->running.end());
-    if (B > 0) {
+    if (B > 0 || n_chunk > 0) {
         int max_ctx = 1;
         for (int64_t id : c->running) max_ctx = std::max(max_ctx, c->reqs[id].ctx_len + 1);
-        const int flip = c->stage_flip ^= 1;
-        if (token_mode && c->pending[flip]) {   // the staging buffers are about to be rewritten
+        const int flip = B > 0 ? (c->stage_flip ^= 1) : c->stage_flip;
+        if (B > 0 && token_mode && c->pending[flip]) {   // the staging buffers are about to be rewritten
             if (c->gpu) HIP_TRY(hipEventSynchronize(c->sampled_ev[flip]));
             harvest(c, flip);
         }
         if (c->gpu) {
-            HIP_TRY(hipEventSynchronize(c->staged[flip]));
+            if (B > 0) HIP_TRY(hipEventSynchronize(c->staged[flip]));
             const int mb = c->max_blk_per_req;
             for (int i = 0; i < B; ++i) {
                 Request &r = c->reqs[c->running[i]];
@@ -1961,16 +1999,62 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 const std::vector<int32_t> &ids = c->owned[r.id];
                 for (int j = 0; j < mb; ++j) c->h_tab[flip][(size_t)i * mb + j] = j < (int)ids.size() ? ids[j] : -1;
             }
-            hipStream_t st = c->side[RS_SIDE_DECODE].stream;
-            HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
-            HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
-            if (token_mode)
-                HIP_TRY(hipMemcpyAsync(c->d_rowslot, c->h_rowslot[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
-            HIP_TRY(hipEventRecord(c->staged[flip], st));
-            if (in->wait_decode) { int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2); if (rc) return rc; }
-            Workspace &w = c->ws[RS_SIDE_DECODE];
+            // a step with a chunk runs on the prefill side's stream and workspace (which holds chunk + batch rows),
+            // a step without one is an ordinary decode step; consecutive steps on different streams are ordered
+            const int sd = n_chunk > 0 ? RS_SIDE_PREFILL : RS_SIDE_DECODE;
+            hipStream_t st = c->side[sd].stream;
+            if (hyb) {
+                if (c->hyb_prev_stream && c->hyb_prev_stream != st && c->step_end_valid[c->step_end_idx])
+                    HIP_TRY(hipStreamWaitEvent(st, c->step_end[c->step_end_idx], 0));
+                c->hyb_prev_stream = st;
+            }
+            if (B > 0) {
+                HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                if (token_mode)
+                    HIP_TRY(hipMemcpyAsync(c->d_rowslot, c->h_rowslot[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipEventRecord(c->staged[flip], st));
+            }
+            if (n_chunk > 0) {   // the chunked prompt's block table and slot
+                HIP_TRY(hipEventSynchronize(c->pstaged));
+                const std::vector<int32_t> &ids = c->owned[chunk_req->id];
+                for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)ids.size() ? ids[j] : -1;
+                c->h_pslots[0] = chunk_req->slot;
+                HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, (size_t)mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipEventRecord(c->pstaged, st));
+            }
+            if (in->wait_decode) { int32_t rc = rs_mark(c, sd, RS_MAX_MARKS - 2); if (rc) return rc; }
+            Workspace &w = c->ws[sd];
             // the step's kernels: embedding (token mode), every layer, head (token mode)
             auto enqueue_kernels = [&](int ctx_bound) -> int32_t {
+                if (n_chunk > 0) {   // hybrid batch: rows [0, n_chunk) the chunk, rows [n_chunk, n_chunk + B) the decode rows
+                    const int dm = c->m.d_model;
+                    SeqInfo seq{};
+                    seq.n_req = 1;
+                    seq.cu[1] = n_chunk;
+                    seq.start[0] = chunk_start;
+                    EmbedArgs ea{c->d_prompts, nullptr, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + sd, n_chunk, dm, c->head.vocab};
+                    ea.slots = c->d_pslots;
+                    ea.slot_stride = c->lim.max_context;
+                    ea.seq = seq;
+                    launch_embed(st, ea);
+                    launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf + (size_t)n_chunk * dm,
+                                               c->err_flag + sd, B, dm, c->head.vocab});
+                    const int32_t cu[2] = {0, n_chunk};
+                    for (int l = 0; l < c->m.n_layers; ++l) {
+                        if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
+                        int32_t rc = hybrid_layer(c, l, w.xbuf, w.xbuf, cu, &chunk_start, 1, c->d_ptab, mb, c->d_ctx, c->d_tab, mb, B, ctx_bound);
+                        if (rc) return rc;
+                    }
+                    if (last_chunk) {   // the prompt's first token, from the chunk's last row (x1 is free after the layers)
+                        launch_gather_last_rows(st, w.xbuf, w.x1, dm, seq);
+                        int32_t rc = head_greedy(c, sd, w.x1, 1, nullptr, c->d_pfirst, c->d_pslots, c->d_tok);
+                        if (rc) return rc;
+                    }
+                    if (B > 0) return head_greedy(c, sd, w.xbuf + (size_t)n_chunk * dm, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
+                    return RS_OK;
+                }
                 const void *x_first = in->decode_hidden;
                 void *x_out = in->decode_out;
                 if (token_mode) {
@@ -1989,7 +2073,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             };
             const auto t_enq = std::chrono::steady_clock::now();
             bool captured_now = false;
-            if (token_mode && c->step_graphs_on) {
+            if (token_mode && c->step_graphs_on && n_chunk == 0) {
                 // Section 4.5.2: decode steps are captured as graphs per batch size and replayed.  The key is
                 // (batch, context bucket, masked stream): the captured launches bake in the batch, a bound on the
                 // contexts (a multiple of 512 tokens) and the stream's CU mask; everything else they read --
@@ -2029,24 +2113,36 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 c->steps_enqueued++;
                 c->step_enqueue_ns += std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t_enq).count();
             }
-            if (token_mode) {
+            if (token_mode && B > 0) {
                 HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-                HIP_TRY(hipMemcpyAsync(&c->h_err[2 + flip], c->err_flag + RS_SIDE_DECODE, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                HIP_TRY(hipMemcpyAsync(&c->h_err[2 + flip], c->err_flag + sd, sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipEventRecord(c->sampled_ev[flip], st));
+            }
+            if (last_chunk) {   // what the end of a whole-prompt pass records
+                HIP_TRY(hipMemcpyAsync(c->h_pfirst, c->d_pfirst, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                HIP_TRY(hipMemcpyAsync(&c->h_err[4], c->err_flag + RS_SIDE_PREFILL, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                HIP_TRY(hipEventRecord(c->prefill_ev, st));
             }
             c->step_end_idx ^= 1;
             HIP_TRY(hipEventRecord(c->step_end[c->step_end_idx], st));
             c->step_end_valid[c->step_end_idx] = true;
             if (in->wait_decode) {
-                int32_t rc = rs_mark(c, RS_SIDE_DECODE, RS_MAX_MARKS - 1);
+                int32_t rc = rs_mark(c, sd, RS_MAX_MARKS - 1);
                 if (rc) return rc;
-                rc = rs_elapsed_ms(c, RS_SIDE_DECODE, RS_MAX_MARKS - 2, RS_SIDE_DECODE, RS_MAX_MARKS - 1, &out->decode_ms);
+                rc = rs_elapsed_ms(c, sd, RS_MAX_MARKS - 2, sd, RS_MAX_MARKS - 1, &out->decode_ms);
                 if (rc) return rc;
             }
         }
-        if (token_mode) {
+        if (token_mode && B > 0) {
             c->inflight[flip].assign(c->running.begin(), c->running.end());
             c->pending[flip] = true;
+        }
+        if (n_chunk > 0) {
+            chunk_req->chunk_done += n_chunk;
+            if (last_chunk) {
+                c->hyb_last = true;
+                if (!c->gpu) c->prefill_host_done = true;   // host-only: seen at the next step
+            }
         }
         for (int64_t id : c->running) {
             Request &r = c->reqs[id];
@@ -2054,11 +2150,12 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             r.generated++;
             r.n_sampled++;
         }
-        if (token_mode && in->wait_decode) {
+        if (token_mode && in->wait_decode && B > 0) {
             int32_t rc = harvest_ready(c, true);
             if (rc) return rc;
         }
     }
+    if (hyb) return RS_OK;   // no separate prefill pass under hybrid batching
 
     // 6. engine: every request whose blocks are allocated goes to the prefill thread, in arrival order
     if (c->engine) {
@@ -2248,6 +2345,7 @@ int32_t rs_engine_start(rs_ctx *c) {
     if (c->engine) return fail(RS_ERR_STATE, "the engine is already running");
     if (!c->have_head) return fail(RS_ERR_STATE, "rs_set_head has not been called");
     if (!c->arrival.empty()) return fail(RS_ERR_STATE, "requests are live on this context");
+    if (c->hybrid_chunk) return fail(RS_ERR_STATE, "hybrid batching is on: the engine threads serve with two sides");
     int32_t rc = enter_mode(c, 2);
     if (rc) return rc;
     if (c->gpu) {
@@ -2301,6 +2399,22 @@ int32_t rs_engine_stats(rs_ctx *c, int64_t stats_out[4]) {
         std::lock_guard<std::mutex> lk(c->res_mu);
         return fail(rc, "engine thread: %s", c->eng_err.c_str());
     }
+    return RS_OK;
+}
+
+int32_t rs_set_hybrid_batching(rs_ctx *c, int32_t chunk_tokens) {
+    if (!c) return fail(RS_ERR_BAD_ARG, "null context");
+    if (c->engine) return fail(RS_ERR_STATE, "the engine threads serve with two sides; stop the engine first");
+    if (!c->arrival.empty() || !c->running.empty() || !c->prefill_ids.empty())
+        return fail(RS_ERR_STATE, "the batching scheme changes only while no request is in flight");
+    if (chunk_tokens < 0 || chunk_tokens % RS_KV_BLOCK)
+        return fail(RS_ERR_BAD_ARG, "chunk of %d tokens: 0 (off) or a multiple of %d", chunk_tokens, RS_KV_BLOCK);
+    if (chunk_tokens > 0 && chunk_tokens + c->lim.max_decode_batch > c->lim.max_prefill_tokens)
+        return fail(RS_ERR_BAD_ARG, "a chunk of %d tokens and %d decode rows exceed max_prefill_tokens %d", chunk_tokens,
+                    c->lim.max_decode_batch, c->lim.max_prefill_tokens);
+    c->hybrid_chunk = chunk_tokens;
+    c->hyb_last = false;
+    c->hyb_prev_stream = nullptr;
     return RS_OK;
 }
 

@@ -257,6 +257,68 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
     assert results[True] == results[False]
 
 
+@pytest.mark.parametrize("n_blocks,chunk", [(64, 16), (64, 48), (7, 16)])
+def test_closed_loop_hybrid_batching_matches_oracle(n_blocks, chunk):
+    """The comparison scheme (section 3.1) as a serving policy: prompts go through in chunks that share each
+    step's batch with the decode rows.  The tokens are checked against the oracle exactly like the other policy's
+    (a request's tokens do not depend on how its prompt was scheduled); the small pool forces a recomputation."""
+    shape, n_layers, vocab = S.TINY, 2, 1000
+    prompts = [(1, 37, 30, 0), (2, 5, 40, 0), (3, 64, 25, 2), (4, 16, 3, 3), (5, 23, 33, 6)] if n_blocks == 64 else \
+              [(1, 20, 40, 0), (2, 20, 40, 0)]
+    requests = [(rid, S.prompt_tokens(pl, vocab, rid), mn, arr) for rid, pl, mn, arr in prompts]
+    hb = S.head_weights(shape.d_model, vocab)
+    wbits = [S.layer_weights(shape, l) for l in range(n_layers)]
+    rig = Rig(shape, n_blocks=n_blocks, max_prefill_tokens=128, max_decode_batch=4, max_context=128, n_layers=n_layers,
+              with_oracle=False)
+    try:
+        hd = {k: to_dev(v) for k, v in hb.items()}
+        rig.ctx.set_head(hd["embed"], hd["final_norm"], hd["lm_head"], vocab, -1)
+        rig.ctx.set_hybrid_batching(chunk)
+        chunks, mixed = [], 0
+        todo = sorted(requests, key=lambda r: r[3])
+        n_pre = n_done = step = 0
+        while n_done < len(requests) and step < 4000:
+            while todo and todo[0][3] <= step:
+                rid, prompt, mn, _ = todo.pop(0)
+                rig.ctx.submit_tokens(rid, prompt, mn)
+            so = rig.ctx.step_tokens(wait_decode=False)
+            n_pre += so.n_preempted
+            n_done += so.n_finished
+            step += 1
+            if so.chunk_req >= 0:
+                chunks.append((so.chunk_req, so.chunk_start, so.chunk_tokens))
+                mixed += so.decode_batch > 0
+                assert (so.prefill_cus, so.decode_cus) == (256, 256)
+            if so.decode_batch == 0:
+                rig.ctx.sync(rs.RS_SIDE_PREFILL)
+        rig.ctx.sync(rs.RS_SIDE_PREFILL)
+        rig.ctx.sync(rs.RS_SIDE_DECODE)
+        for _ in range(3):
+            rig.ctx.step_tokens(wait_decode=True)
+        assert n_done == len(requests)
+        outs = {}
+        for rid, *_ in requests:
+            toks, fin = rig.ctx.request_output(rid)
+            assert fin
+            outs[rid] = toks.tolist()
+        frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, -1, requests, outs)
+        print(f"  chunk {chunk}: {len(chunks)} chunks, {mixed} of them beside decode rows, {n_pre} preemption(s); "
+              f"{frac:.2%} of generated tokens equal the oracle's choice", flush=True)
+        assert frac >= 0.9 and rig.ctx.kv_num_free() == n_blocks
+        # every prompt went through as chunks of the set size, in order; some chunk shared a batch with decode rows
+        assert all(n == chunk or st + n >= 5 for _, st, n in chunks) and all(st % 16 == 0 for _, st, _ in chunks)
+        first = {}
+        for rid, st, n in chunks:
+            if st == 0 and rid not in first:
+                first[rid] = True
+        assert set(first) == {r[0] for r in requests}
+        assert mixed >= 1
+        if n_blocks < 64:
+            assert n_pre >= 1
+    finally:
+        rig.close()
+
+
 def test_closed_loop_with_preemption_matches_oracle():
     # pool of 6 blocks: two 20-token prompts growing to 60 tokens each need 8: one is recomputed
     shape, n_layers, vocab = S.TINY, 2, 1000

@@ -236,6 +236,60 @@ def test_library_life_cycle_matches_oracle(n_blocks, seed, budget):
     assert c.kv_num_free() == n_blocks
 
 
+@pytest.mark.parametrize("n_blocks,seed,chunk", [(1000, 21, 16), (1000, 22, 32), (12, 23, 16), (8, 24, 48), (7, 25, 16), (9, 26, 32)])
+def test_library_hybrid_batching_matches_oracle(n_blocks, seed, chunk):
+    """The library's state machine with hybrid batching on (host-only context, tokens injected) against the
+    oracle's hybrid policy, step by step: every counter, the batch, and the chunk each step takes."""
+    reqs, delays = _trace(seed)
+    lc = Lifecycle(n_blocks, max_batch=4, eos=EOS, hybrid_chunk=chunk)
+    ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lambda rid: None, reqs, delays)
+    c = _host_ctx(n_blocks, 4, EOS)
+    c.set_hybrid_batching(chunk)
+
+    def submit(rid, pl, mn, script):
+        c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
+        for t in script:
+            c.debug_push_sampled(rid, t)
+
+    def step():
+        so = c.step_tokens()
+        o = {k: getattr(so, k) for k in KEYS}
+        o["batch_ids"] = c.decode_batch_ids()
+        o["chunk"] = (so.chunk_req, so.chunk_start, so.chunk_tokens) if so.chunk_req >= 0 else None
+        return o
+
+    got = _drive(submit, step, lambda rid: None, reqs, delays)
+    assert len(got) == len(ref)
+    for i, (a, b) in enumerate(zip(got, ref)):
+        for k in KEYS + ("batch_ids", "chunk"):
+            assert a[k] == b[k], f"step {i}: {k}: library {a[k]} oracle {b[k]}"
+    for rid, pl, mn, script, _ in reqs:
+        toks, fin = c.request_output(rid)
+        assert fin and toks.tolist() == lc.reqs[rid].out == _expected_output(script, mn, EOS)
+    assert c.kv_num_free() == n_blocks
+    if n_blocks < 1000:
+        assert sum(o["n_preempted"] for o in got) > 0
+
+
+def test_library_hybrid_batching_argument_checks():
+    c = _host_ctx(64, 4, EOS, max_prefill=100)
+    for bad in (-16, 8, 24):
+        with pytest.raises(rs.RapidServeError) as e:
+            c.set_hybrid_batching(bad)
+        assert e.value.code == rs.RS_ERR_BAD_ARG
+    with pytest.raises(rs.RapidServeError) as e:      # 112 + 4 decode rows do not fit 100 rows of workspace
+        c.set_hybrid_batching(112)
+    assert e.value.code == rs.RS_ERR_BAD_ARG
+    c.set_hybrid_batching(32)
+    c.submit_tokens(1, np.zeros(40, np.int32), 2)
+    with pytest.raises(rs.RapidServeError) as e:      # not while a request is in flight
+        c.set_hybrid_batching(0)
+    assert e.value.code == rs.RS_ERR_STATE
+    with pytest.raises(rs.RapidServeError) as e:      # the engine threads serve with two sides
+        c.engine_start()
+    assert e.value.code == rs.RS_ERR_STATE
+
+
 @pytest.mark.parametrize("seed", range(100, 130))
 def test_library_life_cycle_matches_oracle_random_pools(seed):
     """Thirty more traces with pool size, batch cap, prefill budget and request count drawn from the seed."""
