@@ -21,13 +21,17 @@ Readings where the paper is silent:
 
 Hybrid batching (`hybrid_chunk` > 0; section 3.1 describes the scheme the paper compares with: a
 prompt is cut into chunks of 512 or 1024 tokens and every chunk shares a batch with the running
-decode tokens).  Readings: one prompt is chunked at a time, first come first served; a step takes the
-next `hybrid_chunk` tokens of it (the rest, if fewer remain) into the same batch as the decode step of
-all running requests; the step that takes a prompt's last chunk also yields its first output token,
-which the scheduler sees at the next step; the prompt taken up in a step has its first chunk in that
-same step; a request being chunked is "being prefilled" for the preemption rule.  Everything else --
-block accounting, promotion, retirement, preemption -- is unchanged, so the tokens a request
-receives are the same under either policy.
+decode tokens).  Readings: `hybrid_chunk` is a step's budget of prompt tokens (the decode rows come on
+top); prompts are served first come first served and the budget is filled in that order -- the
+rest of the prompt in progress first, then the next prompts that have their blocks, the last of
+them possibly in part; a part that is not the end of its prompt is a multiple of 16 tokens (so that
+every later part starts on a block boundary), which may leave a few tokens of the budget unused; at
+most `max_prefill_reqs` prompts have a part in one step; these parts and the decode step of all
+running requests form one batch; the step that takes a prompt's last part also yields its first
+output token, which the scheduler sees at the next step, after that step's decode tokens; a request
+with a part taken and its first token not yet seen is "being prefilled" for the preemption rule.
+Everything else -- block accounting, promotion, retirement, preemption -- is unchanged, so the
+tokens a request receives are the same under either policy.
 
 The tokens themselves come from outside: `script[req]` is the sequence of tokens the request's
 successive sampling events yield (a missing entry yields 0).  Everything is integer and exact.
@@ -59,7 +63,9 @@ class Lifecycle:
                  max_prefill_tokens: int = 1 << 30, max_prefill_reqs: int = 64, hybrid_chunk: int = 0):
         self.max_prefill_tokens, self.max_prefill_reqs = max_prefill_tokens, max_prefill_reqs
         self.hybrid_chunk = hybrid_chunk
-        self.chunk_done = 0                  # tokens of the prompt being chunked that earlier steps took
+        self.hyb_cur: Optional[int] = None   # the prompt of which a part, not yet the last, has been taken
+        self.chunk_done = 0                  # tokens of that prompt that earlier steps took
+        self.hyb_finishing: List[int] = []   # prompts whose last part the previous step took
         self.alloc = KVAllocator(n_blocks)
         self.max_batch, self.eos = max_batch, eos
         self.split = split
@@ -98,6 +104,14 @@ class Lifecycle:
         for rid in self.last_tokens:                       # tokens of the previous decode step
             self._sample(self.reqs[rid])
         self.last_tokens = []
+        for rid in self.hyb_finishing:                     # hybrid batching: first tokens of the previous step
+            r = self.reqs[rid]
+            r.state, r.ctx = PREFILL_DONE, r.n_prefill
+            self._sample(r)
+            if r.complete:
+                self._finish(r)
+                o["n_finished"] += 1
+        self.hyb_finishing = []
         if self.prefilling and self.pass_done:
             self.pass_done = False
             for rid in self.prefilling:
@@ -186,29 +200,43 @@ class Lifecycle:
         return o
 
     def _hybrid_tail(self, o: dict) -> dict:
-        """The rest of a step under hybrid batching: the next chunk and the decode step, one batch."""
+        """The rest of a step under hybrid batching: the prompt parts and the decode step, one batch."""
         o["prefill_started_count"] = 0
-        if not self.prefilling:
-            rid = next((rid for rid in self.arrival if self.reqs[rid].state == PREFILL_READY), None)
-            if rid is not None:
-                self.reqs[rid].state = PREFILLING
-                self.prefilling = [rid]
-                self.chunk_done = 0
-                o["prefill_started_req"] = rid
-                o["prefill_started_tokens"] = self.reqs[rid].n_prefill
-                o["prefill_started_count"] = 1
-                o["prefill_started_ids"] = [rid]
         o["decode_batch"] = len(self.running)
         o["decode_sum_ctx"] = sum(self.reqs[rid].ctx for rid in self.running)
         o["batch_ids"] = list(self.running)
-        o["chunk"] = None
-        if self.prefilling and not self.pass_done:
-            r = self.reqs[self.prefilling[0]]
-            n = min(self.hybrid_chunk, r.n_prefill - self.chunk_done)
-            o["chunk"] = (r.id, self.chunk_done, n)
+        chunks: List[Tuple[int, int, int]] = []
+        budget = self.hybrid_chunk
+        while budget > 0 and len(chunks) < self.max_prefill_reqs:
+            rid = self.hyb_cur
+            if rid is None:                                # the next prompt that has its blocks, if any
+                rid = next((q for q in self.arrival if self.reqs[q].state == PREFILL_READY), None)
+                if rid is None:
+                    break
+            r = self.reqs[rid]
+            done = self.chunk_done if self.hyb_cur is not None else 0
+            rest = r.n_prefill - done
+            n = min(budget, rest)
+            if n < rest:
+                n -= n % 16
+            if n == 0:                                     # what is left of the budget is less than a block
+                break
+            if self.hyb_cur is None:                       # taken up with its first part
+                r.state = PREFILLING
+                self.hyb_cur, self.chunk_done = rid, 0
+                if o["prefill_started_req"] < 0:
+                    o["prefill_started_req"] = rid
+                o["prefill_started_tokens"] += r.n_prefill
+                o["prefill_started_count"] += 1
+                o.setdefault("prefill_started_ids", []).append(rid)
+                o.setdefault("prefill_started_lens", []).append(r.n_prefill)
+            chunks.append((rid, done, n))
             self.chunk_done += n
+            budget -= n
             if self.chunk_done == r.n_prefill:
-                self.pass_done = True           # its first token is seen at the next step
+                self.hyb_finishing.append(rid)             # its first token is seen at the next step
+                self.hyb_cur = None
+        o["chunks"] = chunks
         for rid in self.running:                           # the decode rows of the same batch
             self.reqs[rid].ctx += 1
         self.last_tokens = list(self.running)

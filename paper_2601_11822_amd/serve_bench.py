@@ -13,6 +13,8 @@ the preemption count, for one policy:
     --policy manager   profile-driven split (needs --profile FILE, or --profile measure to run the
                        offline profiler first on a one-layer rig of the same shape)
     --policy over      no profile: both partitions see every CU whenever both have work
+    --policy hybrid    the scheme the paper compares with (section 3.1): no partitions; a prompt goes through in
+                       chunks of --chunk tokens, each in one batch with the decode step (rs_set_hybrid_batching)
 
 With --engine the library's own decode and prefill threads drive the loop (rs_engine_start) and
 the script only submits and polls; per-request inter-token latency is then (last - first token
@@ -235,7 +237,8 @@ def main(argv=None):
     ap.add_argument("--max-out", type=int, default=1024)
     ap.add_argument("--max-batch", type=int, default=64)
     ap.add_argument("--kv-tokens", type=int, default=262144, help="KV pool size in tokens")
-    ap.add_argument("--policy", choices=("manager", "over"), default="over")
+    ap.add_argument("--policy", choices=("manager", "over", "hybrid"), default="over")
+    ap.add_argument("--chunk", type=int, default=512, help="--policy hybrid: prompt tokens per step (a multiple of 16)")
     ap.add_argument("--profile", default=None, help="JSON written by the profiler, or 'measure'")
     ap.add_argument("--slo-ms", type=float, default=50.0)
     ap.add_argument("--profile-ctx-edges", default="32768,131072",
@@ -277,6 +280,10 @@ def main(argv=None):
          f"{work[-1][1]:.1f}s, {sum(len(w[2]) for w in work)} prompt tokens, {sum(w[3] for w in work)} to generate")
     if a.no_step_graphs:
         c.set_step_graphs(False)
+    if a.policy == "hybrid":
+        if a.engine:
+            ap.error("--policy hybrid runs in the host step loop")
+        c.set_hybrid_batching(a.chunk)
     # one throw-away request settles lazy runtime work (first launches, masked streams)
     settle_id = 1 << 40
     c.submit_tokens(settle_id, work[0][2][:64], 4)
@@ -292,6 +299,7 @@ def main(argv=None):
         rec = summarise(c, work, steps, wall)
     rec.update({"policy": a.policy, "shape": shape.name, "layers": a.layers, "rate_per_s": a.rate, "slo_ms": a.slo_ms,
                 "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "experts": a.experts, "data": "synthetic",
+                "chunk": a.chunk if a.policy == "hybrid" else None,
                 "step_graphs": rec.get("step_graphs") if not a.no_step_graphs else "off"})
     line = json.dumps(rec)
     print(line, flush=True)
