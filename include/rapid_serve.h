@@ -371,8 +371,8 @@ typedef struct {
     int32_t n_preempted;             /* rs_step_tokens: running requests sent back to WAITING for want of blocks */
     int32_t prefill_started_count;   /* prompts in the prefill pass that was started (prefill_started_req is the first,
                                         prefill_started_tokens their total) */
-    int64_t chunk_req;               /* hybrid batching: the request whose chunk shared this step's batch, or -1 */
-    int32_t chunk_start, chunk_tokens; /* that chunk's first position and length */
+    int32_t n_chunks, chunk_tokens;  /* hybrid batching: prompt parts in this step's batch and their tokens in all
+                                        (rs_step_chunks names them) */
 } rs_step_out;
 
 int32_t rs_submit(rs_ctx *ctx, int64_t req_id, int32_t prompt_len, int32_t output_len,
@@ -460,14 +460,20 @@ int32_t rs_step_tokens(rs_ctx *ctx, int32_t wait_decode, rs_step_out *out);
 /* The batching scheme of rs_step_tokens.  chunk_tokens = 0 (the default): the paper's own scheme, whole prompts
  * on the prefill side concurrently with decode steps on the decode side (sections 4.1, 4.5.2).  chunk_tokens > 0
  * (a multiple of 16): HYBRID BATCHING, the scheme the paper compares with (section 3.1; its comparison system in
- * section 5.1 runs chunks of 512 and 1024 tokens): one prompt at a time, first come first served, is cut into
- * chunks of chunk_tokens; every step takes the next chunk into one batch with the decode rows of all running
- * requests (rs_hybrid_layer over all layers, all CUs, one stream), the step that takes the last chunk yields the
- * prompt's first token; a step without a chunk is an ordinary decode step.  Block accounting, promotion,
+ * section 5.1 runs chunks of 512 and 1024 tokens).  chunk_tokens is a step's budget of prompt tokens: it is filled
+ * in arrival order -- the rest of the prompt in progress, then the next prompts that have their blocks, the last
+ * of them possibly in part (a part that does not end its prompt is a multiple of 16 tokens; at most
+ * RS_MAX_PREFILL_REQS parts per step) -- and these parts form one batch with the decode rows of all running
+ * requests (rs_hybrid_layer over all layers, all CUs, one stream).  The step that takes a prompt's last part
+ * yields its first token; a step without a part is an ordinary decode step.  Block accounting, promotion,
  * retirement and preemption are unchanged, and so are the tokens every request receives.  Only while no request
  * is in flight and the engine threads are not running; needs chunk_tokens + max_decode_batch <=
- * max_prefill_tokens (RS_ERR_BAD_ARG otherwise).  rs_step_out.chunk_* report each step's chunk. */
+ * max_prefill_tokens (RS_ERR_BAD_ARG otherwise). */
 int32_t rs_set_hybrid_batching(rs_ctx *ctx, int32_t chunk_tokens);
+/* The prompt parts of the latest rs_step_tokens call under hybrid batching, batch order: request, first position,
+ * length (host arrays of `cap` entries, any may be null); *n_out = their number (RS_ERR_BAD_ARG if cap is less). */
+int32_t rs_step_chunks(rs_ctx *ctx, int64_t *req_ids_out, int32_t *starts_out, int32_t *lens_out, int32_t cap,
+                       int32_t *n_out);
 int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int32_t cap, int32_t *n_out,
                           int32_t *finished_out);
 /* rs_step_tokens and the engine's decode thread launch every decode step as ONE captured HIP graph (section

@@ -28,7 +28,7 @@ RS_CU_HIST_BINS = 4096
 
 EXPORTS = [
     "rs_init", "rs_destroy", "rs_set_weights", "rs_last_error", "rs_kv_alloc", "rs_kv_free",
-    "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_decode_layer_noalloc", "rs_hybrid_layer", "rs_set_hybrid_batching", "rs_set_cu_split", "rs_get_cu_split",
+    "rs_kv_num_free", "rs_prefill_layer", "rs_decode_layer", "rs_decode_layer_noalloc", "rs_hybrid_layer", "rs_set_hybrid_batching", "rs_step_chunks", "rs_set_cu_split", "rs_get_cu_split",
     "rs_get_cu_mask", "rs_choose_split", "rs_get_stream", "rs_sync", "rs_mark", "rs_mark_done", "rs_elapsed_ms", "rs_decode_layer_graph", "rs_debug_cu_histogram_graph", "rs_decode_batch_ids", "rs_set_kernel_timing", "rs_kernel_times",
     "rs_debug_cu_histogram", "rs_debug_read_workspace", "rs_debug_stream_read", "rs_debug_mfma_probe", "rs_submit", "rs_step", "rs_request_state", "rs_debug_complete_prefill",
     "rs_set_head", "rs_embed", "rs_lm_head_greedy", "rs_submit_tokens", "rs_step_tokens", "rs_request_output",
@@ -82,7 +82,7 @@ class StepOut(ctypes.Structure):
                 ("prefill_started_req", ctypes.c_int64), ("n_promoted", ctypes.c_int32),
                 ("n_finished", ctypes.c_int32), ("n_waiting", ctypes.c_int32), ("decode_ms", ctypes.c_float),
                 ("n_preempted", ctypes.c_int32), ("prefill_started_count", ctypes.c_int32),
-                ("chunk_req", ctypes.c_int64), ("chunk_start", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32)]
+                ("n_chunks", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32)]
 
 
 class MoeWeights(ctypes.Structure):
@@ -257,6 +257,14 @@ class Context:
 
     def set_hybrid_batching(self, chunk_tokens: int):
         _check(self._lib.rs_set_hybrid_batching(self._h, ctypes.c_int32(chunk_tokens)))
+
+    def step_chunks(self):
+        """[(request, first position, length)] of the prompt parts in the latest step's batch (hybrid batching)."""
+        cap = RS_MAX_PREFILL_REQS
+        ids, st, ln = (ctypes.c_int64 * cap)(), (ctypes.c_int32 * cap)(), (ctypes.c_int32 * cap)()
+        n = ctypes.c_int32(0)
+        _check(self._lib.rs_step_chunks(self._h, ids, st, ln, ctypes.c_int32(cap), ctypes.byref(n)))
+        return [(int(ids[i]), int(st[i]), int(ln[i])) for i in range(n.value)]
 
     def decode_layer_noalloc(self, layer: int, x_in, x_out, ctx_lens, block_tables, max_blk: int, B: int, max_ctx: int):
         _check(self._lib.rs_decode_layer_noalloc(self._h, ctypes.c_int32(layer), _ptr(x_in), _ptr(x_out), _ptr(ctx_lens),

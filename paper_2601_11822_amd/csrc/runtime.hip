@@ -223,8 +223,12 @@ struct rs_ctx {
     // hybrid batching (the comparison scheme of section 3.1): chunk size in tokens, 0 = off; whether the last chunk
     // of the prompt in prefill_ids has been enqueued; the stream the previous step ran on
     int32_t hybrid_chunk = 0;
-    bool hyb_last = false;
+    int64_t hyb_cur = -1;                 // the prompt of which a part, not yet the last, has been taken
     hipStream_t hyb_prev_stream = nullptr;
+    struct HybPart { int64_t id; int32_t start, n; };
+    std::vector<HybPart> last_parts;      // the prompt parts of the latest step (rs_step_chunks)
+    int inflight_nb[2] = {0, 0};          // of inflight[f], the first so many are decode rows; the rest are prompts
+                                          // whose last part rode in that step (their first tokens)
     hipEvent_t prefill_ev = nullptr;    // end of that pass
     int32_t max_blk_per_req = 0;
     int32_t *d_ctx = nullptr, *d_tab = nullptr, *d_ptab = nullptr;   // device staging
@@ -1216,11 +1220,13 @@ int32_t rs_set_head(rs_ctx *c, const rs_head_weights *w) {
             HIP_TRY(hipMalloc((void **)&c->d_pfirst, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
             HIP_TRY(hipHostMalloc((void **)&c->h_pslots, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
             HIP_TRY(hipHostMalloc((void **)&c->h_pfirst, RS_MAX_PREFILL_REQS * sizeof(int32_t)));
-            HIP_TRY(hipMalloc((void **)&c->d_rowslot, nb * sizeof(int32_t)));
-            HIP_TRY(hipMalloc((void **)&c->d_sampled, nb * sizeof(int32_t)));
+            // decode rows, and behind them (hybrid batching) the prompts that end in the same step
+            const size_t nr = nb + RS_MAX_PREFILL_REQS;
+            HIP_TRY(hipMalloc((void **)&c->d_rowslot, nr * sizeof(int32_t)));
+            HIP_TRY(hipMalloc((void **)&c->d_sampled, nr * sizeof(int32_t)));
             for (int i = 0; i < 2; ++i) {
-                HIP_TRY(hipHostMalloc((void **)&c->h_rowslot[i], nb * sizeof(int32_t)));
-                HIP_TRY(hipHostMalloc((void **)&c->h_sampled[i], nb * sizeof(int32_t)));
+                HIP_TRY(hipHostMalloc((void **)&c->h_rowslot[i], nr * sizeof(int32_t)));
+                HIP_TRY(hipHostMalloc((void **)&c->h_sampled[i], nr * sizeof(int32_t)));
                 HIP_TRY(hipEventCreateWithFlags(&c->sampled_ev[i], hipEventDisableTiming));
             }
         }
@@ -1691,6 +1697,10 @@ void harvest(rs_ctx *c, int f) {
     if (!c->pending[f]) return;
     for (size_t i = 0; i < c->inflight[f].size(); ++i) {
         Request &r = c->reqs[c->inflight[f][i]];
+        if ((int)i >= c->inflight_nb[f]) {   // hybrid batching: a prompt whose last part rode in that step
+            set_state(r, PREFILL_DONE);
+            r.ctx_len = r.n_prefill;
+        }
         accept_token(c, r, c->gpu ? c->h_sampled[f][i] : next_injected(r));
     }
     if (c->gpu) c->step_err |= c->h_err[2 + f];   // reported by the serving step that harvested it
@@ -1799,7 +1809,6 @@ int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wa
 int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token_mode) {
     *out = rs_step_out{};
     out->prefill_started_req = -1;
-    out->chunk_req = -1;
     out->decode_ms = -1.f;
     if (c->hybrid_chunk && !token_mode) return fail(RS_ERR_STATE, "hybrid batching serves token requests only (rs_step_tokens)");
     const int maxB = c->lim.max_decode_batch;
@@ -1827,7 +1836,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             accept_token(c, r, c->gpu ? dm.token : next_injected(r));
             if (wants_retire(r)) { release_request(c, r); out->n_finished++; }
         }
-    } else if (!c->prefill_ids.empty() && (!c->hybrid_chunk || c->hyb_last)) {
+    } else if (!c->prefill_ids.empty()) {
         bool done = c->prefill_host_done;
         if (c->gpu) {
             hipError_t q = hipEventQuery(c->prefill_ev);
@@ -1847,9 +1856,13 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 }
             }
             c->prefill_ids.clear();
-            c->hyb_last = false;
         }
     }
+    if (c->hybrid_chunk)   // hybrid batching: first tokens arrive with the harvest; a request they end goes here
+        for (int64_t id : c->arrival) {
+            Request &r = c->reqs[id];
+            if (r.state == PREFILL_DONE && wants_retire(r)) { release_request(c, r); out->n_finished++; }
+        }
     // 1b. retire requests that produced all their tokens
     out->n_finished += retire_finished(c);
     while (!c->arrival.empty() && c->reqs[c->arrival.front()].state == FINISHED) c->arrival.pop_front();
@@ -1952,45 +1965,62 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
     // the previous call may still write: it is ordered behind that step
     const int prev_end = c->step_end_idx;
 
-    // 5h. hybrid batching: the prompt being chunked (taken up here if none is) gives this step its next chunk,
-    //     which shares the step's batch with the decode rows
-    int n_chunk = 0, chunk_start = 0;
-    Request *chunk_req = nullptr;
+    // 5h. hybrid batching: this step's budget of prompt tokens is filled in arrival order -- the rest of the prompt
+    //     in progress, then the next prompts that have their blocks, the last possibly in part (a part that does not
+    //     end its prompt is whole blocks, so that the next one starts on a block boundary)
+    struct Part { Request *r; int32_t start, n; bool last; };
+    std::vector<Part> parts;
     if (hyb) {
-        if (c->prefill_ids.empty() && next_prefill >= 0) {
-            Request &r = c->reqs[next_prefill];
-            r.n_sampled++;
-            r.chunk_done = 0;
-            set_state(r, PREFILLING);
-            c->prefill_ids.assign(1, next_prefill);
-            c->hyb_last = false;
-            out->prefill_started_req = next_prefill;
-            out->prefill_started_tokens = r.n_prefill;
-            out->prefill_started_count = 1;
-        }
-        if (!c->prefill_ids.empty() && !c->hyb_last) {
-            chunk_req = &c->reqs[c->prefill_ids[0]];
-            chunk_start = chunk_req->chunk_done;
-            n_chunk = std::min(c->hybrid_chunk, chunk_req->n_prefill - chunk_start);
-            out->chunk_req = chunk_req->id;
-            out->chunk_start = chunk_start;
-            out->chunk_tokens = n_chunk;
+        int budget = c->hybrid_chunk;
+        while (budget > 0 && (int)parts.size() < RS_MAX_PREFILL_REQS) {
+            Request *r = nullptr;
+            const bool fresh = c->hyb_cur < 0;
+            if (!fresh) r = &c->reqs[c->hyb_cur];
+            else
+                for (int64_t id : c->arrival)
+                    if (c->reqs[id].state == PREFILL_READY) { r = &c->reqs[id]; break; }
+            if (!r) break;
+            const int32_t done = fresh ? 0 : r->chunk_done, rest = r->n_prefill - done;
+            int32_t n = std::min(budget, rest);
+            if (n < rest) n -= n % RS_KV_BLOCK;
+            if (n == 0) break;
+            if (fresh) {   // taken up with its first part
+                r->n_sampled++;
+                set_state(*r, PREFILLING);
+                c->hyb_cur = r->id;
+                if (out->prefill_started_req < 0) out->prefill_started_req = r->id;
+                out->prefill_started_tokens += r->n_prefill;
+                out->prefill_started_count++;
+            }
+            parts.push_back(Part{r, done, n, done + n == r->n_prefill});
+            r->chunk_done = done + n;
+            budget -= n;
+            if (parts.back().last) c->hyb_cur = -1;
         }
     }
-    const bool last_chunk = n_chunk > 0 && chunk_start + n_chunk == chunk_req->n_prefill;
+    c->last_parts.clear();
+    int n_chunk = 0, F = 0;   // prompt rows of this step's batch; prompts that end in it
+    for (const Part &pt : parts) {
+        c->last_parts.push_back(rs_ctx::HybPart{pt.r->id, pt.start, pt.n});
+        n_chunk += pt.n;
+        F += pt.last;
+    }
+    out->n_chunks = (int32_t)parts.size();
+    out->chunk_tokens = n_chunk;
 
     // 5. one decode step over the running batch (hybrid batching: and the chunk, in one batch)
     c->last_batch.assign(c->running.begin(), c->running.end());
     if (B > 0 || n_chunk > 0) {
         int max_ctx = 1;
         for (int64_t id : c->running) max_ctx = std::max(max_ctx, c->reqs[id].ctx_len + 1);
-        const int flip = B > 0 ? (c->stage_flip ^= 1) : c->stage_flip;
-        if (B > 0 && token_mode && c->pending[flip]) {   // the staging buffers are about to be rewritten
+        const int nS = B + F;   // rows whose next token this step chooses
+        const int flip = nS > 0 ? (c->stage_flip ^= 1) : c->stage_flip;
+        if (nS > 0 && token_mode && c->pending[flip]) {   // the staging buffers are about to be rewritten
             if (c->gpu) HIP_TRY(hipEventSynchronize(c->sampled_ev[flip]));
             harvest(c, flip);
         }
         if (c->gpu) {
-            if (B > 0) HIP_TRY(hipEventSynchronize(c->staged[flip]));
+            if (nS > 0) HIP_TRY(hipEventSynchronize(c->staged[flip]));
             const int mb = c->max_blk_per_req;
             for (int i = 0; i < B; ++i) {
                 Request &r = c->reqs[c->running[i]];
@@ -2008,32 +2038,48 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                     HIP_TRY(hipStreamWaitEvent(st, c->step_end[c->step_end_idx], 0));
                 c->hyb_prev_stream = st;
             }
-            if (B > 0) {
-                HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
-                HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+            {   // the slots of the prompts that end in this step follow the decode rows' (their first tokens are
+                // chosen, copied back and harvested with the decode rows' tokens)
+                int j = B;
+                for (const Part &pt : parts)
+                    if (pt.last) c->h_rowslot[flip][j++] = pt.r->slot;
+            }
+            if (nS > 0) {
+                if (B > 0) {
+                    HIP_TRY(hipMemcpyAsync(c->d_ctx, c->h_ctx[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                    HIP_TRY(hipMemcpyAsync(c->d_tab, c->h_tab[flip], (size_t)B * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                }
                 if (token_mode)
-                    HIP_TRY(hipMemcpyAsync(c->d_rowslot, c->h_rowslot[flip], B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                    HIP_TRY(hipMemcpyAsync(c->d_rowslot, c->h_rowslot[flip], nS * sizeof(int32_t), hipMemcpyHostToDevice, st));
                 HIP_TRY(hipEventRecord(c->staged[flip], st));
             }
-            if (n_chunk > 0) {   // the chunked prompt's block table and slot
+            int32_t pcu[RS_MAX_PREFILL_REQS + 1] = {0}, pstart[RS_MAX_PREFILL_REQS] = {0};
+            if (n_chunk > 0) {   // block tables and slots of the prompts with a part in this step
                 HIP_TRY(hipEventSynchronize(c->pstaged));
-                const std::vector<int32_t> &ids = c->owned[chunk_req->id];
-                for (int j = 0; j < mb; ++j) c->h_ptab[j] = j < (int)ids.size() ? ids[j] : -1;
-                c->h_pslots[0] = chunk_req->slot;
-                HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, (size_t)mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
-                HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, sizeof(int32_t), hipMemcpyHostToDevice, st));
+                for (size_t q = 0; q < parts.size(); ++q) {
+                    const std::vector<int32_t> &ids = c->owned[parts[q].r->id];
+                    for (int j = 0; j < mb; ++j) c->h_ptab[q * mb + j] = j < (int)ids.size() ? ids[j] : -1;
+                    c->h_pslots[q] = parts[q].r->slot;
+                    pcu[q + 1] = pcu[q] + parts[q].n;
+                    pstart[q] = parts[q].start;
+                }
+                HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, parts.size() * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
+                HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, parts.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
                 HIP_TRY(hipEventRecord(c->pstaged, st));
             }
             if (in->wait_decode) { int32_t rc = rs_mark(c, sd, RS_MAX_MARKS - 2); if (rc) return rc; }
             Workspace &w = c->ws[sd];
             // the step's kernels: embedding (token mode), every layer, head (token mode)
             auto enqueue_kernels = [&](int ctx_bound) -> int32_t {
-                if (n_chunk > 0) {   // hybrid batch: rows [0, n_chunk) the chunk, rows [n_chunk, n_chunk + B) the decode rows
-                    const int dm = c->m.d_model;
-                    SeqInfo seq{};
-                    seq.n_req = 1;
-                    seq.cu[1] = n_chunk;
-                    seq.start[0] = chunk_start;
+                if (n_chunk > 0) {   // hybrid batch: rows [0, n_chunk) the prompt parts, rows [n_chunk, n_chunk + B) the decode rows
+                    const int dm = c->m.d_model, np = (int)parts.size();
+                    SeqInfo seq{}, fin{};
+                    seq.n_req = np;
+                    for (int q = 0; q < np; ++q) {
+                        seq.cu[q + 1] = pcu[q + 1];
+                        seq.start[q] = pstart[q];
+                        if (parts[q].last) fin.cu[++fin.n_req] = pcu[q + 1];   // the last row of a prompt that ends here
+                    }
                     EmbedArgs ea{c->d_prompts, nullptr, (const bf16_t *)c->head.embed, w.xbuf, c->err_flag + sd, n_chunk, dm, c->head.vocab};
                     ea.slots = c->d_pslots;
                     ea.slot_stride = c->lim.max_context;
@@ -2041,18 +2087,19 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                     launch_embed(st, ea);
                     launch_embed(st, EmbedArgs{c->d_tok, c->d_rowslot, (const bf16_t *)c->head.embed, w.xbuf + (size_t)n_chunk * dm,
                                                c->err_flag + sd, B, dm, c->head.vocab});
-                    const int32_t cu[2] = {0, n_chunk};
                     for (int l = 0; l < c->m.n_layers; ++l) {
                         if (!c->have_weights[l]) return fail(RS_ERR_STATE, "weights of layer %d not set", l);
-                        int32_t rc = hybrid_layer(c, l, w.xbuf, w.xbuf, cu, &chunk_start, 1, c->d_ptab, mb, c->d_ctx, c->d_tab, mb, B, ctx_bound);
+                        int32_t rc = hybrid_layer(c, l, w.xbuf, w.xbuf, pcu, pstart, np, c->d_ptab, mb, c->d_ctx, c->d_tab, mb, B, ctx_bound);
                         if (rc) return rc;
                     }
-                    if (last_chunk) {   // the prompt's first token, from the chunk's last row (x1 is free after the layers)
-                        launch_gather_last_rows(st, w.xbuf, w.x1, dm, seq);
-                        int32_t rc = head_greedy(c, sd, w.x1, 1, nullptr, c->d_pfirst, c->d_pslots, c->d_tok);
+                    if (B > 0) {
+                        int32_t rc = head_greedy(c, sd, w.xbuf + (size_t)n_chunk * dm, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
                         if (rc) return rc;
                     }
-                    if (B > 0) return head_greedy(c, sd, w.xbuf + (size_t)n_chunk * dm, B, nullptr, c->d_sampled, c->d_rowslot, c->d_tok);
+                    if (F > 0) {   // first tokens of the prompts that end here (x1 is free after the layers)
+                        launch_gather_last_rows(st, w.xbuf, w.x1, dm, fin);
+                        return head_greedy(c, sd, w.x1, F, nullptr, c->d_sampled + B, c->d_rowslot + B, c->d_tok);
+                    }
                     return RS_OK;
                 }
                 const void *x_first = in->decode_hidden;
@@ -2113,15 +2160,10 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 c->steps_enqueued++;
                 c->step_enqueue_ns += std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t_enq).count();
             }
-            if (token_mode && B > 0) {
-                HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            if (token_mode && nS > 0) {
+                HIP_TRY(hipMemcpyAsync(c->h_sampled[flip], c->d_sampled, nS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipMemcpyAsync(&c->h_err[2 + flip], c->err_flag + sd, sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 HIP_TRY(hipEventRecord(c->sampled_ev[flip], st));
-            }
-            if (last_chunk) {   // what the end of a whole-prompt pass records
-                HIP_TRY(hipMemcpyAsync(c->h_pfirst, c->d_pfirst, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-                HIP_TRY(hipMemcpyAsync(&c->h_err[4], c->err_flag + RS_SIDE_PREFILL, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-                HIP_TRY(hipEventRecord(c->prefill_ev, st));
             }
             c->step_end_idx ^= 1;
             HIP_TRY(hipEventRecord(c->step_end[c->step_end_idx], st));
@@ -2133,16 +2175,12 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 if (rc) return rc;
             }
         }
-        if (token_mode && B > 0) {
+        if (token_mode && nS > 0) {
             c->inflight[flip].assign(c->running.begin(), c->running.end());
+            c->inflight_nb[flip] = B;
+            for (const Part &pt : parts)
+                if (pt.last) c->inflight[flip].push_back(pt.r->id);
             c->pending[flip] = true;
-        }
-        if (n_chunk > 0) {
-            chunk_req->chunk_done += n_chunk;
-            if (last_chunk) {
-                c->hyb_last = true;
-                if (!c->gpu) c->prefill_host_done = true;   // host-only: seen at the next step
-            }
         }
         for (int64_t id : c->running) {
             Request &r = c->reqs[id];
@@ -2150,7 +2188,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
             r.generated++;
             r.n_sampled++;
         }
-        if (token_mode && in->wait_decode && B > 0) {
+        if (token_mode && in->wait_decode && nS > 0) {
             int32_t rc = harvest_ready(c, true);
             if (rc) return rc;
         }
@@ -2413,8 +2451,22 @@ int32_t rs_set_hybrid_batching(rs_ctx *c, int32_t chunk_tokens) {
         return fail(RS_ERR_BAD_ARG, "a chunk of %d tokens and %d decode rows exceed max_prefill_tokens %d", chunk_tokens,
                     c->lim.max_decode_batch, c->lim.max_prefill_tokens);
     c->hybrid_chunk = chunk_tokens;
-    c->hyb_last = false;
+    c->hyb_cur = -1;
     c->hyb_prev_stream = nullptr;
+    c->last_parts.clear();
+    return RS_OK;
+}
+
+int32_t rs_step_chunks(rs_ctx *c, int64_t *req_ids_out, int32_t *starts_out, int32_t *lens_out, int32_t cap, int32_t *n_out) {
+    if (!c || !n_out) return fail(RS_ERR_BAD_ARG, "null argument");
+    const int n = (int)c->last_parts.size();
+    *n_out = n;
+    if (n > cap) return fail(RS_ERR_BAD_ARG, "%d parts, room for %d", n, cap);
+    for (int i = 0; i < n; ++i) {
+        if (req_ids_out) req_ids_out[i] = c->last_parts[i].id;
+        if (starts_out) starts_out[i] = c->last_parts[i].start;
+        if (lens_out) lens_out[i] = c->last_parts[i].n;
+    }
     return RS_OK;
 }
 

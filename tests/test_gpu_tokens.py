@@ -257,7 +257,7 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
     assert results[True] == results[False]
 
 
-@pytest.mark.parametrize("n_blocks,chunk", [(64, 16), (64, 48), (7, 16)])
+@pytest.mark.parametrize("n_blocks,chunk", [(64, 16), (64, 48), (64, 96), (7, 16)])
 def test_closed_loop_hybrid_batching_matches_oracle(n_blocks, chunk):
     """The comparison scheme (section 3.1) as a serving policy: prompts go through in chunks that share each
     step's batch with the decode rows.  The tokens are checked against the oracle exactly like the other policy's
@@ -274,7 +274,7 @@ def test_closed_loop_hybrid_batching_matches_oracle(n_blocks, chunk):
         hd = {k: to_dev(v) for k, v in hb.items()}
         rig.ctx.set_head(hd["embed"], hd["final_norm"], hd["lm_head"], vocab, -1)
         rig.ctx.set_hybrid_batching(chunk)
-        chunks, mixed = [], 0
+        chunks, mixed, several = [], 0, 0
         todo = sorted(requests, key=lambda r: r[3])
         n_pre = n_done = step = 0
         while n_done < len(requests) and step < 4000:
@@ -285,8 +285,11 @@ def test_closed_loop_hybrid_batching_matches_oracle(n_blocks, chunk):
             n_pre += so.n_preempted
             n_done += so.n_finished
             step += 1
-            if so.chunk_req >= 0:
-                chunks.append((so.chunk_req, so.chunk_start, so.chunk_tokens))
+            if so.n_chunks > 0:
+                parts = rig.ctx.step_chunks()
+                assert len(parts) == so.n_chunks and sum(n for _, _, n in parts) == so.chunk_tokens <= chunk
+                several += len(parts) > 1
+                chunks += parts
                 mixed += so.decode_batch > 0
                 assert (so.prefill_cus, so.decode_cus) == (256, 256)
             if so.decode_batch == 0:
@@ -302,17 +305,18 @@ def test_closed_loop_hybrid_batching_matches_oracle(n_blocks, chunk):
             assert fin
             outs[rid] = toks.tolist()
         frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, -1, requests, outs)
-        print(f"  chunk {chunk}: {len(chunks)} chunks, {mixed} of them beside decode rows, {n_pre} preemption(s); "
+        print(f"  budget {chunk}: {len(chunks)} parts, {mixed} steps with parts beside decode rows, {several} with several prompts, {n_pre} preemption(s); "
               f"{frac:.2%} of generated tokens equal the oracle's choice", flush=True)
         assert frac >= 0.9 and rig.ctx.kv_num_free() == n_blocks
-        # every prompt went through as chunks of the set size, in order; some chunk shared a batch with decode rows
-        assert all(n == chunk or st + n >= 5 for _, st, n in chunks) and all(st % 16 == 0 for _, st, _ in chunks)
-        first = {}
-        for rid, st, n in chunks:
-            if st == 0 and rid not in first:
-                first[rid] = True
-        assert set(first) == {r[0] for r in requests}
-        assert mixed >= 1
+        # every prompt went through in parts that start on block boundaries; some part shared a batch with decode
+        # rows; with the larger budget some step carried parts of several prompts
+        assert all(st % 16 == 0 for _, st, _ in chunks)
+        assert {rid for rid, st, _ in chunks if st == 0} == {r[0] for r in requests}
+        plen = {r[0]: len(r[1]) for r in requests}
+        if n_pre == 0:
+            for rid in plen:
+                assert sum(n for r2, _, n in chunks if r2 == rid) == plen[rid]
+        assert mixed >= 1 and (chunk < 96 or several >= 1)
         if n_blocks < 64:
             assert n_pre >= 1
     finally:

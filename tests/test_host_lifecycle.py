@@ -250,11 +250,11 @@ def test_library_life_cycle_matches_oracle(n_blocks, seed, budget):
     assert c.kv_num_free() == n_blocks
 
 
-@pytest.mark.skip(reason="the oracle's hybrid policy now fills a token budget across prompts; the library side follows")
-@pytest.mark.parametrize("n_blocks,seed,chunk", [(1000, 21, 16), (1000, 22, 32), (12, 23, 16), (8, 24, 48), (7, 25, 16), (9, 26, 32)])
+@pytest.mark.parametrize("n_blocks,seed,chunk", [(1000, 21, 16), (1000, 22, 32), (1000, 27, 96), (1000, 28, 160), (12, 23, 16), (8, 24, 48),
+                                                 (7, 25, 16), (9, 26, 32), (10, 29, 96)])
 def test_library_hybrid_batching_matches_oracle(n_blocks, seed, chunk):
     """The library's state machine with hybrid batching on (host-only context, tokens injected) against the
-    oracle's hybrid policy, step by step: every counter, the batch, and the chunk each step takes."""
+    oracle's hybrid policy, step by step: every counter, the batch, and the prompt parts each step takes."""
     reqs, delays = _trace(seed)
     lc = Lifecycle(n_blocks, max_batch=4, eos=EOS, hybrid_chunk=chunk)
     ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lambda rid: None, reqs, delays)
@@ -270,13 +270,14 @@ def test_library_hybrid_batching_matches_oracle(n_blocks, seed, chunk):
         so = c.step_tokens()
         o = {k: getattr(so, k) for k in KEYS}
         o["batch_ids"] = c.decode_batch_ids()
-        o["chunk"] = (so.chunk_req, so.chunk_start, so.chunk_tokens) if so.chunk_req >= 0 else None
+        o["chunks"] = c.step_chunks()
+        assert so.n_chunks == len(o["chunks"]) and so.chunk_tokens == sum(n for _, _, n in o["chunks"])
         return o
 
     got = _drive(submit, step, lambda rid: None, reqs, delays)
     assert len(got) == len(ref)
     for i, (a, b) in enumerate(zip(got, ref)):
-        for k in KEYS + ("batch_ids", "chunk"):
+        for k in KEYS + ("batch_ids", "chunks"):
             assert a[k] == b[k], f"step {i}: {k}: library {a[k]} oracle {b[k]}"
     for rid, pl, mn, script, _ in reqs:
         toks, fin = c.request_output(rid)
@@ -284,6 +285,8 @@ def test_library_hybrid_batching_matches_oracle(n_blocks, seed, chunk):
     assert c.kv_num_free() == n_blocks
     if n_blocks < 1000:
         assert sum(o["n_preempted"] for o in got) > 0
+    if chunk >= 96:
+        assert any(len(o["chunks"]) > 1 for o in got), "no step batched parts of several prompts"
 
 
 def test_library_hybrid_batching_argument_checks():
