@@ -394,7 +394,9 @@ def main():
                    "prefill_cus": head["prefill_cus"], "decode_cus": head["decode_cus"]},
         # the four targets at the headline split, each with what it is measured against
         "targets": {
-            "itl_corun_vs_alone_256": {"value": head["itl_vs_alone_256"], "target": "<= 1.2"},
+            "itl_corun_vs_alone_256": {"value": head["itl_vs_alone_256"], "target": "<= 1.2",
+                                       # the other reading of "decode-alone": alone on the same partition (interference only)
+                                       "vs_alone_on_the_same_partition": head["itl_vs_alone_same_mask"]},
             "combined_vs_sequential": {"value": head["combined_norm_throughput"] / seq_norm, "target": ">= 1.5"},
             "prefill_frac_mfma_peak_of_share_corun": {"value": head["prefill_frac_mfma_of_share"], "target": ">= 0.60",
                                                       "of_measured_mfma_probe_on_partition": head["prefill_frac_of_partition_mfma_probe"]},
