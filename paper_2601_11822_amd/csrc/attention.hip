@@ -304,6 +304,18 @@ void launch_decode_attention(hipStream_t st, const DecodeAttnArgs &a) {
 // the 16 lanes of a fragment read are then 16 consecutive 16-byte chunks (no bank conflicts, no swizzle), every
 // read address is a per-lane base plus a constant, and a whole tile comes in by LDS-DMA (global -> LDS, no
 // staging registers, no LDS stores).
+//
+// What bounds it on long prompts: every wave reads the whole 32 KB K/V tile from LDS for its 32 queries, one
+// kilobyte of LDS reads per MFMA, which with four matrix cores per CU is the LDS's whole bandwidth (128 bytes
+// per cycle); and per score there are about as many vector cycles (scale, exponential at quarter rate, sum,
+// maximum, conversion) as matrix cycles.  Two workgroups per CU (two waves per SIMD) overlap the two kinds of
+// work as far as the LDS allows.  Measured alternative, dropped: two 32-query strips per wave (each K and V
+// fragment feeds two MFMAs: half the LDS reads), which needs both strips' accumulators (128 registers) and so
+// leaves one wave per SIMD; bit-identical results, but 1.4-1.8x SLOWER at every size (16384 tokens: 3.48
+// against 2.44 ms on the whole chip) although strip 1's exponentials were placed under strip 0's P V MFMAs:
+// with a single wave per SIMD every dependent chain of the softmax (running maximum, half-wave exchanges, the
+// rescale decision) is exposed, and what the second wave hides here for nothing would have to be software
+// pipelined by hand across key tiles.
 // =============================================================================================
 template <int HD>
 __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillAttnArgs a) {
