@@ -153,6 +153,44 @@ def test_8b_hybrid_batch_chunk_512_after_1024_with_32_decode_rows_sampled():
         rig.close()
 
 
+def test_chunk_behind_32800_cached_tokens_reads_block_ids_past_the_kernels_lds_table_mid_shape():
+    """A late chunk of a very long prompt: its rows attend to 32800 cached positions, more than the 2048 block ids
+    the prefill attention kernel keeps in LDS, so the last key tiles (and the chunk's own blocks) take their ids
+    from the table in memory; a ragged chunk length exercises the checked tile path at the end.  Cache written
+    directly (same bits on both sides), every chunk row against the oracle."""
+    shape = S.MID
+    prior, T, B = 32800, 200, 3
+    ctx = np.array([40, 700, 16], np.int32)
+    counts = [prior + T] + [int(c) + 1 for c in ctx]
+    n_blocks = sum(S.blocks_for(c) for c in counts) + 8
+    tabs = S.shuffled_block_tables(counts, n_blocks, max_blk=S.blocks_for(max(counts)))
+    ptab, dtab = tabs[:1], tabs[1:]
+    rig = Rig(shape, n_blocks, T + B, B, prior + T, max_pos=prior + T)
+    try:
+        L = rig.olayers[0]
+        kb, vb = S.kv_cache_bits(n_blocks, shape.n_kv_heads, shape.head_dim)
+        rig.load_pools_from_logical(kb, vb)
+        Kc, Vc = f32(kb), f32(vb)
+        xb = S.hidden_states(T + B, shape.d_model, stream=80)
+        x = f32(xb)
+        y_bits = rig.hybrid(xb, [0, T], [prior], ptab, ctx, dtab)
+        y_ref = L.prefill_chunk(x[:T], [0, T], [prior], ptab, Kc, Vc)
+        check_tensor("late chunk, all rows", f32(y_bits)[:T], y_ref, x[:T], 2, elem_mult=END_TO_END)
+        y_dec = L.decode(x[T:], ctx, dtab, Kc, Vc)
+        check_tensor("decode rows beside it", f32(y_bits)[T:], y_dec, x[T:], 2, elem_mult=END_TO_END)
+        kg, vg = rig.k_bits_logical(), rig.v_bits_logical()
+        changed = (kg != kb).any(axis=(2, 3)) | (vg != vb).any(axis=(2, 3))
+        want = np.zeros_like(changed)
+        pos = np.arange(prior, prior + T)
+        want[ptab[0, pos // 16], pos % 16] = True
+        for i, c in enumerate(ctx):
+            want[dtab[i, c // 16], c % 16] = True
+        assert np.array_equal(changed, want)
+        assert rel_err(f32(kg)[want], Kc[want]) <= TOL and rel_err(f32(vg)[want], Vc[want]) <= TOL
+    finally:
+        rig.close()
+
+
 def test_hybrid_layer_rejects_unaligned_chunk_start_and_oversized_batches():
     shape = S.TINY
     rig = Rig(shape, 8, 64, 2, 128, with_oracle=False)
