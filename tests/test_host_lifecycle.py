@@ -289,6 +289,47 @@ def test_library_hybrid_batching_matches_oracle(n_blocks, seed, chunk):
         assert any(len(o["chunks"]) > 1 for o in got), "no step batched parts of several prompts"
 
 
+@pytest.mark.parametrize("seed", range(300, 330))
+def test_library_hybrid_batching_matches_oracle_random_pools(seed):
+    """Thirty more traces with pool size, batch cap, budget and request count drawn from the seed."""
+    g = np.random.default_rng(seed)
+    n_blocks = int(g.integers(6, 40))
+    max_batch = int(g.integers(1, 7))
+    chunk = int(g.choice([16, 32, 48, 64, 96, 160]))
+    reqs, delays = _trace(seed, n_req=int(g.integers(3, 25)), max_prompt=60, max_new=30)
+    lc = Lifecycle(n_blocks, max_batch=max_batch, eos=EOS, hybrid_chunk=chunk)
+    try:
+        ref = _drive(lambda rid, pl, mn, sc: lc.submit(rid, pl, mn, sc), lc.step, lambda rid: None, reqs, delays)
+    except NoBlocks:
+        pytest.skip("the drawn pool cannot hold one of the drawn requests")
+    c = rs.Context.from_shape(S.TINY, max_pos=8192, n_blocks=n_blocks, max_prefill_tokens=4096, max_decode_batch=max_batch,
+                              max_context=4096, device=rs.RS_HOST_ONLY)
+    c.set_head(None, None, None, vocab=64, eos_token=EOS)
+    c.set_hybrid_batching(chunk)
+
+    def submit(rid, pl, mn, script):
+        c.submit_tokens(rid, np.zeros(pl, np.int32), mn)
+        for t in script:
+            c.debug_push_sampled(rid, t)
+
+    def step():
+        so = c.step_tokens()
+        o = {k: getattr(so, k) for k in KEYS}
+        o["batch_ids"] = c.decode_batch_ids()
+        o["chunks"] = c.step_chunks()
+        return o
+
+    got = _drive(submit, step, lambda rid: None, reqs, delays)
+    assert len(got) == len(ref)
+    for i, (a, b) in enumerate(zip(got, ref)):
+        for k in KEYS + ("batch_ids", "chunks"):
+            assert a[k] == b[k], f"step {i}: {k}: library {a[k]} oracle {b[k]}"
+    for rid, pl, mn, script, _ in reqs:
+        toks, fin = c.request_output(rid)
+        assert fin and toks.tolist() == lc.reqs[rid].out == _expected_output(script, mn, EOS)
+    assert c.kv_num_free() == n_blocks
+
+
 def test_library_hybrid_batching_argument_checks():
     c = _host_ctx(64, 4, EOS, max_prefill=100)
     for bad in (-16, 8, 24):
