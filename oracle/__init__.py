@@ -52,7 +52,8 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # RS_ORACLE_LIB: a test that plants a mistake in a copy of rs_oracle.c points the pins at that copy
+        _lib = ctypes.CDLL(os.environ.get("RS_ORACLE_LIB") or build())
         _lib.orc_prefill_layer.restype = ctypes.c_int
         _lib.orc_decode_layer.restype = ctypes.c_int
         _lib.orc_prefill_chunk_layer.restype = ctypes.c_int

@@ -1,0 +1,69 @@
+"""Are the oracle's pins strong enough?  Each case plants ONE plausible mistake in a copy of the oracle's C
+source (a wrong sign, a misplaced epsilon, an off-by-one mask, a swapped operand, a dropped term ...), builds
+the copy with the oracle's own compiler line and runs the pin suites against it in a fresh interpreter: at
+least one pin must fail.  The mistakes live on the CPU, in the copy only; nothing here touches the GPU path."""
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rs_oracle.c")
+
+# (name, exact text in rs_oracle.c, what a mistaken author might have written, pin files that must notice)
+MUTANTS = [
+    ("rope: sign of the sine term", "v[i] = a * c - b * s;", "v[i] = a * c + b * s;", ["test_oracle_pins.py"]),
+    ("rope: angle uses hd/2 instead of hd", "-2.0 * (double)i / (double)hd", "-2.0 * (double)i / (double)half", ["test_oracle_pins.py"]),
+    ("rmsnorm: epsilon outside the square root", "1.0f / sqrtf(ss / (float)d + eps)", "1.0f / (sqrtf(ss / (float)d) + eps)", ["test_oracle_pins.py"]),
+    ("rmsnorm: sum instead of mean", "sqrtf(ss / (float)d + eps)", "sqrtf(ss + eps)", ["test_oracle_pins.py"]),
+    ("attention: scale 1/hd", "float scale = 1.0f / sqrtf((float)hd);", "float scale = 1.0f / (float)hd;", ["test_oracle_pins.py"]),
+    ("attention: the own position masked out", "int64_t n_keys = r - start + 1; /* keys j <= own position */",
+     "int64_t n_keys = r - start > 0 ? r - start : 1;", ["test_oracle_pins.py"]),
+    ("attention: weights not normalised", "float w = scratch[j] / den;", "float w = scratch[j];", ["test_oracle_pins.py"]),
+    ("swiglu: gate and up exchanged", "out[i] = silu(g[i]) * u[i];", "out[i] = silu(u[i]) * g[i];", ["test_oracle_pins.py"]),
+    ("silu: sign of the exponent", "return z / (1.0f + expf(-z));", "return z / (1.0f + expf(z));", ["test_oracle_pins.py"]),
+    ("first residual dropped", "x1[i] = x_rows[i] + x1[i];", "x1[i] = x1[i];", ["test_oracle_pins.py"]),
+    ("second residual takes x instead of x1", "y_rows[i] = x1[i] + y_rows[i];", "y_rows[i] = x_rows[i] + y_rows[i];", ["test_oracle_pins.py"]),
+    ("second norm uses the first gain", "orc_rmsnorm(x1, L->g2, n, d, L->eps, h2);", "orc_rmsnorm(x1, L->g1, n, d, L->eps, h2);", ["test_oracle_pins.py"]),
+    ("cache write: slot and block index exchanged", "int64_t bi = pos / block, slot = pos % block;",
+     "int64_t bi = pos % block, slot = pos / block;", ["test_oracle_pins.py"]),
+    ("cache write: V stored from K", "memcpy(Vc + off, v, sizeof(float) * Hkv * hd);", "memcpy(Vc + off, k, sizeof(float) * Hkv * hd);", ["test_oracle_pins.py"]),
+    ("decode: the new token does not attend to itself", "nk[i] = ctx_lens[i] + 1;", "nk[i] = ctx_lens[i] > 0 ? ctx_lens[i] : 1;", ["test_oracle_pins.py"]),
+    ("decode: keys rotated at position + 1", "orc_rope(qkv + qd, ctx_lens, B, Hkv, hd, L->rope_base, nqkv);",
+     "{ int32_t *p1 = (int32_t *)malloc(sizeof(int32_t) * B); for (int64_t i = 0; i < B; ++i) p1[i] = ctx_lens[i] + 1; "
+     "orc_rope(qkv + qd, p1, B, Hkv, hd, L->rope_base, nqkv); free(p1); }", ["test_oracle_pins.py"]),
+    ("prefill attention: query heads interleaved over kv heads instead of grouped", "int64_t hk = hq / G;\n            for (int64_t j = 0; j < n_keys; ++j) {",
+     "int64_t hk = hq % Hkv;\n            for (int64_t j = 0; j < n_keys; ++j) {", ["test_oracle_pins.py"]),
+    ("decode attention: query heads interleaved over kv heads instead of grouped",
+     "int64_t hk = hq / G;\n            int bad = 0;\n            for (int64_t j = 0; j < n; ++j) {\n                int64_t blk = tables[i * max_blk + j / block];",
+     "int64_t hk = hq % Hkv;\n            int bad = 0;\n            for (int64_t j = 0; j < n; ++j) {\n                int64_t blk = tables[i * max_blk + j / block];", ["test_oracle_pins.py"]),
+    ("decode attention: block table of the neighbouring request", "int64_t blk = tables[i * max_blk + j / block];",
+     "int64_t blk = tables[(i > 0 ? i - 1 : 0) * max_blk + j / block];", ["test_oracle_pins.py"]),
+    ("chunk rows: cached keys read from the wrong slot", "int64_t off = ((blk * block + j % block) * Hkv + hk) * hd;\n                kp[j] = Kc + off;",
+     "int64_t off = ((blk * block + (j + 1) % block) * Hkv + hk) * hd;\n                kp[j] = Kc + off;", ["test_oracle_pins.py"]),
+    ("chunk rows: a row does not see its own position", "int64_t n = (int64_t)pos_of_row[r] + 1;\n        const int32_t *tab = tables + (int64_t)req_of_row[r] * max_blk;\n        if (n <= 0 || (n + block - 1) / block > max_blk) { err = 1; continue; }\n        const float **kp = (const float **)malloc(sizeof(float *) * n * 2);",
+     "int64_t n = (int64_t)pos_of_row[r] > 0 ? (int64_t)pos_of_row[r] : 1;\n        const int32_t *tab = tables + (int64_t)req_of_row[r] * max_blk;\n        if (n <= 0 || (n + block - 1) / block > max_blk) { err = 1; continue; }\n        const float **kp = (const float **)malloc(sizeof(float *) * n * 2);", ["test_oracle_pins.py"]),
+]
+
+
+def _occurrences(text, pat):
+    return len(re.findall(re.escape(pat), text))
+
+
+@pytest.mark.parametrize("name,good,bad,pins", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_a_planted_mistake_fails_a_pin(tmp_path, name, good, bad, pins):
+    text = open(SRC).read()
+    good, bad = good.replace("\\n", "\n"), bad.replace("\\n", "\n")
+    assert _occurrences(text, good) >= 1, f"{name}: the oracle no longer contains the text this case edits"
+    mutated = text.replace(good, bad, 1)
+    c = tmp_path / "rs_oracle_mutant.c"
+    so = tmp_path / "librs_oracle_mutant.so"
+    c.write_text(mutated)
+    subprocess.check_call(["gcc", "-O2", "-ftree-vectorize", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(so), str(c), "-lm"])
+    env = dict(os.environ, RS_ORACLE_LIB=str(so))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", "-p", "no:cacheprovider", "-m", "not gpu"]
+                       + [os.path.join(ROOT, "tests", f) for f in pins], cwd=ROOT, env=env, capture_output=True, text=True)
+    assert r.returncode != 0, f"{name}: every pin still passes with this mistake planted\n{r.stdout[-800:]}"
+    assert "failed" in r.stdout or "error" in r.stdout.lower(), r.stdout[-400:]
