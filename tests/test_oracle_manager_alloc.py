@@ -77,6 +77,9 @@ def test_allocator_growth_keeps_prefix_and_failure_changes_nothing():
     a = KVAllocator(4)
     assert a.alloc(1, 16) == [0]
     assert a.alloc(2, 20) == [1, 2]
+    with pytest.raises(NoBlocks):            # one block is free, three more are needed: nothing may be taken
+        a.alloc(2, 80)
+    assert a.n_free() == 1 and a.owned[2] == [1, 2] and a.free == [3]
     assert a.alloc(1, 17) == [0, 3]
     with pytest.raises(NoBlocks):
         a.alloc(2, 49)
