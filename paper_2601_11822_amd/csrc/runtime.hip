@@ -2130,7 +2130,18 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 const auto key = std::make_tuple((int32_t)B, (int32_t)bucket, st);
                 auto it = c->step_graphs.find(key);
                 if (it == c->step_graphs.end()) {
-                    if (c->step_graphs.size() >= 512) drop_step_graphs(c);   // set-up work either way; start over
+                    if (c->step_graphs.size() >= 512) {   // set-up work either way; start over
+                        // a replay of a cached graph may still be running: wait for the streams they were recorded on
+                        std::vector<hipStream_t> seen;
+                        for (auto &kv : c->step_graphs) {
+                            hipStream_t gs = std::get<2>(kv.first);
+                            if (std::find(seen.begin(), seen.end(), gs) == seen.end()) {
+                                seen.push_back(gs);
+                                HIP_TRY(hipStreamSynchronize(gs));
+                            }
+                        }
+                        drop_step_graphs(c);
+                    }
                     hipGraph_t graph = nullptr;
                     hipGraphExec_t exec = nullptr;
                     HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
