@@ -89,8 +89,9 @@ def build_model(shape, n_layers: int, vocab: int, n_blocks: int, max_prefill: in
     return c, keep
 
 
-def serve(c: Context, work, wait_decode: bool, time_limit: float):
-    """Runs the arrival process; returns per-step records and per-request times."""
+def serve(c: Context, work, wait_decode: bool, time_limit: float, max_live: int = 1 << 30):
+    """Runs the arrival process; returns per-step records and per-request times.  Arrivals beyond max_live
+    requests in flight wait on the host (their time to first token counts from their submission)."""
     todo = list(work)
     steps = []
     live = 0
@@ -102,7 +103,7 @@ def serve(c: Context, work, wait_decode: bool, time_limit: float):
         now = time.perf_counter() - t0
         if now > time_limit:
             raise RuntimeError(f"time limit: {n_done} of {len(work)} requests finished in {now:.1f}s")
-        while todo and todo[0][1] <= now:
+        while todo and todo[0][1] <= now and live < max_live:   # the library holds 4 * max_batch + 64 live requests
             rid, _, prompt, n_out = todo.pop(0)
             c.submit_tokens(rid, prompt, n_out)
             live += 1
@@ -133,7 +134,7 @@ def serve(c: Context, work, wait_decode: bool, time_limit: float):
     return steps, wall
 
 
-def serve_engine(c: Context, work, time_limit: float):
+def serve_engine(c: Context, work, time_limit: float, max_live: int = 1 << 30):
     """The same arrival process against the library's own two threads (rs_engine_start)."""
     todo = list(work)
     c.engine_start()
@@ -142,10 +143,10 @@ def serve_engine(c: Context, work, time_limit: float):
     try:
         while True:
             now = time.perf_counter() - t0
-            while todo and todo[0][1] <= now:
+            st = c.engine_stats()
+            while todo and todo[0][1] <= now and len(work) - len(todo) - st["finished"] < max_live:
                 rid, _, prompt, n_out = todo.pop(0)
                 c.submit_tokens(rid, prompt, n_out)
-            st = c.engine_stats()
             if not todo and st["finished"] >= len(work):
                 break
             if now > time_limit:
@@ -292,10 +293,10 @@ def main(argv=None):
         if time.time() - t_settle > 30:
             raise RuntimeError("the settling request did not finish")
     if a.engine:
-        stats, wall = serve_engine(c, work, a.time_limit)
+        stats, wall = serve_engine(c, work, a.time_limit, max_live=4 * a.max_batch + 60)
         rec = summarise_engine(c, work, stats, wall)
     else:
-        steps, wall = serve(c, work, a.wait_decode, a.time_limit)
+        steps, wall = serve(c, work, a.wait_decode, a.time_limit, max_live=4 * a.max_batch + 60)
         rec = summarise(c, work, steps, wall)
     rec.update({"policy": a.policy, "shape": shape.name, "layers": a.layers, "rate_per_s": a.rate, "slo_ms": a.slo_ms,
                 "wait_decode": bool(a.wait_decode), "driver": "engine threads" if a.engine else "host step loop", "max_batch_cap": a.max_batch, "experts": a.experts, "data": "synthetic",
