@@ -483,7 +483,9 @@ int32_t rs_request_output(rs_ctx *ctx, int64_t req_id, int32_t *tokens_out, int3
  * and block tables are read from library buffers that are refreshed before every launch.  The first step of a
  * new key records and instantiates (set-up work: allocates inside the runtime); at most 512 graphs are kept.
  * Results are bit-identical to the uncaptured step.  rs_set_step_graphs(ctx, 0) turns this off (the step's
- * kernels are then launched one by one); not while the engine runs (RS_ERR_STATE).
+ * kernels are then launched one by one), 1 turns it on, a value n > 1 turns it on and keeps at most n graphs
+ * (when a new key arrives at the limit the library waits for the streams the cached graphs were recorded on and
+ * drops them all); not while the engine runs (RS_ERR_STATE).
  * rs_step_graph_stats: stats_out[0] graphs captured so far, [1] steps launched as a graph, [2] decode steps
  * enqueued by the serving loop outside of a capture, [3] host nanoseconds those steps' launches took in total
  * (one graph launch, or the step's kernel launches one by one). */

@@ -422,8 +422,9 @@ class Context:
     def request_release(self, req_id: int):
         _check(self._lib.rs_request_release(self._h, ctypes.c_int64(req_id)))
 
-    def set_step_graphs(self, on: bool):
-        _check(self._lib.rs_set_step_graphs(self._h, ctypes.c_int32(1 if on else 0)))
+    def set_step_graphs(self, on):
+        """False / True, or an int n > 1: on, keeping at most n captured steps."""
+        _check(self._lib.rs_set_step_graphs(self._h, ctypes.c_int32(int(on))))
 
     def step_graph_stats(self):
         """(graphs captured, decode steps launched as a graph, decode steps enqueued outside a capture, host ns of their launches)."""

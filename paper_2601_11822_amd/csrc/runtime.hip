@@ -195,6 +195,7 @@ struct rs_ctx {
     // bucket, masked decode stream); every pointer in them is a library buffer
     std::map<std::tuple<int32_t, int32_t, hipStream_t>, hipGraphExec_t> step_graphs;
     bool step_graphs_on = true;
+    int step_graph_cap = 512;   // captured steps kept; when a new key arrives at the cap all are dropped
     int64_t step_graph_captures = 0, step_graph_launches = 0;
     int64_t steps_enqueued = 0, step_enqueue_ns = 0;   // decode steps of the serving loop and the host time their launches took
     bool capturing = false;      // a decode step is being recorded: no event records on the stream
@@ -1370,6 +1371,7 @@ int32_t rs_set_step_graphs(rs_ctx *c, int32_t on) {
     if (!c) return fail(RS_ERR_BAD_ARG, "null context");
     if (c->engine) return fail(RS_ERR_STATE, "the engine's threads drive this context");
     c->step_graphs_on = on != 0;
+    c->step_graph_cap = on > 1 ? on : 512;
     return RS_OK;
 }
 
@@ -2130,7 +2132,7 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                 const auto key = std::make_tuple((int32_t)B, (int32_t)bucket, st);
                 auto it = c->step_graphs.find(key);
                 if (it == c->step_graphs.end()) {
-                    if (c->step_graphs.size() >= 512) {   // set-up work either way; start over
+                    if ((int)c->step_graphs.size() >= c->step_graph_cap) {   // set-up work either way; start over
                         // a replay of a cached graph may still be running: wait for the streams they were recorded on
                         std::vector<hipStream_t> seen;
                         for (auto &kv : c->step_graphs) {

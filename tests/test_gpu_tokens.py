@@ -233,8 +233,8 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
     requests = [(rid, S.prompt_tokens(pl, vocab, rid), mn, arr) for rid, pl, mn, arr in prompts]
     hb = S.head_weights(shape.d_model, vocab)
     wbits = [S.layer_weights(shape, l) for l in range(n_layers)]
-    results = {}
-    for graphs in (True, False):
+    results, results_captured, results_launched = {}, {}, {}
+    for graphs in (True, 2, False):   # 2: at most two graphs kept, so the cache is dropped and refilled over and over
         rig = Rig(shape, n_blocks=64, max_prefill_tokens=128, max_decode_batch=4, max_context=128, n_layers=n_layers,
                   with_oracle=False)
         try:
@@ -245,7 +245,10 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
             outs, _ = _serve(rig, hb, vocab, -1, requests, wait=False)
             captured, launched, _, _ = rig.ctx.step_graph_stats()
             print(f"  graphs={graphs}: {captured} graphs captured, {launched} steps launched as graphs", flush=True)
-            if graphs:
+            if graphs == 2:
+                assert captured > results_captured[True] and launched == results_launched[True]
+            elif graphs:
+                results_captured[True], results_launched[True] = captured, launched
                 assert captured >= 2 and launched >= 30 and launched > 3 * captured
                 frac = _check_against_oracle(shape, n_layers, hb, wbits, vocab, -1, requests, outs)
                 assert frac >= 0.9
@@ -254,7 +257,7 @@ def test_closed_loop_steps_run_as_captured_graphs_and_match_oracle_and_eager():
             results[graphs] = outs
         finally:
             rig.close()
-    assert results[True] == results[False]
+    assert results[True] == results[False] == results[2]
 
 
 @pytest.mark.parametrize("n_blocks,chunk", [(64, 16), (64, 48), (64, 96), (7, 16)])
