@@ -41,6 +41,10 @@ __global__ __launch_bounds__(256, 2) void dstream_kernel(DGemmArgs a, int kb_per
     // An activation piece is stored 8 steps after its load was issued, right behind a weight fragment that is
     // consumed PD steps after ITS issue: with PD == 8 the two are due together and the in-order wait counts cost
     // nothing; a deeper ring would make every piece wait for weights that are not needed yet (measured: 2x slower).
+    // Taking the pieces out of these waves altogether -- one or two extra waves per workgroup that only stage the
+    // next slab, the four streaming waves with a ring of 16 (128 KB of weights in flight per workgroup) -- gave the
+    // same results and was slower on all 256 CUs (QKV 20.2 -> 23.9 us, gate/up 42.6 -> 50.4, output/down 21.3 -> 22.3)
+    // and no faster beside a prefill pass on 128: depth in flight is not what bounds this stream.
     static_assert(CH % PD == 0, "ring slots are static inside an unrolled chunk");
     static_assert(!PAIR || RT == 2, "a pair is a gate tile and an up tile");
     extern __shared__ __attribute__((aligned(1024))) bf16_t slab[];   // [2][CH][2 row tiles][64 lanes][8]
