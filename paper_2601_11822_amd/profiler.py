@@ -106,7 +106,7 @@ class Rig:
 
 
 def _itl_corun(rig: Rig, steps: int, warmup: int):
-    """(decode step p50 ms, prefill pass ms) with both sides running; one settling run first."""
+    """(decode step p50 ms, prefill pass ms) with both sides running; measured again (at most twice) if a host call stalled inside the timed window."""
     out = None
     for _ in range(3):
         out = timing.run_corun(rig.c, rig.enqueue_prefill, rig.enqueue_decode, steps, warmup)
