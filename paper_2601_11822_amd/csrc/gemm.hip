@@ -372,43 +372,47 @@ __device__ __forceinline__ void gemm_direct_tile(const GemmArgs &a, const int bm
         }
         return;
     }
+    // Output addresses without a branch per store: the 4 columns c0 + 32q + 8j + 4h (c0 a multiple of 32) of row m
+    // sit at row_term(m) + col_term(c0, h) + (2q + j/2) * S16 + (j%2) * S8 in either layout, where a step of 16 columns
+    // is S16 = Mt*512 elements in the fragment-packed layout and 16 row-major, a step of 8 columns 256 or 8.
+    const bool packed = a.out_packed;
+    const size_t S16 = packed ? (size_t)packed_mt(a.M) * 512 : 16;
+    const int S8 = packed ? 256 : 8;
+    const int c0 = EPI == EPI_SWIGLU ? nb * (BN / 2) + wn * (TN / 2) * 32 : nb * BN + wn * WN;
+    constexpr int NQ = EPI == EPI_SWIGLU ? TN / 2 : TN;
+    const size_t col_term = (packed ? (size_t)(c0 >> 4) * S16 : (size_t)c0) + 4 * h;
+    const bool whole = c0 + 32 * NQ <= N;     // wave-uniform: no column of this wave's tile is past the edge
+    auto rows = [&](auto checked) {
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int m = bm + wm * WM + 32 * tm + c32;
-        if (m >= M) continue;
-        if (EPI == EPI_SWIGLU) {
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = bm + wm * WM + 32 * tm + c32;
+            if (m >= M) continue;
+            bf16_t *dst = a.out + (packed ? (size_t)(m >> 5) * 512 + (size_t)(m & 31) * 8 : (size_t)m * N) + col_term;
+            const bf16_t *res = EPI == EPI_RESIDUAL ? a.resid + (size_t)m * N + c0 + 4 * h : nullptr;
 #pragma unroll
-            for (int p = 0; p < TN / 2; ++p)
+            for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int f = nb * (BN / 2) + (wn * (TN / 2) + p) * 32 + 8 * j + 4 * h;
-                    if (f >= N) continue;
+                    if (decltype(checked)::value && c0 + 32 * q + 8 * j + 4 * h >= N) continue;
                     bf16x4 v;
+                    if (EPI == EPI_SWIGLU) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        v[i] = (bf16_t)(silu_f(acc[2 * p][tm][4 * j + i]) * acc[2 * p + 1][tm][4 * j + i]);
-                    store_out4(a, m, f, v);
-                }
-        } else {
+                        for (int i = 0; i < 4; ++i)
+                            v[i] = (bf16_t)(silu_f(acc[2 * q][tm][4 * j + i]) * acc[2 * q + 1][tm][4 * j + i]);
+                    } else if (EPI == EPI_RESIDUAL) {
+                        const bf16x4 r = *(const bf16x4 *)(res + 32 * q + 8 * j);
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n = nb * BN + wn * WN + 32 * tn + 8 * j + 4 * h;
-                    if (n >= N) continue;
-                    bf16x4 v;
-                    if (EPI == EPI_RESIDUAL) {
-                        const bf16x4 r = *(const bf16x4 *)(a.resid + (size_t)m * N + n);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(acc[tn][tm][4 * j + i] + (float)r[i]);
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)(acc[q][tm][4 * j + i] + (float)r[i]);
                     } else {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[tn][tm][4 * j + i];
+                        for (int i = 0; i < 4; ++i) v[i] = (bf16_t)acc[q][tm][4 * j + i];
                     }
-                    store_out4(a, m, n, v);
+                    *(bf16x4 *)(dst + (size_t)(2 * q + (j >> 1)) * S16 + (j & 1) * S8) = v;
                 }
         }
-    }
+    };
+    if (whole) rows(std::false_type{});
+    else rows(std::true_type{});
 }
 
 // Order of the output tiles: super columns of four column tiles, inside one the row tiles four at a time, a
