@@ -233,3 +233,19 @@ def test_bench_refuses_more_than_one_gpu():
     p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert p.returncode != 0
     assert "ONE GPU" in (p.stderr + p.stdout)
+
+
+def test_bench_traffic_constants_are_the_profile_totals():
+    """The `traffic` fields of the bench line are stored counter totals: they must be the ones the committed
+    counter summary ends with, so that the two cannot drift apart when the profile is taken again."""
+    import importlib.util
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "profiles", "hbm_traffic_alone_256cu_llama8b_layer.md")).read()
+    m = re.search(r"`roofline\.traffic` = (\d+) and `roofline_decode\.traffic` = (\d+) bytes", text)
+    assert m, "the summary no longer states the two totals"
+    spec = importlib.util.spec_from_file_location("bench_for_constants", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    assert int(bench.TRAFFIC_BYTES["gateup"]) == int(m.group(1))
+    assert int(bench.TRAFFIC_BYTES["decode_attn"]) == int(m.group(2))
