@@ -75,7 +75,11 @@ MID = LayerShape("mid-gqa", 512, 8, 2, 128, 1376, 1e-5, 500000.0)
 # A wider GQA shape whose GEMMs all take the large-tile path (K multiples of 64, N >= 1024).
 WIDE = LayerShape("wide-gqa", 1024, 8, 2, 128, 2816, 1e-5, 500000.0)
 
-SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA70B, MID, WIDE)}
+# Widths that are multiples of 32 but of no tile width: the large-tile GEMMs end in partly (and wholly) empty
+# column tiles for every projection (1152 = 4.5 x 256, 1920 = 7.5 x 256, 3104 = 24.25 x 128).
+ODD = LayerShape("odd-widths", 1152, 9, 3, 128, 3104, 1e-5, 500000.0)
+
+SHAPES = {s.name: s for s in (TINY, LLAMA8B, LLAMA70B, MID, WIDE, ODD)}
 
 
 def _rng(seed: int, stream: int = 0) -> np.random.Generator:

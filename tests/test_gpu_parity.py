@@ -113,6 +113,16 @@ def test_prefill_mid_gqa_ragged():
     _run_prefill_parity(S.MID, [200, 100, 77])
 
 
+def test_prefill_odd_widths_large_tile_edges():
+    """Every projection's width is a multiple of 32 but of no tile width, and the row counts are ragged against the
+    tile heights: the large-tile kernels' edge path (column checks per store, row-major and packed outputs,
+    residual reads) is what writes the last columns of q/k/v, x1, the SwiGLU output and the layer output.
+    513 rows: few tiles, so the output and down projections go through the K-split kernel and its epilogue;
+    3400 rows: enough tiles that every projection ends in the large-tile kernel's own epilogue."""
+    _run_prefill_parity(S.ODD, [300, 213])
+    _run_prefill_parity(S.ODD, [2000, 1400])
+
+
 def test_prefill_wide_large_tile_path_ragged():
     """d_model 1024: every prefill GEMM takes the large-tile LDS-DMA kernel; 600 rows is ragged
     against both tile heights."""
