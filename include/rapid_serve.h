@@ -250,12 +250,11 @@ int32_t rs_decode_layer_noalloc(rs_ctx *ctx, int32_t layer, const void *x_in, vo
 
 /* ---- CU partitioning (sections 4.2, 4.5.3) -------------------------------------------------
  * Selects the masks for SUBSEQUENT enqueues.  Each count is 0 or a multiple of
- * RS_CU_GRANULE up to 256.  prefill+decode <= 256 gives disjoint masks.  Mask bit b is unit
- * b/8 of XCD b%8, and unit j of an XCD sits in shader engine j%4; each side keeps the same
- * units in all 8 XCDs and equally many units in every shader engine it uses: whole engines
- * when its count is a multiple of 64 (prefill from engine 0 upward, decode from engine 3
- * downward), else a contiguous range of bits (prefill from bit 0 upward, decode from bit 255
- * downward: the same number of units in all four engines).  (256,256) is over-allocation: both sides see every
+ * RS_CU_GRANULE up to 256.  prefill+decode <= 256 gives disjoint masks: prefill takes mask
+ * bits from 0 upward, decode from 255 downward.  Mask bit b is unit b/8 of XCD b%8, and unit j
+ * of an XCD sits in shader engine j%4, so each side keeps the same units in all 8 XCDs and
+ * equally many in each of the four shader engines, and a side's masks are nested (a smaller
+ * count is a subset of a larger one).  (256,256) is over-allocation: both sides see every
  * CU.  Any other overlapping pair is RS_ERR_BAD_SPLIT.  A side with 0 CUs refuses work
  * (RS_ERR_STATE).  Work already enqueued keeps the mask it was enqueued with; later work of
  * the same side is ordered after it. */

@@ -289,31 +289,19 @@ struct rs_ctx {
 namespace {
 
 // Mask bit b is compute unit j = b/8 of XCD b%8, and inside an XCD unit j sits in shader engine j%4 (both read
-// back from the hardware-id registers by rs_debug_cu_histogram).  A side takes the same units in every XCD, and
-// the same number of units in every shader engine it uses: workgroups are dealt to the engines in turn whatever
-// the number of enabled units behind each, so an uneven share makes the thinnest engine the pace of the launch
-// (measured: 2x).
-//   * counts that are multiples of 64 (8 units per XCD = one engine's worth): whole shader engines, prefill from
-//     engine 0 upward, decode from engine 3 downward.  Against a contiguous range of bits (both sides in all four
-//     engines) the decode step is 2.6 % faster alone and 1.9 % faster beside a prefill pass at 128/128 (6 % at
-//     192/64), the prefill pass 0.8-2.3 % slower beside decode, and their combined throughput 0.5-2 % higher.
-//   * other counts (32 mod 64): a contiguous range of bits, prefill from bit 0 upward and decode from bit 255
-//     downward, which gives each side the same number of units in all four engines.
+// back from the hardware-id registers by rs_debug_cu_histogram).  Prefill takes the bits [0, p) and decode the bits
+// [256 - d, 256).  That gives each side the same units in every XCD and the same number of units in each of the four
+// shader engines (workgroups are dealt to the engines in turn whatever the number of enabled units behind each: an
+// uneven share measured 2x slower), and it makes the masks of a side NESTED: a smaller count is a subset of a larger
+// one.  Nesting is what keeps a change of split harmless while a prefill pass is still running under the previous
+// mask: a decode side that shrinks never lands on units the old pass still occupies.
+// Measured and dropped: whole shader engines per side where the counts allow (multiples of 64).  At a fixed split it
+// is better for decode (128/128: step 2.6 % faster alone, 1.9 % beside prefill; 192/64: 6 %) at 0.8-2.3 % of the
+// prefill rate, but no order of the units is both nested and balanced at the other multiples of 32, and with two
+// layouts a move from 128/128 to 160/96 put half of decode's units under the prefill pass still in flight: decode
+// steps of 40 ms instead of 10 for the length of that pass, every time the manager moved the split under load.
 void mask_for(int side, int cus, uint32_t out[8]) {
     for (int i = 0; i < 8; ++i) out[i] = 0;
-    const int per_xcd = cus / 8;
-    if (per_xcd % 8 == 0) {
-        const int n_se = per_xcd / 8;
-        for (int j = 0; j < 32; ++j) {
-            const int se = j & 3;
-            if (side == RS_SIDE_PREFILL ? se >= n_se : se < 4 - n_se) continue;
-            for (int x = 0; x < 8; ++x) {
-                const int bit = j * 8 + x;
-                out[bit >> 5] |= 1u << (bit & 31);
-            }
-        }
-        return;
-    }
     const int lo = side == RS_SIDE_PREFILL ? 0 : RS_TOTAL_CUS - cus;
     for (int b = lo; b < lo + cus; ++b) out[b >> 5] |= 1u << (b & 31);
 }

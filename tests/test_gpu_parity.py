@@ -93,9 +93,6 @@ def test_cu_masks_confine_workgroups():
                     for x in range(8):
                         per_se = [sum(1 for c in s_ if c >> 8 == x and (c >> 5) & 7 == e) for e in range(8)]
                         assert len({k for k in per_se if k}) == 1, f"uneven shader engines {per_se} in XCD {x}"
-                if p % 64 == 0:
-                    # counts that fill whole shader engines: the two sides share none
-                    assert not ({(c >> 5) & 7 for c in cus_p} & {(c >> 5) & 7 for c in cus_d})
         assert len(seen[(256, 256)][0]) == 256
     finally:
         rig.close()

@@ -101,11 +101,13 @@ def test_split_validation():
     assert c.get_cu_split() == (256, 256)
 
 
-def test_masks_are_disjoint_balanced_and_right_sized():
+def test_masks_are_disjoint_balanced_nested_and_right_sized():
     """Section 4.2.  Mask bit b is unit b // 8 of XCD b % 8, and unit j of an XCD sits in shader engine j % 4:
-    a side must hold the same units in every XCD and equally many in every engine it uses (workgroups are dealt
-    to the engines in turn), in whole engines where its count allows."""
+    a side must hold the same units in every XCD and equally many in each of the four engines (workgroups are
+    dealt to the engines in turn), and a side's masks must be nested, so that a side that shrinks while the other
+    side's previous pass is still running never lands on that pass's units."""
     c = host_ctx()
+    prev_p, masks_d = 0, []
     for p in range(0, 257, 32):
         d = 256 - p
         c.set_cu_split(p, d)
@@ -117,16 +119,11 @@ def test_masks_are_disjoint_balanced_and_right_sized():
             units = [sorted(j for j in range(32) if (m >> (8 * j + x)) & 1) for x in range(8)]
             assert all(u == units[0] for u in units) and len(units[0]) == n // 8     # the same units in every XCD
             per_se = [sum(1 for j in units[0] if j % 4 == se) for se in range(4)]
-            used = [k for k in per_se if k]
-            assert len(set(used)) <= 1, f"uneven engines {per_se} at {n} CUs"
-            if n % 64 == 0:
-                assert all(k == 8 for k in used) and len(used) == n // 64            # whole engines
-            else:
-                assert per_se == [n // 32] * 4
-        if p % 64 == 0 and 0 < p < 256:
-            # prefill from engine 0 upward, decode from engine 3 downward
-            assert all(j % 4 < p // 64 for j in range(32) if (mp >> (8 * j)) & 1)
-            assert all(j % 4 >= p // 64 for j in range(32) if (md >> (8 * j)) & 1)
+            assert per_se == [n // 32] * 4, f"uneven engines {per_se} at {n} CUs"
+        assert mp & prev_p == prev_p                       # prefill masks grow by adding units
+        assert all(larger & md == md for larger in masks_d[-1:])    # decode masks shrink by dropping units
+        prev_p = mp
+        masks_d.append(md)
     c.set_cu_split(256, 256)
     assert int.from_bytes(c.get_cu_mask(0).tobytes(), "little") == (1 << 256) - 1
 
