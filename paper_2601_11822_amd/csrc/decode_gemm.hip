@@ -223,9 +223,9 @@ size_t dgemm_partial_elems(int M, int N, int K, bool pair) {
 // `narrow`: workgroups of 128 weight rows (one tile per wave) instead of 256, twice as many of them, for the
 // projections that are not a gate/up pair.  The K slices and the order of every sum are those of the plan, so the
 // results are the same bits; only the number of compute units that have a workgroup changes.  The caller asks for it
-// when the side owns more than half of the chip: the plan's 96-128 workgroups then leave units idle (Llama-3-8B
-// decode step alone on 256 CUs 0.243 -> 0.2325 ms), whereas on a 128-CU partition one large workgroup per unit is
-// the faster shape (0.2914 against 0.2992 ms).
+// when the side owns more than 192 units: the plan's 96-128 workgroups then leave too many of them idle (Llama-3-8B
+// decode step alone on 256 CUs 0.243 -> 0.2325 ms), whereas on a partition one large workgroup per unit is the faster
+// shape (128 CUs: 0.2914 against 0.2992 ms; 160 CUs: 0.280 against 0.288 ms; 192 CUs: equal).
 void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &p, bool narrow) {
     constexpr int lds = 2 * DS_CH * 2048;
     const dim3 grid(p.cols, p.S), grid_narrow(2 * p.cols, p.S), block(256);

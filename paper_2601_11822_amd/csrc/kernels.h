@@ -116,7 +116,7 @@ struct DGemmPlan {
 bool dgemm_applies(int N, int K);
 DGemmPlan dgemm_plan(int N, int K, bool pair);
 size_t dgemm_partial_elems(int M, int N, int K, bool pair);
-// narrow: half-height workgroups, twice as many (same sums, same bits); for a side that owns more than half the chip
+// narrow: half-height workgroups, twice as many (same sums, same bits); for a side that owns (nearly) the whole chip
 void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &p, bool narrow);
 struct DEpiArgs {
     const float *part;        // [S][M][Nv]

@@ -755,7 +755,7 @@ int32_t decode_layer(rs_ctx *c, Workspace &w, int32_t layer, const void *x_in, v
         const rs_ctx::PackedLayer &pl = c->packed[layer];
         const int f = m.ffn_dim;
         float *ssq1 = w.ssq, *ssq2 = w.ssq + 64 * 64;
-        const bool narrow = c->side[RS_SIDE_DECODE].cus > RS_TOTAL_CUS / 2;   // more units than the plan has workgroups
+        const bool narrow = c->side[RS_SIDE_DECODE].cus > 192;   // (nearly) the whole chip: more units than the plan has workgroups
         tick(c, RS_SIDE_DECODE, 0);
         tick(c, RS_SIDE_DECODE, 1);
         const DGemmPlan pq = dgemm_plan(nqkv, d, false);
