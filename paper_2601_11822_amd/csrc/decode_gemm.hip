@@ -37,7 +37,9 @@ __device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_r
 //        epilogue write them.
 // ACT 1: activations row-major [M][K]; multiplied by gain[K] while staged; sums of squares written out.
 // PAIR : RT == 2 and the wave's two tiles are row tile f of Wp (gate) and of Wp2 (up); else RT tiles of Wp.
-template <int ACT, int RT, bool PAIR, int PD>
+// PSPLIT: RT == 1 and the pair is spread over waves: waves 0-1 take gate tiles 2x, 2x+1 of Wp, waves 2-3 the matching
+//         up tiles of Wp2 (half as many features per workgroup as PAIR, the same sums and the same output columns).
+template <int ACT, int RT, bool PAIR, int PD, bool PSPLIT = false>
 __global__ __launch_bounds__(256, 2) void dstream_kernel(DGemmArgs a, int kb_per_wg, int Nv) {
     constexpr int CH = DS_CH;
     // An activation piece is stored 8 steps after its load was issued, right behind a weight fragment that is
@@ -49,6 +51,7 @@ __global__ __launch_bounds__(256, 2) void dstream_kernel(DGemmArgs a, int kb_per
     // and no faster beside a prefill pass on 128: depth in flight is not what bounds this stream.
     static_assert(CH % PD == 0, "ring slots are static inside an unrolled chunk");
     static_assert(!PAIR || RT == 2, "a pair is a gate tile and an up tile");
+    static_assert(!PSPLIT || (RT == 1 && !PAIR), "a split pair is one tile per wave");
     extern __shared__ __attribute__((aligned(1024))) bf16_t slab[];   // [2][CH][2 row tiles][64 lanes][8]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c32 = lane & 31, h = lane >> 5;
@@ -63,6 +66,8 @@ __global__ __launch_bounds__(256, 2) void dstream_kernel(DGemmArgs a, int kb_per
     for (int t = 0; t < RT; ++t) {
         if (PAIR)
             w[t] = (t ? a.Wp2 : a.Wp) + (size_t)min(4 * (int)blockIdx.x + wave, Nt - 1) * 512 + lane * 8;
+        else if (PSPLIT)
+            w[t] = (wave >= 2 ? a.Wp2 : a.Wp) + (size_t)min(2 * (int)blockIdx.x + (wave & 1), Nt - 1) * 512 + lane * 8;
         else
             w[t] = a.Wp + (size_t)min((4 * (int)blockIdx.x + wave) * RT + t, Nt - 1) * 512 + lane * 8;
     }
@@ -166,7 +171,10 @@ __global__ __launch_bounds__(256, 2) void dstream_kernel(DGemmArgs a, int kb_per
         for (int tm = 0; tm < 2; ++tm) {
             const int m = 32 * tm + c32;
             if (m >= M) continue;
-            float *dst = a.part + ((size_t)blockIdx.y * M + m) * Nv + blockIdx.x * (128 * RT) + wave * (32 * RT) + 32 * tn;
+            // virtual columns: 64 per feature tile of a pair (32 gate, then 32 up), else the weight rows themselves
+            const int col = PSPLIT ? (2 * (int)blockIdx.x + (wave & 1)) * 64 + 32 * (wave >> 1)
+                                   : (int)blockIdx.x * (128 * RT) + wave * (32 * RT) + 32 * tn;
+            float *dst = a.part + ((size_t)blockIdx.y * M + m) * Nv + col;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 f32x4 v = {acc[tn][tm][4 * j], acc[tn][tm][4 * j + 1], acc[tn][tm][4 * j + 2], acc[tn][tm][4 * j + 3]};
@@ -202,11 +210,12 @@ DGemmPlan dgemm_plan(int N, int K, bool pair) {
     p.Nv = p.cols * 256;
     const int Kb = K / 16;
     // K slices: as many as keep the launch within about one workgroup per compute unit of a half-chip partition
-    // (128; a gate/up pair, whose N is wide, 256) with at least 32 k-blocks (two chunks) per slice, in whole
-    // chunks.  Measured on the Llama-3-8B shapes: on a partition the stream is bound by what one compute unit can
+    // (128) with at least 32 k-blocks (two chunks) per slice, in whole chunks.  (A wide gate/up pair was split
+    // once more before, for the whole chip's sake: 2 % slower on a 128-CU partition; the whole chip now gets its
+    // workgroups from the half-height forms of the launcher instead, which leave the sums as they are.)  Measured on the Llama-3-8B shapes: on a partition the stream is bound by what one compute unit can
     // pull, so one large workgroup per unit beats two half-sized ones (the activation rows are staged once
     // instead of twice); on the whole chip more, smaller workgroups win a little -- this is the better compromise.
-    const int cap = pair ? 256 : 128;
+    const int cap = 128;
     int S = 1;
     for (int s = 2; s <= 64; ++s)
         if (Kb % (s * DS_CH) == 0 && Kb / s >= 2 * DS_CH && p.cols * s <= cap) S = s;
@@ -220,8 +229,9 @@ size_t dgemm_partial_elems(int M, int N, int K, bool pair) {
     return (size_t)p.S * (size_t)M * (size_t)p.Nv;
 }
 
-// `narrow`: workgroups of 128 weight rows (one tile per wave) instead of 256, twice as many of them, for the
-// projections that are not a gate/up pair.  The K slices and the order of every sum are those of the plan, so the
+// `narrow`: workgroups of 128 weight rows (one tile per wave) instead of 256, twice as many of them; for a gate/up
+// pair, 64 features per workgroup (two gate tiles and their two up tiles, one per wave) instead of 128.
+// The K slices and the order of every sum are those of the plan, so the
 // results are the same bits; only the number of compute units that have a workgroup changes.  The caller asks for it
 // when the side owns more than 192 units: the plan's 96-128 workgroups then leave too many of them idle (Llama-3-8B
 // decode step alone on 256 CUs 0.243 -> 0.2325 ms), whereas on a partition one large workgroup per unit is the faster
@@ -230,7 +240,10 @@ void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &
     constexpr int lds = 2 * DS_CH * 2048;
     const dim3 grid(p.cols, p.S), grid_narrow(2 * p.cols, p.S), block(256);
     const bool rows = a.X_rows != nullptr;
-    if (p.pair) {
+    if (p.pair && narrow) {
+        if (rows) hipLaunchKernelGGL((dstream_kernel<1, 1, false, 8, true>), grid_narrow, block, lds, st, a, p.kb_per_wg, p.Nv);
+        else hipLaunchKernelGGL((dstream_kernel<0, 1, false, 8, true>), grid_narrow, block, lds, st, a, p.kb_per_wg, p.Nv);
+    } else if (p.pair) {
         if (rows) hipLaunchKernelGGL((dstream_kernel<1, 2, true, 8>), grid, block, lds, st, a, p.kb_per_wg, p.Nv);
         else hipLaunchKernelGGL((dstream_kernel<0, 2, true, 8>), grid, block, lds, st, a, p.kb_per_wg, p.Nv);
     } else if (narrow) {
@@ -376,4 +389,6 @@ void decode_gemm_kernels_init() {
     set((const void *)dstream_kernel<1, 2, true, 8>);
     set((const void *)dstream_kernel<0, 1, false, 8>);
     set((const void *)dstream_kernel<1, 1, false, 8>);
+    set((const void *)dstream_kernel<0, 1, false, 8, true>);
+    set((const void *)dstream_kernel<1, 1, false, 8, true>);
 }
