@@ -199,6 +199,11 @@ struct rs_ctx {
     int64_t step_graph_captures = 0, step_graph_launches = 0;
     int64_t steps_enqueued = 0, step_enqueue_ns = 0;   // decode steps of the serving loop and the host time their launches took
     bool capturing = false;      // a decode step is being recorded: no event records on the stream
+    // Held while a step is being recorded, and by the prefill thread around its wait on an event of the decode
+    // stream: the runtime takes a wait on an event whose stream is recording at that moment for a dependency inside the
+    // recording and draws the waiting stream into it (seen once in some ten engine runs: the prefill stream's next
+    // wait then failed with "dependency created on uncaptured work in another stream").
+    std::mutex capture_mu;
     std::vector<int64_t> last_batch;   // request ids of the rows of the most recent rs_step's decode batch
     Side side[2];
     bool over_alloc = true;
@@ -1797,7 +1802,10 @@ int32_t enqueue_prompts(rs_ctx *c, const PromptItem *items, int n, hipEvent_t wa
     }
     for (int q = 0; q <= n; ++q) seq.cu[q] = cu[q];
     const int T = cu[n];
-    if (wait_for) HIP_TRY(hipStreamWaitEvent(st, wait_for, 0));
+    if (wait_for) {
+        std::lock_guard<std::mutex> hold(c->capture_mu);   // not while the decode stream is recording a step
+        HIP_TRY(hipStreamWaitEvent(st, wait_for, 0));
+    }
     HIP_TRY(hipMemcpyAsync(c->d_ptab, c->h_ptab, (size_t)n * mb * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(c->d_pslots, c->h_pslots, n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipEventRecord(c->pstaged, st));
@@ -2157,11 +2165,16 @@ int32_t serve_step(rs_ctx *c, const rs_step_in *in, rs_step_out *out, bool token
                     }
                     hipGraph_t graph = nullptr;
                     hipGraphExec_t exec = nullptr;
-                    HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-                    c->capturing = true;
-                    const int32_t rc = enqueue_kernels(bucket);
-                    c->capturing = false;
-                    const hipError_t e = hipStreamEndCapture(st, &graph);
+                    int32_t rc;
+                    hipError_t e;
+                    {
+                        std::lock_guard<std::mutex> hold(c->capture_mu);
+                        HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+                        c->capturing = true;
+                        rc = enqueue_kernels(bucket);
+                        c->capturing = false;
+                        e = hipStreamEndCapture(st, &graph);
+                    }
                     if (rc) {
                         if (graph) (void)hipGraphDestroy(graph);
                         return rc;
