@@ -232,10 +232,22 @@ size_t dgemm_partial_elems(int M, int N, int K, bool pair) {
 // `narrow`: workgroups of 128 weight rows (one tile per wave) instead of 256, twice as many of them; for a gate/up
 // pair, 64 features per workgroup (two gate tiles and their two up tiles, one per wave) instead of 128.
 // The K slices and the order of every sum are those of the plan, so the
-// results are the same bits; only the number of compute units that have a workgroup changes.  The caller asks for it
-// when the side owns more than 192 units: the plan's 96-128 workgroups then leave too many of them idle (Llama-3-8B
-// decode step alone on 256 CUs 0.243 -> 0.2325 ms), whereas on a partition one large workgroup per unit is the faster
-// shape (128 CUs: 0.2914 against 0.2992 ms; 160 CUs: 0.280 against 0.288 ms; 192 CUs: equal).
+// results are the same bits; only the number of compute units that have a workgroup changes.  The caller picks the
+// form per projection with dgemm_prefers_half_height: on the whole chip the plan's 96-128 workgroups leave too many
+// units idle (Llama-3-8B decode step alone on 256 CUs 0.243 -> 0.2325 ms with half-height workgroups), on a 128-CU
+// partition one large workgroup per unit is the faster shape (0.2914 against 0.2992 ms), and where the full-height
+// count fills the units badly (128 workgroups on 96 units: two rounds, the second a third full) the half-height
+// form's three shorter rounds win (decode step on 96 CUs 0.402 -> 0.393 ms, on 192 CUs 0.265 -> 0.261 ms).
+// Which of the two forms a side of `cus` compute units launches: rounds of workgroups (one per unit) times what a
+// workgroup moves.  A full-height workgroup streams its weights plus a quarter as many activation bytes (64 rows
+// against 256), a half-height one half the weights and the same activations: 0.6 of the bytes.
+bool dgemm_prefers_half_height(const DGemmPlan &p, int cus) {
+    if (cus <= 0) return false;
+    const int wgs = p.cols * p.S;
+    const double full = (double)((wgs + cus - 1) / cus), half = 0.6 * (double)((2 * wgs + cus - 1) / cus);
+    return half < full;
+}
+
 void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &p, bool narrow) {
     constexpr int lds = 2 * DS_CH * 2048;
     const dim3 grid(p.cols, p.S), grid_narrow(2 * p.cols, p.S), block(256);

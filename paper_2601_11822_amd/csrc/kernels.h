@@ -116,8 +116,10 @@ struct DGemmPlan {
 bool dgemm_applies(int N, int K);
 DGemmPlan dgemm_plan(int N, int K, bool pair);
 size_t dgemm_partial_elems(int M, int N, int K, bool pair);
-// narrow: half-height workgroups, twice as many (same sums, same bits); for a side that owns (nearly) the whole chip
+// narrow: half-height workgroups, twice as many (same sums, same bits); dgemm_prefers_half_height says when, from the
+// number of compute units the side owns
 void launch_dgemm_partials(hipStream_t st, const DGemmArgs &a, const DGemmPlan &p, bool narrow);
+bool dgemm_prefers_half_height(const DGemmPlan &p, int cus);
 struct DEpiArgs {
     const float *part;        // [S][M][Nv]
     int S, Nv;

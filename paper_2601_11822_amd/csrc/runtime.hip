@@ -760,11 +760,11 @@ int32_t decode_layer(rs_ctx *c, Workspace &w, int32_t layer, const void *x_in, v
         const rs_ctx::PackedLayer &pl = c->packed[layer];
         const int f = m.ffn_dim;
         float *ssq1 = w.ssq, *ssq2 = w.ssq + 64 * 64;
-        const bool narrow = c->side[RS_SIDE_DECODE].cus > 192;   // (nearly) the whole chip: more units than the plan has workgroups
+        const int dcus = c->side[RS_SIDE_DECODE].cus;
         tick(c, RS_SIDE_DECODE, 0);
         tick(c, RS_SIDE_DECODE, 1);
         const DGemmPlan pq = dgemm_plan(nqkv, d, false);
-        launch_dgemm_partials(st, DGemmArgs{nullptr, (const bf16_t *)x_in, (const bf16_t *)lw.g1, ssq1, pl.wqkv, nullptr, w.partials, B, nqkv, d}, pq, narrow);
+        launch_dgemm_partials(st, DGemmArgs{nullptr, (const bf16_t *)x_in, (const bf16_t *)lw.g1, ssq1, pl.wqkv, nullptr, w.partials, B, nqkv, d}, pq, dgemm_prefers_half_height(pq, dcus));
         launch_qkv_rope_epilogue(st, QkvEpiArgs{w.partials, ssq1, pq.S, pq.Nv, d, m.rms_eps, w.qkv, c->rope, kp, vp, tables, ctx_lens,
                                                 c->err_flag + RS_SIDE_DECODE, B, m.n_q_heads, m.n_kv_heads, hd, max_blk,
                                                 c->pool.n_blocks, m.max_pos});
@@ -777,17 +777,17 @@ int32_t decode_layer(rs_ctx *c, Workspace &w, int32_t layer, const void *x_in, v
         launch_decode_attention(st, da);
         tick(c, RS_SIDE_DECODE, 4);
         const DGemmPlan po = dgemm_plan(d, qd, false);
-        launch_dgemm_partials(st, DGemmArgs{w.attn, nullptr, nullptr, nullptr, pl.wo, nullptr, w.partials, B, d, qd}, po, narrow);
+        launch_dgemm_partials(st, DGemmArgs{w.attn, nullptr, nullptr, nullptr, pl.wo, nullptr, w.partials, B, d, qd}, po, dgemm_prefers_half_height(po, dcus));
         launch_dgemm_epilogue(st, DEpiArgs{w.partials, po.S, po.Nv, nullptr, 0, d, m.rms_eps, (const bf16_t *)x_in, w.x1, B, d}, EPI_RESIDUAL);
         tick(c, RS_SIDE_DECODE, 5);
         tick(c, RS_SIDE_DECODE, 6);
         const DGemmPlan pg = dgemm_plan(f, d, true);
-        launch_dgemm_partials(st, DGemmArgs{nullptr, w.x1, (const bf16_t *)lw.g2, ssq2, pl.wg, pl.wu, w.partials, B, f, d}, pg, narrow);
+        launch_dgemm_partials(st, DGemmArgs{nullptr, w.x1, (const bf16_t *)lw.g2, ssq2, pl.wg, pl.wu, w.partials, B, f, d}, pg, dgemm_prefers_half_height(pg, dcus));
         launch_dgemm_epilogue(st, DEpiArgs{w.partials, pg.S, pg.Nv, ssq2, pg.S, d, m.rms_eps, nullptr, w.act, B, f}, EPI_SWIGLU);
         tick(c, RS_SIDE_DECODE, 7);
         if (dgemm_applies(d, f)) {
             const DGemmPlan pd = dgemm_plan(d, f, false);
-            launch_dgemm_partials(st, DGemmArgs{w.act, nullptr, nullptr, nullptr, pl.wd, nullptr, w.partials, B, d, f}, pd, narrow);
+            launch_dgemm_partials(st, DGemmArgs{w.act, nullptr, nullptr, nullptr, pl.wd, nullptr, w.partials, B, d, f}, pd, dgemm_prefers_half_height(pd, dcus));
             launch_dgemm_epilogue(st, DEpiArgs{w.partials, pd.S, pd.Nv, nullptr, 0, d, m.rms_eps, w.x1, (bf16_t *)x_out, B, d}, EPI_RESIDUAL);
         } else {
             GemmArgs gd{w.act, (const bf16_t *)lw.wd, nullptr, pl.wd, nullptr, w.x1, (bf16_t *)x_out, B, d, f, EPI_RESIDUAL,
