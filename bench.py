@@ -43,8 +43,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 # what the same counter reads for the 1 GiB device copy that run ends with (reads x2.0, writes
 # x1.0); the summaries are under profiles/.  Valid for the default workload only.
 TRAFFIC_BYTES = {
-    "gateup": 797909141.0,        # (360945 KiB fetched x 2.0 + 57344 KiB written) x 1024
-    "decode_attn": 680908372.0,   # ((326400 + 2961) KiB x 2.0 + 5739 + 512 KiB) x 1024, attention + merge
+    "gateup": 797909069.0,        # (360945 KiB fetched x 2.0 + 57344 KiB written) x 1024
+    "decode_attn": 680901140.0,   # ((326400 + 2961) KiB x 2.0 + 5739 + 512 KiB) x 1024, attention + merge
 }
 
 
